@@ -1,0 +1,379 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Every check below compares `oracle.tva_oracle` with an independent statement of
+the same fact: a textbook routine (scipy softmax / logsumexp on explicitly
+gathered keys), a closed form, an invariant or brute force.  The paper prints
+no numeric example of the attention path, so these pins fix the semantics
+(Tree Reranking Phase: a linearised subtree in which each token attends only to
+its ancestors; Method: batch B, context c, n verified tokens).
+"""
+import itertools
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp, softmax
+
+from oracle import tva_oracle as orc
+from paper_2510_26577_amd import workloads as wl
+
+
+def f64(bits):
+    return wl.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def seq_kv(w, b):
+    """[cache; tree] keys and values of sequence b as float64 [L+T, Hkv, D] (dense or paged)."""
+    L, t0, t1 = int(w.L[b]), int(w.cu_T[b]), int(w.cu_T[b + 1])
+    if w.paged:
+        idx = np.arange(L)
+        pages = w.page_table[b, idx // w.page_size]
+        kc = w.k_cache[pages, idx % w.page_size]
+        vc = w.v_cache[pages, idx % w.page_size]
+    else:
+        kc = w.k_cache[w.cu_L[b]:w.cu_L[b + 1]]
+        vc = w.v_cache[w.cu_L[b]:w.cu_L[b + 1]]
+    K = np.concatenate([f64(kc), f64(w.k_tree[t0:t1])], axis=0)
+    V = np.concatenate([f64(vc), f64(w.v_tree[t0:t1])], axis=0)
+    return K, V
+
+
+def plain_attention(q, K, V, scale):
+    """Unmasked single-query attention with library softmax: q [D], K,V [n, D]."""
+    s = scale * (K @ q)
+    return softmax(s) @ V, logsumexp(s)
+
+
+def path_gather_reference(w):
+    """Second, independent definition: for every node copy [cache; root..node]
+    into a fresh array and run plain unmasked attention for that node's query."""
+    out = np.zeros((w.sum_T, w.Hq, w.D))
+    lse = np.zeros((w.sum_T, w.Hq))
+    scale = float(np.float32(w.scale))
+    for b in range(w.B):
+        K, V = seq_kv(w, b)
+        L, t0 = int(w.L[b]), int(w.cu_T[b])
+        par = w.parent[t0:int(w.cu_T[b + 1])]
+        for i in range(len(par)):
+            path = []
+            a = i
+            while a >= 0:
+                path.append(a)
+                a = int(par[a])
+            keys = np.concatenate([np.arange(L), L + np.array(path[::-1], dtype=np.int64)])
+            for h in range(w.Hq):
+                g = h // w.G
+                o, l = plain_attention(f64(w.q[t0 + i, h]), K[keys, g], V[keys, g], scale)
+                out[t0 + i, h] = o
+                lse[t0 + i, h] = l
+    return out, lse
+
+
+def depths(par):
+    d = np.zeros(len(par), dtype=np.int64)
+    for i, p in enumerate(par):
+        d[i] = 0 if p < 0 else d[p] + 1
+    return d
+
+
+TOL = dict(rtol=1e-11, atol=1e-11)
+
+
+# ---------------------------------------------------------------- P6 / P13
+@pytest.mark.parametrize("name,mk", [
+    ("cfg1", wl.config1),
+    ("ragged_gqa", lambda: wl.random_workload(7, 3, 8, 2, 64, [5, 0, 33], [9, 4, 17], max_depth=5)),
+    ("paged", lambda: wl.random_workload(8, 2, 4, 2, 64, [37, 64], [6, 11], page_size=16)),
+    ("t72_two_words", lambda: wl.random_workload(9, 1, 2, 1, 64, [3], [72], max_depth=13)),
+])
+def test_path_gather_equals_masked(name, mk):
+    w = mk()
+    o, l = orc.tree_verify_attn(w)
+    ro, rl = path_gather_reference(w)
+    np.testing.assert_allclose(o, ro, **TOL)
+    np.testing.assert_allclose(l, rl, **TOL)
+
+
+# ---------------------------------------------------------------- P1
+def test_chain_tree_is_causal_attention():
+    rng = np.random.Generator(np.random.PCG64(11))
+    w = wl.make_workload("chain", 11, 2, 4, 2, 64, [19, 0], [wl.tree_chain(7), wl.tree_chain(5)], rng=rng)
+    o, l = orc.tree_verify_attn(w)
+    for b in range(w.B):
+        K, V = seq_kv(w, b)
+        L, t0 = int(w.L[b]), int(w.cu_T[b])
+        n = L + int(w.T[b])
+        for h in range(w.Hq):
+            g = h // w.G
+            Qs = f64(w.q[t0:t0 + int(w.T[b]), h])
+            S = float(np.float32(w.scale)) * (Qs @ K[:, g].T)         # [T, n]
+            pos_q = L + np.arange(int(w.T[b]))
+            S = np.where(np.arange(n)[None, :] <= pos_q[:, None], S, -np.inf)  # ordinary causal mask
+            np.testing.assert_allclose(o[t0:t0 + int(w.T[b]), h], softmax(S, axis=1) @ V[:, g], **TOL)
+            np.testing.assert_allclose(l[t0:t0 + int(w.T[b]), h], logsumexp(S, axis=1), **TOL)
+
+
+# ---------------------------------------------------------------- P2
+def test_single_node_is_decode_attention():
+    w = wl.random_workload(12, 3, 8, 4, 64, [40, 1, 0], [1, 1, 1])
+    o, l = orc.tree_verify_attn(w)
+    for b in range(3):
+        K, V = seq_kv(w, b)   # L+1 keys: the new token sees its own K/V
+        assert K.shape[0] == int(w.L[b]) + 1
+        for h in range(w.Hq):
+            ro, rl = plain_attention(f64(w.q[b, h]), K[:, h // w.G], V[:, h // w.G], float(np.float32(w.scale)))
+            np.testing.assert_allclose(o[b, h], ro, **TOL)
+            np.testing.assert_allclose(l[b, h], rl, **TOL)
+
+
+# ---------------------------------------------------------------- P5
+def test_all_ancestors_is_full_attention():
+    """The last node of a chain has every tree node as ancestor: unmasked attention over L+T keys."""
+    rng = np.random.Generator(np.random.PCG64(13))
+    w = wl.make_workload("chain", 13, 1, 2, 2, 64, [21], [wl.tree_chain(9)], rng=rng)
+    o, l = orc.tree_verify_attn(w)
+    K, V = seq_kv(w, 0)
+    for h in range(2):
+        ro, rl = plain_attention(f64(w.q[8, h]), K[:, h], V[:, h], float(np.float32(w.scale)))
+        np.testing.assert_allclose(o[8, h], ro, **TOL)
+        np.testing.assert_allclose(l[8, h], rl, **TOL)
+
+
+# ---------------------------------------------------------------- P3
+def test_sibling_swap_permutes_outputs():
+    rng = np.random.Generator(np.random.PCG64(14))
+    par = np.array([-1, 0, 0, 1, 1, 2, 4], dtype=np.int32)  # 3 and 4 are sibling leaves? 4 has child 6
+    par = np.array([-1, 0, 0, 1, 1, 2, 2], dtype=np.int32)  # 3,4 sibling leaves; 5,6 sibling leaves
+    w = wl.make_workload("sib", 14, 1, 4, 2, 64, [10], [par], rng=rng)
+    o, l = orc.tree_verify_attn(w)
+    perm = np.arange(7)
+    perm[[3, 4]] = [4, 3]
+    w2 = wl.make_workload("sib", 14, 1, 4, 2, 64, [10], [par], rng=np.random.Generator(np.random.PCG64(14)))
+    w2.q, w2.k_tree, w2.v_tree = w.q[perm].copy(), w.k_tree[perm].copy(), w.v_tree[perm].copy()
+    o2, l2 = orc.tree_verify_attn(w2)
+    np.testing.assert_allclose(o2, o[perm], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(l2, l[perm], rtol=0, atol=1e-13)
+    assert not np.allclose(o[3], o[4])
+
+
+# ---------------------------------------------------------------- P4
+def dp_masks(par):
+    """Independent construction: mask[i] = bit(i) | mask[parent[i]] with Python integers."""
+    m = []
+    for i, p in enumerate(par):
+        m.append((1 << i) | (m[p] if p >= 0 else 0))
+    return m
+
+
+def pack(masks, W):
+    out = np.zeros((len(masks), W), dtype=np.uint64)
+    for i, m in enumerate(masks):
+        for w_ in range(W):
+            out[i, w_] = (m >> (64 * w_)) & 0xFFFFFFFFFFFFFFFF
+    return out
+
+
+def test_ancestor_mask_exhaustive_small_trees():
+    """All topological parent arrays with one root for T <= 8 ((T-1)! of them), in one batch per T."""
+    for T in range(1, 9):
+        trees = [(-1,) + t for t in itertools.product(*[range(i) for i in range(1, T)])]
+        parent = np.array(trees, dtype=np.int32).reshape(-1)
+        cu_T = np.arange(len(trees) + 1, dtype=np.int32) * T
+        got = orc.ancestor_mask(parent, cu_T)
+        want = np.concatenate([pack(dp_masks(t), 1) for t in trees])
+        assert np.array_equal(got, want), T
+
+
+def test_ancestor_mask_random_large_and_forest():
+    rng = np.random.Generator(np.random.PCG64(15))
+    trees = [wl.tree_uniform(rng, T, md) for T, md in [(128, 13), (72, 13), (65, 3), (64, 64), (1, 1), (100, 100)]]
+    forest = wl.tree_uniform(rng, 90, 6)
+    forest[[17, 40, 70]] = -1  # several roots
+    trees.append(forest)
+    cu_T = np.zeros(len(trees) + 1, dtype=np.int32)
+    cu_T[1:] = np.cumsum([len(t) for t in trees])
+    got = orc.ancestor_mask(np.concatenate(trees), cu_T)
+    assert got.shape[1] == 2
+    want = np.concatenate([pack(dp_masks(t), 2) for t in trees])
+    assert np.array_equal(got, want)
+    # reachability by boolean matrix closure, a third formulation
+    for t, b in zip(trees, range(len(trees))):
+        T = len(t)
+        A = np.eye(T, dtype=bool)
+        for i, p in enumerate(t):
+            if p >= 0:
+                A[i, p] = True
+        R = A.copy()
+        for _ in range(8):  # (I+A)^(2^8) covers depth <= 128
+            R = (R.astype(np.int64) @ R.astype(np.int64)) > 0
+        bits = np.zeros((T, 128), dtype=bool)
+        m = got[cu_T[b]:cu_T[b + 1]]
+        for j in range(128):
+            bits[:, j] = (m[:, j // 64] >> np.uint64(j % 64)) & np.uint64(1)
+        assert np.array_equal(bits[:, :T], R)
+        assert not bits[:, T:].any()
+
+
+def test_ancestor_mask_rejects_bad_tree():
+    with pytest.raises(ValueError):
+        orc.ancestor_mask(np.array([-1, 1, 0], np.int32), np.array([0, 3], np.int32))
+    with pytest.raises(ValueError):
+        orc.ancestor_mask(np.array([-1, -2], np.int32), np.array([0, 2], np.int32))
+
+
+# ---------------------------------------------------------------- P7
+def test_zero_query_closed_form():
+    w = wl.random_workload(16, 2, 4, 2, 64, [13, 0], [10, 6], max_depth=4)
+    w.q[:] = 0
+    o, l = orc.tree_verify_attn(w)
+    for b in range(2):
+        K, V = seq_kv(w, b)
+        L, t0 = int(w.L[b]), int(w.cu_T[b])
+        par = w.parent[t0:int(w.cu_T[b + 1])]
+        dep = depths(par)
+        for i in range(len(par)):
+            np.testing.assert_allclose(l[t0 + i], np.log(L + dep[i] + 1.0), rtol=1e-13)
+            anc = [i]
+            while par[anc[-1]] >= 0:
+                anc.append(int(par[anc[-1]]))
+            keys = list(range(L)) + [L + a for a in anc]
+            for h in range(w.Hq):
+                np.testing.assert_allclose(o[t0 + i, h], V[keys, h // w.G].mean(axis=0), rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P8
+def test_constant_values_closed_form():
+    w = wl.random_workload(17, 2, 4, 4, 64, [9, 30], [7, 5], page_size=16)
+    v0 = wl.f32_to_bf16_bits(np.linspace(-2, 2, 64, dtype=np.float32))
+    w.v_cache[:] = v0
+    w.v_tree[:] = v0
+    o, _ = orc.tree_verify_attn(w)
+    np.testing.assert_allclose(o, np.broadcast_to(f64(v0), o.shape), rtol=1e-13, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P9
+def test_dominant_key_and_non_ancestor_has_no_effect():
+    par = np.array([-1, 0, 0, 1, 2], dtype=np.int32)
+    rng = np.random.Generator(np.random.PCG64(18))
+    w = wl.make_workload("dom", 18, 1, 1, 1, 64, [12], [par], rng=rng, scale=1.0)
+    w.q[:] = wl.f32_to_bf16_bits(np.full(64, 1.0, np.float32))       # q = ones
+    w.k_cache[:] = 0
+    w.k_tree[:] = 0
+    w.k_tree[1] = wl.f32_to_bf16_bits(np.full(64, 1.0, np.float32))  # node 1 scores 64, everything else 0
+    o, l = orc.tree_verify_attn(w)
+    V1 = f64(w.v_tree[1, 0])
+    for i in (1, 3):           # node 1 and its child see it: it dominates by e^64
+        np.testing.assert_allclose(o[i, 0], V1, atol=1e-20 + 1e-12)
+        np.testing.assert_allclose(l[i, 0], 64.0, atol=1e-12)
+    # nodes 0, 2, 4 do not have node 1 as ancestor: result is the zero-score mean
+    K, V = seq_kv(w, 0)
+    for i, anc in ((0, [0]), (2, [0, 2]), (4, [0, 2, 4])):
+        keys = list(range(12)) + [12 + a for a in anc]
+        np.testing.assert_allclose(o[i, 0], V[keys, 0].mean(axis=0), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(l[i, 0], np.log(len(keys)), rtol=1e-13)
+
+
+# ---------------------------------------------------------------- P10
+@pytest.mark.parametrize("cuts", [(0, 7), (5,), (20, 24, 26), (1, 2, 3, 30)])
+def test_split_and_merge_equals_whole(cuts):
+    w = wl.random_workload(19, 1, 4, 2, 64, [23], [8])
+    o, l = orc.tree_verify_attn(w)
+    edges = [0] + list(cuts) + [23 + 8]
+    po, pl = [], []
+    for lo, hi in zip(edges[:-1], edges[1:]):
+        a, b_ = orc.tree_verify_attn(w, key_range=(lo, hi))
+        po.append(a.reshape(-1, w.D))
+        pl.append(b_.reshape(-1))
+    mo, ml = orc.merge_splits(np.stack(po), np.stack(pl))
+    np.testing.assert_allclose(mo, o.reshape(-1, w.D), **TOL)
+    np.testing.assert_allclose(ml, l.reshape(-1), **TOL)
+    # and merging by library logsumexp / explicit weights, independent of merge_splits
+    PL = np.stack(pl)
+    ref_l = logsumexp(PL, axis=0)
+    wts = np.exp(PL - ref_l[None])
+    np.testing.assert_allclose(ml, ref_l, **TOL)
+    np.testing.assert_allclose(mo, (wts[..., None] * np.stack(po)).sum(0), **TOL)
+
+
+def test_key_range_rows_and_empty_partial():
+    w = wl.random_workload(20, 2, 2, 1, 64, [6, 9], [3, 4])
+    o, l = orc.tree_verify_attn(w)
+    rows = [(1, 3, 1), (0, 0, 0), (1, 0, 1)]
+    ro, rl = orc.tree_verify_attn(w, rows=rows)
+    for n, (b, i, h) in enumerate(rows):
+        assert np.array_equal(ro[n], o[w.cu_T[b] + i, h]) and rl[n] == l[w.cu_T[b] + i, h]
+    # a key range holding only a non-ancestor tree key is an empty partial: lse = -inf, out = 0
+    par = w.parent[w.cu_T[1]:]
+    leaf = 3
+    non_anc = [j for j in range(4) if j not in (leaf, *_ancestors(par, leaf))]
+    if non_anc:
+        k = int(w.L[1]) + non_anc[0]
+        eo, el = orc.tree_verify_attn(w, rows=[(1, leaf, 0)], key_range=(k, k + 1))
+        assert el[0] == -np.inf and not eo.any()
+
+
+def _ancestors(par, i):
+    out = []
+    while par[i] >= 0:
+        i = int(par[i])
+        out.append(i)
+    return out
+
+
+# ---------------------------------------------------------------- P11
+def test_gqa_equals_mha_with_repeated_kv_heads():
+    w = wl.random_workload(21, 2, 8, 2, 64, [17, 4], [6, 9])
+    o, l = orc.tree_verify_attn(w)
+    w2 = wl.random_workload(21, 2, 8, 2, 64, [17, 4], [6, 9])
+    G = w.G
+    w2.Hkv = 8
+    w2.k_tree, w2.v_tree = np.repeat(w.k_tree, G, axis=1), np.repeat(w.v_tree, G, axis=1)
+    w2.k_cache, w2.v_cache = np.repeat(w.k_cache, G, axis=1), np.repeat(w.v_cache, G, axis=1)
+    o2, l2 = orc.tree_verify_attn(w2)
+    assert np.array_equal(o, o2) and np.array_equal(l, l2)
+
+
+# ---------------------------------------------------------------- P12
+def test_paged_equals_dense():
+    w = wl.random_workload(22, 3, 4, 2, 64, [33, 16, 0], [5, 7, 3])
+    o, l = orc.tree_verify_attn(w)
+    ps = 16
+    rng = np.random.Generator(np.random.PCG64(23))
+    npg = [(int(x) + ps - 1) // ps for x in w.L]
+    pool = sum(npg) + 3
+    perm = rng.permutation(pool)
+    pt = np.full((3, max(npg)), -1, np.int32)
+    kp = np.full((pool, ps, w.Hkv, w.D), 0x7FC0, np.uint16)  # NaN everywhere not written
+    vp = np.full((pool, ps, w.Hkv, w.D), 0x7FC0, np.uint16)
+    used = 0
+    for b in range(3):
+        pt[b, :npg[b]] = perm[used:used + npg[b]]
+        used += npg[b]
+        for t in range(int(w.L[b])):
+            kp[pt[b, t // ps], t % ps] = w.k_cache[w.cu_L[b] + t]
+            vp[pt[b, t // ps], t % ps] = w.v_cache[w.cu_L[b] + t]
+    w.k_cache, w.v_cache, w.page_table, w.page_size, w.cu_L = kp, vp, pt, ps, None
+    o2, l2 = orc.tree_verify_attn(w)
+    assert np.array_equal(o, o2) and np.array_equal(l, l2)  # also: NaN tails and -1 entries never read
+
+
+# ---------------------------------------------------------------- scale / LSE convention
+def test_scale_and_natural_log_convention():
+    """One cached key, one node, D=64: two keys with known scores -> LSE = ln(e^{s0}+e^{s1})."""
+    rng = np.random.Generator(np.random.PCG64(24))
+    w = wl.make_workload("two", 24, 1, 1, 1, 64, [1], [wl.tree_chain(1)], rng=rng, scale=0.125)
+    one = wl.f32_to_bf16_bits(np.ones(64, np.float32))
+    w.q[:] = one
+    w.k_cache[:] = one                                                 # s0 = 0.125 * 64 = 8
+    w.k_tree[:] = wl.f32_to_bf16_bits(np.full(64, 0.5, np.float32))    # s1 = 4
+    w.v_cache[:] = wl.f32_to_bf16_bits(np.full(64, 1.0, np.float32))
+    w.v_tree[:] = wl.f32_to_bf16_bits(np.full(64, -1.0, np.float32))
+    o, l = orc.tree_verify_attn(w)
+    np.testing.assert_allclose(l[0, 0], np.log(np.exp(8.0) + np.exp(4.0)), rtol=1e-14)
+    p0 = 1.0 / (1.0 + np.exp(-4.0))
+    np.testing.assert_allclose(o[0, 0], np.full(64, p0 - (1 - p0)), rtol=1e-13)
+
+
+def test_bf16_round_trip_and_rounding():
+    x = np.array([1.0, 1.00390625, 1.005859375, -3.140625, 0.0, 65280.0], np.float32)
+    b = wl.f32_to_bf16_bits(x)
+    assert np.array_equal(wl.bf16_bits_to_f32(b), np.array([1.0, 1.0, 1.0078125, -3.140625, 0.0, 65280.0], np.float32))
