@@ -1,0 +1,165 @@
+/*
+ * libtva -- tree-masked verification attention for AMD MI355X (gfx950).
+ *
+ * C ABI of the data-parallel hot path of cost-aware draft-tree speculative
+ * decoding: in the target model's verification pass every draft-tree token of
+ * every sequence in the batch attends to that sequence's cached context plus
+ * its own ancestors in the tree (paper: "Tree Reranking Phase", last paragraph:
+ * the selected subtree is linearised and the attention mask lets each token see
+ * only its ancestors; "Method", opening paragraphs: a batch of B samples with
+ * context length c verifies n tree tokens, at a cost f_T(B, c, n) that the
+ * tree builder trades against acceptance).
+ *
+ * Conventions shared by all entry points
+ *   - Every pointer marked "device" is GPU memory the CALLER owns and keeps
+ *     alive until the work queued on `stream` has finished.  The library never
+ *     allocates, frees or synchronises; inputs are never written.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     work is queued on it and the call returns immediately.
+ *   - bf16 tensors are raw 16-bit patterns, innermost dimension contiguous.
+ *   - Return value: TVA_OK (0) or a negative tva_status; tva_strerror() names it.
+ *     A failing call queues nothing.
+ *   - Trees: node indices are local to their tree, parent = -1 marks a root,
+ *     and the linearised order must be topological (parent[i] < i).  A node
+ *     attends to itself and to its ancestors.
+ */
+#ifndef TVA_H
+#define TVA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TVA_OK = 0,
+  TVA_INVALID_ARG = -1,         /* null pointer, bad sizes, both / neither cache form */
+  TVA_UNSUPPORTED = -2,         /* D not in {64,128}, max_T > 128, ... */
+  TVA_WORKSPACE_TOO_SMALL = -3, /* see tva_workspace_bytes() */
+  TVA_HIP_ERROR = -4            /* a launch failed; hipGetLastError has details */
+} tva_status;
+
+#define TVA_MAX_TREE 128 /* nodes per tree supported by the attention kernels (2 mask words) */
+
+/*
+ * Arguments of tva_tree_verify_attn.
+ *
+ * Shapes: B sequences; sequence b verifies T_b = cu_T[b+1]-cu_T[b] tree tokens
+ * against L[b] cached tokens.  Hq query heads, Hkv KV heads (Hq % Hkv == 0),
+ * query head h reads KV head h / (Hq/Hkv).  Head dimension D is 64 or 128.
+ *
+ * KV cache, exactly one of two forms:
+ *   dense : cu_L != NULL, page_table == NULL.  Token t of sequence b is row
+ *           cu_L[b] + t of k_cache / v_cache.
+ *   paged : page_table != NULL, cu_L == NULL.  Token t of sequence b is slot
+ *           t % page_size of page page_table[b*max_pages + t/page_size].
+ *           Entries past ceil(L[b]/page_size) and slots past L[b] in the last
+ *           page are never read.
+ * In both forms element d of KV head g of a token lives at
+ *   base + page*stride_page + slot*stride_tok + g*stride_head + d   (elements),
+ * with page = 0 and slot = the row index in the dense form.  A stride given as
+ * 0 takes its packed default ([.., Hkv, D] token-major: stride_head = D,
+ * stride_tok = Hkv*D, stride_page = page_size*stride_tok).  Addresses of rows
+ * must be 16-byte aligned (strides multiples of 8 elements).
+ */
+typedef struct tva_args {
+  int32_t B, Hq, Hkv, D;
+  int32_t sum_T;      /* cu_T[B]: total tree tokens */
+  int32_t max_T;      /* host-side upper bound of T_b, <= TVA_MAX_TREE */
+  int32_t mask_words; /* 64-bit words per ancestor-mask row, >= ceil(max_T/64), <= 2 */
+  int32_t max_L;      /* host-side upper bound of L[b] (sizes the launch; a value
+                         below some L[b] truncates that sequence's context) */
+  float scale;        /* softmax scale applied to q.k, > 0 (1/sqrt(D) usually) */
+
+  const int32_t *cu_T; /* device [B+1] */
+  const int32_t *L;    /* device [B], each >= 0 */
+  const void *q;       /* device bf16 [sum_T, Hq, D] */
+  const void *k_tree;  /* device bf16 [sum_T, Hkv, D]: keys of the tree tokens */
+  const void *v_tree;  /* device bf16 [sum_T, Hkv, D] */
+  const uint64_t *anc_mask; /* device [sum_T, mask_words]: bit j of row i set iff node j
+                               is node i or one of its ancestors (tva_build_ancestor_mask) */
+
+  const void *k_cache, *v_cache; /* device bf16, dense or paged (above) */
+  const int32_t *cu_L;           /* device [B+1] or NULL */
+  const int32_t *page_table;     /* device [B, max_pages] or NULL */
+  int32_t page_size, max_pages;  /* paged form only */
+  int64_t stride_page, stride_tok, stride_head; /* elements; 0 = packed default */
+
+  float *out; /* device fp32 [sum_T, Hq, D] */
+  float *lse; /* device fp32 [sum_T, Hq]: natural-log sum-exp of the scaled scores */
+
+  void *workspace;        /* device scratch for the KV splits, may be NULL if 0 bytes */
+  size_t workspace_bytes; /* >= tva_workspace_bytes(args) */
+  int32_t num_splits;     /* KV splits per sequence; 0 = library chooses */
+} tva_args;
+
+/*
+ * Ancestor masks from parent arrays (paper: Tree Reranking Phase -- after the
+ * subtree is linearised "each token attends only to its ancestors").
+ *   parent   device int32 [cu_T[B]]  local parent index per node, -1 = root
+ *   cu_T     device int32 [B+1]
+ *   max_T    host upper bound of the tree sizes (any value >= 1)
+ *   mask_words  words per mask row, >= ceil(max_T/64)
+ *   mask     device uint64 [cu_T[B], mask_words], fully overwritten: bit (j%64) of
+ *            word (j/64) of row i is set iff j == i or j is an ancestor of i
+ *   err_flag device int32[1] or NULL.  If given it must be zero on entry; a node
+ *            whose parent is outside [-1, i-1] makes the kernel store
+ *            1 + (smallest such global node index) there, and that node's row
+ *            then holds only the bits gathered before the bad link.  The call
+ *            itself still returns TVA_OK (detection is asynchronous).
+ * One launch per decode step serves all layers of the verification pass.
+ */
+int tva_build_ancestor_mask(const int32_t *parent, const int32_t *cu_T, int32_t B, int32_t max_T,
+                            int32_t mask_words, uint64_t *mask, int32_t *err_flag, void *stream);
+
+/*
+ * Scratch bytes tva_tree_verify_attn needs for these shapes.  Only the shape
+ * fields, max_L and num_splits are read (no device memory is touched).
+ * Returns 0 when a single split is used, (size_t)-1 on invalid arguments.
+ */
+size_t tva_workspace_bytes(const tva_args *a);
+
+/*
+ * Number of KV splits the library will use for these shapes (>= 1), after
+ * applying num_splits (0 = automatic) and rounding; -1 on invalid arguments.
+ */
+int32_t tva_plan_splits(const tva_args *a);
+
+/*
+ * The attention itself.  For sequence b, tree node i, query head h (KV head
+ * g = h / (Hq/Hkv)) with keys k = the L[b] cached tokens followed by the tree
+ * tokens j for which bit j of anc_mask row i is set:
+ *     s_k   = scale * <q[b,i,h,:], K[b,k,g,:]>
+ *     lse   = log sum_k exp(s_k)
+ *     out   = sum_k exp(s_k - lse) * V[b,k,g,:]
+ * computed with bf16 inputs, fp32 accumulation, online softmax over KV splits
+ * and a final merge of the splits.  Rows whose mask row is empty and L[b] = 0
+ * get out = 0, lse = -inf.
+ */
+int tva_tree_verify_attn(const tva_args *a, void *stream);
+
+/*
+ * Merge of split partial results (the step that follows from splitting a
+ * softmax over disjoint key sets; also what a context-parallel deployment
+ * would run after gathering per-device partials):
+ *     lse = log sum_s exp(lse_s),  out = sum_s exp(lse_s - lse) * out_s.
+ *   part_out device fp32 [S, n_rows, D]   normalised partial outputs
+ *   part_lse device fp32 [S, n_rows]      natural-log partial LSE (-inf = empty)
+ *   out      device fp32 [n_rows, D];  lse device fp32 [n_rows]
+ */
+int tva_merge_splits(const float *part_out, const float *part_lse, int32_t S, int64_t n_rows,
+                     int32_t D, float *out, float *lse, void *stream);
+
+const char *tva_strerror(int code);
+
+/* Library version and sizeof(tva_args), for a binding to check that it loaded
+ * what it expects and mirrors the struct correctly. */
+int tva_version(void);
+size_t tva_sizeof_args(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TVA_H */

@@ -1,0 +1,212 @@
+"""Thin ctypes binding of libtva (argument marshalling only).
+
+Every step of the path runs in the HIP kernels of ``libtva.so``; this module
+turns torch tensors into raw device pointers and fills the C argument struct
+declared in ``include/tva.h``.  torch is used for device memory and streams
+only.  There is no CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+LIB_PATH = os.path.join(_HERE, "libtva.so")
+SRC_PATH = os.path.join(_HERE, "csrc", "tva.hip")
+INCLUDE_DIR = os.path.join(_ROOT, "include")
+
+TVA_OK = 0
+TVA_MAX_TREE = 128
+EXPECTED_VERSION = 1
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/tva.hip for gfx950 into libtva.so (in-tree)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-shared", "-fPIC", "-o", LIB_PATH, SRC_PATH]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    lines = [l for l in res.stdout.splitlines() if "is not a recognized feature" not in l]
+    if verbose or res.returncode:
+        print("\n".join(lines))
+    if res.returncode:
+        raise RuntimeError("hipcc failed building libtva.so")
+    return LIB_PATH
+
+
+class TvaArgs(ctypes.Structure):
+    """Mirror of `struct tva_args`."""
+    _fields_ = [
+        ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32),
+        ("sum_T", ctypes.c_int32), ("max_T", ctypes.c_int32), ("mask_words", ctypes.c_int32),
+        ("max_L", ctypes.c_int32), ("scale", ctypes.c_float),
+        ("cu_T", ctypes.c_void_p), ("L", ctypes.c_void_p),
+        ("q", ctypes.c_void_p), ("k_tree", ctypes.c_void_p), ("v_tree", ctypes.c_void_p),
+        ("anc_mask", ctypes.c_void_p),
+        ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+        ("cu_L", ctypes.c_void_p), ("page_table", ctypes.c_void_p),
+        ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
+        ("stride_page", ctypes.c_int64), ("stride_tok", ctypes.c_int64), ("stride_head", ctypes.c_int64),
+        ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("num_splits", ctypes.c_int32),
+    ]
+
+
+EXPORTS = ("tva_build_ancestor_mask", "tva_workspace_bytes", "tva_plan_splits",
+           "tva_tree_verify_attn", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
+
+_lib = None
+
+
+def load_library():
+    """Load libtva.so; raises if it is absent (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.tva_version.restype = ctypes.c_int
+    lib.tva_strerror.restype = ctypes.c_char_p
+    lib.tva_strerror.argtypes = [ctypes.c_int]
+    lib.tva_build_ancestor_mask.restype = ctypes.c_int
+    lib.tva_build_ancestor_mask.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                            ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.tva_workspace_bytes.restype = ctypes.c_size_t
+    lib.tva_workspace_bytes.argtypes = [ctypes.POINTER(TvaArgs)]
+    lib.tva_plan_splits.restype = ctypes.c_int32
+    lib.tva_plan_splits.argtypes = [ctypes.POINTER(TvaArgs)]
+    lib.tva_tree_verify_attn.restype = ctypes.c_int
+    lib.tva_tree_verify_attn.argtypes = [ctypes.POINTER(TvaArgs), ctypes.c_void_p]
+    lib.tva_merge_splits.restype = ctypes.c_int
+    lib.tva_merge_splits.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
+                                     ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.tva_sizeof_args.restype = ctypes.c_size_t
+    if lib.tva_version() != EXPECTED_VERSION or lib.tva_sizeof_args() != ctypes.sizeof(TvaArgs):
+        raise RuntimeError("libtva.so is stale: rebuild it")
+    _lib = lib
+    return lib
+
+
+class TvaError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"libtva: {load_library().tva_strerror(code).decode()} ({code})")
+
+
+def _check(code: int) -> None:
+    if code != TVA_OK:
+        raise TvaError(code)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _p(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def build_ancestor_mask(parent, cu_T, max_T: int, mask=None, err_flag=None, stream=None):
+    """parent int32 [sum_T], cu_T int32 [B+1] (device) -> mask int64 [sum_T, W]
+    holding the uint64 bit patterns.  `err_flag` (int32[1], zeroed by the
+    caller) receives 1 + index of the first malformed node, asynchronously."""
+    import torch
+    lib = load_library()
+    B = cu_T.numel() - 1
+    W = max(1, (int(max_T) + 63) // 64)
+    if mask is None:
+        mask = torch.empty((parent.numel(), W), dtype=torch.int64, device=parent.device)
+    else:
+        W = mask.shape[1]
+    _check(lib.tva_build_ancestor_mask(_p(parent), _p(cu_T), B, int(max_T), W, _p(mask), _p(err_flag),
+                                       _stream_ptr(stream)))
+    return mask
+
+
+def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: int, max_L: int,
+              scale: float, cu_L=None, page_table=None, page_size: int = 0, strides=(0, 0, 0),
+              num_splits: int = 0, out=None, lse=None, workspace=None) -> TvaArgs:
+    """Fill `tva_args` from tensors (q [sum_T,Hq,D], k_tree [sum_T,Hkv,D], ...)."""
+    a = TvaArgs()
+    a.B = cu_T.numel() - 1
+    a.sum_T, a.Hq, a.D = int(q.shape[0]), int(q.shape[1]), int(q.shape[2])
+    a.Hkv = int(k_tree.shape[1])
+    a.max_T, a.max_L = int(max_T), int(max_L)
+    a.mask_words = int(anc_mask.shape[1]) if anc_mask is not None else max(1, (int(max_T) + 63) // 64)
+    a.scale = float(scale)
+    a.cu_T, a.L = _p(cu_T), _p(L)
+    a.q, a.k_tree, a.v_tree, a.anc_mask = _p(q), _p(k_tree), _p(v_tree), _p(anc_mask)
+    a.k_cache, a.v_cache = _p(k_cache), _p(v_cache)
+    a.cu_L, a.page_table = _p(cu_L), _p(page_table)
+    a.page_size = int(page_size)
+    a.max_pages = int(page_table.shape[1]) if page_table is not None else 0
+    a.stride_page, a.stride_tok, a.stride_head = (int(s) for s in strides)
+    a.out, a.lse = _p(out), _p(lse)
+    a.workspace = _p(workspace)
+    a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    a.num_splits = int(num_splits)
+    return a
+
+
+def workspace_bytes(args: TvaArgs) -> int:
+    n = load_library().tva_workspace_bytes(ctypes.byref(args))
+    if n == ctypes.c_size_t(-1).value:
+        raise TvaError(-1)
+    return int(n)
+
+
+def plan_splits(args: TvaArgs) -> int:
+    n = load_library().tva_plan_splits(ctypes.byref(args))
+    if n < 0:
+        raise TvaError(-1)
+    return int(n)
+
+
+def tree_verify_attn_raw(args: TvaArgs, stream=None) -> None:
+    """Queue the attention on `stream` with a prepared argument struct."""
+    _check(load_library().tva_tree_verify_attn(ctypes.byref(args), _stream_ptr(stream)))
+
+
+def tree_verify_attn(q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, *, max_T: int, max_L: int,
+                     scale: float, cu_L=None, page_table=None, page_size: int = 0, strides=(0, 0, 0),
+                     num_splits: int = 0, out=None, lse=None, workspace=None, stream=None):
+    """Tree-masked verification attention.  Returns (out fp32 [sum_T,Hq,D], lse fp32 [sum_T,Hq]).
+    bf16 tensors may be torch.bfloat16 or int16/uint16 bit patterns."""
+    import torch
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    args = make_args(q=q, k_tree=k_tree, v_tree=v_tree, k_cache=k_cache, v_cache=v_cache, anc_mask=anc_mask,
+                     cu_T=cu_T, L=L, max_T=max_T, max_L=max_L, scale=scale, cu_L=cu_L, page_table=page_table,
+                     page_size=page_size, strides=strides, num_splits=num_splits, out=out, lse=lse)
+    need = workspace_bytes(args)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty((need + 3) // 4, dtype=torch.float32, device=q.device)
+    if workspace is not None:
+        args.workspace = workspace.data_ptr()
+        args.workspace_bytes = workspace.numel() * workspace.element_size()
+    tree_verify_attn_raw(args, stream)
+    return out, lse
+
+
+def merge_splits(part_out, part_lse, out=None, lse=None, stream=None):
+    """part_out fp32 [S, n, D], part_lse fp32 [S, n] -> (out [n, D], lse [n])."""
+    import torch
+    S, n, D = part_out.shape
+    if out is None:
+        out = torch.empty((n, D), dtype=torch.float32, device=part_out.device)
+    if lse is None:
+        lse = torch.empty((n,), dtype=torch.float32, device=part_out.device)
+    _check(load_library().tva_merge_splits(_p(part_out), _p(part_lse), S, n, D, _p(out), _p(lse),
+                                           _stream_ptr(stream)))
+    return out, lse

@@ -1,0 +1,714 @@
+// libtva: tree-masked verification attention for gfx950 (MI355X).
+//
+// Kernels
+//   anc_mask_kernel   parent arrays -> ancestor-or-self bitmasks (Tree Reranking Phase:
+//                     each linearised tree token attends only to its ancestors)
+//   attn_kernel       split-KV attention of all tree tokens of one (sequence, KV head)
+//                     against one chunk of that sequence's cache (+ the tree's own
+//                     keys under the ancestor mask, folded into the last chunk)
+//   merge_kernel      merges the KV splits
+//
+// attn_kernel in one paragraph.  The T_b*G query rows that share a KV head
+// (row = node*G + head-in-group) form the N side of 32x32x16 bf16 MFMAs; keys
+// form the M side, so that S^T = K Q^T comes out with one query row per lane
+// (row max / row sum need one cross-half exchange, no LDS) and the
+// probabilities are already in the B-operand layout of the second product
+// O^T = V^T P^T.  K/V tiles are staged once per workgroup in LDS; the V^T
+// operand is fetched with the LDS transpose read (ds_read_b64_tr_b16), so V
+// stays in its natural [key][d] layout.  Waves of a workgroup are arranged
+// WM x WK: WM groups own different query rows, WK groups own different keys of
+// each tile and are merged through LDS at the end (used when few rows share a
+// KV head, so that the workgroup still has four waves streaming keys).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tva.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---------------------------------------------------------------------------------------
+// ancestor masks
+// ---------------------------------------------------------------------------------------
+// One thread per node walks its parent chain.  A link that does not go strictly
+// downward (or below -1) is reported and ends the walk, so every thread finishes
+// in at most T_b steps.
+__global__ void anc_mask_kernel(const int32_t *__restrict__ parent, const int32_t *__restrict__ cu_T,
+                                int B, int W, uint64_t *__restrict__ mask, int32_t *err_flag) {
+  const int b = blockIdx.x;
+  const int t0 = cu_T[b], T = cu_T[b + 1] - t0;
+  for (int i = threadIdx.x; i < T; i += blockDim.x) {
+    uint64_t m[4] = {0, 0, 0, 0};  // W <= 4 handled in registers, larger W spills to the loop below
+    uint64_t *row = mask + (size_t)(t0 + i) * W;
+    if (W > 4)
+      for (int w = 0; w < W; ++w) row[w] = 0;
+    int a = i;
+    while (true) {
+      if ((a >> 6) < W) {  // a tree larger than the mask row (caller's max_T too small) loses bits, never memory
+        if (W <= 4) m[a >> 6] |= 1ull << (a & 63);
+        else row[a >> 6] |= 1ull << (a & 63);
+      }
+      const int p = parent[t0 + a];
+      if (p < -1 || p >= a) {
+        if (err_flag) {
+          // smallest offending global index + 1 (0 = none yet)
+          const int code = t0 + a + 1;
+          int old = atomicCAS(err_flag, 0, code);
+          while (old != 0 && old > code) {
+            const int seen = atomicCAS(err_flag, old, code);
+            if (seen == old) break;
+            old = seen;
+          }
+        }
+        break;
+      }
+      if (p < 0) break;
+      a = p;
+    }
+    if (W <= 4)
+      for (int w = 0; w < W; ++w) row[w] = m[w];
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// attention
+// ---------------------------------------------------------------------------------------
+struct AttnParams {
+  const __bf16 *q, *k_tree, *v_tree, *k_cache, *v_cache;
+  const int32_t *cu_T, *L, *cu_L, *page_table;
+  const uint64_t *mask;
+  float *out, *lse;            // final results
+  float *part_out, *part_lse;  // [S, sum_T, Hq, D], [S, sum_T, Hq] when S > 1
+  int B, Hq, Hkv, G, sum_T, W;
+  int chunk_keys, n_chunks, n_row_blocks, max_L;
+  int page_size, max_pages;
+  int64_t stride_page, stride_tok, stride_head;
+  float scale_log2;  // scale * log2(e)
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// max over the two 32-lane halves (lanes l and l^32 hold the same query row)
+__device__ __forceinline__ float half_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int D, int WM, int WK, int RB, int KB, bool PAGED>
+struct AttnCfg {
+  static constexpr int NW = WM * WK;
+  static constexpr int NT = NW * 64;
+  static constexpr int TK = WK * KB * 32;  // keys per tile
+  static constexpr int BM = WM * RB * 32;  // query rows per workgroup
+  static constexpr int DC = D / 8;         // 16-byte chunks per K/V row
+  static constexpr int KP = D * 2 + 16;    // LDS row pitch of K (bytes): b128 reads, key per lane
+  static constexpr int VP = D * 2 + 32;    // LDS row pitch of V (bytes): transpose reads, 4 keys x 32 B
+  static constexpr int NLOAD = TK * DC / NT;
+  static constexpr int TILE_BYTES = TK * (KP + VP);
+  static constexpr int MERGE_BYTES = (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
+  static constexpr int SMEM = TILE_BYTES > MERGE_BYTES ? TILE_BYTES : MERGE_BYTES;
+  static_assert(TK * DC % NT == 0, "tile must divide evenly over the threads");
+};
+
+template <int D, int WM, int WK, int RB, int KB, bool PAGED>
+__global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
+  using C = AttnCfg<D, WM, WK, RB, KB, PAGED>;
+  constexpr int NT = C::NT, TK = C::TK, BM = C::BM, DC = C::DC, KP = C::KP, VP = C::VP, NLOAD = C::NLOAD;
+  constexpr int NS = D / 16;  // k-steps of the QK product
+  constexpr int ND = D / 32;  // 32-wide d blocks of the PV product
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char *sK = smem;
+  unsigned char *sV = smem + TK * KP;
+
+  // ---- which (sequence, KV head, row block, chunk) ----
+  int id = blockIdx.x;
+  const int kvh = id % p.Hkv;
+  id /= p.Hkv;
+  const int rblk = id % p.n_row_blocks;
+  id /= p.n_row_blocks;
+  const int chunk = id % p.n_chunks;
+  const int b = id / p.n_chunks;
+
+  const int t0 = p.cu_T[b];
+  const int Tb = p.cu_T[b + 1] - t0;
+  const int R = Tb * p.G;
+  if (rblk * BM >= R) return;
+  int Lb = p.L[b];
+  Lb = Lb < p.max_L ? Lb : p.max_L;
+  int nc = (Lb + p.chunk_keys - 1) / p.chunk_keys;
+  nc = nc < 1 ? 1 : nc;
+  if (chunk >= nc) return;
+  const int k0 = chunk * p.chunk_keys;
+  const int k1 = (k0 + p.chunk_keys < Lb) ? k0 + p.chunk_keys : Lb;
+  const bool has_tree = (chunk == nc - 1);
+  const int n_ct = (k1 - k0 + TK - 1) / TK;
+  const int n_tt = has_tree ? (Tb + TK - 1) / TK : 0;
+  const int n_tiles = n_ct + n_tt;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wk = wave / WM;
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  // ---- Q operands (B operand of S^T = K Q^T: lane = query row, 8 consecutive d per k-step) ----
+  bf16x8 qreg[RB][NS];
+  uint64_t mrow[RB][2];
+  bool rvalid[RB];
+  int64_t orow[RB];  // (global token * Hq + head) of the lane's row
+#pragma unroll
+  for (int r = 0; r < RB; ++r) {
+    const int row = rblk * BM + (wm * RB + r) * 32 + l32;
+    rvalid[r] = row < R;
+    const int t = rvalid[r] ? row / p.G : 0;
+    const int g = rvalid[r] ? row - t * p.G : 0;
+    orow[r] = (int64_t)(t0 + t) * p.Hq + kvh * p.G + g;
+    const __bf16 *qp = p.q + orow[r] * D + 8 * hh;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      if (rvalid[r]) qreg[r][s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+      else qreg[r][s] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    mrow[r][0] = mrow[r][1] = 0;
+    if (has_tree && rvalid[r]) {
+      mrow[r][0] = p.mask[(size_t)(t0 + t) * p.W];
+      if (p.W > 1) mrow[r][1] = p.mask[(size_t)(t0 + t) * p.W + 1];
+    }
+  }
+
+  // ---- running softmax state (log2 domain) ----
+  float m_run[RB], l_run[RB];
+  f32x16 oacc[RB][ND];
+#pragma unroll
+  for (int r = 0; r < RB; ++r) {
+    m_run[r] = -INFINITY;
+    l_run[r] = 0.f;
+#pragma unroll
+    for (int d = 0; d < ND; ++d)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[r][d][i] = 0.f;
+  }
+
+  // ---- tile staging: global -> registers -> LDS ----
+  u32x4 kst[NLOAD], vst[NLOAD];
+  const int64_t cache_base = PAGED ? 0 : (int64_t)p.cu_L[b] * p.stride_tok;
+  auto load_tile = [&](int it) {
+    const bool tree = it >= n_ct;
+    const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
+    const int limit = tree ? Tb : k1;
+#pragma unroll
+    for (int n = 0; n < NLOAD; ++n) {
+      const int j = tid + n * NT;
+      const int kl = j / DC, c = j % DC;
+      const int key = base + kl;
+      u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+      if (key < limit) {
+        int64_t off;
+        const __bf16 *kb_, *vb_;
+        if (tree) {
+          off = ((int64_t)(t0 + key) * p.Hkv + kvh) * D + c * 8;
+          kb_ = p.k_tree;
+          vb_ = p.v_tree;
+        } else {
+          if (PAGED) {
+            const int pg = p.page_table[(int64_t)b * p.max_pages + key / p.page_size];
+            off = (int64_t)pg * p.stride_page + (int64_t)(key % p.page_size) * p.stride_tok;
+          } else {
+            off = cache_base + (int64_t)key * p.stride_tok;
+          }
+          off += (int64_t)kvh * p.stride_head + c * 8;
+          kb_ = p.k_cache;
+          vb_ = p.v_cache;
+        }
+        kv = *reinterpret_cast<const u32x4 *>(kb_ + off);
+        vv = *reinterpret_cast<const u32x4 *>(vb_ + off);
+      }
+      kst[n] = kv;
+      vst[n] = vv;
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int n = 0; n < NLOAD; ++n) {
+      const int j = tid + n * NT;
+      const int kl = j / DC, c = j % DC;
+      *reinterpret_cast<u32x4 *>(sK + kl * KP + c * 16) = kst[n];
+      *reinterpret_cast<u32x4 *>(sV + kl * VP + c * 16) = vst[n];
+    }
+  };
+
+  auto compute_tile = [&](int it) {
+    const bool tree = it >= n_ct;
+    const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
+    const int limit = tree ? Tb : k1;
+    const int wofs = wk * KB * 32;  // this wave's first key inside the tile
+    if (base + wofs >= limit) return;  // nothing for this wave in this tile (wave-uniform)
+    const bool edge = tree || (base + TK > limit);
+
+    // S^T = K Q^T for KB key blocks x RB row blocks
+    f32x16 sacc[KB][RB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+      for (int r = 0; r < RB; ++r)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[kb][r][i] = 0.f;
+      const unsigned char *krow = sK + (wofs + kb * 32 + l32) * KP + hh * 16;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(krow + s * 32);
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+          sacc[kb][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[kb][r], 0, 0, 0);
+      }
+    }
+    // masking: keys past the limit, and for tree tiles keys that are not ancestors
+    if (edge) {
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = base + wofs + kb * 32 + 8 * (i / 4) + 4 * hh + (i % 4);
+          const bool inb = key < limit;
+#pragma unroll
+          for (int r = 0; r < RB; ++r) {
+            bool ok = inb;
+            if (tree) {
+              const uint64_t mw = (key < 64) ? mrow[r][0] : mrow[r][1];
+              ok = ok && ((mw >> (key & 63)) & 1ull);
+            }
+            if (!ok) sacc[kb][r][i] = -INFINITY;
+          }
+        }
+    }
+    // online softmax
+    bf16x8 pb[KB][2][RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][r][i]);
+      mx = half_max(mx) * p.scale_log2;
+      const float m_new = fmaxf(m_run[r], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run[r] - m_use);
+      m_run[r] = m_new;
+      float ls = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float pv = fast_exp2(fmaf(sacc[kb][r][i], p.scale_log2, -m_use));
+          ls += pv;
+          pb[kb][i / 8][r][i % 8] = (__bf16)pv;
+        }
+      l_run[r] = l_run[r] * alpha + ls;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[r][d][i] *= alpha;
+      }
+    }
+    // O^T += V^T P^T
+    const int L16 = lane & 15, grp1 = (lane >> 4) & 1;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const unsigned char *vbase =
+            sV + (wofs + kb * 32 + 16 * s2 + 4 * hh + (L16 >> 2)) * VP + (16 * grp1 + 4 * (L16 & 3)) * 2;
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vbase + d * 64));
+          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vbase + 8 * VP + d * 64));
+          const s16x8 v8 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 va = __builtin_bit_cast(bf16x8, v8);
+#pragma unroll
+          for (int r = 0; r < RB; ++r)
+            oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kb][s2][r], oacc[r][d], 0, 0, 0);
+        }
+      }
+  };
+
+  // ---- main loop ----
+  if (n_tiles > 0) load_tile(0);
+  for (int it = 0; it < n_tiles; ++it) {
+    store_tile();
+    __syncthreads();
+    if (it + 1 < n_tiles) load_tile(it + 1);
+    compute_tile(it);
+    __syncthreads();
+  }
+
+  // ---- combine the two lane halves' partial sums ----
+  float l_tot[RB];
+#pragma unroll
+  for (int r = 0; r < RB; ++r) l_tot[r] = half_sum(l_run[r]);
+
+  // ---- merge the WK key groups through LDS ----
+  if constexpr (WK > 1) {
+    float *sm = reinterpret_cast<float *>(smem);                      // [WK][WM][RB][32]
+    float *so = sm + WK * WM * RB * 32;                               // [WM][RB*ND*16 + RB][64]
+    constexpr int OSTRIDE = (RB * ND * 16 + RB) * 64;
+    if (hh == 0) {
+#pragma unroll
+      for (int r = 0; r < RB; ++r) sm[((wk * WM + wm) * RB + r) * 32 + l32] = m_run[r];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      float mf = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < WK; ++w) mf = fmaxf(mf, sm[((w * WM + wm) * RB + r) * 32 + l32]);
+      const float m_use = (mf == -INFINITY) ? 0.f : mf;
+      const float a = fast_exp2(m_run[r] - m_use);
+      m_run[r] = mf;
+      l_tot[r] *= a;
+#pragma unroll
+      for (int d = 0; d < ND; ++d)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[r][d][i] *= a;
+    }
+    __syncthreads();
+    for (int w = WK - 1; w >= 1; --w) {
+      float *dst = so + wm * OSTRIDE;
+      if (wk == w) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+#pragma unroll
+          for (int d = 0; d < ND; ++d)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dst[((r * ND + d) * 16 + i) * 64 + lane] = oacc[r][d][i];
+          dst[(RB * ND * 16 + r) * 64 + lane] = l_tot[r];
+        }
+      }
+      __syncthreads();
+      if (wk == 0) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+#pragma unroll
+          for (int d = 0; d < ND; ++d)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[r][d][i] += dst[((r * ND + d) * 16 + i) * 64 + lane];
+          l_tot[r] += dst[(RB * ND * 16 + r) * 64 + lane];
+        }
+      }
+      __syncthreads();
+    }
+    if (wk != 0) return;
+  }
+
+  // ---- write (normalised) result: final when there is one split, else the partial ----
+  const bool final_out = (p.n_chunks == 1);
+  float *obase = final_out ? p.out : p.part_out + (size_t)chunk * p.sum_T * p.Hq * D;
+  float *lbase = final_out ? p.lse : p.part_lse + (size_t)chunk * p.sum_T * p.Hq;
+#pragma unroll
+  for (int r = 0; r < RB; ++r) {
+    if (!rvalid[r]) continue;
+    const float inv = l_tot[r] > 0.f ? 1.f / l_tot[r] : 0.f;
+    float *orow_p = obase + orow[r] * D + 4 * hh;
+#pragma unroll
+    for (int d = 0; d < ND; ++d)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = oacc[r][d][i4 * 4 + e] * inv;
+        *reinterpret_cast<f32x4 *>(orow_p + 32 * d + 8 * i4) = v;
+      }
+    if (hh == 0) lbase[orow[r]] = l_tot[r] > 0.f ? (m_run[r] + __builtin_amdgcn_logf(l_tot[r])) * kLn2 : -INFINITY;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// merge of the KV splits
+// ---------------------------------------------------------------------------------------
+// One wave per output row (token, head).  When cu_T / L are given the number of
+// valid splits of the row's sequence is derived from them (splits past it were
+// never written); otherwise all S splits are read.
+template <int D>
+__global__ void __launch_bounds__(256) merge_kernel(const float *__restrict__ part_out,
+                                                    const float *__restrict__ part_lse, int S, int64_t n_rows,
+                                                    float *__restrict__ out, float *__restrict__ lse,
+                                                    const int32_t *__restrict__ cu_T, const int32_t *__restrict__ L,
+                                                    int B, int Hq, int chunk_keys, int max_L) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows) return;
+  int ns = S;
+  if (cu_T) {
+    const int tok = (int)(row / Hq);
+    int lo = 0, hi = B;  // largest b with cu_T[b] <= tok
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (cu_T[mid] <= tok) lo = mid; else hi = mid;
+    }
+    int Lb = L[lo];
+    Lb = Lb < max_L ? Lb : max_L;
+    ns = (Lb + chunk_keys - 1) / chunk_keys;
+    ns = ns < 1 ? 1 : (ns > S ? S : ns);
+  }
+  float mx = -INFINITY;
+  for (int s = lane; s < ns; s += 64) mx = fmaxf(mx, part_lse[(size_t)s * n_rows + row]);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  constexpr int E = D / 64;  // elements per lane
+  float acc[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) acc[e] = 0.f;
+  if (mx == -INFINITY) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) out[row * D + lane * E + e] = 0.f;
+    if (lane == 0) lse[row] = -INFINITY;
+    return;
+  }
+  float z = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const float w = __expf(part_lse[(size_t)s * n_rows + row] - mx);
+    z += w;
+    const float *po = part_out + ((size_t)s * n_rows + row) * D + lane * E;
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] += w * po[e];
+  }
+  const float inv = 1.f / z;
+#pragma unroll
+  for (int e = 0; e < E; ++e) out[row * D + lane * E + e] = acc[e] * inv;
+  if (lane == 0) lse[row] = mx + __logf(z);
+}
+
+// ---------------------------------------------------------------------------------------
+// host side: validation, plan, launch
+// ---------------------------------------------------------------------------------------
+struct Plan {
+  int variant;  // index into the kernel table
+  int BM, TK;
+  int n_row_blocks, n_chunks, chunk_keys;
+};
+
+enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3 };
+
+bool make_plan(const tva_args *a, Plan *pl) {
+  if (!a || a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv) return false;
+  if (a->sum_T < 0 || a->max_T < 0 || a->max_L < 0 || a->num_splits < 0) return false;
+  const int G = a->Hq / a->Hkv;
+  const int rows = a->max_T * G;
+  if (rows > 128) { pl->variant = V_R256; pl->BM = 256; pl->TK = 64; }
+  else if (rows > 64) { pl->variant = V_R128; pl->BM = 128; pl->TK = 64; }
+  else if (rows > 32) { pl->variant = V_R64; pl->BM = 64; pl->TK = 128; }
+  else { pl->variant = V_R32; pl->BM = 32; pl->TK = 128; }
+  pl->n_row_blocks = rows > 0 ? (rows + pl->BM - 1) / pl->BM : 1;
+  int S = a->num_splits;
+  const int max_by_len = a->max_L > 0 ? (a->max_L + pl->TK - 1) / pl->TK : 1;
+  if (S == 0) {
+    // enough workgroups to occupy the 256 CUs, but no split shorter than four tiles
+    const int natural = a->B * a->Hkv * pl->n_row_blocks;
+    S = (256 + natural - 1) / natural;
+    const int cap = a->max_L > 0 ? (a->max_L + 4 * pl->TK - 1) / (4 * pl->TK) : 1;
+    if (S > cap) S = cap;
+  }
+  if (S > max_by_len) S = max_by_len;
+  if (S < 1) S = 1;
+  int ck = a->max_L > 0 ? (a->max_L + S - 1) / S : pl->TK;
+  ck = (ck + pl->TK - 1) / pl->TK * pl->TK;
+  pl->chunk_keys = ck;
+  pl->n_chunks = a->max_L > 0 ? (a->max_L + ck - 1) / ck : 1;
+  return true;
+}
+
+typedef void (*attn_fn)(const AttnParams);
+
+template <int D, int WM, int WK, int RB, int KB, bool PAGED>
+hipError_t launch_attn(const AttnParams &p, int grid, hipStream_t st) {
+  using C = AttnCfg<D, WM, WK, RB, KB, PAGED>;
+  static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent
+  auto kfn = attn_kernel<D, WM, WK, RB, KB, PAGED>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kfn),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kfn, dim3(grid), dim3(C::NT), C::SMEM, st, p);
+  return hipGetLastError();
+}
+
+template <int D, bool PAGED>
+hipError_t dispatch_variant(int variant, const AttnParams &p, int grid, hipStream_t st) {
+  switch (variant) {
+    case V_R256: return launch_attn<D, 4, 1, 2, 2, PAGED>(p, grid, st);
+    case V_R128: return launch_attn<D, 2, 2, 2, 1, PAGED>(p, grid, st);
+    case V_R64: return launch_attn<D, 1, 4, 2, 1, PAGED>(p, grid, st);
+    default: return launch_attn<D, 1, 4, 1, 1, PAGED>(p, grid, st);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int tva_version(void) { return 1; }
+
+size_t tva_sizeof_args(void) { return sizeof(tva_args); }
+
+const char *tva_strerror(int code) {
+  switch (code) {
+    case TVA_OK: return "ok";
+    case TVA_INVALID_ARG: return "invalid argument";
+    case TVA_UNSUPPORTED: return "unsupported shape";
+    case TVA_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case TVA_HIP_ERROR: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int tva_build_ancestor_mask(const int32_t *parent, const int32_t *cu_T, int32_t B, int32_t max_T,
+                            int32_t mask_words, uint64_t *mask, int32_t *err_flag, void *stream) {
+  if (B < 0 || max_T < 0 || mask_words < 1 || mask_words * 64 < max_T) return TVA_INVALID_ARG;
+  if (B == 0) return TVA_OK;
+  if (!parent || !cu_T || !mask) return TVA_INVALID_ARG;
+  int threads = ((max_T + 63) / 64) * 64;
+  threads = threads < 64 ? 64 : (threads > 256 ? 256 : threads);
+  hipLaunchKernelGGL(anc_mask_kernel, dim3(B), dim3(threads), 0, (hipStream_t)stream, parent, cu_T, B,
+                     mask_words, mask, err_flag);
+  return hipGetLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+static int check_args(const tva_args *a, bool shapes_only) {
+  if (!a) return TVA_INVALID_ARG;
+  if (a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv) return TVA_INVALID_ARG;
+  if (a->sum_T < 0 || a->max_T < 0 || a->max_L < 0 || a->num_splits < 0) return TVA_INVALID_ARG;
+  if (a->D != 64 && a->D != 128) return TVA_UNSUPPORTED;
+  if (a->max_T > TVA_MAX_TREE) return TVA_UNSUPPORTED;
+  if (a->mask_words < 1 || a->mask_words > 2 || a->mask_words * 64 < a->max_T) return TVA_UNSUPPORTED;
+  if (shapes_only) return TVA_OK;
+  if (!(a->scale > 0.f)) return TVA_INVALID_ARG;
+  if (a->sum_T == 0) return TVA_OK;
+  if (!a->cu_T || !a->L || !a->q || !a->k_tree || !a->v_tree || !a->anc_mask || !a->out || !a->lse)
+    return TVA_INVALID_ARG;
+  const bool dense = a->cu_L != nullptr, paged = a->page_table != nullptr;
+  if (dense == paged) return TVA_INVALID_ARG;
+  if (a->max_L > 0 && (!a->k_cache || !a->v_cache)) return TVA_INVALID_ARG;
+  if (paged && (a->page_size <= 0 || a->max_pages <= 0)) return TVA_INVALID_ARG;
+  if (paged && (int64_t)a->max_pages * a->page_size < a->max_L) return TVA_INVALID_ARG;
+  if ((a->stride_page | a->stride_tok | a->stride_head) % 8) return TVA_INVALID_ARG;
+  if (a->stride_page < 0 || a->stride_tok < 0 || a->stride_head < 0) return TVA_INVALID_ARG;
+  return TVA_OK;
+}
+
+int32_t tva_plan_splits(const tva_args *a) {
+  if (check_args(a, true) != TVA_OK) return -1;
+  Plan pl;
+  if (!make_plan(a, &pl)) return -1;
+  return pl.n_chunks;
+}
+
+size_t tva_workspace_bytes(const tva_args *a) {
+  if (check_args(a, true) != TVA_OK) return (size_t)-1;
+  Plan pl;
+  if (!make_plan(a, &pl)) return (size_t)-1;
+  if (pl.n_chunks <= 1) return 0;
+  return (size_t)pl.n_chunks * a->sum_T * a->Hq * (a->D + 1) * sizeof(float);
+}
+
+int tva_tree_verify_attn(const tva_args *a, void *stream) {
+  int rc = check_args(a, false);
+  if (rc != TVA_OK) return rc;
+  if (a->sum_T == 0 || a->max_T == 0) return TVA_OK;
+  Plan pl;
+  if (!make_plan(a, &pl)) return TVA_INVALID_ARG;
+  const size_t need = pl.n_chunks > 1 ? (size_t)pl.n_chunks * a->sum_T * a->Hq * (a->D + 1) * sizeof(float) : 0;
+  if (need > 0 && (!a->workspace || a->workspace_bytes < need)) return TVA_WORKSPACE_TOO_SMALL;
+
+  AttnParams p;
+  p.q = (const __bf16 *)a->q;
+  p.k_tree = (const __bf16 *)a->k_tree;
+  p.v_tree = (const __bf16 *)a->v_tree;
+  p.k_cache = (const __bf16 *)a->k_cache;
+  p.v_cache = (const __bf16 *)a->v_cache;
+  p.cu_T = a->cu_T;
+  p.L = a->L;
+  p.cu_L = a->cu_L;
+  p.page_table = a->page_table;
+  p.mask = a->anc_mask;
+  p.out = a->out;
+  p.lse = a->lse;
+  p.part_out = (float *)a->workspace;
+  p.part_lse = p.part_out ? p.part_out + (size_t)pl.n_chunks * a->sum_T * a->Hq * a->D : nullptr;
+  p.B = a->B;
+  p.Hq = a->Hq;
+  p.Hkv = a->Hkv;
+  p.G = a->Hq / a->Hkv;
+  p.sum_T = a->sum_T;
+  p.W = a->mask_words;
+  p.chunk_keys = pl.chunk_keys;
+  p.n_chunks = pl.n_chunks;
+  p.n_row_blocks = pl.n_row_blocks;
+  p.max_L = a->max_L;
+  p.page_size = a->page_size > 0 ? a->page_size : 1;
+  p.max_pages = a->max_pages;
+  p.stride_head = a->stride_head ? a->stride_head : a->D;
+  p.stride_tok = a->stride_tok ? a->stride_tok : (int64_t)a->Hkv * a->D;
+  p.stride_page = a->stride_page ? a->stride_page : (int64_t)p.page_size * p.stride_tok;
+  p.scale_log2 = a->scale * kLog2e;
+
+  const int64_t grid64 = (int64_t)a->B * pl.n_chunks * pl.n_row_blocks * a->Hkv;
+  if (grid64 <= 0 || grid64 > 0x7fffffff) return TVA_UNSUPPORTED;
+  const int grid = (int)grid64;
+  const bool paged = a->page_table != nullptr;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e;
+  if (a->D == 128)
+    e = paged ? dispatch_variant<128, true>(pl.variant, p, grid, st) : dispatch_variant<128, false>(pl.variant, p, grid, st);
+  else
+    e = paged ? dispatch_variant<64, true>(pl.variant, p, grid, st) : dispatch_variant<64, false>(pl.variant, p, grid, st);
+  if (e != hipSuccess) return TVA_HIP_ERROR;
+
+  if (pl.n_chunks > 1) {
+    const int64_t n_rows = (int64_t)a->sum_T * a->Hq;
+    const int mgrid = (int)((n_rows + 3) / 4);
+    if (a->D == 128)
+      hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, p.part_out, p.part_lse, pl.n_chunks,
+                         n_rows, a->out, a->lse, a->cu_T, a->L, a->B, a->Hq, pl.chunk_keys, a->max_L);
+    else
+      hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, p.part_out, p.part_lse, pl.n_chunks,
+                         n_rows, a->out, a->lse, a->cu_T, a->L, a->B, a->Hq, pl.chunk_keys, a->max_L);
+    if (hipGetLastError() != hipSuccess) return TVA_HIP_ERROR;
+  }
+  return TVA_OK;
+}
+
+int tva_merge_splits(const float *part_out, const float *part_lse, int32_t S, int64_t n_rows, int32_t D,
+                     float *out, float *lse, void *stream) {
+  if (S < 1 || n_rows < 0) return TVA_INVALID_ARG;
+  if (D != 64 && D != 128) return TVA_UNSUPPORTED;
+  if (n_rows == 0) return TVA_OK;
+  if (!part_out || !part_lse || !out || !lse) return TVA_INVALID_ARG;
+  if ((n_rows + 3) / 4 > 0x7fffffff) return TVA_UNSUPPORTED;
+  const int mgrid = (int)((n_rows + 3) / 4);
+  hipStream_t st = (hipStream_t)stream;
+  if (D == 128)
+    hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse,
+                       (const int32_t *)nullptr, (const int32_t *)nullptr, 0, 1, 1, 0);
+  else
+    hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse,
+                       (const int32_t *)nullptr, (const int32_t *)nullptr, 0, 1, 1, 0);
+  return hipGetLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+}  // extern "C"

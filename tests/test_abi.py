@@ -1,0 +1,120 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the
+header declares, mirrors the argument struct, and its host-side validation and
+split planning behave (those paths return before any launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_26577_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        binding.build_library()
+    return binding.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tva.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tva_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_match_header(lib):
+    syms = declared_symbols()
+    assert set(syms) == set(binding.EXPORTS)
+    for s in syms:
+        assert getattr(lib, s) is not None
+
+
+def test_struct_mirror_and_version(lib):
+    assert lib.tva_sizeof_args() == ctypes.sizeof(binding.TvaArgs)
+    assert lib.tva_version() == binding.EXPECTED_VERSION
+    assert lib.tva_strerror(0) == b"ok" and b"workspace" in lib.tva_strerror(-3)
+
+
+def shape_args(**kw):
+    a = binding.TvaArgs()
+    a.B, a.Hq, a.Hkv, a.D = 1, 32, 8, 128
+    a.sum_T, a.max_T, a.mask_words, a.max_L = 60, 60, 1, 2048
+    a.scale = 0.088
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_plan_and_workspace(lib):
+    a = shape_args(num_splits=1)
+    assert binding.plan_splits(a) == 1 and binding.workspace_bytes(a) == 0
+    a = shape_args(num_splits=4)
+    assert binding.plan_splits(a) == 4
+    assert binding.workspace_bytes(a) == 4 * 60 * 32 * 129 * 4
+    a = shape_args(num_splits=1000)  # capped by the tile size
+    s = binding.plan_splits(a)
+    assert 1 <= s <= 2048 // 64
+    a = shape_args(num_splits=0)
+    assert binding.plan_splits(a) >= 1
+    a = shape_args(max_L=0)
+    assert binding.plan_splits(a) == 1
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(D=96), -2), (dict(max_T=129, mask_words=3), -2), (dict(mask_words=0), -2),
+    (dict(Hq=30), -1), (dict(B=0), -1), (dict(max_L=-1), -1), (dict(max_T=100, mask_words=1), -2),
+])
+def test_invalid_shapes_rejected_before_launch(lib, kw, code):
+    a = shape_args(**kw)
+    assert lib.tva_plan_splits(ctypes.byref(a)) == -1
+    assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == code
+
+
+def test_null_pointers_and_cache_form_rejected(lib):
+    a = shape_args()
+    assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == -1      # null tensors
+    a = shape_args(scale=0.0)
+    assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == -1      # scale must be > 0
+    for f in ("cu_T", "L", "q", "k_tree", "v_tree", "anc_mask", "out", "lse", "k_cache", "v_cache"):
+        setattr(a, f, 0x1000)  # never dereferenced: the call fails validation first
+    a.scale = 0.1
+    assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == -1      # neither cache form
+    a.cu_L = 0x1000
+    a.page_table = 0x1000
+    assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == -1      # both cache forms
+    a.cu_L = None
+    a.page_size, a.max_pages = 16, 4                                   # 64 tokens < max_L
+    assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == -1
+    a.max_pages = 128
+    a.stride_tok = 1001                                                # not 16-byte aligned rows
+    assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == -1
+    a.stride_tok = 0
+    a.num_splits = 4                                                   # workspace missing
+    assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == -3
+
+
+def test_mask_and_merge_argument_checks(lib):
+    assert lib.tva_build_ancestor_mask(None, None, 1, 8, 1, None, None, None) == -1
+    assert lib.tva_build_ancestor_mask(None, None, 0, 8, 1, None, None, None) == 0   # empty batch
+    assert lib.tva_build_ancestor_mask(0x1000, 0x1000, 1, 100, 1, 0x1000, None, None) == -1
+    assert lib.tva_merge_splits(None, None, 2, 4, 128, None, None, None) == -1
+    assert lib.tva_merge_splits(0x1000, 0x1000, 2, 4, 96, 0x1000, 0x1000, None) == -2
+    assert lib.tva_merge_splits(None, None, 2, 0, 128, None, None, None) == 0
+
+
+def test_no_oracle_in_product_path():
+    """The product package never imports the oracle, and vice versa."""
+    pkg = os.path.join(ROOT, "paper_2510_26577_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                txt = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+\.*oracle", txt, flags=re.M), f
+                assert "tva_oracle" not in txt and "libtva_oracle" not in txt, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            txt = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2510_26577_amd" not in txt and "libtva.so" not in txt and "tva.h" not in txt
