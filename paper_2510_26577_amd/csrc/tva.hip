@@ -37,6 +37,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+// A tile takes the low-order P pass when, for some row, (largest probability of the tile) >
+// kLoThreshold * (that lane half's running sum): then one weight can exceed ~1/16 of the row's
+// total and its bf16 rounding (2^-9 relative) would be visible at the 2e-3 output tolerance.
+constexpr float kLoThreshold = 0.125f;
 
 // ---------------------------------------------------------------------------------------
 // ancestor masks
@@ -294,8 +298,12 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
           }
         }
     }
-    // online softmax
+    // online softmax.  P is rounded to bf16 for the second product; where a row's
+    // largest probability of this tile is not small against its running sum (few
+    // effective keys: rounding one weight by 2^-9 would show in O) the rounding
+    // remainder is fed through a second, low-order MFMA pass (wave-uniform choice).
     bf16x8 pb[KB][2][RB];
+    bool need_lo = false;
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
       float mx = -INFINITY;
@@ -307,6 +315,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       const float m_new = fmaxf(m_run[r], mx);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = fast_exp2(m_run[r] - m_use);
+      const float pmax = fast_exp2(mx - m_use);
       m_run[r] = m_new;
       float ls = 0.f;
 #pragma unroll
@@ -315,9 +324,11 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
         for (int i = 0; i < 16; ++i) {
           const float pv = fast_exp2(fmaf(sacc[kb][r][i], p.scale_log2, -m_use));
           ls += pv;
+          sacc[kb][r][i] = pv;
           pb[kb][i / 8][r][i % 8] = (__bf16)pv;
         }
       l_run[r] = l_run[r] * alpha + ls;
+      need_lo = need_lo || (pmax > kLoThreshold * l_run[r]);
       if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
 #pragma unroll
         for (int d = 0; d < ND; ++d)
@@ -325,6 +336,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
           for (int i = 0; i < 16; ++i) oacc[r][d][i] *= alpha;
       }
     }
+    const bool lo_pass = __builtin_amdgcn_ballot_w64(need_lo) != 0;
     // O^T += V^T P^T
     const int L16 = lane & 15, grp1 = (lane >> 4) & 1;
 #pragma unroll
@@ -333,6 +345,14 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       for (int s2 = 0; s2 < 2; ++s2) {
         const unsigned char *vbase =
             sV + (wofs + kb * 32 + 16 * s2 + 4 * hh + (L16 >> 2)) * VP + (16 * grp1 + 4 * (L16 & 3)) * 2;
+        bf16x8 plo[RB];
+        if (lo_pass) {
+#pragma unroll
+          for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              plo[r][j] = (__bf16)(sacc[kb][r][8 * s2 + j] - (float)pb[kb][s2][r][j]);
+        }
 #pragma unroll
         for (int d = 0; d < ND; ++d) {
           const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vbase + d * 64));
@@ -342,6 +362,11 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
 #pragma unroll
           for (int r = 0; r < RB; ++r)
             oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kb][s2][r], oacc[r][d], 0, 0, 0);
+          if (lo_pass) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+              oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, plo[r], oacc[r][d], 0, 0, 0);
+          }
         }
       }
   };
