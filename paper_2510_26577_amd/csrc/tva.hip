@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "tva.h"
 
 namespace {
@@ -41,6 +43,9 @@ constexpr float kLn2 = 0.6931471805599453f;
 // kLoThreshold * (that lane half's running sum): then one weight can exceed ~1/16 of the row's
 // total and its bf16 rounding (2^-9 relative) would be visible at the 2e-3 output tolerance.
 constexpr float kLoThreshold = 0.125f;
+// The reference maximum of a row is only moved (and O, l rescaled) when a tile maximum exceeds it by
+// more than 2^kLazy: probabilities then stay below 2^kLazy, harmless in fp32 sums and bf16 operands.
+constexpr float kLazy = 8.f;
 
 // ---------------------------------------------------------------------------------------
 // ancestor masks
@@ -96,7 +101,7 @@ struct AttnParams {
   float *part_out, *part_lse;  // [S, sum_T, Hq, D], [S, sum_T, Hq] when S > 1
   int B, Hq, Hkv, G, sum_T, W;
   int chunk_keys, n_chunks, n_row_blocks, max_L;
-  int page_size, max_pages;
+  int page_size, page_shift, max_pages;
   int64_t stride_page, stride_tok, stride_head;
   float scale_log2;  // scale * log2(e)
 };
@@ -113,31 +118,71 @@ __device__ __forceinline__ float half_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int D, int WM, int WK, int RB, int KB, bool PAGED>
+template <int D, int WM, int WK, int RB, bool PAGED>
 struct AttnCfg {
   static constexpr int NW = WM * WK;
   static constexpr int NT = NW * 64;
-  static constexpr int TK = WK * KB * 32;  // keys per tile
-  static constexpr int BM = WM * RB * 32;  // query rows per workgroup
-  static constexpr int DC = D / 8;         // 16-byte chunks per K/V row
-  static constexpr int KP = D * 2 + 16;    // LDS row pitch of K (bytes): b128 reads, key per lane
-  static constexpr int VP = D * 2 + 32;    // LDS row pitch of V (bytes): transpose reads, 4 keys x 32 B
-  static constexpr int NLOAD = TK * DC / NT;
-  static constexpr int TILE_BYTES = TK * (KP + VP);
+  static constexpr int KBW = (WK == 1) ? 2 : 1;  // 32-key blocks each wave owns in a tile
+  static constexpr int TK = WK * KBW * 32;       // keys per tile
+  static constexpr int BM = WM * RB * 32;        // query rows per workgroup
+  static constexpr int DC = D / 8;               // 16-byte chunks per K/V row
+  static constexpr int ROWB = D * 2;             // bytes per K/V row
+  static constexpr int RPI = 64 / DC;            // rows one wave-wide 16-byte-per-lane load covers
+  static constexpr int NLDK = TK / RPI / NW;     // such loads per wave per tile, for K (same for V)
+  static constexpr int NLD = 2 * NLDK;
+  // LDS tile layout: NBLK blocks; block n holds rows n, n+NBLK, n+2*NBLK, ... back to back, and
+  // blocks are PAD bytes further apart than their size.  Rows that are read together (16
+  // consecutive keys, one per lane, by the K operand load; 4 consecutive keys x 32 bytes by one
+  // 16-lane group of the V transpose load) then sit in different blocks, PAD apart in bank
+  // position, and every read address is one per-lane base plus a compile-time offset.
+  static constexpr int NBLK = DC;                // 16 (D=128) or 8 (D=64)
+  static constexpr int SUBS = TK / NBLK;         // rows per block
+  static constexpr int BLKB = SUBS * ROWB;       // 1 KiB (TK=64) or 2 KiB (TK=128)
+  static constexpr int IPB = BLKB / 1024;        // load instructions per block
+  static constexpr int PK = BLKB + 16;           // block pitch of the K tile
+  static constexpr int PV = BLKB + 32;           // block pitch of the V tile
+  static constexpr int KTILE = NBLK * PK, VTILE = NBLK * PV;
+  static constexpr int STAGE_BYTES = (KTILE + VTILE + 1023) / 1024 * 1024;
+  static constexpr int NSTAGE = (3 * STAGE_BYTES <= 120 * 1024) ? 3 : 2;
+  static constexpr int PD = NSTAGE - 1;          // tiles in flight ahead of the one being computed
   static constexpr int MERGE_BYTES = (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
-  static constexpr int SMEM = TILE_BYTES > MERGE_BYTES ? TILE_BYTES : MERGE_BYTES;
-  static_assert(TK * DC % NT == 0, "tile must divide evenly over the threads");
+  static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
+  static constexpr int SMEM = RING_BYTES > MERGE_BYTES ? RING_BYTES : MERGE_BYTES;
+  static_assert(TK % (RPI * NW) == 0, "tile must divide evenly over the waves");
+  static_assert(BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
 };
 
-template <int D, int WM, int WK, int RB, int KB, bool PAGED>
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | (((n >> 4) & 3) << 14); }
+
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+
+// LDS transpose read of four 16-bit elements per lane (see the V operand comment in attn_kernel),
+// issued from inline assembly: the compiler cannot tell these reads apart from the ring stages the
+// asynchronous tile loads are still filling and would otherwise drain all outstanding loads
+// (vmcnt 0) in front of every one of them.  The matching wait is lds_wait below.
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_read_tr(uint32_t addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+// Waits for every outstanding LDS read of this wave; the operands tie the wait to the values.
+__device__ __forceinline__ void lds_wait(s16x4 &a, s16x4 &b, s16x4 &c, s16x4 &d) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+
+template <int D, int WM, int WK, int RB, bool PAGED>
 __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
-  using C = AttnCfg<D, WM, WK, RB, KB, PAGED>;
-  constexpr int NT = C::NT, TK = C::TK, BM = C::BM, DC = C::DC, KP = C::KP, VP = C::VP, NLOAD = C::NLOAD;
+  using C = AttnCfg<D, WM, WK, RB, PAGED>;
+  constexpr int TK = C::TK, BM = C::BM, DC = C::DC, ROWB = C::ROWB, RPI = C::RPI, NLDK = C::NLDK, NLD = C::NLD;
+  constexpr int KBW = C::KBW, NSTAGE = C::NSTAGE, PD = C::PD, STAGE_BYTES = C::STAGE_BYTES;
+  constexpr int NBLK = C::NBLK, IPB = C::IPB, PK = C::PK, PV = C::PV, KTILE = C::KTILE;
   constexpr int NS = D / 16;  // k-steps of the QK product
   constexpr int ND = D / 32;  // 32-wide d blocks of the PV product
-  extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char *sK = smem;
-  unsigned char *sV = smem + TK * KP;
+  extern __shared__ __align__(1024) unsigned char smem[];
+  lds_byte *const lds = (lds_byte *)smem;
 
   // ---- which (sequence, KV head, row block, chunk) ----
   int id = blockIdx.x;
@@ -160,11 +205,13 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   const int k0 = chunk * p.chunk_keys;
   const int k1 = (k0 + p.chunk_keys < Lb) ? k0 + p.chunk_keys : Lb;
   const bool has_tree = (chunk == nc - 1);
+  const int n_full = (k1 - k0) / TK;               // cache tiles that need no masking
   const int n_ct = (k1 - k0 + TK - 1) / TK;
   const int n_tt = has_tree ? (Tb + TK - 1) / TK : 0;
   const int n_tiles = n_ct + n_tt;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % WM, wk = wave / WM;
   const int l32 = lane & 31, hh = lane >> 5;
 
@@ -190,10 +237,13 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
     if (has_tree && rvalid[r]) {
       mrow[r][0] = p.mask[(size_t)(t0 + t) * p.W];
       if (p.W > 1) mrow[r][1] = p.mask[(size_t)(t0 + t) * p.W + 1];
+      // bits at or above T_b can never be keys
+      if (Tb < 64) { mrow[r][0] &= (1ull << Tb) - 1; mrow[r][1] = 0; }
+      else if (Tb < 128) mrow[r][1] &= (1ull << (Tb - 64)) - 1;
     }
   }
 
-  // ---- running softmax state (log2 domain) ----
+  // ---- running softmax state (log2 domain; m_run is the reference the exponentials use) ----
   float m_run[RB], l_run[RB];
   f32x16 oacc[RB][ND];
 #pragma unroll
@@ -206,180 +256,225 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       for (int i = 0; i < 16; ++i) oacc[r][d][i] = 0.f;
   }
 
-  // ---- tile staging: global -> registers -> LDS ----
-  u32x4 kst[NLOAD], vst[NLOAD];
-  const int64_t cache_base = PAGED ? 0 : (int64_t)p.cu_L[b] * p.stride_tok;
-  auto load_tile = [&](int it) {
-    const bool tree = it >= n_ct;
-    const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
+  // ---- tile loads: global -> LDS directly (16 bytes per lane, 1 KiB per wave instruction) ----
+  // Instruction n of a tile fills part n%IPB of block n/IPB; lane l lands at sub-row
+  // (n%IPB)*RPI + l/DC of that block, chunk l%DC.  Rows past the tile's limit re-read the last
+  // valid row (finite data; their scores are masked to -inf), so LDS never holds stale values.
+  const int lsub = lane / DC, lpos = lane % DC;
+  const int64_t cache_base = PAGED ? 0 : (int64_t)p.cu_L[b] * p.stride_tok + (int64_t)kvh * p.stride_head;
+  auto issue_tile = [&](int t) {
+    const bool tree = t >= n_ct;
+    const int base = tree ? (t - n_ct) * TK : k0 + t * TK;
     const int limit = tree ? Tb : k1;
+    lds_byte *stage = lds + (t % NSTAGE) * STAGE_BYTES;
 #pragma unroll
-    for (int n = 0; n < NLOAD; ++n) {
-      const int j = tid + n * NT;
-      const int kl = j / DC, c = j % DC;
-      const int key = base + kl;
-      u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-      if (key < limit) {
-        int64_t off;
-        const __bf16 *kb_, *vb_;
-        if (tree) {
-          off = ((int64_t)(t0 + key) * p.Hkv + kvh) * D + c * 8;
-          kb_ = p.k_tree;
-          vb_ = p.v_tree;
-        } else {
-          if (PAGED) {
-            const int pg = p.page_table[(int64_t)b * p.max_pages + key / p.page_size];
-            off = (int64_t)pg * p.stride_page + (int64_t)(key % p.page_size) * p.stride_tok;
-          } else {
-            off = cache_base + (int64_t)key * p.stride_tok;
-          }
-          off += (int64_t)kvh * p.stride_head + c * 8;
-          kb_ = p.k_cache;
-          vb_ = p.v_cache;
+    for (int j = 0; j < NLDK; ++j) {
+      const int n = wave * NLDK + j;
+      const int blk = n / IPB, part = n % IPB;
+      const __bf16 *ksrc, *vsrc;
+      if (tree) {
+        int key = base + blk + NBLK * (part * RPI + lsub);
+        key = key < limit ? key : limit - 1;
+        const int64_t off = ((int64_t)(t0 + key) * p.Hkv + kvh) * D + lpos * 8;
+        ksrc = p.k_tree + off;
+        vsrc = p.v_tree + off;
+      } else if (PAGED) {
+        // one scalar page-table read per row of the instruction; each lane keeps its row's
+        int64_t off = 0;
+#pragma unroll
+        for (int u = 0; u < RPI; ++u) {
+          int key = base + blk + NBLK * (part * RPI + u);
+          key = key < limit ? key : limit - 1;
+          const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
+          const int pg = p.page_table[(int64_t)b * p.max_pages + pidx];
+          const int64_t o = (int64_t)pg * p.stride_page + (int64_t)(key - pidx * p.page_size) * p.stride_tok;
+          off = (lsub == u) ? o : off;
         }
-        kv = *reinterpret_cast<const u32x4 *>(kb_ + off);
-        vv = *reinterpret_cast<const u32x4 *>(vb_ + off);
+        off += (int64_t)kvh * p.stride_head + lpos * 8;
+        ksrc = p.k_cache + off;
+        vsrc = p.v_cache + off;
+      } else {
+        int key = base + blk + NBLK * (part * RPI + lsub);
+        key = key < limit ? key : limit - 1;
+        const int64_t off = cache_base + (int64_t)key * p.stride_tok + lpos * 8;
+        ksrc = p.k_cache + off;
+        vsrc = p.v_cache + off;
       }
-      kst[n] = kv;
-      vst[n] = vv;
-    }
-  };
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int n = 0; n < NLOAD; ++n) {
-      const int j = tid + n * NT;
-      const int kl = j / DC, c = j % DC;
-      *reinterpret_cast<u32x4 *>(sK + kl * KP + c * 16) = kst[n];
-      *reinterpret_cast<u32x4 *>(sV + kl * VP + c * 16) = vst[n];
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + blk * PK + part * 1024, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + KTILE + blk * PV + part * 1024, 16, 0, 0);
     }
   };
 
-  auto compute_tile = [&](int it) {
-    const bool tree = it >= n_ct;
-    const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
-    const int limit = tree ? Tb : k1;
-    const int wofs = wk * KB * 32;  // this wave's first key inside the tile
-    if (base + wofs >= limit) return;  // nothing for this wave in this tile (wave-uniform)
-    const bool edge = tree || (base + TK > limit);
+  // per-lane LDS read bases (row r of a tile: block r % NBLK, sub-row r / NBLK)
+  const int L16 = lane & 15, grp1 = (lane >> 4) & 1;
+  const int wave_sub = wk * KBW * (32 / NBLK);  // first sub-row of this wave's keys
+  const int kbase_off = (l32 % NBLK) * PK + (wave_sub + l32 / NBLK) * ROWB + hh * 16;
+  const int vbase_off = KTILE + (4 * hh + (L16 >> 2)) * PV + wave_sub * ROWB + (2 * grp1 + ((L16 & 3) >> 1)) * 16 +
+                        ((L16 & 1) << 3);
 
-    // S^T = K Q^T for KB key blocks x RB row blocks
-    f32x16 sacc[KB][RB];
+  // ---- one 32-key block of one tile: S^T = K Q^T, online softmax, O^T += V^T P^T ----
+  auto compute_block = [&](const lds_byte *stage, auto kb_tag, int base, int limit, bool tree, auto masked_tag) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    constexpr int kb = decltype(kb_tag)::value;
+    constexpr int KBOFF = kb * (32 / NBLK) * ROWB;     // this 32-key block inside the wave's part of the tile
+    constexpr int V8 = (NBLK == 16) ? 8 * PV : ROWB;   // V rows 8 keys further on
+    const int kofs = (wk * KBW + kb) * 32;
+    const lds_byte *kp = stage + kbase_off + KBOFF;
+    const uint32_t va = (uint32_t)(uintptr_t)(stage + vbase_off);
+    f32x16 sacc[RB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[r][i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(kp + s * 32);
 #pragma unroll
       for (int r = 0; r < RB; ++r)
+        sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
+    }
+    // V^T operands of the first 16 keys: in flight during the softmax arithmetic
+    s16x4 vlo[2][ND], vhi[2][ND];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[kb][r][i] = 0.f;
-      const unsigned char *krow = sK + (wofs + kb * 32 + l32) * KP + hh * 16;
+    for (int d = 0; d < ND; ++d) {
+      vlo[0][d] = lds_read_tr<KBOFF + 0>(va + d * 64);
+      vhi[0][d] = lds_read_tr<KBOFF + V8>(va + d * 64);
+    }
+    // bit i of ok[r]: element i of this lane (key base+kofs+8*(i/4)+4*hh+i%4) may be attended
+    unsigned ok[RB];
 #pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(krow + s * 32);
+    for (int r = 0; r < RB; ++r) {
+      ok[r] = 0xFFFFu;
+      if (MASKED) {
+        ok[r] = 0;
 #pragma unroll
-        for (int r = 0; r < RB; ++r)
-          sacc[kb][r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[kb][r], 0, 0, 0);
+        for (int qd = 0; qd < 4; ++qd) {
+          const int p0 = base + kofs + 8 * qd + 4 * hh;  // first of 4 consecutive keys
+          unsigned nib;
+          if (tree) {
+            const uint64_t mw = (p0 < 64) ? mrow[r][0] : mrow[r][1];
+            nib = (unsigned)(mw >> (p0 & 63)) & 0xFu;
+          } else {
+            const int left = limit - p0;
+            nib = left >= 4 ? 0xFu : (left <= 0 ? 0u : ((1u << left) - 1u));
+          }
+          ok[r] |= nib << (4 * qd);
+        }
       }
     }
-    // masking: keys past the limit, and for tree tiles keys that are not ancestors
-    if (edge) {
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = base + wofs + kb * 32 + 8 * (i / 4) + 4 * hh + (i % 4);
-          const bool inb = key < limit;
-#pragma unroll
-          for (int r = 0; r < RB; ++r) {
-            bool ok = inb;
-            if (tree) {
-              const uint64_t mw = (key < 64) ? mrow[r][0] : mrow[r][1];
-              ok = ok && ((mw >> (key & 63)) & 1ull);
-            }
-            if (!ok) sacc[kb][r][i] = -INFINITY;
-          }
-        }
-    }
-    // online softmax.  P is rounded to bf16 for the second product; where a row's
-    // largest probability of this tile is not small against its running sum (few
-    // effective keys: rounding one weight by 2^-9 would show in O) the rounding
-    // remainder is fed through a second, low-order MFMA pass (wave-uniform choice).
-    bf16x8 pb[KB][2][RB];
+    bf16x8 pb[2][RB];
+    float m_use[RB];
     bool need_lo = false;
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
+      float sv[16];
       float mx = -INFINITY;
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][r][i]);
+      for (int i = 0; i < 16; ++i) {
+        sv[i] = sacc[r][i];
+        if (MASKED) sv[i] = ((ok[r] >> i) & 1u) ? sv[i] : -INFINITY;
+        mx = fmaxf(mx, sv[i]);
+      }
       mx = half_max(mx) * p.scale_log2;
-      const float m_new = fmaxf(m_run[r], mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = fast_exp2(m_run[r] - m_use);
-      const float pmax = fast_exp2(mx - m_use);
-      m_run[r] = m_new;
-      float ls = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float pv = fast_exp2(fmaf(sacc[kb][r][i], p.scale_log2, -m_use));
-          ls += pv;
-          sacc[kb][r][i] = pv;
-          pb[kb][i / 8][r][i % 8] = (__bf16)pv;
-        }
-      l_run[r] = l_run[r] * alpha + ls;
-      need_lo = need_lo || (pmax > kLoThreshold * l_run[r]);
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+      // lazy reference update: only when some row's tile maximum exceeds its reference by > 2^kLazy
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[r] + kLazy) != 0) {
+        const float m_new = fmaxf(m_run[r], mx);
+        const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_run[r] - m_new);
+        m_run[r] = m_new;
+        l_run[r] *= alpha;
 #pragma unroll
         for (int d = 0; d < ND; ++d)
 #pragma unroll
           for (int i = 0; i < 16; ++i) oacc[r][d][i] *= alpha;
       }
+      m_use[r] = (m_run[r] == -INFINITY) ? 0.f : m_run[r];
+      const float pmax = fast_exp2(mx - m_use[r]);
+      float ls = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float pv = fast_exp2(fmaf(sv[i], p.scale_log2, -m_use[r]));
+        ls += pv;
+        pb[i / 8][r][i % 8] = (__bf16)pv;
+      }
+      l_run[r] += ls;
+      need_lo = need_lo || (pmax > kLoThreshold * l_run[r]);
     }
-    const bool lo_pass = __builtin_amdgcn_ballot_w64(need_lo) != 0;
-    // O^T += V^T P^T
-    const int L16 = lane & 15, grp1 = (lane >> 4) & 1;
+    // O^T += V^T P^T: first 16 keys while the operands of the second 16 arrive
+    constexpr int S2OFF = (16 / NBLK) * ROWB;
+    static_assert(ND == 4 || ND == 2, "head dimension 128 or 64");
+    if constexpr (ND == 4) lds_wait(vlo[0][0], vlo[0][1], vlo[0][2], vlo[0][3]), lds_wait(vhi[0][0], vhi[0][1], vhi[0][2], vhi[0][3]);
+    else lds_wait(vlo[0][0], vlo[0][1], vhi[0][0], vhi[0][1]);
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
+    for (int d = 0; d < ND; ++d) {
+      vlo[1][d] = lds_read_tr<KBOFF + S2OFF>(va + d * 64);
+      vhi[1][d] = lds_read_tr<KBOFF + S2OFF + V8>(va + d * 64);
+    }
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const unsigned char *vbase =
-            sV + (wofs + kb * 32 + 16 * s2 + 4 * hh + (L16 >> 2)) * VP + (16 * grp1 + 4 * (L16 & 3)) * 2;
-        bf16x8 plo[RB];
-        if (lo_pass) {
+    for (int d = 0; d < ND; ++d) {
+      const bf16x8 vop = __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[0][d], vhi[0][d], 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
-          for (int r = 0; r < RB; ++r)
+      for (int r = 0; r < RB; ++r)
+        oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pb[0][r], oacc[r][d], 0, 0, 0);
+    }
+    if constexpr (ND == 4) lds_wait(vlo[1][0], vlo[1][1], vlo[1][2], vlo[1][3]), lds_wait(vhi[1][0], vhi[1][1], vhi[1][2], vhi[1][3]);
+    else lds_wait(vlo[1][0], vlo[1][1], vhi[1][0], vhi[1][1]);
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-              plo[r][j] = (__bf16)(sacc[kb][r][8 * s2 + j] - (float)pb[kb][s2][r][j]);
+    for (int d = 0; d < ND; ++d) {
+      const bf16x8 vop = __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[1][d], vhi[1][d], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+      for (int r = 0; r < RB; ++r)
+        oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pb[1][r], oacc[r][d], 0, 0, 0);
+    }
+    // low-order pass (rare): the bf16 rounding remainder of P, recomputed from the scores
+    if (__builtin_amdgcn_ballot_w64(need_lo) != 0) {
+      bf16x8 plo[2][RB];
+#pragma unroll
+      for (int r = 0; r < RB; ++r)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float sv = sacc[r][i];
+          if (MASKED) sv = ((ok[r] >> i) & 1u) ? sv : -INFINITY;
+          const float pv = fast_exp2(fmaf(sv, p.scale_log2, -m_use[r]));
+          plo[i / 8][r][i % 8] = (__bf16)(pv - (float)pb[i / 8][r][i % 8]);
         }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
         for (int d = 0; d < ND; ++d) {
-          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vbase + d * 64));
-          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vbase + 8 * VP + d * 64));
-          const s16x8 v8 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-          const bf16x8 va = __builtin_bit_cast(bf16x8, v8);
+          const bf16x8 vop =
+              __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[s2][d], vhi[s2][d], 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
           for (int r = 0; r < RB; ++r)
-            oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kb][s2][r], oacc[r][d], 0, 0, 0);
-          if (lo_pass) {
-#pragma unroll
-            for (int r = 0; r < RB; ++r)
-              oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, plo[r], oacc[r][d], 0, 0, 0);
-          }
+            oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[s2][r], oacc[r][d], 0, 0, 0);
         }
-      }
+    }
   };
 
-  // ---- main loop ----
-  if (n_tiles > 0) load_tile(0);
-  for (int it = 0; it < n_tiles; ++it) {
-    store_tile();
-    __syncthreads();
-    if (it + 1 < n_tiles) load_tile(it + 1);
-    compute_tile(it);
-    __syncthreads();
-  }
+  // ---- one pipeline step: wait for tile `it`, refill the stage tile it-1 used, compute ----
+  auto step = [&](int it, auto masked_tag) {
+    // this wave's loads of tile `it` have landed once at most the later tiles' loads are outstanding
+    if (PD >= 2 && it + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * (PD - 1)));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();  // everyone's part of tile `it` is in LDS; everyone is done with tile it-1
+    if (it + PD < n_tiles) issue_tile(it + PD);
+    const bool tree = it >= n_ct;
+    const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
+    const int limit = tree ? Tb : k1;
+    const lds_byte *stage = lds + (it % NSTAGE) * STAGE_BYTES;
+    if (base + wk * KBW * 32 < limit) {  // wave-uniform: some key of this wave's first block exists
+      compute_block(stage, std::integral_constant<int, 0>{}, base, limit, tree, masked_tag);
+      if (KBW > 1 && base + (wk * KBW + 1) * 32 < limit)
+        compute_block(stage, std::integral_constant<int, KBW - 1>{}, base, limit, tree, masked_tag);
+    }
+  };
+
+#pragma unroll
+  for (int t = 0; t < PD; ++t)
+    if (t < n_tiles) issue_tile(t);
+  int it = 0;
+  for (; it < n_full; ++it) step(it, std::false_type{});
+  for (; it < n_tiles; ++it) step(it, std::true_type{});
+  __builtin_amdgcn_s_barrier();  // all waves are done reading the ring before it is reused below
 
   // ---- combine the two lane halves' partial sums ----
   float l_tot[RB];
@@ -558,11 +653,11 @@ bool make_plan(const tva_args *a, Plan *pl) {
 
 typedef void (*attn_fn)(const AttnParams);
 
-template <int D, int WM, int WK, int RB, int KB, bool PAGED>
+template <int D, int WM, int WK, int RB, bool PAGED>
 hipError_t launch_attn(const AttnParams &p, int grid, hipStream_t st) {
-  using C = AttnCfg<D, WM, WK, RB, KB, PAGED>;
+  using C = AttnCfg<D, WM, WK, RB, PAGED>;
   static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent
-  auto kfn = attn_kernel<D, WM, WK, RB, KB, PAGED>;
+  auto kfn = attn_kernel<D, WM, WK, RB, PAGED>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kfn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
@@ -576,10 +671,10 @@ hipError_t launch_attn(const AttnParams &p, int grid, hipStream_t st) {
 template <int D, bool PAGED>
 hipError_t dispatch_variant(int variant, const AttnParams &p, int grid, hipStream_t st) {
   switch (variant) {
-    case V_R256: return launch_attn<D, 4, 1, 2, 2, PAGED>(p, grid, st);
-    case V_R128: return launch_attn<D, 2, 2, 2, 1, PAGED>(p, grid, st);
-    case V_R64: return launch_attn<D, 1, 4, 2, 1, PAGED>(p, grid, st);
-    default: return launch_attn<D, 1, 4, 1, 1, PAGED>(p, grid, st);
+    case V_R256: return launch_attn<D, 4, 1, 2, PAGED>(p, grid, st);
+    case V_R128: return launch_attn<D, 2, 2, 2, PAGED>(p, grid, st);
+    case V_R64: return launch_attn<D, 1, 4, 2, PAGED>(p, grid, st);
+    default: return launch_attn<D, 1, 4, 1, PAGED>(p, grid, st);
   }
 }
 
@@ -686,6 +781,9 @@ int tva_tree_verify_attn(const tva_args *a, void *stream) {
   p.n_row_blocks = pl.n_row_blocks;
   p.max_L = a->max_L;
   p.page_size = a->page_size > 0 ? a->page_size : 1;
+  p.page_shift = -1;
+  for (int sft = 0; sft < 31; ++sft)
+    if ((1 << sft) == p.page_size) p.page_shift = sft;
   p.max_pages = a->max_pages;
   p.stride_head = a->stride_head ? a->stride_head : a->D;
   p.stride_tok = a->stride_tok ? a->stride_tok : (int64_t)a->Hkv * a->D;
