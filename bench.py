@@ -40,6 +40,12 @@ def get_workload(name):
         return wl.config4()
     if name == "cfg5":
         return wl.config5()
+    if name.startswith("custom:"):
+        # custom:B=32,Hq=32,Hkv=8,D=128,L=2048,T=60[,page=16]  (uniform L and T, random trees of depth <= 8)
+        kv = dict(item.split("=") for item in name[7:].split(","))
+        g = lambda k, d: int(kv.get(k, d))
+        return wl.random_workload(12345, g("B", 1), g("Hq", 32), g("Hkv", 8), g("D", 128), g("L", 2048), g("T", 60),
+                                  max_depth=8, page_size=g("page", 0), name=name)
     raise SystemExit(f"unknown workload {name}")
 
 

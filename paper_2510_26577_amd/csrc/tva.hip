@@ -173,6 +173,13 @@ __device__ __forceinline__ void lds_wait(s16x4 &a, s16x4 &b, s16x4 &c, s16x4 &d)
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
+#ifdef TVA_TIMING
+__device__ long long tva_dbg[64];
+#define TVA_STAMP(i) do { if (blockIdx.x == gridDim.x / 2 && threadIdx.x == 0) tva_dbg[i] = clock64(); } while (0)
+#else
+#define TVA_STAMP(i) do { } while (0)
+#endif
+
 template <int D, int WM, int WK, int RB, bool PAGED>
 __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   using C = AttnCfg<D, WM, WK, RB, PAGED>;
@@ -183,6 +190,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   constexpr int ND = D / 32;  // 32-wide d blocks of the PV product
   extern __shared__ __align__(1024) unsigned char smem[];
   lds_byte *const lds = (lds_byte *)smem;
+  TVA_STAMP(0);
 
   // ---- which (sequence, KV head, row block, chunk) ----
   int id = blockIdx.x;
@@ -468,12 +476,16 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
     }
   };
 
+  TVA_STAMP(1);
 #pragma unroll
   for (int t = 0; t < PD; ++t)
     if (t < n_tiles) issue_tile(t);
+  TVA_STAMP(2);
   int it = 0;
-  for (; it < n_full; ++it) step(it, std::false_type{});
+  for (; it < n_full; ++it) { step(it, std::false_type{}); if (it < 8) TVA_STAMP(8 + it); }
+  TVA_STAMP(3);
   for (; it < n_tiles; ++it) step(it, std::true_type{});
+  TVA_STAMP(4);
   __builtin_amdgcn_s_barrier();  // all waves are done reading the ring before it is reused below
 
   // ---- combine the two lane halves' partial sums ----
@@ -535,14 +547,20 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   }
 
   // ---- write (normalised) result: final when there is one split, else the partial ----
+  // The accumulators hold O^T (lane = row, registers = 16 scattered d per 32-wide block); each
+  // wave transposes one 32-row block at a time through its own LDS patch so that global stores
+  // are whole contiguous rows.
   const bool final_out = (p.n_chunks == 1);
   float *obase = final_out ? p.out : p.part_out + (size_t)chunk * p.sum_T * p.Hq * D;
   float *lbase = final_out ? p.lse : p.part_lse + (size_t)chunk * p.sum_T * p.Hq;
+  constexpr int TP = D + 4;         // patch row pitch in floats: 16 rows x 16 B apart in bank position
+  constexpr int LPR = D / 4;        // lanes that cover one row with 16 bytes each
+  constexpr int RPP = 64 / LPR;     // rows per wave-wide store
+  static_assert(C::SMEM >= WM * 32 * TP * 4, "transpose patches fit in the ring");
+  float *tbuf = reinterpret_cast<float *>(smem) + wm * (32 * TP);
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
-    if (!rvalid[r]) continue;
     const float inv = l_tot[r] > 0.f ? 1.f / l_tot[r] : 0.f;
-    float *orow_p = obase + orow[r] * D + 4 * hh;
 #pragma unroll
     for (int d = 0; d < ND; ++d)
 #pragma unroll
@@ -550,10 +568,20 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
         f32x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = oacc[r][d][i4 * 4 + e] * inv;
-        *reinterpret_cast<f32x4 *>(orow_p + 32 * d + 8 * i4) = v;
+        *reinterpret_cast<f32x4 *>(tbuf + l32 * TP + 32 * d + 8 * i4 + 4 * hh) = v;
       }
-    if (hh == 0) lbase[orow[r]] = l_tot[r] > 0.f ? (m_run[r] + __builtin_amdgcn_logf(l_tot[r])) * kLn2 : -INFINITY;
+    const int my_row = rvalid[r] ? (int)orow[r] : -1;  // lane l (< 32) owns patch row l
+#pragma unroll 4
+    for (int i = 0; i < 32 / RPP; ++i) {
+      const int rl = i * RPP + lane / LPR;
+      const int og = __shfl(my_row, rl);
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(tbuf + rl * TP + (lane % LPR) * 4);
+      if (og >= 0) *reinterpret_cast<f32x4 *>(obase + (int64_t)og * D + (lane % LPR) * 4) = v;
+    }
+    if (rvalid[r] && hh == 0)
+      lbase[orow[r]] = l_tot[r] > 0.f ? (m_run[r] + __builtin_amdgcn_logf(l_tot[r])) * kLn2 : -INFINITY;
   }
+  TVA_STAMP(5);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -685,6 +713,12 @@ extern "C" {
 int tva_version(void) { return 1; }
 
 size_t tva_sizeof_args(void) { return sizeof(tva_args); }
+
+#ifdef TVA_TIMING
+int tva_debug_stamps(long long *host64) {
+  return hipMemcpyFromSymbol(host64, HIP_SYMBOL(tva_dbg), sizeof(long long) * 64) == hipSuccess ? 0 : -4;
+}
+#endif
 
 const char *tva_strerror(int code) {
   switch (code) {
