@@ -21,6 +21,7 @@
 // KV head, so that the workgroup still has four waves streaming keys).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include <type_traits>
 
@@ -50,15 +51,23 @@ constexpr float kLazy = 8.f;
 // ---------------------------------------------------------------------------------------
 // ancestor masks
 // ---------------------------------------------------------------------------------------
-// One thread per node walks its parent chain.  A link that does not go strictly
-// downward (or below -1) is reported and ends the walk, so every thread finishes
-// in at most T_b steps.
+// One workgroup per tree: the parent array is staged in LDS (trees of up to kMaskLds nodes; larger
+// ones are walked in global memory), then one thread per node walks its parent chain.  A link that
+// does not go strictly downward (or below -1) is reported and ends the walk, so every thread
+// finishes in at most T_b steps.
+constexpr int kMaskLds = 1024;
 __global__ void anc_mask_kernel(const int32_t *__restrict__ parent, const int32_t *__restrict__ cu_T,
                                 int B, int W, uint64_t *__restrict__ mask, int32_t *err_flag) {
+  __shared__ int32_t spar[kMaskLds];
   const int b = blockIdx.x;
   const int t0 = cu_T[b], T = cu_T[b + 1] - t0;
+  const bool in_lds = T <= kMaskLds;
+  if (in_lds) {
+    for (int i = threadIdx.x; i < T; i += blockDim.x) spar[i] = parent[t0 + i];
+    __syncthreads();
+  }
   for (int i = threadIdx.x; i < T; i += blockDim.x) {
-    uint64_t m[4] = {0, 0, 0, 0};  // W <= 4 handled in registers, larger W spills to the loop below
+    uint64_t m[4] = {0, 0, 0, 0};  // W <= 4 handled in registers, larger W goes through memory
     uint64_t *row = mask + (size_t)(t0 + i) * W;
     if (W > 4)
       for (int w = 0; w < W; ++w) row[w] = 0;
@@ -68,7 +77,7 @@ __global__ void anc_mask_kernel(const int32_t *__restrict__ parent, const int32_
         if (W <= 4) m[a >> 6] |= 1ull << (a & 63);
         else row[a >> 6] |= 1ull << (a & 63);
       }
-      const int p = parent[t0 + a];
+      const int p = in_lds ? spar[a] : parent[t0 + a];
       if (p < -1 || p >= a) {
         if (err_flag) {
           // smallest offending global index + 1 (0 = none yet)
@@ -118,11 +127,31 @@ __device__ __forceinline__ float half_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+#ifndef TVA_PRIO_MODE
+#define TVA_PRIO_MODE 0
+#endif
+#if TVA_PRIO_MODE == 1
+#define TVA_PRIO_MFMA() __builtin_amdgcn_s_setprio(1)
+#define TVA_PRIO_VALU() __builtin_amdgcn_s_setprio(0)
+#elif TVA_PRIO_MODE == 2
+#define TVA_PRIO_MFMA() __builtin_amdgcn_s_setprio(0)
+#define TVA_PRIO_VALU() __builtin_amdgcn_s_setprio(1)
+#else
+#define TVA_PRIO_MFMA() do { } while (0)
+#define TVA_PRIO_VALU() do { } while (0)
+#endif
+#ifndef TVA_W8_KBW
+#define TVA_W8_KBW 2
+#endif
+#ifndef TVA_FAST_PATH
+#define TVA_FAST_PATH 0
+#endif
+
 template <int D, int WM, int WK, int RB, bool PAGED>
 struct AttnCfg {
   static constexpr int NW = WM * WK;
   static constexpr int NT = NW * 64;
-  static constexpr int KBW = (WK == 1) ? 2 : 1;  // 32-key blocks each wave owns in a tile
+  static constexpr int KBW = (WK == 1) ? ((WM == 8 && RB == 1) ? TVA_W8_KBW : 2) : 1;  // 32-key blocks each wave owns in a tile
   static constexpr int TK = WK * KBW * 32;       // keys per tile
   static constexpr int BM = WM * RB * 32;        // query rows per workgroup
   static constexpr int DC = D / 8;               // 16-byte chunks per K/V row
@@ -143,11 +172,17 @@ struct AttnCfg {
   static constexpr int PV = BLKB + 32;           // block pitch of the V tile
   static constexpr int KTILE = NBLK * PK, VTILE = NBLK * PV;
   static constexpr int STAGE_BYTES = (KTILE + VTILE + 1023) / 1024 * 1024;
-  static constexpr int NSTAGE = (3 * STAGE_BYTES <= 120 * 1024) ? 3 : 2;
-  static constexpr int PD = NSTAGE - 1;          // tiles in flight ahead of the one being computed
+  // TK = 64: four stages, two tiles in flight, and the software-pipelined loop (which still reads
+  // the V operands of tile t-1 after tile t has been entered, hence one stage more than PD + 1).
+  // TK = 128: two stages, one tile in flight, plain loop.
+  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1);
+  static constexpr int NSTAGE = FAST ? 4 : (TK == 64 ? 3 : 2);
+  static constexpr int PD = TK == 64 ? 2 : 1;    // tiles in flight ahead of the one being computed
   static constexpr int MERGE_BYTES = (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
   static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
-  static constexpr int SMEM = RING_BYTES > MERGE_BYTES ? RING_BYTES : MERGE_BYTES;
+  static constexpr int PATCH_BYTES = WM * 32 * (D + 4) * 4;  // output transpose patches of the epilogue
+  static constexpr int SMEM0 = RING_BYTES > MERGE_BYTES ? RING_BYTES : MERGE_BYTES;
+  static constexpr int SMEM = SMEM0 > PATCH_BYTES ? SMEM0 : PATCH_BYTES;
   static_assert(TK % (RPI * NW) == 0, "tile must divide evenly over the waves");
   static_assert(BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
 };
@@ -209,10 +244,18 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   Lb = Lb < p.max_L ? Lb : p.max_L;
   int nc = (Lb + p.chunk_keys - 1) / p.chunk_keys;
   nc = nc < 1 ? 1 : nc;
-  if (chunk >= nc) return;
+  if (chunk >= nc) {
+    // this sequence has fewer chunks than the launch provides: mark the slot empty for the merge
+    for (int row = rblk * BM + (int)threadIdx.x; row < R && row < (rblk + 1) * BM; row += blockDim.x) {
+      const int t = row / p.G, g = row - t * p.G;
+      p.part_lse[(size_t)chunk * p.sum_T * p.Hq + (size_t)(t0 + t) * p.Hq + kvh * p.G + g] = -INFINITY;
+    }
+    return;
+  }
   const int k0 = chunk * p.chunk_keys;
   const int k1 = (k0 + p.chunk_keys < Lb) ? k0 + p.chunk_keys : Lb;
   const bool has_tree = (chunk == nc - 1);
+  TVA_STAMP(6);
   const int n_full = (k1 - k0) / TK;               // cache tiles that need no masking
   const int n_ct = (k1 - k0 + TK - 1) / TK;
   const int n_tt = has_tree ? (Tb + TK - 1) / TK : 0;
@@ -270,11 +313,25 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   // valid row (finite data; their scores are masked to -inf), so LDS never holds stale values.
   const int lsub = lane / DC, lpos = lane % DC;
   const int64_t cache_base = PAGED ? 0 : (int64_t)p.cu_L[b] * p.stride_tok + (int64_t)kvh * p.stride_head;
-  auto issue_tile = [&](int t) {
-    const bool tree = t >= n_ct;
+  // full tiles of a dense cache: a wave-uniform row pointer plus one tile-independent lane offset
+  const uint32_t lane_off = (uint32_t)(NBLK * lsub) * (uint32_t)p.stride_tok * 2u + (uint32_t)lpos * 16u;
+  auto issue_impl = [&](int t, auto tree_tag) __attribute__((always_inline)) {
+    constexpr bool tree = decltype(tree_tag)::value;
     const int base = tree ? (t - n_ct) * TK : k0 + t * TK;
     const int limit = tree ? Tb : k1;
     lds_byte *stage = lds + (t % NSTAGE) * STAGE_BYTES;
+    if (!PAGED && t < n_full) {
+#pragma unroll
+      for (int j = 0; j < NLDK; ++j) {
+        const int n = wave * NLDK + j;
+        const int blk = n / IPB, part = n % IPB;
+        const int64_t urow = cache_base + (int64_t)(base + blk + NBLK * part * RPI) * p.stride_tok;
+        const char *ksrc = reinterpret_cast<const char *>(p.k_cache + urow) + lane_off;
+        const char *vsrc = reinterpret_cast<const char *>(p.v_cache + urow) + lane_off;
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + blk * PK + part * 1024, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + KTILE + blk * PV + part * 1024, 16, 0, 0);
+      }
+    } else {
 #pragma unroll
     for (int j = 0; j < NLDK; ++j) {
       const int n = wave * NLDK + j;
@@ -311,6 +368,12 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + blk * PK + part * 1024, 16, 0, 0);
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + KTILE + blk * PV + part * 1024, 16, 0, 0);
     }
+    }
+  };
+
+  auto issue_tile = [&](int t) __attribute__((always_inline)) {
+    if (t >= n_ct) issue_impl(t, std::true_type{});
+    else issue_impl(t, std::false_type{});
   };
 
   // per-lane LDS read bases (row r of a tile: block r % NBLK, sub-row r / NBLK)
@@ -321,7 +384,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
                         ((L16 & 1) << 3);
 
   // ---- one 32-key block of one tile: S^T = K Q^T, online softmax, O^T += V^T P^T ----
-  auto compute_block = [&](const lds_byte *stage, auto kb_tag, int base, int limit, bool tree, auto masked_tag) {
+  auto compute_block = [&](const lds_byte *stage, auto kb_tag, int base, int limit, bool tree, auto masked_tag) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_tag)::value;
     constexpr int kb = decltype(kb_tag)::value;
     constexpr int KBOFF = kb * (32 / NBLK) * ROWB;     // this 32-key block inside the wave's part of the tile
@@ -334,6 +397,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
     for (int r = 0; r < RB; ++r)
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[r][i] = 0.f;
+    TVA_PRIO_MFMA();
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(kp + s * 32);
@@ -341,6 +405,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       for (int r = 0; r < RB; ++r)
         sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
     }
+    TVA_PRIO_VALU();
     // V^T operands of the first 16 keys: in flight during the softmax arithmetic
     s16x4 vlo[2][ND], vhi[2][ND];
 #pragma unroll
@@ -408,6 +473,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       need_lo = need_lo || (pmax > kLoThreshold * l_run[r]);
     }
     // O^T += V^T P^T: first 16 keys while the operands of the second 16 arrive
+    TVA_PRIO_MFMA();
     constexpr int S2OFF = (16 / NBLK) * ROWB;
     static_assert(ND == 4 || ND == 2, "head dimension 128 or 64");
     if constexpr (ND == 4) lds_wait(vlo[0][0], vlo[0][1], vlo[0][2], vlo[0][3]), lds_wait(vhi[0][0], vhi[0][1], vhi[0][2], vhi[0][3]);
@@ -458,22 +524,199 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
     }
   };
 
+  // ---- software-pipelined path for runs of full (unmasked) tiles ----
+  // One wave has a single instruction stream per SIMD, so the matrix pipe and the vector ALU only
+  // overlap if independent MFMA and VALU work alternates in program order.  Each pass of
+  // fast_body therefore computes the QK^T product of the NEXT 32-key block next to the
+  // exponentials of the CURRENT one, then the PV product of the current block next to reading
+  // back the next block's scores.  The reference maximum is an integer (log2 domain) and is only
+  // moved between passes, when the next block's maximum calls for it, so a pass is branch-free;
+  // moving it multiplies O and l by an exact power of two.
+  struct Scores {
+    float sv[RB][16];  // scores of a block (this lane's 16 keys per row block)
+    float mx[RB];      // block maximum per row, scaled to the log2 domain
+  };
+
+  auto tile_enter = [&](int t) __attribute__((always_inline)) {
+    if (PD >= 2 && t + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * (PD - 1)));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();
+    if (t + PD < n_tiles) issue_tile(t + PD);
+  };
+
+  // S^T of block (tile t, kb): MFMAs only; fast_readback turns the accumulators into Scores
+  auto fast_qk = [&](int t, auto kb_tag, f32x16 (&sacc)[RB]) {
+    constexpr int kb = decltype(kb_tag)::value;
+    constexpr int KBOFF = kb * (32 / NBLK) * ROWB;
+    const lds_byte *kp = lds + (t % NSTAGE) * STAGE_BYTES + kbase_off + KBOFF;
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[r][i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(kp + s * 32);
+#pragma unroll
+      for (int r = 0; r < RB; ++r)
+        sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
+    }
+  };
+  auto fast_readback = [&](const f32x16 (&sacc)[RB], Scores &x) {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        x.sv[r][i] = sacc[r][i];
+        mx = fmaxf(mx, x.sv[r][i]);
+      }
+      x.mx[r] = half_max(mx) * p.scale_log2;
+    }
+  };
+  // moves the reference of rows whose next block exceeds it (nothing is pending between passes)
+  auto fast_reference = [&](const Scores &nx) __attribute__((always_inline)) {
+    bool move = false;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) move = move || (nx.mx[r] > m_run[r] + kLazy);
+    if (__builtin_amdgcn_ballot_w64(move) != 0) {
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+        const float m_new = ceilf(fmaxf(m_run[r], nx.mx[r]));
+        const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_run[r] - m_new);  // exact power of two
+        m_run[r] = m_new;
+        l_run[r] *= alpha;
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[r][d][i] *= alpha;
+      }
+    }
+  };
+  // Does block n need the low-order P pass?  Decided before its exponentials, from its maximum
+  // and the running sum so far: the block's largest probability p adds at least p to the sum, so
+  // p > thr * (l + p) is the (slightly conservative) form of the test the plain path applies.
+  auto fast_needs_lo = [&](const Scores &n) __attribute__((always_inline)) {
+    bool need = false;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const float m_use = (m_run[r] == -INFINITY) ? 0.f : m_run[r];
+      const float pmax = fast_exp2(n.mx[r] - m_use);
+      need = need || (pmax * (1.f - kLoThreshold) > kLoThreshold * l_run[r]);
+    }
+    return __builtin_amdgcn_ballot_w64(need) != 0;
+  };
+  // exponentials of block c; with LO also the bf16 rounding remainder of P (second MFMA pass)
+  auto fast_exps = [&](const Scores &c, bf16x8 (&pb)[2][RB], bf16x8 (&plo)[2][RB], auto lo_tag) {
+    constexpr bool LO = decltype(lo_tag)::value;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const float m_use = (m_run[r] == -INFINITY) ? 0.f : m_run[r];
+      float ls = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float pv = fast_exp2(fmaf(c.sv[r][i], p.scale_log2, -m_use));
+        ls += pv;
+        pb[i / 8][r][i % 8] = (__bf16)pv;
+        if (LO) plo[i / 8][r][i % 8] = (__bf16)(pv - (float)pb[i / 8][r][i % 8]);
+      }
+      l_run[r] += ls;
+    }
+  };
+  struct VOps {
+    s16x4 lo[2][ND], hi[2][ND];
+  };
+  auto fast_vread = [&](int t, auto kb_tag, VOps &v) __attribute__((always_inline)) {
+    constexpr int kb = decltype(kb_tag)::value;
+    constexpr int KBOFF = kb * (32 / NBLK) * ROWB;
+    constexpr int V8 = (NBLK == 16) ? 8 * PV : ROWB;
+    constexpr int S2OFF = (16 / NBLK) * ROWB;
+    const uint32_t va = (uint32_t)(uintptr_t)(lds + (t % NSTAGE) * STAGE_BYTES + vbase_off);
+#pragma unroll
+    for (int d = 0; d < ND; ++d) {
+      v.lo[0][d] = lds_read_tr<KBOFF>(va + d * 64);
+      v.hi[0][d] = lds_read_tr<KBOFF + V8>(va + d * 64);
+    }
+#pragma unroll
+    for (int d = 0; d < ND; ++d) {
+      v.lo[1][d] = lds_read_tr<KBOFF + S2OFF>(va + d * 64);
+      v.hi[1][d] = lds_read_tr<KBOFF + S2OFF + V8>(va + d * 64);
+    }
+  };
+  auto fast_vwait = [&](VOps &v) __attribute__((always_inline)) {
+    static_assert(ND == 4 || ND == 2, "head dimension 128 or 64");
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      if constexpr (ND == 4) {
+        lds_wait(v.lo[s2][0], v.lo[s2][1], v.lo[s2][2], v.lo[s2][3]);
+        lds_wait(v.hi[s2][0], v.hi[s2][1], v.hi[s2][2], v.hi[s2][3]);
+      } else {
+        lds_wait(v.lo[s2][0], v.lo[s2][1], v.hi[s2][0], v.hi[s2][1]);
+      }
+    }
+  };
+  auto fast_pv = [&](const bf16x8 (&pbx)[2][RB], const VOps &v) {
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int d = 0; d < ND; ++d) {
+        const bf16x8 vop =
+            __builtin_bit_cast(bf16x8, __builtin_shufflevector(v.lo[s2][d], v.hi[s2][d], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+          oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pbx[s2][r], oacc[r][d], 0, 0, 0);
+      }
+  };
+  // One pass.  In: scores of the current block (tc, kbc) in `sc`, with the reference valid for
+  // them, and whether that block takes the low-order pass.  Out: `sc` holds the scores of the
+  // next block (tn, kbn), the reference is valid for those, and the return value says whether
+  // that block takes the low-order pass.  HAS_NEXT = false drains the pipeline.
+  auto fast_body = [&](int tc, auto kbc_tag, int tn, auto kbn_tag, Scores &sc, bool lo, auto has_next_tag) __attribute__((always_inline)) {
+    constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
+    constexpr int kbn = decltype(kbn_tag)::value;
+    if (HAS_NEXT && kbn == 0) tile_enter(tn);
+    VOps v;
+    fast_vread(tc, kbc_tag, v);
+    f32x16 sacc[RB];
+    bf16x8 pb[2][RB], plo[2][RB];
+    if (lo) {  // rare: few effective keys so far
+      fast_exps(sc, pb, plo, std::true_type{});
+      if (HAS_NEXT) fast_qk(tn, kbn_tag, sacc);
+      fast_vwait(v);
+      fast_pv(pb, v);
+      fast_pv(plo, v);
+    } else {
+      if (HAS_NEXT) fast_qk(tn, kbn_tag, sacc);
+      fast_exps(sc, pb, plo, std::false_type{});
+      fast_vwait(v);
+      fast_pv(pb, v);
+    }
+    if (HAS_NEXT) {
+      fast_readback(sacc, sc);
+      fast_reference(sc);
+      return fast_needs_lo(sc);
+    }
+    return false;
+  };
+
   // ---- one pipeline step: wait for tile `it`, refill the stage tile it-1 used, compute ----
-  auto step = [&](int it, auto masked_tag) {
+  auto step = [&](int it, auto masked_tag, auto tree_tag) __attribute__((always_inline)) {
     // this wave's loads of tile `it` have landed once at most the later tiles' loads are outstanding
     if (PD >= 2 && it + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * (PD - 1)));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();  // everyone's part of tile `it` is in LDS; everyone is done with tile it-1
     if (it + PD < n_tiles) issue_tile(it + PD);
-    const bool tree = it >= n_ct;
+    constexpr bool tree = decltype(tree_tag)::value;
     const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
     const int limit = tree ? Tb : k1;
     const lds_byte *stage = lds + (it % NSTAGE) * STAGE_BYTES;
-    if (base + wk * KBW * 32 < limit) {  // wave-uniform: some key of this wave's first block exists
-      compute_block(stage, std::integral_constant<int, 0>{}, base, limit, tree, masked_tag);
-      if (KBW > 1 && base + (wk * KBW + 1) * 32 < limit)
-        compute_block(stage, std::integral_constant<int, KBW - 1>{}, base, limit, tree, masked_tag);
-    }
+    // wave-uniform: a block is skipped when none of its keys exists
+    if (base + wk * KBW * 32 < limit) compute_block(stage, std::integral_constant<int, 0>{}, base, limit, tree, masked_tag);
+    if constexpr (KBW > 1)
+      if (base + (wk * KBW + 1) * 32 < limit) compute_block(stage, std::integral_constant<int, 1>{}, base, limit, tree, masked_tag);
+    if constexpr (KBW > 2)
+      if (base + (wk * KBW + 2) * 32 < limit) compute_block(stage, std::integral_constant<int, 2>{}, base, limit, tree, masked_tag);
+    if constexpr (KBW > 3)
+      if (base + (wk * KBW + 3) * 32 < limit) compute_block(stage, std::integral_constant<int, 3>{}, base, limit, tree, masked_tag);
   };
 
   TVA_STAMP(1);
@@ -482,9 +725,30 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
     if (t < n_tiles) issue_tile(t);
   TVA_STAMP(2);
   int it = 0;
-  for (; it < n_full; ++it) { step(it, std::false_type{}); if (it < 8) TVA_STAMP(8 + it); }
+  if (C::FAST && n_full > 0) {
+    using kb0 = std::integral_constant<int, 0>;
+    using kb1 = std::integral_constant<int, KBW - 1>;
+    Scores sc;
+    {
+      f32x16 sacc[RB];
+      tile_enter(0);
+      fast_qk(0, kb0{}, sacc);
+      fast_readback(sacc, sc);
+      fast_reference(sc);
+    }
+    bool lo = fast_needs_lo(sc);
+    for (int t = 0; t < n_full; ++t) {
+      if constexpr (KBW == 2) lo = fast_body(t, kb0{}, t, kb1{}, sc, lo, std::true_type{});
+      if (t + 1 < n_full) lo = fast_body(t, kb1{}, t + 1, kb0{}, sc, lo, std::true_type{});
+      else fast_body(t, kb1{}, t + 1, kb0{}, sc, lo, std::false_type{});
+      if (t < 8) TVA_STAMP(8 + t);
+    }
+    it = n_full;
+  }
+  for (; it < n_full; ++it) step(it, std::false_type{}, std::false_type{});
   TVA_STAMP(3);
-  for (; it < n_tiles; ++it) step(it, std::true_type{});
+  for (; it < n_ct; ++it) step(it, std::true_type{}, std::false_type{});   // the partial cache tile
+  for (; it < n_tiles; ++it) step(it, std::true_type{}, std::true_type{});  // the tree's own keys
   TVA_STAMP(4);
   __builtin_amdgcn_s_barrier();  // all waves are done reading the ring before it is reused below
 
@@ -546,6 +810,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
     if (wk != 0) return;
   }
 
+  TVA_STAMP(7);
   // ---- write (normalised) result: final when there is one split, else the partial ----
   // The accumulators hold O^T (lane = row, registers = 16 scattered d per 32-wide block); each
   // wave transposes one 32-row block at a time through its own LDS patch so that global stores
@@ -571,7 +836,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
         *reinterpret_cast<f32x4 *>(tbuf + l32 * TP + 32 * d + 8 * i4 + 4 * hh) = v;
       }
     const int my_row = rvalid[r] ? (int)orow[r] : -1;  // lane l (< 32) owns patch row l
-#pragma unroll 4
+#pragma unroll
     for (int i = 0; i < 32 / RPP; ++i) {
       const int rl = i * RPP + lane / LPR;
       const int og = __shfl(my_row, rl);
@@ -587,56 +852,47 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
 // ---------------------------------------------------------------------------------------
 // merge of the KV splits
 // ---------------------------------------------------------------------------------------
-// One wave per output row (token, head).  When cu_T / L are given the number of
-// valid splits of the row's sequence is derived from them (splits past it were
-// never written); otherwise all S splits are read.
+// One wave per output row (token, head).  The two 32-lane halves take the even and the odd
+// splits, 16 bytes of the row per lane (D = 128; one half-wave covers two splits' worth at
+// D = 64), and are added at the end.  Splits whose LSE is -inf (empty, or never computed because
+// the sequence is shorter than the launch's split count) are skipped without reading their O.
 template <int D>
 __global__ void __launch_bounds__(256) merge_kernel(const float *__restrict__ part_out,
                                                     const float *__restrict__ part_lse, int S, int64_t n_rows,
-                                                    float *__restrict__ out, float *__restrict__ lse,
-                                                    const int32_t *__restrict__ cu_T, const int32_t *__restrict__ L,
-                                                    int B, int Hq, int chunk_keys, int max_L) {
+                                                    float *__restrict__ out, float *__restrict__ lse) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= n_rows) return;
-  int ns = S;
-  if (cu_T) {
-    const int tok = (int)(row / Hq);
-    int lo = 0, hi = B;  // largest b with cu_T[b] <= tok
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (cu_T[mid] <= tok) lo = mid; else hi = mid;
-    }
-    int Lb = L[lo];
-    Lb = Lb < max_L ? Lb : max_L;
-    ns = (Lb + chunk_keys - 1) / chunk_keys;
-    ns = ns < 1 ? 1 : (ns > S ? S : ns);
-  }
+  constexpr int LPR = D / 4;      // lanes covering one row with 16 bytes each
+  constexpr int GROUPS = 64 / LPR;  // splits processed side by side in one wave
+  const int grp = lane / LPR, col = (lane % LPR) * 4;
   float mx = -INFINITY;
-  for (int s = lane; s < ns; s += 64) mx = fmaxf(mx, part_lse[(size_t)s * n_rows + row]);
+  for (int s = lane; s < S; s += 64) mx = fmaxf(mx, part_lse[(size_t)s * n_rows + row]);
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-  constexpr int E = D / 64;  // elements per lane
-  float acc[E];
-#pragma unroll
-  for (int e = 0; e < E; ++e) acc[e] = 0.f;
   if (mx == -INFINITY) {
-#pragma unroll
-    for (int e = 0; e < E; ++e) out[row * D + lane * E + e] = 0.f;
+    if (grp == 0) *reinterpret_cast<f32x4 *>(out + row * D + col) = f32x4{0.f, 0.f, 0.f, 0.f};
     if (lane == 0) lse[row] = -INFINITY;
     return;
   }
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   float z = 0.f;
-  for (int s = 0; s < ns; ++s) {
+#pragma unroll 8
+  for (int s = grp; s < S; s += GROUPS) {
     const float w = __expf(part_lse[(size_t)s * n_rows + row] - mx);
     z += w;
-    const float *po = part_out + ((size_t)s * n_rows + row) * D + lane * E;
-#pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] += w * po[e];
+    if (w != 0.f) {
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(part_out + ((size_t)s * n_rows + row) * D + col);
+      acc += v * w;
+    }
   }
-  const float inv = 1.f / z;
 #pragma unroll
-  for (int e = 0; e < E; ++e) out[row * D + lane * E + e] = acc[e] * inv;
+  for (int o = 32; o >= LPR; o >>= 1) {
+    z += __shfl_xor(z, o);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], o);
+  }
+  if (grp == 0) *reinterpret_cast<f32x4 *>(out + row * D + col) = acc * (1.f / z);
   if (lane == 0) lse[row] = mx + __logf(z);
 }
 
@@ -649,17 +905,22 @@ struct Plan {
   int n_row_blocks, n_chunks, chunk_keys;
 };
 
-enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3 };
+enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5 };
 
 bool make_plan(const tva_args *a, Plan *pl) {
   if (!a || a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv) return false;
   if (a->sum_T < 0 || a->max_T < 0 || a->max_L < 0 || a->num_splits < 0) return false;
   const int G = a->Hq / a->Hkv;
   const int rows = a->max_T * G;
-  if (rows > 128) { pl->variant = V_R256; pl->BM = 256; pl->TK = 64; }
-  else if (rows > 64) { pl->variant = V_R128; pl->BM = 128; pl->TK = 64; }
-  else if (rows > 32) { pl->variant = V_R64; pl->BM = 64; pl->TK = 128; }
-  else { pl->variant = V_R32; pl->BM = 32; pl->TK = 128; }
+  int variant = rows > 128 ? V_R256 : rows > 64 ? V_R128 : rows > 32 ? V_R64 : V_R32;
+  // benchmarking aid: TVA_FORCE_VARIANT=0..3 picks the workgroup shape (256/128/64/32 query rows)
+  if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
+    const int v = atoi(fv);
+    if (v >= V_R256 && v <= V_W4) variant = v;
+  }
+  pl->variant = variant;
+  pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4) ? 128 : variant == V_R64 ? 64 : 32;
+  pl->TK = (variant == V_R64 || variant == V_R32) ? 128 : (variant == V_W8 ? 32 * TVA_W8_KBW : 64);
   pl->n_row_blocks = rows > 0 ? (rows + pl->BM - 1) / pl->BM : 1;
   int S = a->num_splits;
   const int max_by_len = a->max_L > 0 ? (a->max_L + pl->TK - 1) / pl->TK : 1;
@@ -702,6 +963,8 @@ hipError_t dispatch_variant(int variant, const AttnParams &p, int grid, hipStrea
     case V_R256: return launch_attn<D, 4, 1, 2, PAGED>(p, grid, st);
     case V_R128: return launch_attn<D, 2, 2, 2, PAGED>(p, grid, st);
     case V_R64: return launch_attn<D, 1, 4, 2, PAGED>(p, grid, st);
+    case V_W8: return launch_attn<D, 8, 1, 1, PAGED>(p, grid, st);
+    case V_W4: return launch_attn<D, 4, 1, 1, PAGED>(p, grid, st);
     default: return launch_attn<D, 1, 4, 1, PAGED>(p, grid, st);
   }
 }
@@ -762,6 +1025,7 @@ static int check_args(const tva_args *a, bool shapes_only) {
   if (paged && (int64_t)a->max_pages * a->page_size < a->max_L) return TVA_INVALID_ARG;
   if ((a->stride_page | a->stride_tok | a->stride_head) % 8) return TVA_INVALID_ARG;
   if (a->stride_page < 0 || a->stride_tok < 0 || a->stride_head < 0) return TVA_INVALID_ARG;
+  if (a->stride_tok >= (1 << 24)) return TVA_UNSUPPORTED;  // lane offsets inside a tile are 32-bit
   return TVA_OK;
 }
 
@@ -841,10 +1105,10 @@ int tva_tree_verify_attn(const tva_args *a, void *stream) {
     const int mgrid = (int)((n_rows + 3) / 4);
     if (a->D == 128)
       hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, p.part_out, p.part_lse, pl.n_chunks,
-                         n_rows, a->out, a->lse, a->cu_T, a->L, a->B, a->Hq, pl.chunk_keys, a->max_L);
+                         n_rows, a->out, a->lse);
     else
       hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, p.part_out, p.part_lse, pl.n_chunks,
-                         n_rows, a->out, a->lse, a->cu_T, a->L, a->B, a->Hq, pl.chunk_keys, a->max_L);
+                         n_rows, a->out, a->lse);
     if (hipGetLastError() != hipSuccess) return TVA_HIP_ERROR;
   }
   return TVA_OK;
@@ -860,11 +1124,9 @@ int tva_merge_splits(const float *part_out, const float *part_lse, int32_t S, in
   const int mgrid = (int)((n_rows + 3) / 4);
   hipStream_t st = (hipStream_t)stream;
   if (D == 128)
-    hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse,
-                       (const int32_t *)nullptr, (const int32_t *)nullptr, 0, 1, 1, 0);
+    hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse);
   else
-    hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse,
-                       (const int32_t *)nullptr, (const int32_t *)nullptr, 0, 1, 1, 0);
+    hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse);
   return hipGetLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 
