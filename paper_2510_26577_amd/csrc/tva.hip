@@ -144,7 +144,7 @@ __device__ __forceinline__ float half_sum(float x) {
 #define TVA_W8_KBW 2
 #endif
 #ifndef TVA_FAST_PATH
-#define TVA_FAST_PATH 0
+#define TVA_FAST_PATH 1
 #endif
 
 template <int D, int WM, int WK, int RB, bool PAGED>
@@ -175,9 +175,14 @@ struct AttnCfg {
   // TK = 64: four stages, two tiles in flight, and the software-pipelined loop (which still reads
   // the V operands of tile t-1 after tile t has been entered, hence one stage more than PD + 1).
   // TK = 128: two stages, one tile in flight, plain loop.
-  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1);
+  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4);
+#ifdef TVA_EXP_PD
+  static constexpr int NSTAGE = TK == 64 ? TVA_EXP_PD + 1 : 2;
+  static constexpr int PD = TK == 64 ? TVA_EXP_PD : 1;
+#else
   static constexpr int NSTAGE = FAST ? 4 : (TK == 64 ? 3 : 2);
   static constexpr int PD = TK == 64 ? 2 : 1;    // tiles in flight ahead of the one being computed
+#endif
   static constexpr int MERGE_BYTES = (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
   static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
   static constexpr int PATCH_BYTES = WM * 32 * (D + 4) * 4;  // output transpose patches of the epilogue
@@ -209,10 +214,16 @@ __device__ __forceinline__ void lds_wait(s16x4 &a, s16x4 &b, s16x4 &c, s16x4 &d)
 }
 
 #ifdef TVA_TIMING
+#define TVA_PHASE_DECL long long ph_acc[7] = {0, 0, 0, 0, 0, 0, 0}; long long ph_t = clock64();
+#define TVA_PHASE(i) do { const long long ph_n = clock64(); ph_acc[i] += ph_n - ph_t; ph_t = ph_n; } while (0)
+#define TVA_PHASE_DUMP do { if (blockIdx.x == gridDim.x / 2 && (threadIdx.x & 63) == 0) for (int i = 0; i < 7; ++i) tva_dbg[8 + (threadIdx.x >> 6) * 7 + i] = ph_acc[i]; } while (0)
 __device__ long long tva_dbg[64];
 #define TVA_STAMP(i) do { if (blockIdx.x == gridDim.x / 2 && threadIdx.x == 0) tva_dbg[i] = clock64(); } while (0)
 #else
 #define TVA_STAMP(i) do { } while (0)
+#define TVA_PHASE_DECL
+#define TVA_PHASE(i) do { } while (0)
+#define TVA_PHASE_DUMP do { } while (0)
 #endif
 
 template <int D, int WM, int WK, int RB, bool PAGED>
@@ -226,6 +237,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   extern __shared__ __align__(1024) unsigned char smem[];
   lds_byte *const lds = (lds_byte *)smem;
   TVA_STAMP(0);
+  TVA_PHASE_DECL
 
   // ---- which (sequence, KV head, row block, chunk) ----
   int id = blockIdx.x;
@@ -313,6 +325,27 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   // valid row (finite data; their scores are masked to -inf), so LDS never holds stale values.
   const int lsub = lane / DC, lpos = lane % DC;
   const int64_t cache_base = PAGED ? 0 : (int64_t)p.cu_L[b] * p.stride_tok + (int64_t)kvh * p.stride_head;
+  // paged cache: page numbers of the rows this wave loads for one cache tile (wave-uniform, hence
+  // scalar loads), fetched one tile ahead of their use so that issuing a tile never waits on them
+  int pages[NLDK][RPI];
+  auto load_pages = [&](int t) __attribute__((always_inline)) {
+    if (!PAGED) return;
+    const int base = k0 + t * TK;
+#pragma unroll
+    for (int j = 0; j < NLDK; ++j) {
+      const int n = wave * NLDK + j;
+      const int blk = n / IPB, part = n % IPB;
+#pragma unroll
+      for (int u = 0; u < RPI; ++u) {
+        int key = base + blk + NBLK * (part * RPI + u);
+        key = key < k1 ? key : k1 - 1;
+        key = key < 0 ? 0 : key;
+        const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
+        pages[j][u] = p.page_table[(int64_t)b * p.max_pages + pidx];
+      }
+    }
+  };
+  if (PAGED && n_ct > 0) load_pages(0);
   // full tiles of a dense cache: a wave-uniform row pointer plus one tile-independent lane offset
   const uint32_t lane_off = (uint32_t)(NBLK * lsub) * (uint32_t)p.stride_tok * 2u + (uint32_t)lpos * 16u;
   auto issue_impl = [&](int t, auto tree_tag) __attribute__((always_inline)) {
@@ -344,15 +377,15 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
         ksrc = p.k_tree + off;
         vsrc = p.v_tree + off;
       } else if (PAGED) {
-        // one scalar page-table read per row of the instruction; each lane keeps its row's
+        // the page of each row of this instruction was read (scalar loads) when the previous tile
+        // was issued; each lane keeps its own row's
         int64_t off = 0;
 #pragma unroll
         for (int u = 0; u < RPI; ++u) {
           int key = base + blk + NBLK * (part * RPI + u);
           key = key < limit ? key : limit - 1;
           const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
-          const int pg = p.page_table[(int64_t)b * p.max_pages + pidx];
-          const int64_t o = (int64_t)pg * p.stride_page + (int64_t)(key - pidx * p.page_size) * p.stride_tok;
+          const int64_t o = (int64_t)pages[j][u] * p.stride_page + (int64_t)(key - pidx * p.page_size) * p.stride_tok;
           off = (lsub == u) ? o : off;
         }
         off += (int64_t)kvh * p.stride_head + lpos * 8;
@@ -372,8 +405,12 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   };
 
   auto issue_tile = [&](int t) __attribute__((always_inline)) {
-    if (t >= n_ct) issue_impl(t, std::true_type{});
-    else issue_impl(t, std::false_type{});
+    if (t >= n_ct) {
+      issue_impl(t, std::true_type{});
+    } else {
+      issue_impl(t, std::false_type{});
+      if (PAGED && t + 1 < n_ct) load_pages(t + 1);  // tiles are issued in order: t + 1 comes next
+    }
   };
 
   // per-lane LDS read bases (row r of a tile: block r % NBLK, sub-row r / NBLK)
@@ -397,7 +434,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
     for (int r = 0; r < RB; ++r)
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[r][i] = 0.f;
-    TVA_PRIO_MFMA();
+    TVA_PHASE(0);
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(kp + s * 32);
@@ -405,7 +442,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       for (int r = 0; r < RB; ++r)
         sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
     }
-    TVA_PRIO_VALU();
+    TVA_PHASE(1);
     // V^T operands of the first 16 keys: in flight during the softmax arithmetic
     s16x4 vlo[2][ND], vhi[2][ND];
 #pragma unroll
@@ -473,7 +510,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       need_lo = need_lo || (pmax > kLoThreshold * l_run[r]);
     }
     // O^T += V^T P^T: first 16 keys while the operands of the second 16 arrive
-    TVA_PRIO_MFMA();
+    TVA_PHASE(2);
     constexpr int S2OFF = (16 / NBLK) * ROWB;
     static_assert(ND == 4 || ND == 2, "head dimension 128 or 64");
     if constexpr (ND == 4) lds_wait(vlo[0][0], vlo[0][1], vlo[0][2], vlo[0][3]), lds_wait(vhi[0][0], vhi[0][1], vhi[0][2], vhi[0][3]);
@@ -499,6 +536,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       for (int r = 0; r < RB; ++r)
         oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pb[1][r], oacc[r][d], 0, 0, 0);
     }
+    TVA_PHASE(3);
     // low-order pass (rare): the bf16 rounding remainder of P, recomputed from the scores
     if (__builtin_amdgcn_ballot_w64(need_lo) != 0) {
       bf16x8 plo[2][RB];
@@ -703,12 +741,19 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
     // this wave's loads of tile `it` have landed once at most the later tiles' loads are outstanding
     if (PD >= 2 && it + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * (PD - 1)));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    TVA_PHASE(5);
     __builtin_amdgcn_s_barrier();  // everyone's part of tile `it` is in LDS; everyone is done with tile it-1
+    TVA_PHASE(6);
     if (it + PD < n_tiles) issue_tile(it + PD);
     constexpr bool tree = decltype(tree_tag)::value;
     const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
     const int limit = tree ? Tb : k1;
     const lds_byte *stage = lds + (it % NSTAGE) * STAGE_BYTES;
+    TVA_PHASE(4);
+#ifdef TVA_EXP_NOCOMPUTE
+    if (threadIdx.x > 100000)
+#endif
+    {
     // wave-uniform: a block is skipped when none of its keys exists
     if (base + wk * KBW * 32 < limit) compute_block(stage, std::integral_constant<int, 0>{}, base, limit, tree, masked_tag);
     if constexpr (KBW > 1)
@@ -717,6 +762,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       if (base + (wk * KBW + 2) * 32 < limit) compute_block(stage, std::integral_constant<int, 2>{}, base, limit, tree, masked_tag);
     if constexpr (KBW > 3)
       if (base + (wk * KBW + 3) * 32 < limit) compute_block(stage, std::integral_constant<int, 3>{}, base, limit, tree, masked_tag);
+    }
   };
 
   TVA_STAMP(1);
@@ -741,7 +787,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       if constexpr (KBW == 2) lo = fast_body(t, kb0{}, t, kb1{}, sc, lo, std::true_type{});
       if (t + 1 < n_full) lo = fast_body(t, kb1{}, t + 1, kb0{}, sc, lo, std::true_type{});
       else fast_body(t, kb1{}, t + 1, kb0{}, sc, lo, std::false_type{});
-      if (t < 8) TVA_STAMP(8 + t);
+      
     }
     it = n_full;
   }
@@ -847,6 +893,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
       lbase[orow[r]] = l_tot[r] > 0.f ? (m_run[r] + __builtin_amdgcn_logf(l_tot[r])) * kLn2 : -INFINITY;
   }
   TVA_STAMP(5);
+  TVA_PHASE_DUMP;
 }
 
 // ---------------------------------------------------------------------------------------
