@@ -902,7 +902,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
 // One wave per output row (token, head).  The two 32-lane halves take the even and the odd
 // splits, 16 bytes of the row per lane (D = 128; one half-wave covers two splits' worth at
 // D = 64), and are added at the end.  Splits whose LSE is -inf (empty, or never computed because
-// the sequence is shorter than the launch's split count) are skipped without reading their O.
+// the sequence is shorter than the launch's split count) get weight zero.
 template <int D>
 __global__ void __launch_bounds__(256) merge_kernel(const float *__restrict__ part_out,
                                                     const float *__restrict__ part_lse, int S, int64_t n_rows,
@@ -926,12 +926,13 @@ __global__ void __launch_bounds__(256) merge_kernel(const float *__restrict__ pa
   float z = 0.f;
 #pragma unroll 8
   for (int s = grp; s < S; s += GROUPS) {
+    // O of an empty split may be uninitialised memory: read it anyway (so that the loads of all
+    // splits are in flight together) and drop it by selection, never by multiplication
     const float w = __expf(part_lse[(size_t)s * n_rows + row] - mx);
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(part_out + ((size_t)s * n_rows + row) * D + col);
     z += w;
-    if (w != 0.f) {
-      const f32x4 v = *reinterpret_cast<const f32x4 *>(part_out + ((size_t)s * n_rows + row) * D + col);
-      acc += v * w;
-    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] += (w != 0.f) ? v[e] * w : 0.f;
   }
 #pragma unroll
   for (int o = 32; o >= LPR; o >>= 1) {
@@ -959,8 +960,12 @@ bool make_plan(const tva_args *a, Plan *pl) {
   if (a->sum_T < 0 || a->max_T < 0 || a->max_L < 0 || a->num_splits < 0) return false;
   const int G = a->Hq / a->Hkv;
   const int rows = a->max_T * G;
-  int variant = rows > 128 ? V_R256 : rows > 64 ? V_R128 : rows > 32 ? V_R64 : V_R32;
-  // benchmarking aid: TVA_FORCE_VARIANT=0..3 picks the workgroup shape (256/128/64/32 query rows)
+  // Workgroup shape, from sweeps over the benchmark shapes: up to 64 rows per KV head use
+  // 32-row workgroups whose four waves split the keys; above that, four waves of 32 rows each
+  // (128 rows, software-pipelined loop), or eight such waves (256 rows) once there are enough
+  // (sequence, KV head) pairs that 256-row workgroups still fill the chip with few KV splits.
+  int variant = rows <= 64 ? V_R32 : (rows > 128 && a->B * a->Hkv >= 32) ? V_W8 : V_W4;
+  // benchmarking aid: TVA_FORCE_VARIANT=0..5 picks the workgroup shape
   if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
     const int v = atoi(fv);
     if (v >= V_R256 && v <= V_W4) variant = v;
@@ -972,10 +977,11 @@ bool make_plan(const tva_args *a, Plan *pl) {
   int S = a->num_splits;
   const int max_by_len = a->max_L > 0 ? (a->max_L + pl->TK - 1) / pl->TK : 1;
   if (S == 0) {
-    // enough workgroups to occupy the 256 CUs, but no split shorter than four tiles
+    // one workgroup per CU (256) if the batch allows, but no split shorter than two tiles:
+    // every split costs a partial O of the size of the output, written and read back
     const int natural = a->B * a->Hkv * pl->n_row_blocks;
     S = (256 + natural - 1) / natural;
-    const int cap = a->max_L > 0 ? (a->max_L + 4 * pl->TK - 1) / (4 * pl->TK) : 1;
+    const int cap = a->max_L > 0 ? (a->max_L + 2 * pl->TK - 1) / (2 * pl->TK) : 1;
     if (S > cap) S = cap;
   }
   if (S > max_by_len) S = max_by_len;
