@@ -128,6 +128,13 @@ size_t tva_workspace_bytes(const tva_args *a);
 int32_t tva_plan_splits(const tva_args *a);
 
 /*
+ * Cached keys per KV split for these shapes: split s of sequence b covers cached keys
+ * [s*c, min((s+1)*c, L[b])) with c the returned value; the sequence's last non-empty split
+ * (split 0 when L[b] = 0) also covers the tree's own keys.  -1 on invalid arguments.
+ */
+int32_t tva_plan_chunk_keys(const tva_args *a);
+
+/*
  * The attention itself.  For sequence b, tree node i, query head h (KV head
  * g = h / (Hq/Hkv)) with keys k = the L[b] cached tokens followed by the tree
  * tokens j for which bit j of anc_mask row i is set:
@@ -139,6 +146,21 @@ int32_t tva_plan_splits(const tva_args *a);
  * get out = 0, lse = -inf.
  */
 int tva_tree_verify_attn(const tva_args *a, void *stream);
+
+/*
+ * The split-KV part of tva_tree_verify_attn alone: same arguments, but the merge of the KV
+ * splits is left to the caller.  With S = tva_plan_splits(a):
+ *   S == 1: out / lse hold the final result, the workspace is not touched;
+ *   S  > 1: the workspace holds the per-split normalised partial outputs, fp32
+ *           [S, sum_T*Hq, D], followed by their natural-log LSE, fp32 [S, sum_T*Hq]
+ *           (-inf where a sequence is shorter than the split's first key); out / lse are
+ *           not written.  tva_merge_splits(ws, ws + S*sum_T*Hq*D, S, sum_T*Hq, D, out, lse)
+ *           completes the computation.
+ * This is the piece a context-parallel deployment runs per KV shard before gathering the
+ * partials (same definition as above, restricted to the split's keys), and what the benchmark
+ * times to price the dominant kernel on its own.
+ */
+int tva_tree_verify_attn_splits(const tva_args *a, void *stream);
 
 /*
  * Merge of split partial results (the step that follows from splitting a

@@ -58,8 +58,8 @@ class TvaArgs(ctypes.Structure):
     ]
 
 
-EXPORTS = ("tva_build_ancestor_mask", "tva_workspace_bytes", "tva_plan_splits",
-           "tva_tree_verify_attn", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
+EXPORTS = ("tva_build_ancestor_mask", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys",
+           "tva_tree_verify_attn", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
 
 _lib = None
 
@@ -82,8 +82,12 @@ def load_library():
     lib.tva_workspace_bytes.argtypes = [ctypes.POINTER(TvaArgs)]
     lib.tva_plan_splits.restype = ctypes.c_int32
     lib.tva_plan_splits.argtypes = [ctypes.POINTER(TvaArgs)]
+    lib.tva_plan_chunk_keys.restype = ctypes.c_int32
+    lib.tva_plan_chunk_keys.argtypes = [ctypes.POINTER(TvaArgs)]
     lib.tva_tree_verify_attn.restype = ctypes.c_int
     lib.tva_tree_verify_attn.argtypes = [ctypes.POINTER(TvaArgs), ctypes.c_void_p]
+    lib.tva_tree_verify_attn_splits.restype = ctypes.c_int
+    lib.tva_tree_verify_attn_splits.argtypes = [ctypes.POINTER(TvaArgs), ctypes.c_void_p]
     lib.tva_merge_splits.restype = ctypes.c_int
     lib.tva_merge_splits.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
                                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -171,9 +175,21 @@ def plan_splits(args: TvaArgs) -> int:
     return int(n)
 
 
+def plan_chunk_keys(args: TvaArgs) -> int:
+    n = load_library().tva_plan_chunk_keys(ctypes.byref(args))
+    if n < 0:
+        raise TvaError(-1)
+    return int(n)
+
+
 def tree_verify_attn_raw(args: TvaArgs, stream=None) -> None:
     """Queue the attention on `stream` with a prepared argument struct."""
     _check(load_library().tva_tree_verify_attn(ctypes.byref(args), _stream_ptr(stream)))
+
+
+def tree_verify_attn_splits_raw(args: TvaArgs, stream=None) -> None:
+    """Queue only the split-KV attention kernel (no merge) with a prepared argument struct."""
+    _check(load_library().tva_tree_verify_attn_splits(ctypes.byref(args), _stream_ptr(stream)))
 
 
 def tree_verify_attn(q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, *, max_T: int, max_L: int,

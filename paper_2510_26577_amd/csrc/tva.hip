@@ -1089,6 +1089,13 @@ int32_t tva_plan_splits(const tva_args *a) {
   return pl.n_chunks;
 }
 
+int32_t tva_plan_chunk_keys(const tva_args *a) {
+  if (check_args(a, true) != TVA_OK) return -1;
+  Plan pl;
+  if (!make_plan(a, &pl)) return -1;
+  return pl.chunk_keys;
+}
+
 size_t tva_workspace_bytes(const tva_args *a) {
   if (check_args(a, true) != TVA_OK) return (size_t)-1;
   Plan pl;
@@ -1097,7 +1104,13 @@ size_t tva_workspace_bytes(const tva_args *a) {
   return (size_t)pl.n_chunks * a->sum_T * a->Hq * (a->D + 1) * sizeof(float);
 }
 
-int tva_tree_verify_attn(const tva_args *a, void *stream) {
+static int run_attention(const tva_args *a, void *stream, bool merge);
+
+int tva_tree_verify_attn(const tva_args *a, void *stream) { return run_attention(a, stream, true); }
+
+int tva_tree_verify_attn_splits(const tva_args *a, void *stream) { return run_attention(a, stream, false); }
+
+static int run_attention(const tva_args *a, void *stream, bool merge) {
   int rc = check_args(a, false);
   if (rc != TVA_OK) return rc;
   if (a->sum_T == 0 || a->max_T == 0) return TVA_OK;
@@ -1153,7 +1166,7 @@ int tva_tree_verify_attn(const tva_args *a, void *stream) {
     e = paged ? dispatch_variant<64, true>(pl.variant, p, grid, st) : dispatch_variant<64, false>(pl.variant, p, grid, st);
   if (e != hipSuccess) return TVA_HIP_ERROR;
 
-  if (pl.n_chunks > 1) {
+  if (merge && pl.n_chunks > 1) {
     const int64_t n_rows = (int64_t)a->sum_T * a->Hq;
     const int mgrid = (int)((n_rows + 3) / 4);
     if (a->D == 128)

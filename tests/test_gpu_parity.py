@@ -263,3 +263,45 @@ def test_repeated_calls_are_deterministic(gpu):
     b, lb = gpu.attention(dw, mask, num_splits=4)
     torch.cuda.synchronize()
     assert torch.equal(a, b) and torch.equal(la, lb)
+
+
+@pytest.mark.parametrize("splits", [2, 3, 7])
+def test_splits_entry_point_partials_match_oracle_key_ranges(gpu, splits):
+    """tva_tree_verify_attn_splits leaves per-split partials that equal the oracle restricted to
+    each split's keys; merging them with tva_merge_splits gives the full result."""
+    import torch
+    from paper_2510_26577_amd import binding
+    w = wl.random_workload(600 + splits, 2, 8, 2, 128, [700, 300], [24, 9])
+    dw = gpu.to_device(w)
+    mask = gpu.build_mask(dw)
+    out = torch.zeros((w.sum_T, w.Hq, w.D), dtype=torch.float32, device="cuda:0")
+    lse = torch.zeros((w.sum_T, w.Hq), dtype=torch.float32, device="cuda:0")
+    args = binding.make_args(q=dw.q, k_tree=dw.k_tree, v_tree=dw.v_tree, k_cache=dw.k_cache, v_cache=dw.v_cache,
+                             anc_mask=mask, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale,
+                             cu_L=dw.cu_L, num_splits=splits, out=out, lse=lse)
+    S, ck = binding.plan_splits(args), binding.plan_chunk_keys(args)
+    assert S >= 2
+    ws = torch.empty(binding.workspace_bytes(args) // 4, dtype=torch.float32, device="cuda:0")
+    args.workspace, args.workspace_bytes = ws.data_ptr(), ws.numel() * 4
+    binding.tree_verify_attn_splits_raw(args)
+    torch.cuda.synchronize()
+    n = w.sum_T * w.Hq
+    po = ws[: S * n * w.D].view(S, n, w.D)
+    pl = ws[S * n * w.D: S * n * (w.D + 1)].view(S, n)
+    for b in range(w.B):
+        Lb, r0, r1 = int(w.L[b]), int(w.cu_T[b]) * w.Hq, int(w.cu_T[b + 1]) * w.Hq
+        nc = max(1, -(-Lb // ck))
+        for s in range(S):
+            got_l = pl[s, r0:r1].cpu().numpy()
+            if s >= nc:
+                assert np.all(np.isneginf(got_l))
+                continue
+            hi = Lb + int(w.T[b]) if s == nc - 1 else (s + 1) * ck
+            rows = [(b, i, h) for i in range(int(w.T[b])) for h in range(w.Hq)]
+            ro, rl = orc.tree_verify_attn(w, rows=rows, key_range=(s * ck, hi))
+            assert np.abs(got_l - rl).max() <= TOL_LSE
+            assert np.abs(po[s, r0:r1].cpu().numpy() - ro).max() <= TOL_O
+    binding.merge_splits(po, pl, out=out.view(n, w.D), lse=lse.view(n))
+    torch.cuda.synchronize()
+    fo, fl = orc.tree_verify_attn(w)
+    assert np.abs(out.cpu().numpy() - fo).max() <= TOL_O and np.abs(lse.cpu().numpy() - fl).max() <= TOL_LSE
