@@ -209,9 +209,11 @@ def main():
     # counters cannot be read from inside this process); only quoted for the launch shape it was taken on
     traffic = None
     try:
-        t = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json"))).get(w.name)
-        if t and t["kv_splits"] == n_splits and not a.head_major:
-            traffic = t["attn_kernel_bytes"]
+        for line in open(os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.txt")):
+            if line.startswith("traffic "):
+                kv = dict(item.split("=") for item in line.split()[1:])
+                if kv["workload"] == w.name and int(kv["kv_splits"]) == n_splits and not a.head_major:
+                    traffic = float(kv["attn_kernel_bytes"])
     except (OSError, ValueError, KeyError):
         pass
     value = kv_bytes / (ms_step * 1e-3) / 1e9
