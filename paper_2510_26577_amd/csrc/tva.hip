@@ -108,7 +108,7 @@ struct AttnParams {
   const uint64_t *mask;
   float *out, *lse;            // final results
   float *part_out, *part_lse;  // [S, sum_T, Hq, D], [S, sum_T, Hq] when S > 1
-  int B, Hq, Hkv, G, sum_T, W;
+  int B, Hq, Hkv, G, g_shift, sum_T, W;
   int chunk_keys, n_chunks, n_row_blocks, max_L;
   int page_size, page_shift, max_pages;
   int64_t stride_page, stride_tok, stride_head;
@@ -147,7 +147,7 @@ __device__ __forceinline__ float half_sum(float x) {
 #define TVA_FAST_PATH 1
 #endif
 
-template <int D, int WM, int WK, int RB, bool PAGED>
+template <int D, int WM, int WK, int RB, bool PAGED, bool DUO>
 struct AttnCfg {
   static constexpr int NW = WM * WK;
   static constexpr int NT = NW * 64;
@@ -175,13 +175,14 @@ struct AttnCfg {
   // TK = 64: four stages, two tiles in flight, and the software-pipelined loop (which still reads
   // the V operands of tile t-1 after tile t has been entered, hence one stage more than PD + 1).
   // TK = 128: two stages, one tile in flight, plain loop.
-  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4);
+  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4) && !DUO;
 #ifdef TVA_EXP_PD
   static constexpr int NSTAGE = TK == 64 ? TVA_EXP_PD + 1 : 2;
   static constexpr int PD = TK == 64 ? TVA_EXP_PD : 1;
 #else
-  static constexpr int NSTAGE = FAST ? 4 : (TK == 64 ? 3 : 2);
-  static constexpr int PD = TK == 64 ? 2 : 1;    // tiles in flight ahead of the one being computed
+  static constexpr bool TWO_PER_CU = DUO;  // two-stage ring, small enough that two workgroups share a CU
+  static constexpr int NSTAGE = FAST ? 4 : (TK == 64 && !TWO_PER_CU ? 3 : 2);
+  static constexpr int PD = (TK == 64 && !TWO_PER_CU) ? 2 : 1;    // tiles in flight ahead of the one being computed
 #endif
   static constexpr int MERGE_BYTES = (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
   static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
@@ -216,9 +217,9 @@ __device__ __forceinline__ void lds_wait(s16x4 &a, s16x4 &b, s16x4 &c, s16x4 &d)
 #ifdef TVA_TIMING
 #define TVA_PHASE_DECL long long ph_acc[7] = {0, 0, 0, 0, 0, 0, 0}; long long ph_t = clock64();
 #define TVA_PHASE(i) do { const long long ph_n = clock64(); ph_acc[i] += ph_n - ph_t; ph_t = ph_n; } while (0)
-#define TVA_PHASE_DUMP do { if (blockIdx.x == gridDim.x / 2 && (threadIdx.x & 63) == 0) for (int i = 0; i < 7; ++i) tva_dbg[8 + (threadIdx.x >> 6) * 7 + i] = ph_acc[i]; } while (0)
+#define TVA_PHASE_DUMP do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == gridDim.z / 2 && (threadIdx.x & 63) == 0) for (int i = 0; i < 7; ++i) tva_dbg[8 + (threadIdx.x >> 6) * 7 + i] = ph_acc[i]; } while (0)
 __device__ long long tva_dbg[64];
-#define TVA_STAMP(i) do { if (blockIdx.x == gridDim.x / 2 && threadIdx.x == 0) tva_dbg[i] = clock64(); } while (0)
+#define TVA_STAMP(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == gridDim.z / 2 && threadIdx.x == 0) tva_dbg[i] = clock64(); } while (0)
 #else
 #define TVA_STAMP(i) do { } while (0)
 #define TVA_PHASE_DECL
@@ -226,9 +227,9 @@ __device__ long long tva_dbg[64];
 #define TVA_PHASE_DUMP do { } while (0)
 #endif
 
-template <int D, int WM, int WK, int RB, bool PAGED>
-__global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
-  using C = AttnCfg<D, WM, WK, RB, PAGED>;
+template <int D, int WM, int WK, int RB, bool PAGED, bool DUO>
+__global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const AttnParams p) {
+  using C = AttnCfg<D, WM, WK, RB, PAGED, DUO>;
   constexpr int TK = C::TK, BM = C::BM, DC = C::DC, ROWB = C::ROWB, RPI = C::RPI, NLDK = C::NLDK, NLD = C::NLD;
   constexpr int KBW = C::KBW, NSTAGE = C::NSTAGE, PD = C::PD, STAGE_BYTES = C::STAGE_BYTES;
   constexpr int NBLK = C::NBLK, IPB = C::IPB, PK = C::PK, PV = C::PV, KTILE = C::KTILE;
@@ -240,13 +241,11 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   TVA_PHASE_DECL
 
   // ---- which (sequence, KV head, row block, chunk) ----
-  int id = blockIdx.x;
-  const int kvh = id % p.Hkv;
-  id /= p.Hkv;
-  const int rblk = id % p.n_row_blocks;
-  id /= p.n_row_blocks;
-  const int chunk = id % p.n_chunks;
-  const int b = id / p.n_chunks;
+  // grid = (Hkv, row blocks, B * splits): the KV head varies fastest in dispatch order
+  const int kvh = blockIdx.x;
+  const int rblk = blockIdx.y;
+  const int b = (int)blockIdx.z / p.n_chunks;
+  const int chunk = (int)blockIdx.z - b * p.n_chunks;
 
   const int t0 = p.cu_T[b];
   const int Tb = p.cu_T[b + 1] - t0;
@@ -259,7 +258,7 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   if (chunk >= nc) {
     // this sequence has fewer chunks than the launch provides: mark the slot empty for the merge
     for (int row = rblk * BM + (int)threadIdx.x; row < R && row < (rblk + 1) * BM; row += blockDim.x) {
-      const int t = row / p.G, g = row - t * p.G;
+      const int t = p.g_shift >= 0 ? (row >> p.g_shift) : row / p.G, g = row - t * p.G;
       p.part_lse[(size_t)chunk * p.sum_T * p.Hq + (size_t)(t0 + t) * p.Hq + kvh * p.G + g] = -INFINITY;
     }
     return;
@@ -287,14 +286,15 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   for (int r = 0; r < RB; ++r) {
     const int row = rblk * BM + (wm * RB + r) * 32 + l32;
     rvalid[r] = row < R;
-    const int t = rvalid[r] ? row / p.G : 0;
-    const int g = rvalid[r] ? row - t * p.G : 0;
+    // rows past the end compute on a copy of the last row (finite data) and are never stored
+    const int rowc = rvalid[r] ? row : R - 1;
+    const int t = p.g_shift >= 0 ? (rowc >> p.g_shift) : rowc / p.G;
+    const int g = rowc - t * p.G;
     orow[r] = (int64_t)(t0 + t) * p.Hq + kvh * p.G + g;
     const __bf16 *qp = p.q + orow[r] * D + 8 * hh;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      if (rvalid[r]) qreg[r][s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
-      else qreg[r][s] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      qreg[r][s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
     }
     mrow[r][0] = mrow[r][1] = 0;
     if (has_tree && rvalid[r]) {
@@ -405,6 +405,9 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
   };
 
   auto issue_tile = [&](int t) __attribute__((always_inline)) {
+#ifdef TVA_EXP_NOLOAD
+    if (t >= 0) return;
+#endif
     if (t >= n_ct) {
       issue_impl(t, std::true_type{});
     } else {
@@ -881,13 +884,15 @@ __global__ void __launch_bounds__(WM *WK * 64) attn_kernel(const AttnParams p) {
         for (int e = 0; e < 4; ++e) v[e] = oacc[r][d][i4 * 4 + e] * inv;
         *reinterpret_cast<f32x4 *>(tbuf + l32 * TP + 32 * d + 8 * i4 + 4 * hh) = v;
       }
-    const int my_row = rvalid[r] ? (int)orow[r] : -1;  // lane l (< 32) owns patch row l
+    const int row0 = rblk * BM + (wm * RB + r) * 32;
 #pragma unroll
     for (int i = 0; i < 32 / RPP; ++i) {
       const int rl = i * RPP + lane / LPR;
-      const int og = __shfl(my_row, rl);
+      const int row = row0 + rl;
+      const int t = p.g_shift >= 0 ? (row >> p.g_shift) : row / p.G;
+      const int64_t og = (int64_t)(t0 + t) * p.Hq + kvh * p.G + (row - t * p.G);
       const f32x4 v = *reinterpret_cast<const f32x4 *>(tbuf + rl * TP + (lane % LPR) * 4);
-      if (og >= 0) *reinterpret_cast<f32x4 *>(obase + (int64_t)og * D + (lane % LPR) * 4) = v;
+      if (row < R) *reinterpret_cast<f32x4 *>(obase + og * D + (lane % LPR) * 4) = v;
     }
     if (rvalid[r] && hh == 0)
       lbase[orow[r]] = l_tot[r] > 0.f ? (m_run[r] + __builtin_amdgcn_logf(l_tot[r])) * kLn2 : -INFINITY;
@@ -953,25 +958,27 @@ struct Plan {
   int n_row_blocks, n_chunks, chunk_keys;
 };
 
-enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5 };
+enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5, V_K2 = 6, V_K2R2 = 7, V_M2K2 = 8, V_W4D = 9 };
 
 bool make_plan(const tva_args *a, Plan *pl) {
   if (!a || a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv) return false;
   if (a->sum_T < 0 || a->max_T < 0 || a->max_L < 0 || a->num_splits < 0) return false;
   const int G = a->Hq / a->Hkv;
   const int rows = a->max_T * G;
-  // Workgroup shape, from sweeps over the benchmark shapes: up to 64 rows per KV head use
-  // 32-row workgroups whose four waves split the keys; above that, four waves of 32 rows each
-  // (128 rows, software-pipelined loop), or eight such waves (256 rows) once there are enough
-  // (sequence, KV head) pairs that 256-row workgroups still fill the chip with few KV splits.
-  int variant = rows <= 64 ? V_R32 : (rows > 128 && a->B * a->Hkv >= 32) ? V_W8 : V_W4;
-  // benchmarking aid: TVA_FORCE_VARIANT=0..5 picks the workgroup shape
+  // Workgroup shape, from sweeps over the benchmark shapes.  Up to 32 rows per KV head: 32-row
+  // workgroups of two waves that split the keys of 64-key tiles.  Up to 128 rows, or more rows
+  // but few (sequence, KV head) pairs: 64-row workgroups of 2 x 2 waves (two row groups x two key
+  // groups).  Both keep a two-stage ring, small enough that two workgroups share a CU and hide
+  // each other's start-up and drain.  Otherwise eight waves of 32 rows each (256 rows, two waves
+  // per SIMD), which fill the chip with few KV splits.
+  int variant = rows <= 32 ? V_K2 : (rows > 128 && a->B * a->Hkv >= 32) ? V_W8 : V_M2K2;
+  // benchmarking aid: TVA_FORCE_VARIANT=0..9 picks the workgroup shape
   if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
     const int v = atoi(fv);
-    if (v >= V_R256 && v <= V_W4) variant = v;
+    if (v >= V_R256 && v <= V_W4D) variant = v;
   }
   pl->variant = variant;
-  pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4) ? 128 : variant == V_R64 ? 64 : 32;
+  pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4 || variant == V_W4D) ? 128 : (variant == V_R64 || variant == V_K2R2 || variant == V_M2K2) ? 64 : 32;
   pl->TK = (variant == V_R64 || variant == V_R32) ? 128 : (variant == V_W8 ? 32 * TVA_W8_KBW : 64);
   pl->n_row_blocks = rows > 0 ? (rows + pl->BM - 1) / pl->BM : 1;
   int S = a->num_splits;
@@ -995,29 +1002,33 @@ bool make_plan(const tva_args *a, Plan *pl) {
 
 typedef void (*attn_fn)(const AttnParams);
 
-template <int D, int WM, int WK, int RB, bool PAGED>
-hipError_t launch_attn(const AttnParams &p, int grid, hipStream_t st) {
-  using C = AttnCfg<D, WM, WK, RB, PAGED>;
+template <int D, int WM, int WK, int RB, bool PAGED, bool DUO = false>
+hipError_t launch_attn(const AttnParams &p, dim3 grid, hipStream_t st) {
+  using C = AttnCfg<D, WM, WK, RB, PAGED, DUO>;
   static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent
-  auto kfn = attn_kernel<D, WM, WK, RB, PAGED>;
+  auto kfn = attn_kernel<D, WM, WK, RB, PAGED, DUO>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kfn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kfn, dim3(grid), dim3(C::NT), C::SMEM, st, p);
+  hipLaunchKernelGGL(kfn, grid, dim3(C::NT), C::SMEM, st, p);
   return hipGetLastError();
 }
 
 template <int D, bool PAGED>
-hipError_t dispatch_variant(int variant, const AttnParams &p, int grid, hipStream_t st) {
+hipError_t dispatch_variant(int variant, const AttnParams &p, dim3 grid, hipStream_t st) {
   switch (variant) {
     case V_R256: return launch_attn<D, 4, 1, 2, PAGED>(p, grid, st);
     case V_R128: return launch_attn<D, 2, 2, 2, PAGED>(p, grid, st);
     case V_R64: return launch_attn<D, 1, 4, 2, PAGED>(p, grid, st);
     case V_W8: return launch_attn<D, 8, 1, 1, PAGED>(p, grid, st);
     case V_W4: return launch_attn<D, 4, 1, 1, PAGED>(p, grid, st);
+    case V_K2: return launch_attn<D, 1, 2, 1, PAGED, true>(p, grid, st);
+    case V_K2R2: return launch_attn<D, 1, 2, 2, PAGED, true>(p, grid, st);
+    case V_M2K2: return launch_attn<D, 2, 2, 1, PAGED, true>(p, grid, st);
+    case V_W4D: return launch_attn<D, 4, 1, 1, PAGED, true>(p, grid, st);
     default: return launch_attn<D, 1, 4, 1, PAGED>(p, grid, st);
   }
 }
@@ -1138,6 +1149,9 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   p.Hq = a->Hq;
   p.Hkv = a->Hkv;
   p.G = a->Hq / a->Hkv;
+  p.g_shift = -1;
+  for (int sft = 0; sft < 31; ++sft)
+    if ((1 << sft) == p.G) p.g_shift = sft;
   p.sum_T = a->sum_T;
   p.W = a->mask_words;
   p.chunk_keys = pl.chunk_keys;
@@ -1154,9 +1168,8 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   p.stride_page = a->stride_page ? a->stride_page : (int64_t)p.page_size * p.stride_tok;
   p.scale_log2 = a->scale * kLog2e;
 
-  const int64_t grid64 = (int64_t)a->B * pl.n_chunks * pl.n_row_blocks * a->Hkv;
-  if (grid64 <= 0 || grid64 > 0x7fffffff) return TVA_UNSUPPORTED;
-  const int grid = (int)grid64;
+  if ((int64_t)a->B * pl.n_chunks > 65535 || pl.n_row_blocks > 65535) return TVA_UNSUPPORTED;
+  const dim3 grid(a->Hkv, pl.n_row_blocks, a->B * pl.n_chunks);
   const bool paged = a->page_table != nullptr;
   hipStream_t st = (hipStream_t)stream;
   hipError_t e;
