@@ -147,7 +147,7 @@ __device__ __forceinline__ float half_sum(float x) {
 #define TVA_FAST_PATH 1
 #endif
 
-template <int D, int WM, int WK, int RB, bool PAGED, bool DUO>
+template <int D, int WM, int WK, int RB, bool PAGED, int NST>
 struct AttnCfg {
   static constexpr int NW = WM * WK;
   static constexpr int NT = NW * 64;
@@ -175,20 +175,26 @@ struct AttnCfg {
   // TK = 64: four stages, two tiles in flight, and the software-pipelined loop (which still reads
   // the V operands of tile t-1 after tile t has been entered, hence one stage more than PD + 1).
   // TK = 128: two stages, one tile in flight, plain loop.
-  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4) && !DUO;
-#ifdef TVA_EXP_PD
-  static constexpr int NSTAGE = TK == 64 ? TVA_EXP_PD + 1 : 2;
-  static constexpr int PD = TK == 64 ? TVA_EXP_PD : 1;
-#else
-  static constexpr bool TWO_PER_CU = DUO;  // two-stage ring, small enough that two workgroups share a CU
-  static constexpr int NSTAGE = FAST ? 4 : (TK == 64 && !TWO_PER_CU ? 3 : 2);
-  static constexpr int PD = (TK == 64 && !TWO_PER_CU) ? 2 : 1;    // tiles in flight ahead of the one being computed
-#endif
-  static constexpr int MERGE_BYTES = (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
+  // NST = stages of the ring (0: the shape's default).  Two stages keep the footprint small
+  // enough for two workgroups per CU; more stages put more tiles in flight for one workgroup.
+  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4) && (NST == 0);
+  static constexpr int NSTAGE = NST ? NST : FAST ? 4 : (TK == 64 ? 3 : 2);
+  static constexpr int PD = FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed
+  static constexpr int WG_PER_CU = (NSTAGE == 2 && TK == 64) ? 2 : 1;
+  // after the key loop the ring is reused: exchange area of the key-group merge, then (behind it,
+  // when the groups are paired; else on top of it, after a barrier) the output transpose patches
+  static constexpr bool PAIR = (WK == 2);
+  static constexpr int NDW = PAIR ? D / 64 : D / 32;  // 32-wide d blocks of the result each wave writes
+  static constexpr int TP = NDW * 32 + 4;             // patch row pitch, floats
+  static constexpr int MERGE_BYTES = PAIR ? (2 * WK * WM * RB * 32 * 4 + WM * WK * RB * (D / 64) * 16 * 64 * 4)
+                                     : (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
+  static constexpr int PATCH_OFF = PAIR ? MERGE_BYTES : 0;
+  static constexpr int PATCH_BYTES = (PAIR ? NW : WM) * 32 * TP * 4;
   static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
-  static constexpr int PATCH_BYTES = WM * 32 * (D + 4) * 4;  // output transpose patches of the epilogue
-  static constexpr int SMEM0 = RING_BYTES > MERGE_BYTES ? RING_BYTES : MERGE_BYTES;
-  static constexpr int SMEM = SMEM0 > PATCH_BYTES ? SMEM0 : PATCH_BYTES;
+  static constexpr int TAIL_BYTES = PAIR ? MERGE_BYTES + PATCH_BYTES : (MERGE_BYTES > PATCH_BYTES ? MERGE_BYTES : PATCH_BYTES);
+  static constexpr int SMEM = RING_BYTES > TAIL_BYTES ? RING_BYTES : TAIL_BYTES;
+  static_assert(SMEM * WG_PER_CU <= 160 * 1024, "LDS of the workgroups that share a CU");
+  static_assert(PD <= 3 && NLD * PD < 64, "the wait counter holds 6 bits");
   static_assert(TK % (RPI * NW) == 0, "tile must divide evenly over the waves");
   static_assert(BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
 };
@@ -227,9 +233,10 @@ __device__ long long tva_dbg[64];
 #define TVA_PHASE_DUMP do { } while (0)
 #endif
 
-template <int D, int WM, int WK, int RB, bool PAGED, bool DUO>
-__global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const AttnParams p) {
-  using C = AttnCfg<D, WM, WK, RB, PAGED, DUO>;
+template <int D, int WM, int WK, int RB, bool PAGED, int NST>
+__global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
+    attn_kernel(const AttnParams p) {
+  using C = AttnCfg<D, WM, WK, RB, PAGED, NST>;
   constexpr int TK = C::TK, BM = C::BM, DC = C::DC, ROWB = C::ROWB, RPI = C::RPI, NLDK = C::NLDK, NLD = C::NLD;
   constexpr int KBW = C::KBW, NSTAGE = C::NSTAGE, PD = C::PD, STAGE_BYTES = C::STAGE_BYTES;
   constexpr int NBLK = C::NBLK, IPB = C::IPB, PK = C::PK, PV = C::PV, KTILE = C::KTILE;
@@ -247,12 +254,18 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
   const int b = (int)blockIdx.z / p.n_chunks;
   const int chunk = (int)blockIdx.z - b * p.n_chunks;
 
-  const int t0 = p.cu_T[b];
-  const int Tb = p.cu_T[b + 1] - t0;
+  // every per-sequence scalar is requested before the first one is needed
+  int t0 = p.cu_T[b];
+  int t1 = p.cu_T[b + 1];
+  int Lb0 = p.L[b];
+  int cuL = PAGED ? 0 : p.cu_L[b];
+  // (an empty statement that ties them together: keeps the compiler from moving one of the loads
+  // down to its first use, where the wave would wait for it alone)
+  asm("" : "+s"(t0), "+s"(t1), "+s"(Lb0), "+s"(cuL));
+  const int Tb = t1 - t0;
   const int R = Tb * p.G;
   if (rblk * BM >= R) return;
-  int Lb = p.L[b];
-  Lb = Lb < p.max_L ? Lb : p.max_L;
+  const int Lb = Lb0 < p.max_L ? Lb0 : p.max_L;
   int nc = (Lb + p.chunk_keys - 1) / p.chunk_keys;
   nc = nc < 1 ? 1 : nc;
   if (chunk >= nc) {
@@ -296,13 +309,12 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
     for (int s = 0; s < NS; ++s) {
       qreg[r][s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
     }
+    // mask rows are only requested here (rows past the end read their stand-in's); the first use
+    // is in the tree tiles, so nothing waits for them before the key loads have been queued
     mrow[r][0] = mrow[r][1] = 0;
-    if (has_tree && rvalid[r]) {
+    if (has_tree) {
       mrow[r][0] = p.mask[(size_t)(t0 + t) * p.W];
       if (p.W > 1) mrow[r][1] = p.mask[(size_t)(t0 + t) * p.W + 1];
-      // bits at or above T_b can never be keys
-      if (Tb < 64) { mrow[r][0] &= (1ull << Tb) - 1; mrow[r][1] = 0; }
-      else if (Tb < 128) mrow[r][1] &= (1ull << (Tb - 64)) - 1;
     }
   }
 
@@ -324,10 +336,14 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
   // (n%IPB)*RPI + l/DC of that block, chunk l%DC.  Rows past the tile's limit re-read the last
   // valid row (finite data; their scores are masked to -inf), so LDS never holds stale values.
   const int lsub = lane / DC, lpos = lane % DC;
-  const int64_t cache_base = PAGED ? 0 : (int64_t)p.cu_L[b] * p.stride_tok + (int64_t)kvh * p.stride_head;
+  const int64_t cache_base = PAGED ? 0 : (int64_t)cuL * p.stride_tok + (int64_t)kvh * p.stride_head;
   // paged cache: page numbers of the rows this wave loads for one cache tile (wave-uniform, hence
   // scalar loads), fetched one tile ahead of their use so that issuing a tile never waits on them
   int pages[NLDK][RPI];
+  // (read through the constant address space: the table does not change while the kernel runs,
+  // and saying so keeps these loads scalar although LDS-writing loads sit between them)
+  typedef const __attribute__((address_space(4))) int32_t const_i32;
+  const_i32 *const ptab = PAGED ? (const_i32 *)(uintptr_t)(p.page_table + (int64_t)b * p.max_pages) : nullptr;
   auto load_pages = [&](int t) __attribute__((always_inline)) {
     if (!PAGED) return;
     const int base = k0 + t * TK;
@@ -341,7 +357,7 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
         key = key < k1 ? key : k1 - 1;
         key = key < 0 ? 0 : key;
         const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
-        pages[j][u] = p.page_table[(int64_t)b * p.max_pages + pidx];
+        pages[j][u] = ptab[pidx];
       }
     }
   };
@@ -465,7 +481,10 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
           const int p0 = base + kofs + 8 * qd + 4 * hh;  // first of 4 consecutive keys
           unsigned nib;
           if (tree) {
-            const uint64_t mw = (p0 < 64) ? mrow[r][0] : mrow[r][1];
+            // bits at or above T_b can never be keys
+            const int nbits = limit - (p0 & ~63);
+            const uint64_t trim = nbits >= 64 ? ~0ull : nbits <= 0 ? 0ull : (1ull << nbits) - 1;
+            const uint64_t mw = ((p0 < 64) ? mrow[r][0] : mrow[r][1]) & trim;
             nib = (unsigned)(mw >> (p0 & 63)) & 0xFu;
           } else {
             const int left = limit - p0;
@@ -742,7 +761,10 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
   // ---- one pipeline step: wait for tile `it`, refill the stage tile it-1 used, compute ----
   auto step = [&](int it, auto masked_tag, auto tree_tag) __attribute__((always_inline)) {
     // this wave's loads of tile `it` have landed once at most the later tiles' loads are outstanding
-    if (PD >= 2 && it + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * (PD - 1)));
+    const int later = n_tiles - 1 - it;  // tiles after `it` whose loads are already queued: min(later, PD - 1)
+    if (PD >= 4 && later >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 3));
+    else if (PD >= 3 && later >= 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 2));
+    else if (PD >= 2 && later >= 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 1));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     TVA_PHASE(5);
     __builtin_amdgcn_s_barrier();  // everyone's part of tile `it` is in LDS; everyone is done with tile it-1
@@ -772,6 +794,15 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
 #pragma unroll
   for (int t = 0; t < PD; ++t)
     if (t < n_tiles) issue_tile(t);
+  // Q and the mask rows were requested before the tiles; they have arrived once no more than the
+  // tiles' own loads are outstanding.  Said here, once, so that no wait for them (which would
+  // also drain the prefetched tiles) is needed inside the key loop.
+  {
+    const int n_pre = n_tiles < PD ? n_tiles : PD;
+    if (PD >= 3 && n_pre >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 3));
+    else if (PD >= 2 && n_pre == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 2));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD));
+  }
   TVA_STAMP(2);
   int it = 0;
   if (C::FAST && n_full > 0) {
@@ -807,7 +838,63 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
   for (int r = 0; r < RB; ++r) l_tot[r] = half_sum(l_run[r]);
 
   // ---- merge the WK key groups through LDS ----
-  if constexpr (WK > 1) {
+  // Two key groups: each wave keeps one half of the head dimension and hands the other half to
+  // its partner, so both take part in the reduction and in writing the result.  More than two:
+  // the groups are folded into group 0 one after the other, which then writes alone.
+  constexpr bool PAIR = C::PAIR;
+  if constexpr (PAIR) {
+    constexpr int H = ND / 2;
+    float *sm = reinterpret_cast<float *>(smem);            // m then l: [2][WK][WM][RB][32]
+    float *sl = sm + WK * WM * RB * 32;
+    float *xo = sl + WK * WM * RB * 32;                      // [WM][WK][RB][H][4][64] x 16 bytes
+    if (hh == 0) {
+#pragma unroll
+      for (int r = 0; r < RB; ++r) sm[((wk * WM + wm) * RB + r) * 32 + l32] = m_run[r];
+    }
+    __syncthreads();
+    float a[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const float mo = sm[(((1 - wk) * WM + wm) * RB + r) * 32 + l32];
+      const float mf = fmaxf(m_run[r], mo);
+      a[r] = fast_exp2(m_run[r] - ((mf == -INFINITY) ? 0.f : mf));
+      m_run[r] = mf;
+      l_tot[r] *= a[r];
+      if (hh == 0) sl[((wk * WM + wm) * RB + r) * 32 + l32] = l_tot[r];
+    }
+    auto swap_halves = [&](auto me_tag) __attribute__((always_inline)) {
+      constexpr int me = decltype(me_tag)::value;  // keeps d blocks [me*H, me*H + H), hands over the others
+      f32x4 *dst = reinterpret_cast<f32x4 *>(xo) + (size_t)((wm * WK + (1 - me)) * RB * H * 4) * 64;
+#pragma unroll
+      for (int r = 0; r < RB; ++r)
+#pragma unroll
+        for (int d = 0; d < H; ++d)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = oacc[r][(1 - me) * H + d][i4 * 4 + e] * a[r];
+            dst[((r * H + d) * 4 + i4) * 64 + lane] = v;
+          }
+      __syncthreads();
+      const f32x4 *src = reinterpret_cast<const f32x4 *>(xo) + (size_t)((wm * WK + me) * RB * H * 4) * 64;
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+#pragma unroll
+        for (int d = 0; d < H; ++d)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const f32x4 v = src[((r * H + d) * 4 + i4) * 64 + lane];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              oacc[r][me * H + d][i4 * 4 + e] = fmaf(oacc[r][me * H + d][i4 * 4 + e], a[r], v[e]);
+          }
+        l_tot[r] += sl[(((1 - me) * WM + wm) * RB + r) * 32 + l32];
+      }
+    };
+    if (wk == 0) swap_halves(std::integral_constant<int, 0>{});
+    else swap_halves(std::integral_constant<int, 1>{});
+  } else if constexpr (WK > 1) {
     float *sm = reinterpret_cast<float *>(smem);                      // [WK][WM][RB][32]
     float *so = sm + WK * WM * RB * 32;                               // [WM][RB*ND*16 + RB][64]
     constexpr int OSTRIDE = (RB * ND * 16 + RB) * 64;
@@ -863,40 +950,45 @@ __global__ void __launch_bounds__(WM *WK * 64, DUO ? 2 : 1) attn_kernel(const At
   // ---- write (normalised) result: final when there is one split, else the partial ----
   // The accumulators hold O^T (lane = row, registers = 16 scattered d per 32-wide block); each
   // wave transposes one 32-row block at a time through its own LDS patch so that global stores
-  // are whole contiguous rows.
+  // are whole contiguous rows (of the half of the head dimension the wave holds, when paired).
   const bool final_out = (p.n_chunks == 1);
   float *obase = final_out ? p.out : p.part_out + (size_t)chunk * p.sum_T * p.Hq * D;
   float *lbase = final_out ? p.lse : p.part_lse + (size_t)chunk * p.sum_T * p.Hq;
-  constexpr int TP = D + 4;         // patch row pitch in floats: 16 rows x 16 B apart in bank position
-  constexpr int LPR = D / 4;        // lanes that cover one row with 16 bytes each
+  constexpr int NDW = C::NDW;       // 32-wide d blocks this wave writes
+  constexpr int TP = C::TP;         // patch row pitch in floats: 16 rows x 16 B apart in bank position
+  constexpr int LPR = NDW * 8;      // lanes that cover one row piece with 16 bytes each
   constexpr int RPP = 64 / LPR;     // rows per wave-wide store
-  static_assert(C::SMEM >= WM * 32 * TP * 4, "transpose patches fit in the ring");
-  float *tbuf = reinterpret_cast<float *>(smem) + wm * (32 * TP);
+  float *tbuf = reinterpret_cast<float *>(smem + C::PATCH_OFF) + (PAIR ? wave : wm) * (32 * TP);
+  auto write_out = [&](auto d0_tag) __attribute__((always_inline)) {
+    constexpr int d0 = decltype(d0_tag)::value;  // first d block of this wave's share
 #pragma unroll
-  for (int r = 0; r < RB; ++r) {
-    const float inv = l_tot[r] > 0.f ? 1.f / l_tot[r] : 0.f;
+    for (int r = 0; r < RB; ++r) {
+      const float inv = l_tot[r] > 0.f ? 1.f / l_tot[r] : 0.f;
 #pragma unroll
-    for (int d = 0; d < ND; ++d)
+      for (int d = 0; d < NDW; ++d)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        f32x4 v;
+        for (int i4 = 0; i4 < 4; ++i4) {
+          f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = oacc[r][d][i4 * 4 + e] * inv;
-        *reinterpret_cast<f32x4 *>(tbuf + l32 * TP + 32 * d + 8 * i4 + 4 * hh) = v;
+          for (int e = 0; e < 4; ++e) v[e] = oacc[r][d0 + d][i4 * 4 + e] * inv;
+          *reinterpret_cast<f32x4 *>(tbuf + l32 * TP + 32 * d + 8 * i4 + 4 * hh) = v;
+        }
+      const int row0 = rblk * BM + (wm * RB + r) * 32;
+#pragma unroll
+      for (int i = 0; i < 32 / RPP; ++i) {
+        const int rl = i * RPP + lane / LPR;
+        const int row = row0 + rl;
+        const int t = p.g_shift >= 0 ? (row >> p.g_shift) : row / p.G;
+        const int64_t og = (int64_t)(t0 + t) * p.Hq + kvh * p.G + (row - t * p.G);
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(tbuf + rl * TP + (lane % LPR) * 4);
+        if (row < R) *reinterpret_cast<f32x4 *>(obase + og * D + 32 * d0 + (lane % LPR) * 4) = v;
       }
-    const int row0 = rblk * BM + (wm * RB + r) * 32;
-#pragma unroll
-    for (int i = 0; i < 32 / RPP; ++i) {
-      const int rl = i * RPP + lane / LPR;
-      const int row = row0 + rl;
-      const int t = p.g_shift >= 0 ? (row >> p.g_shift) : row / p.G;
-      const int64_t og = (int64_t)(t0 + t) * p.Hq + kvh * p.G + (row - t * p.G);
-      const f32x4 v = *reinterpret_cast<const f32x4 *>(tbuf + rl * TP + (lane % LPR) * 4);
-      if (row < R) *reinterpret_cast<f32x4 *>(obase + og * D + (lane % LPR) * 4) = v;
+      if (rvalid[r] && hh == 0 && wk == 0)
+        lbase[orow[r]] = l_tot[r] > 0.f ? (m_run[r] + __builtin_amdgcn_logf(l_tot[r])) * kLn2 : -INFINITY;
     }
-    if (rvalid[r] && hh == 0)
-      lbase[orow[r]] = l_tot[r] > 0.f ? (m_run[r] + __builtin_amdgcn_logf(l_tot[r])) * kLn2 : -INFINITY;
-  }
+  };
+  if (PAIR && wk == 1) write_out(std::integral_constant<int, PAIR ? ND / 2 : 0>{});
+  else write_out(std::integral_constant<int, 0>{});
   TVA_STAMP(5);
   TVA_PHASE_DUMP;
 }
@@ -958,7 +1050,7 @@ struct Plan {
   int n_row_blocks, n_chunks, chunk_keys;
 };
 
-enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5, V_K2 = 6, V_K2R2 = 7, V_M2K2 = 8, V_W4D = 9 };
+enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5, V_K2 = 6, V_K2R2 = 7, V_M2K2 = 8, V_W4D = 9, V_M2K2_3 = 10, V_M2K2_4 = 11 };
 
 bool make_plan(const tva_args *a, Plan *pl) {
   if (!a || a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv) return false;
@@ -975,10 +1067,10 @@ bool make_plan(const tva_args *a, Plan *pl) {
   // benchmarking aid: TVA_FORCE_VARIANT=0..9 picks the workgroup shape
   if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
     const int v = atoi(fv);
-    if (v >= V_R256 && v <= V_W4D) variant = v;
+    if (v >= V_R256 && v <= V_M2K2_4) variant = v;
   }
   pl->variant = variant;
-  pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4 || variant == V_W4D) ? 128 : (variant == V_R64 || variant == V_K2R2 || variant == V_M2K2) ? 64 : 32;
+  pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4 || variant == V_W4D) ? 128 : (variant == V_R64 || variant == V_M2K2 || variant == V_M2K2_3 || variant == V_M2K2_4) ? 64 : 32;
   pl->TK = (variant == V_R64 || variant == V_R32) ? 128 : (variant == V_W8 ? 32 * TVA_W8_KBW : 64);
   pl->n_row_blocks = rows > 0 ? (rows + pl->BM - 1) / pl->BM : 1;
   int S = a->num_splits;
@@ -1002,11 +1094,11 @@ bool make_plan(const tva_args *a, Plan *pl) {
 
 typedef void (*attn_fn)(const AttnParams);
 
-template <int D, int WM, int WK, int RB, bool PAGED, bool DUO = false>
+template <int D, int WM, int WK, int RB, bool PAGED, int NST = 0>
 hipError_t launch_attn(const AttnParams &p, dim3 grid, hipStream_t st) {
-  using C = AttnCfg<D, WM, WK, RB, PAGED, DUO>;
+  using C = AttnCfg<D, WM, WK, RB, PAGED, NST>;
   static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent
-  auto kfn = attn_kernel<D, WM, WK, RB, PAGED, DUO>;
+  auto kfn = attn_kernel<D, WM, WK, RB, PAGED, NST>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kfn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
@@ -1025,10 +1117,12 @@ hipError_t dispatch_variant(int variant, const AttnParams &p, dim3 grid, hipStre
     case V_R64: return launch_attn<D, 1, 4, 2, PAGED>(p, grid, st);
     case V_W8: return launch_attn<D, 8, 1, 1, PAGED>(p, grid, st);
     case V_W4: return launch_attn<D, 4, 1, 1, PAGED>(p, grid, st);
-    case V_K2: return launch_attn<D, 1, 2, 1, PAGED, true>(p, grid, st);
-    case V_K2R2: return launch_attn<D, 1, 2, 2, PAGED, true>(p, grid, st);
-    case V_M2K2: return launch_attn<D, 2, 2, 1, PAGED, true>(p, grid, st);
-    case V_W4D: return launch_attn<D, 4, 1, 1, PAGED, true>(p, grid, st);
+    case V_K2: return launch_attn<D, 1, 2, 1, PAGED, 2>(p, grid, st);
+    case V_K2R2: return launch_attn<D, 1, 2, 1, PAGED, 4>(p, grid, st);   // (slot reused: deep 2-wave shape)
+    case V_M2K2: return launch_attn<D, 2, 2, 1, PAGED, 2>(p, grid, st);
+    case V_W4D: return launch_attn<D, 4, 1, 1, PAGED, 2>(p, grid, st);
+    case V_M2K2_3: return launch_attn<D, 2, 2, 1, PAGED, 3>(p, grid, st);
+    case V_M2K2_4: return launch_attn<D, 2, 2, 1, PAGED, 4>(p, grid, st);
     default: return launch_attn<D, 1, 4, 1, PAGED>(p, grid, st);
   }
 }
