@@ -191,15 +191,22 @@ struct AttnCfg {
   static constexpr int PATCH_OFF = PAIR ? MERGE_BYTES : 0;
   static constexpr int PATCH_BYTES = (PAIR ? NW : WM) * 32 * TP * 4;
   static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
+  // paged cache: table entries of the next two tiles, fetched by the same LDS-writing loads as the
+  // tiles themselves: [2 slots][wave][load instruction of a tile][lane], behind the ring
+  static constexpr int NPG = PAGED ? NLDK : 0;   // table-entry loads per wave and tile
+  static constexpr int TILE_OPS = NLD + NPG;     // this wave's memory operations per tile
+  static constexpr int PG_SLOT = NW * NLDK * 256;
+  static constexpr int PG_BYTES = PAGED ? 2 * PG_SLOT : 0;
   static constexpr int TAIL_BYTES = PAIR ? MERGE_BYTES + PATCH_BYTES : (MERGE_BYTES > PATCH_BYTES ? MERGE_BYTES : PATCH_BYTES);
-  static constexpr int SMEM = RING_BYTES > TAIL_BYTES ? RING_BYTES : TAIL_BYTES;
+  static constexpr int SMEM = RING_BYTES + PG_BYTES > TAIL_BYTES ? RING_BYTES + PG_BYTES : TAIL_BYTES;
   static_assert(SMEM * WG_PER_CU <= 160 * 1024, "LDS of the workgroups that share a CU");
-  static_assert(PD <= 3 && NLD * PD < 64, "the wait counter holds 6 bits");
+  static_assert(PD <= 3 && TILE_OPS * (PD > 1 ? PD - 1 : 1) < 64, "the wait counter holds 6 bits");
   static_assert(TK % (RPI * NW) == 0, "tile must divide evenly over the waves");
   static_assert(BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
 };
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+constexpr int vm_cap(int n) { return n > 63 ? 63 : n; }  // the counter holds 6 bits; waiting for less is safe
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | (((n >> 4) & 3) << 14); }
 
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -255,10 +262,13 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   const int chunk = (int)blockIdx.z - b * p.n_chunks;
 
   // every per-sequence scalar is requested before the first one is needed
-  int t0 = p.cu_T[b];
-  int t1 = p.cu_T[b + 1];
-  int Lb0 = p.L[b];
-  int cuL = PAGED ? 0 : p.cu_L[b];
+  // (read through the constant address space: none of these arrays changes while the kernel
+  // runs, and saying so keeps the loads scalar wherever they sit)
+  typedef const __attribute__((address_space(4))) int32_t const_i32;
+  int t0 = ((const_i32 *)(uintptr_t)p.cu_T)[b];
+  int t1 = ((const_i32 *)(uintptr_t)p.cu_T)[b + 1];
+  int Lb0 = ((const_i32 *)(uintptr_t)p.L)[b];
+  int cuL = PAGED ? 0 : ((const_i32 *)(uintptr_t)p.cu_L)[b];
   // (an empty statement that ties them together: keeps the compiler from moving one of the loads
   // down to its first use, where the wave would wait for it alone)
   asm("" : "+s"(t0), "+s"(t1), "+s"(Lb0), "+s"(cuL));
@@ -337,31 +347,28 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   // valid row (finite data; their scores are masked to -inf), so LDS never holds stale values.
   const int lsub = lane / DC, lpos = lane % DC;
   const int64_t cache_base = PAGED ? 0 : (int64_t)cuL * p.stride_tok + (int64_t)kvh * p.stride_head;
-  // paged cache: page numbers of the rows this wave loads for one cache tile (wave-uniform, hence
-  // scalar loads), fetched one tile ahead of their use so that issuing a tile never waits on them
-  int pages[NLDK][RPI];
-  // (read through the constant address space: the table does not change while the kernel runs,
-  // and saying so keeps these loads scalar although LDS-writing loads sit between them)
-  typedef const __attribute__((address_space(4))) int32_t const_i32;
-  const_i32 *const ptab = PAGED ? (const_i32 *)(uintptr_t)(p.page_table + (int64_t)b * p.max_pages) : nullptr;
-  auto load_pages = [&](int t) __attribute__((always_inline)) {
+  // paged cache: each lane needs the page of the row it loads, one table entry per load
+  // instruction of a cache tile.  The entries of tile t + 2 are requested right after the loads of
+  // tile t have been queued, by LDS-writing loads like the tiles' own, into one of two slots; the
+  // wave's memory operations then come in a fixed order and number per tile (every tile, also a
+  // tree tile or the last ones, is followed by a request: past the end it re-reads the entry of the
+  // last key), which is what the counted waits below rely on.
+  lds_byte *const pg_lds = lds + C::RING_BYTES + wave * (NLDK * 256);
+  auto request_pages = [&](int t) __attribute__((always_inline)) {
     if (!PAGED) return;
     const int base = k0 + t * TK;
 #pragma unroll
     for (int j = 0; j < NLDK; ++j) {
       const int n = wave * NLDK + j;
       const int blk = n / IPB, part = n % IPB;
-#pragma unroll
-      for (int u = 0; u < RPI; ++u) {
-        int key = base + blk + NBLK * (part * RPI + u);
-        key = key < k1 ? key : k1 - 1;
-        key = key < 0 ? 0 : key;
-        const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
-        pages[j][u] = ptab[pidx];
-      }
+      int key = base + blk + NBLK * (part * RPI + lsub);
+      key = key < k1 ? key : k1 - 1;
+      key = key < 0 ? 0 : key;
+      const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
+      const int32_t *src = p.page_table + (int64_t)b * p.max_pages + pidx;
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), pg_lds + (t & 1) * C::PG_SLOT + j * 256, 4, 0, 0);
     }
   };
-  if (PAGED && n_ct > 0) load_pages(0);
   // full tiles of a dense cache: a wave-uniform row pointer plus one tile-independent lane offset
   const uint32_t lane_off = (uint32_t)(NBLK * lsub) * (uint32_t)p.stride_tok * 2u + (uint32_t)lpos * 16u;
   auto issue_impl = [&](int t, auto tree_tag) __attribute__((always_inline)) {
@@ -393,18 +400,12 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
         ksrc = p.k_tree + off;
         vsrc = p.v_tree + off;
       } else if (PAGED) {
-        // the page of each row of this instruction was read (scalar loads) when the previous tile
-        // was issued; each lane keeps its own row's
-        int64_t off = 0;
-#pragma unroll
-        for (int u = 0; u < RPI; ++u) {
-          int key = base + blk + NBLK * (part * RPI + u);
-          key = key < limit ? key : limit - 1;
-          const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
-          const int64_t o = (int64_t)pages[j][u] * p.stride_page + (int64_t)(key - pidx * p.page_size) * p.stride_tok;
-          off = (lsub == u) ? o : off;
-        }
-        off += (int64_t)kvh * p.stride_head + lpos * 8;
+        int key = base + blk + NBLK * (part * RPI + lsub);
+        key = key < limit ? key : limit - 1;
+        const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
+        const int page = *reinterpret_cast<const __attribute__((address_space(3))) int *>(pg_lds + (t & 1) * C::PG_SLOT + j * 256 + lane * 4);
+        const int64_t off = (int64_t)page * p.stride_page + (int64_t)(key - pidx * p.page_size) * p.stride_tok +
+                            (int64_t)kvh * p.stride_head + lpos * 8;
         ksrc = p.k_cache + off;
         vsrc = p.v_cache + off;
       } else {
@@ -424,12 +425,9 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
 #ifdef TVA_EXP_NOLOAD
     if (t >= 0) return;
 #endif
-    if (t >= n_ct) {
-      issue_impl(t, std::true_type{});
-    } else {
-      issue_impl(t, std::false_type{});
-      if (PAGED && t + 1 < n_ct) load_pages(t + 1);  // tiles are issued in order: t + 1 comes next
-    }
+    if (t >= n_ct) issue_impl(t, std::true_type{});
+    else issue_impl(t, std::false_type{});
+    request_pages(t + 2);
   };
 
   // per-lane LDS read bases (row r of a tile: block r % NBLK, sub-row r / NBLK)
@@ -584,6 +582,24 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     }
   };
 
+  // ---- wait until this wave's loads of tile `it` (and, paged, the table entries the tile queued
+  // next needs) have landed: all but the operations queued after them are complete ----
+  auto wait_tile = [&](int it) __attribute__((always_inline)) {
+    constexpr int OPS = C::TILE_OPS;
+    const int later = n_tiles - 1 - it;  // tiles after `it` whose loads are already queued: min(later, PD - 1)
+    if constexpr (PAGED) {
+      // queued after the loads of tile `it`: entries(it+2), then per later tile its loads and the
+      // entries two tiles on.  entries(it+PD) are needed next, so at most one later tile may stay.
+      if (PD >= 2 && later >= 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(OPS));
+      else if (PD == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::NPG));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    } else {
+      if (PD >= 3 && later >= 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 2));
+      else if (PD >= 2 && later >= 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 1));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
+  };
+
   // ---- software-pipelined path for runs of full (unmasked) tiles ----
   // One wave has a single instruction stream per SIMD, so the matrix pipe and the vector ALU only
   // overlap if independent MFMA and VALU work alternates in program order.  Each pass of
@@ -598,8 +614,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   };
 
   auto tile_enter = [&](int t) __attribute__((always_inline)) {
-    if (PD >= 2 && t + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * (PD - 1)));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    wait_tile(t);
     __builtin_amdgcn_s_barrier();
     if (t + PD < n_tiles) issue_tile(t + PD);
   };
@@ -761,11 +776,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   // ---- one pipeline step: wait for tile `it`, refill the stage tile it-1 used, compute ----
   auto step = [&](int it, auto masked_tag, auto tree_tag) __attribute__((always_inline)) {
     // this wave's loads of tile `it` have landed once at most the later tiles' loads are outstanding
-    const int later = n_tiles - 1 - it;  // tiles after `it` whose loads are already queued: min(later, PD - 1)
-    if (PD >= 4 && later >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 3));
-    else if (PD >= 3 && later >= 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 2));
-    else if (PD >= 2 && later >= 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 1));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    wait_tile(it);
     TVA_PHASE(5);
     __builtin_amdgcn_s_barrier();  // everyone's part of tile `it` is in LDS; everyone is done with tile it-1
     TVA_PHASE(6);
@@ -791,17 +802,28 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   };
 
   TVA_STAMP(1);
+  request_pages(0);
+  request_pages(1);
 #pragma unroll
   for (int t = 0; t < PD; ++t)
-    if (t < n_tiles) issue_tile(t);
+    if (t < n_tiles) {
+      if constexpr (PAGED) {
+        // entries(t) have landed once only what was queued after them is outstanding
+        if (t == 0) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::NPG));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::TILE_OPS));
+        asm volatile("" ::: "memory");  // the entries are read from LDS below this line, not above
+      }
+      issue_tile(t);
+    }
   // Q and the mask rows were requested before the tiles; they have arrived once no more than the
   // tiles' own loads are outstanding.  Said here, once, so that no wait for them (which would
   // also drain the prefetched tiles) is needed inside the key loop.
   {
+    constexpr int OPS = C::TILE_OPS, PRE = 2 * C::NPG;
     const int n_pre = n_tiles < PD ? n_tiles : PD;
-    if (PD >= 3 && n_pre >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 3));
-    else if (PD >= 2 && n_pre == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 2));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD));
+    if (PD >= 3 && n_pre >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(vm_cap(PRE + OPS * 3)));
+    else if (PD >= 2 && n_pre == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(vm_cap(PRE + OPS * 2)));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(vm_cap(PRE + OPS)));
   }
   TVA_STAMP(2);
   int it = 0;
@@ -830,6 +852,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   for (; it < n_ct; ++it) step(it, std::true_type{}, std::false_type{});   // the partial cache tile
   for (; it < n_tiles; ++it) step(it, std::true_type{}, std::true_type{});  // the tree's own keys
   TVA_STAMP(4);
+  if constexpr (PAGED) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the last (unused) table entries have landed
   __builtin_amdgcn_s_barrier();  // all waves are done reading the ring before it is reused below
 
   // ---- combine the two lane halves' partial sums ----
