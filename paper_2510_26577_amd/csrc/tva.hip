@@ -242,8 +242,14 @@ __device__ long long tva_dbg[64];
 
 template <int D, int WM, int WK, int RB, bool PAGED, int NST>
 __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
-    attn_kernel(const AttnParams p) {
+    attn_kernel(const AttnParams p_in) {
   using C = AttnCfg<D, WM, WK, RB, PAGED, NST>;
+  // The arguments the prologue needs, tied together by an empty statement so that they are fetched
+  // in one batch at the top rather than one by one, each with its own wait, at their first uses.
+  AttnParams p = p_in;
+  asm("" : "+s"(p.cu_T), "+s"(p.L), "+s"(p.cu_L), "+s"(p.q), "+s"(p.k_cache), "+s"(p.v_cache), "+s"(p.mask),
+      "+s"(p.stride_tok), "+s"(p.stride_head), "+s"(p.G), "+s"(p.g_shift), "+s"(p.Hq), "+s"(p.chunk_keys),
+      "+s"(p.n_chunks), "+s"(p.max_L));
   constexpr int TK = C::TK, BM = C::BM, DC = C::DC, ROWB = C::ROWB, RPI = C::RPI, NLDK = C::NLDK, NLD = C::NLD;
   constexpr int KBW = C::KBW, NSTAGE = C::NSTAGE, PD = C::PD, STAGE_BYTES = C::STAGE_BYTES;
   constexpr int NBLK = C::NBLK, IPB = C::IPB, PK = C::PK, PV = C::PV, KTILE = C::KTILE;
@@ -317,14 +323,15 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     const __bf16 *qp = p.q + orow[r] * D + 8 * hh;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      qreg[r][s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+      qreg[r][s] = *(const __attribute__((address_space(1))) bf16x8 *)(uintptr_t)(qp + 16 * s);
     }
     // mask rows are only requested here (rows past the end read their stand-in's); the first use
     // is in the tree tiles, so nothing waits for them before the key loads have been queued
     mrow[r][0] = mrow[r][1] = 0;
     if (has_tree) {
-      mrow[r][0] = p.mask[(size_t)(t0 + t) * p.W];
-      if (p.W > 1) mrow[r][1] = p.mask[(size_t)(t0 + t) * p.W + 1];
+      const auto *mp = (const __attribute__((address_space(1))) uint64_t *)(uintptr_t)(p.mask + (size_t)(t0 + t) * p.W);
+      mrow[r][0] = mp[0];
+      if (p.W > 1) mrow[r][1] = mp[1];
     }
   }
 
