@@ -172,13 +172,13 @@ struct AttnCfg {
   static constexpr int PV = BLKB + 32;           // block pitch of the V tile
   static constexpr int KTILE = NBLK * PK, VTILE = NBLK * PV;
   static constexpr int STAGE_BYTES = (KTILE + VTILE + 1023) / 1024 * 1024;
-  // TK = 64: four stages, two tiles in flight, and the software-pipelined loop (which still reads
-  // the V operands of tile t-1 after tile t has been entered, hence one stage more than PD + 1).
-  // TK = 128: two stages, one tile in flight, plain loop.
-  // NST = stages of the ring (0: the shape's default).  Two stages keep the footprint small
-  // enough for two workgroups per CU; more stages put more tiles in flight for one workgroup.
+  // NST = stages of the ring, 0 for the shape's default: four for the software-pipelined loop
+  // (two tiles in flight; it still reads the V operands of tile t-1 after tile t has been entered,
+  // hence one stage more than tiles in flight + 1) and for the eight-wave shape (three in flight:
+  // its LDS footprint is set by the output patches anyway), else three (TK = 64) or two (TK = 128).
+  // Two stages keep the footprint small enough for two workgroups per CU.
   static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4) && (NST == 0);
-  static constexpr int NSTAGE = NST ? NST : FAST ? 4 : (TK == 64 ? 3 : 2);
+  static constexpr int NSTAGE = NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
   static constexpr int PD = FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed
   static constexpr int WG_PER_CU = (NSTAGE == 2 && TK == 64) ? 2 : 1;
   // after the key loop the ring is reused: exchange area of the key-group merge, then (behind it,
@@ -811,9 +811,13 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   TVA_STAMP(1);
   request_pages(0);
   request_pages(1);
+  // The first PD tiles (fewer if the chunk has fewer).  Q and the mask rows were requested before
+  // them and have arrived once no more than the tiles' own operations are outstanding; that wait
+  // sits in the same branch as the loads it counts, so that the number is plainly a constant.
+  auto issue_first = [&](auto n_tag) __attribute__((always_inline)) {
+    constexpr int n = decltype(n_tag)::value;
 #pragma unroll
-  for (int t = 0; t < PD; ++t)
-    if (t < n_tiles) {
+    for (int t = 0; t < n; ++t) {
       if constexpr (PAGED) {
         // entries(t) have landed once only what was queued after them is outstanding
         if (t == 0) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::NPG));
@@ -822,16 +826,11 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
       }
       issue_tile(t);
     }
-  // Q and the mask rows were requested before the tiles; they have arrived once no more than the
-  // tiles' own loads are outstanding.  Said here, once, so that no wait for them (which would
-  // also drain the prefetched tiles) is needed inside the key loop.
-  {
-    constexpr int OPS = C::TILE_OPS, PRE = 2 * C::NPG;
-    const int n_pre = n_tiles < PD ? n_tiles : PD;
-    if (PD >= 3 && n_pre >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(vm_cap(PRE + OPS * 3)));
-    else if (PD >= 2 && n_pre == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(vm_cap(PRE + OPS * 2)));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(vm_cap(PRE + OPS)));
-  }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(vm_cap(2 * C::NPG + C::TILE_OPS * n)));
+  };
+  if (PD >= 3 && n_tiles >= 3) issue_first(std::integral_constant<int, PD >= 3 ? 3 : 1>{});
+  else if (PD >= 2 && n_tiles >= 2) issue_first(std::integral_constant<int, PD >= 2 ? 2 : 1>{});
+  else issue_first(std::integral_constant<int, 1>{});
   TVA_STAMP(2);
   int it = 0;
   if (C::FAST && n_full > 0) {
