@@ -169,7 +169,10 @@ struct AttnCfg {
   static constexpr int BLKB = SUBS * ROWB;       // 1 KiB (TK=64) or 2 KiB (TK=128)
   static constexpr int IPB = BLKB / 1024;        // load instructions per block
   static constexpr int PK = BLKB + 16;           // block pitch of the K tile
-  static constexpr int PV = BLKB + 32;           // block pitch of the V tile
+#ifndef TVA_PV_PAD
+#define TVA_PV_PAD 32
+#endif
+  static constexpr int PV = BLKB + TVA_PV_PAD;   // block pitch of the V tile
   static constexpr int KTILE = NBLK * PK, VTILE = NBLK * PV;
   static constexpr int STAGE_BYTES = (KTILE + VTILE + 1023) / 1024 * 1024;
   // NST = stages of the ring, 0 for the shape's default: four for the software-pipelined loop
