@@ -132,6 +132,20 @@ def test_split_counts_ragged(gpu, splits):
     check_full(gpu, w, num_splits=splits, label=f"splits={splits}")
 
 
+@pytest.mark.parametrize("variant", list(range(12)))
+def test_every_workgroup_shape(gpu, variant, monkeypatch):
+    """The launch plan picks three of the kernel's workgroup shapes; the others (64-row-per-wave shapes,
+    four-wave shapes, deeper rings) stay selectable through TVA_FORCE_VARIANT and must agree with the
+    oracle too: dense with several splits and ragged tails, paged, and head dimension 64."""
+    monkeypatch.setenv("TVA_FORCE_VARIANT", str(variant))
+    check_full(gpu, wl.random_workload(700 + variant, 3, 8, 2, 128, [900, 130, 0], [70, 33, 8], max_depth=10),
+               num_splits=3, label=f"shape {variant} dense")
+    check_full(gpu, wl.random_workload(720 + variant, 2, 8, 2, 128, [517, 64], [40, 64], page_size=16),
+               label=f"shape {variant} paged")
+    check_full(gpu, wl.random_workload(740 + variant, 2, 8, 4, 64, [300, 77], [60, 9]),
+               num_splits=2, label=f"shape {variant} D=64")
+
+
 def test_empty_trees_in_batch_and_chain_and_star(gpu):
     rng = np.random.Generator(np.random.PCG64(500))
     trees = [wl.tree_chain(13), np.zeros(0, np.int32), wl.tree_star(30), wl.tree_chain(1)]
