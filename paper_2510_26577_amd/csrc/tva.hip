@@ -309,6 +309,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   const int wm = wave % WM, wk = wave / WM;
   const int l32 = lane & 31, hh = lane >> 5;
 
+  const bool wave_has_rows = rblk * BM + wm * RB * 32 < R;  // wave-uniform
   // ---- Q operands (B operand of S^T = K Q^T: lane = query row, 8 consecutive d per k-step) ----
   bf16x8 qreg[RB][NS];
   uint64_t mrow[RB][2];
@@ -800,7 +801,9 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     if (threadIdx.x > 100000)
 #endif
     {
-    // wave-uniform: a block is skipped when none of its keys exists
+    // wave-uniform: a block is skipped when none of its keys exists, and all of them by a wave
+    // none of whose query rows exists (it still loads its share of every tile)
+    if (!wave_has_rows) return;
     if (base + wk * KBW * 32 < limit) compute_block(stage, std::integral_constant<int, 0>{}, base, limit, tree, masked_tag);
     if constexpr (KBW > 1)
       if (base + (wk * KBW + 1) * 32 < limit) compute_block(stage, std::integral_constant<int, 1>{}, base, limit, tree, masked_tag);
@@ -836,7 +839,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   else issue_first(std::integral_constant<int, 1>{});
   TVA_STAMP(2);
   int it = 0;
-  if (C::FAST && n_full > 0) {
+  if (C::FAST && n_full > 0 && wave_has_rows) {
     using kb0 = std::integral_constant<int, 0>;
     using kb1 = std::integral_constant<int, KBW - 1>;
     Scores sc;
