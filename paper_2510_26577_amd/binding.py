@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libtva.so")
 SRC_PATH = os.path.join(_HERE, "csrc", "tva.hip")
+CAST_SRC_PATH = os.path.join(_HERE, "csrc", "cast.cpp")  # host part: tree-size selection
 INCLUDE_DIR = os.path.join(_ROOT, "include")
 
 TVA_OK = 0
@@ -27,9 +28,10 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile csrc/tva.hip for gfx950 into libtva.so (in-tree)."""
+    """Compile csrc/tva.hip (gfx950 kernels + their C ABI) and csrc/cast.cpp (host logic) into
+    libtva.so (in-tree)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-shared", "-fPIC", "-o", LIB_PATH, SRC_PATH]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-shared", "-fPIC", "-o", LIB_PATH, SRC_PATH, CAST_SRC_PATH]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     lines = [l for l in res.stdout.splitlines() if "is not a recognized feature" not in l]
     if verbose or res.returncode:
@@ -60,6 +62,11 @@ class TvaArgs(ctypes.Structure):
 
 EXPORTS = ("tva_build_ancestor_mask", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys",
            "tva_tree_verify_attn", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
+# host entry points of include/tva_cast.h (bound in cast.py)
+CAST_EXPORTS = ("tva_cast_select_context", "tva_cast_select_max_valid_index", "tva_cast_layer_utility",
+                "tva_cast_layer_cost", "tva_cast_breadth_prune", "tva_cast_depth_bytes", "tva_cast_depth_init",
+                "tva_cast_depth_alpha", "tva_cast_depth_should_expand", "tva_cast_depth_update",
+                "tva_cast_expansion_plan", "tva_cast_rerank_count", "tva_cast_select_subtree")
 
 _lib = None
 

@@ -19,8 +19,8 @@ def lib():
     return binding.load_library()
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "tva.h")).read()
+def declared_symbols(header="tva.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(tva_[a-z_]+)\s*\(", text)))
 
@@ -28,6 +28,13 @@ def declared_symbols():
 def test_exports_match_header(lib):
     syms = declared_symbols()
     assert set(syms) == set(binding.EXPORTS)
+    for s in syms:
+        assert getattr(lib, s) is not None
+
+
+def test_host_exports_match_header(lib):
+    syms = declared_symbols("tva_cast.h")
+    assert set(syms) == set(binding.CAST_EXPORTS)
     for s in syms:
         assert getattr(lib, s) is not None
 
