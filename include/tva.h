@@ -38,7 +38,9 @@ typedef enum {
   TVA_INVALID_ARG = -1,         /* null pointer, bad sizes, both / neither cache form */
   TVA_UNSUPPORTED = -2,         /* D not in {64,128}, max_T > 128, ... */
   TVA_WORKSPACE_TOO_SMALL = -3, /* see tva_workspace_bytes() */
-  TVA_HIP_ERROR = -4            /* a launch failed; hipGetLastError has details */
+  TVA_HIP_ERROR = -4            /* a launch failed: the error is left for hipGetLastError (an older
+                                   error of the process is cleared before each launch, so the status
+                                   is this launch's); TVA_VERBOSE=1 in the environment names it on stderr */
 } tva_status;
 
 #define TVA_MAX_TREE 128 /* nodes per tree supported by the attention kernels (2 mask words) */

@@ -78,6 +78,9 @@ def load_library():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    # torch first: it brings the HIP runtime the process shares.  Loaded the other way round, libtva.so
+    # pulls in the system's copy, torch then loads its own, and the second one finds no device.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     lib.tva_version.restype = ctypes.c_int
     lib.tva_strerror.restype = ctypes.c_char_p

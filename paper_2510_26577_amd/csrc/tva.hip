@@ -21,6 +21,7 @@
 // KV head, so that the workgroup still has four waves streaming keys).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 
 #include <type_traits>
@@ -1129,6 +1130,16 @@ bool make_plan(const tva_args *a, Plan *pl) {
 
 typedef void (*attn_fn)(const AttnParams);
 
+// Launch status.  An error some earlier HIP call of the process left behind is cleared before a
+// launch, so that the status reflects this launch only; a failure is left in place (peeked, not
+// consumed) for the caller's hipGetLastError, and named on stderr when TVA_VERBOSE is set.
+inline void clear_stale_hip_error() { (void)hipGetLastError(); }
+inline hipError_t launch_status(const char *what) {
+  const hipError_t e = hipPeekAtLastError();
+  if (e != hipSuccess && getenv("TVA_VERBOSE")) fprintf(stderr, "libtva: %s: %s\n", what, hipGetErrorString(e));
+  return e;
+}
+
 template <int D, int WM, int WK, int RB, bool PAGED, int NST = 0>
 hipError_t launch_attn(const AttnParams &p, dim3 grid, hipStream_t st) {
   using C = AttnCfg<D, WM, WK, RB, PAGED, NST>;
@@ -1140,8 +1151,9 @@ hipError_t launch_attn(const AttnParams &p, dim3 grid, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
+  clear_stale_hip_error();
   hipLaunchKernelGGL(kfn, grid, dim3(C::NT), C::SMEM, st, p);
-  return hipGetLastError();
+  return launch_status("attention kernel launch");
 }
 
 template <int D, bool PAGED>
@@ -1194,9 +1206,10 @@ int tva_build_ancestor_mask(const int32_t *parent, const int32_t *cu_T, int32_t 
   if (!parent || !cu_T || !mask) return TVA_INVALID_ARG;
   int threads = ((max_T + 63) / 64) * 64;
   threads = threads < 64 ? 64 : (threads > 256 ? 256 : threads);
+  clear_stale_hip_error();
   hipLaunchKernelGGL(anc_mask_kernel, dim3(B), dim3(threads), 0, (hipStream_t)stream, parent, cu_T, B,
                      mask_words, mask, err_flag);
-  return hipGetLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+  return launch_status("ancestor mask kernel launch") == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 
 static int check_args(const tva_args *a, bool shapes_only) {
@@ -1311,13 +1324,14 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   if (merge && pl.n_chunks > 1) {
     const int64_t n_rows = (int64_t)a->sum_T * a->Hq;
     const int mgrid = (int)((n_rows + 3) / 4);
+    clear_stale_hip_error();
     if (a->D == 128)
       hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, p.part_out, p.part_lse, pl.n_chunks,
                          n_rows, a->out, a->lse);
     else
       hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, p.part_out, p.part_lse, pl.n_chunks,
                          n_rows, a->out, a->lse);
-    if (hipGetLastError() != hipSuccess) return TVA_HIP_ERROR;
+    if (launch_status("merge kernel launch") != hipSuccess) return TVA_HIP_ERROR;
   }
   return TVA_OK;
 }
@@ -1331,11 +1345,12 @@ int tva_merge_splits(const float *part_out, const float *part_lse, int32_t S, in
   if ((n_rows + 3) / 4 > 0x7fffffff) return TVA_UNSUPPORTED;
   const int mgrid = (int)((n_rows + 3) / 4);
   hipStream_t st = (hipStream_t)stream;
+  clear_stale_hip_error();
   if (D == 128)
     hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse);
   else
     hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse);
-  return hipGetLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+  return launch_status("merge kernel launch") == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 
 }  // extern "C"
