@@ -1,8 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the tree-verification attention hot path on one MI355X.
 
-A step = one pass of the whole path (ancestor masks -> split-KV attention ->
-merge) over one batch of seeded synthetic input already resident in HBM.  The
+A step = one pass of the whole path (ancestor sets -> split-KV attention ->
+merge) over one batch of seeded synthetic input already resident in HBM, made
+as one library call: the trees' parent arrays are passed and the attention
+kernel derives each node's ancestor set itself.  The same pass as two calls
+(ancestor-mask kernel, then attention on the masks -- what a many-layer model
+does once per decode step and once per layer) is timed beside it and reported
+as `ms_per_step_two_calls`.  The
 default workload is the Llama-3-8B-shaped layer (B=1, Hq=32, Hkv=8, D=128,
 L=2048, T=60).  Steps cycle through `rotate` distinct copies of the inputs whose
 total size exceeds the last-level cache, and are replayed from one HIP graph so
@@ -100,18 +105,33 @@ def main():
                                  cu_L=dw.cu_L, page_table=dw.page_table, page_size=w.page_size,
                                  strides=strides, num_splits=a.splits, out=o, lse=l)
         argv.append(args)
+    # the same calls with the parent arrays in place of ancestor masks (the kernel derives the masks)
+    argv_parent = []
+    for dw, o, l in zip(sets, outs, lses):
+        argv_parent.append(binding.make_args(
+            q=dw.q, k_tree=dw.k_tree, v_tree=dw.v_tree, k_cache=dw.k_cache, v_cache=dw.v_cache, anc_mask=None,
+            parent=dw.parent, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale, cu_L=dw.cu_L,
+            page_table=dw.page_table, page_size=w.page_size, strides=strides, num_splits=a.splits, out=o, lse=l))
     n_splits = binding.plan_splits(argv[0])
     ws_bytes = binding.workspace_bytes(argv[0])
     wss = []
-    for args in argv:
+    for args, args_p in zip(argv, argv_parent):
         if ws_bytes:
             ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device="cuda:0")
             wss.append(ws)
             args.workspace, args.workspace_bytes = ws.data_ptr(), ws_bytes
+            args_p.workspace, args_p.workspace_bytes = ws.data_ptr(), ws_bytes
 
     stream = torch.cuda.Stream()   # default priority; all launches and events use this stream
 
-    def step(i, with_mask=True):
+    def step(i):
+        """One pass of the whole path as ONE call: the parent arrays are passed and the attention
+        kernel derives the ancestor sets itself (then the merge of the KV splits)."""
+        binding.tree_verify_attn_raw(argv_parent[i % R], stream=stream)
+
+    def step_two_calls(i, with_mask=True):
+        """The same path as two calls: the ancestor-mask kernel, then attention reading the masks
+        (what a model with many layers does: masks once per decode step, attention per layer)."""
         j = i % R
         if with_mask:
             binding.build_ancestor_mask(sets[j].parent, sets[j].cu_T, w.max_T, mask=masks[j], stream=stream)
@@ -134,8 +154,15 @@ def main():
             for i in range(n):
                 fn(i)
         with torch.cuda.stream(stream):
-            g.replay()            # untimed first replay (graph upload)
-            torch.cuda.synchronize()
+            # untimed replays first (graph upload, then enough work for the clocks to settle under
+            # this load: the first region timed after the host-side set-up otherwise reads ~7 % slow
+            # on the large workloads), then the timed one
+            t_warm = time.perf_counter()
+            while True:
+                g.replay()
+                torch.cuda.synchronize()
+                if time.perf_counter() - t_warm > 0.1:
+                    break
             e0.record(stream)
             g.replay()
             e1.record(stream)
@@ -146,6 +173,7 @@ def main():
     with torch.cuda.stream(stream):
         for i in range(max(a.warmup, R)):
             step(i)
+            step_two_calls(i)
     torch.cuda.synchronize()
 
     # ---- the timed region: exactly K steps of the whole path ----
@@ -156,7 +184,8 @@ def main():
     #      same rotation; the average includes the dispatch gap between back-to-back launches),
     #      and the merge kernel alone the same way ----
     ms_kernel = timed(a.steps, lambda i: binding.tree_verify_attn_splits_raw(argv[i % R], stream=stream)) / a.steps
-    ms_attn_call = timed(a.steps, lambda i: step(i, with_mask=False)) / a.steps
+    ms_attn_call = timed(a.steps, lambda i: step_two_calls(i, with_mask=False)) / a.steps
+    ms_step_two_calls = timed(a.steps, step_two_calls) / a.steps
     ms_merge = 0.0
     if n_splits > 1:
         n_rows = w.sum_T * w.Hq
@@ -226,12 +255,15 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
                    "L": [int(w.L.min()), int(w.L.max())], "T": int(w.max_T), "paged": bool(w.paged),
-                   "kv_splits": n_splits, "rotating_input_copies": R, "launch": "eager" if a.no_graph else "hip-graph"},
+                   "kv_splits": n_splits, "rotating_input_copies": R, "launch": "eager" if a.no_graph else "hip-graph",
+                   "step": "one tva_tree_verify_attn call on parent arrays (ancestor sets derived in the kernel) "
+                           "incl. merge of the KV splits; ms_per_step_two_calls = mask kernel + attention on masks"},
         "tflops": flops / (ms_step * 1e-3) / 1e12,
         "pct_hbm_peak": 100 * value / HBM_PEAK_GBS,
         "pct_mfma_peak": 100 * flops / (ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "kv_bytes_per_step": kv_bytes, "algorithmic_bytes_per_step": alg_bytes, "algorithmic_flops_per_step": flops,
         "max_abs_err_O": err_o, "max_abs_err_LSE": err_l,
+        "ms_per_step_two_calls": ms_step_two_calls,
         "roofline": {"bound": "hbm", "kernel": "attn_kernel (split-KV attention)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel_ms": ms_kernel, "attn_call_ms": ms_attn_call, "merge_ms": ms_merge,

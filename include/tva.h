@@ -81,7 +81,8 @@ typedef struct tva_args {
   const void *k_tree;  /* device bf16 [sum_T, Hkv, D]: keys of the tree tokens */
   const void *v_tree;  /* device bf16 [sum_T, Hkv, D] */
   const uint64_t *anc_mask; /* device [sum_T, mask_words]: bit j of row i set iff node j
-                               is node i or one of its ancestors (tva_build_ancestor_mask) */
+                               is node i or one of its ancestors (tva_build_ancestor_mask);
+                               or NULL, then `parent` below is used */
 
   const void *k_cache, *v_cache; /* device bf16, dense or paged (above) */
   const int32_t *cu_L;           /* device [B+1] or NULL */
@@ -95,6 +96,13 @@ typedef struct tva_args {
   void *workspace;        /* device scratch for the KV splits, may be NULL if 0 bytes */
   size_t workspace_bytes; /* >= tva_workspace_bytes(args) */
   int32_t num_splits;     /* KV splits per sequence; 0 = library chooses */
+
+  const int32_t *parent;  /* device int32 [sum_T] or NULL: local parent index per node (-1 = root,
+                             parent[i] < i), read only when anc_mask is NULL.  The attention kernel
+                             then derives each row's ancestor set itself (same sets as
+                             tva_build_ancestor_mask; no separate launch, nothing written).  A link
+                             that does not point backwards is not reported here: it just ends that
+                             node's walk -- validate with tva_build_ancestor_mask's err_flag. */
 } tva_args;
 
 /*

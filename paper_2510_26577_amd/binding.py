@@ -21,7 +21,7 @@ INCLUDE_DIR = os.path.join(_ROOT, "include")
 
 TVA_OK = 0
 TVA_MAX_TREE = 128
-EXPECTED_VERSION = 1
+EXPECTED_VERSION = 2
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -57,6 +57,7 @@ class TvaArgs(ctypes.Structure):
         ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("num_splits", ctypes.c_int32),
+        ("parent", ctypes.c_void_p),
     ]
 
 
@@ -148,7 +149,7 @@ def build_ancestor_mask(parent, cu_T, max_T: int, mask=None, err_flag=None, stre
 
 def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: int, max_L: int,
               scale: float, cu_L=None, page_table=None, page_size: int = 0, strides=(0, 0, 0),
-              num_splits: int = 0, out=None, lse=None, workspace=None) -> TvaArgs:
+              num_splits: int = 0, out=None, lse=None, workspace=None, parent=None) -> TvaArgs:
     """Fill `tva_args` from tensors (q [sum_T,Hq,D], k_tree [sum_T,Hkv,D], ...)."""
     a = TvaArgs()
     a.B = cu_T.numel() - 1
@@ -168,6 +169,7 @@ def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: 
     a.workspace = _p(workspace)
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     a.num_splits = int(num_splits)
+    a.parent = _p(parent)
     return a
 
 
@@ -204,9 +206,10 @@ def tree_verify_attn_splits_raw(args: TvaArgs, stream=None) -> None:
 
 def tree_verify_attn(q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, *, max_T: int, max_L: int,
                      scale: float, cu_L=None, page_table=None, page_size: int = 0, strides=(0, 0, 0),
-                     num_splits: int = 0, out=None, lse=None, workspace=None, stream=None):
+                     num_splits: int = 0, out=None, lse=None, workspace=None, stream=None, parent=None):
     """Tree-masked verification attention.  Returns (out fp32 [sum_T,Hq,D], lse fp32 [sum_T,Hq]).
-    bf16 tensors may be torch.bfloat16 or int16/uint16 bit patterns."""
+    bf16 tensors may be torch.bfloat16 or int16/uint16 bit patterns.  anc_mask may be None when the
+    trees' parent array (int32 [sum_T]) is passed instead: the kernel then derives the masks itself."""
     import torch
     if out is None:
         out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
@@ -214,7 +217,7 @@ def tree_verify_attn(q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, *, 
         lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
     args = make_args(q=q, k_tree=k_tree, v_tree=v_tree, k_cache=k_cache, v_cache=v_cache, anc_mask=anc_mask,
                      cu_T=cu_T, L=L, max_T=max_T, max_L=max_L, scale=scale, cu_L=cu_L, page_table=page_table,
-                     page_size=page_size, strides=strides, num_splits=num_splits, out=out, lse=lse)
+                     page_size=page_size, strides=strides, num_splits=num_splits, out=out, lse=lse, parent=parent)
     need = workspace_bytes(args)
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty((need + 3) // 4, dtype=torch.float32, device=q.device)

@@ -107,6 +107,7 @@ struct AttnParams {
   const __bf16 *q, *k_tree, *v_tree, *k_cache, *v_cache;
   const int32_t *cu_T, *L, *cu_L, *page_table;
   const uint64_t *mask;
+  const int32_t *parent;  // used when mask is null: ancestor masks are derived in the kernel
   float *out, *lse;            // final results
   float *part_out, *part_lse;  // [S, sum_T, Hq, D], [S, sum_T, Hq] when S > 1
   int B, Hq, Hkv, G, g_shift, sum_T, W;
@@ -201,8 +202,11 @@ struct AttnCfg {
   static constexpr int TILE_OPS = NLD + NPG;     // this wave's memory operations per tile
   static constexpr int PG_SLOT = NW * NLDK * 256;
   static constexpr int PG_BYTES = PAGED ? 2 * PG_SLOT : 0;
+  // parent indices of the sequence's tree (used when no ancestor masks are passed), behind those
+  static constexpr int PARENT_OFF = RING_BYTES + PG_BYTES;
+  static constexpr int PARENT_BYTES = TVA_MAX_TREE * 4;
   static constexpr int TAIL_BYTES = PAIR ? MERGE_BYTES + PATCH_BYTES : (MERGE_BYTES > PATCH_BYTES ? MERGE_BYTES : PATCH_BYTES);
-  static constexpr int SMEM = RING_BYTES + PG_BYTES > TAIL_BYTES ? RING_BYTES + PG_BYTES : TAIL_BYTES;
+  static constexpr int SMEM = PARENT_OFF + PARENT_BYTES > TAIL_BYTES ? PARENT_OFF + PARENT_BYTES : TAIL_BYTES;
   static_assert(SMEM * WG_PER_CU <= 160 * 1024, "LDS of the workgroups that share a CU");
   static_assert(PD <= 3 && TILE_OPS * (PD > 1 ? PD - 1 : 1) < 64, "the wait counter holds 6 bits");
   static_assert(TK % (RPI * NW) == 0, "tile must divide evenly over the waves");
@@ -333,7 +337,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     // mask rows are only requested here (rows past the end read their stand-in's); the first use
     // is in the tree tiles, so nothing waits for them before the key loads have been queued
     mrow[r][0] = mrow[r][1] = 0;
-    if (has_tree) {
+    if (has_tree && p.mask != nullptr) {
       const auto *mp = (const __attribute__((address_space(1))) uint64_t *)(uintptr_t)(p.mask + (size_t)(t0 + t) * p.W);
       mrow[r][0] = mp[0];
       if (p.W > 1) mrow[r][1] = mp[1];
@@ -816,6 +820,14 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   };
 
   TVA_STAMP(1);
+  // No ancestor masks passed: the tree's parent array goes to LDS (by the first two waves, with the
+  // same LDS-writing loads as everything else here, so it is covered by the counted wait below).
+  const bool derive_masks = has_tree && p.mask == nullptr;
+  if (derive_masks && wave < 2) {
+    int idx = wave * 64 + lane;
+    idx = idx < Tb ? idx : Tb - 1;
+    __builtin_amdgcn_global_load_lds(GLOBAL_PTR(p.parent + t0 + idx), lds + C::PARENT_OFF + wave * 256, 4, 0, 0);
+  }
   request_pages(0);
   request_pages(1);
   // The first PD tiles (fewer if the chunk has fewer).  Q and the mask rows were requested before
@@ -838,6 +850,29 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   if (PD >= 3 && n_tiles >= 3) issue_first(std::integral_constant<int, PD >= 3 ? 3 : 1>{});
   else if (PD >= 2 && n_tiles >= 2) issue_first(std::integral_constant<int, PD >= 2 ? 2 : 1>{});
   else issue_first(std::integral_constant<int, 1>{});
+  if (derive_masks) {
+    // Every wave has waited for its own loads queued before the tiles; after the barrier the parent
+    // array is complete.  Each lane walks from its node to the root (paper, Tree Reranking Phase:
+    // a token attends to its ancestors; and to itself), at most T_b steps whatever the array holds.
+    // (A bare barrier: the fenced one would wait for the tiles in flight too.)
+    __builtin_amdgcn_s_barrier();
+    const auto *par = reinterpret_cast<const __attribute__((address_space(3))) int32_t *>(lds + C::PARENT_OFF);
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const int row = rblk * BM + (wm * RB + r) * 32 + l32;
+      const int rowc = row < R ? row : R - 1;
+      int node = p.g_shift >= 0 ? (rowc >> p.g_shift) : rowc / p.G;
+      uint64_t b0 = 0, b1 = 0;
+      for (int step = 0; step < Tb && node >= 0; ++step) {
+        if (node < 64) b0 |= 1ull << node;
+        else b1 |= 1ull << (node - 64);
+        const int up = par[node];
+        node = up < node ? up : -1;  // a link that does not point backwards ends the walk
+      }
+      mrow[r][0] = b0;
+      mrow[r][1] = b1;
+    }
+  }
   TVA_STAMP(2);
   int it = 0;
   if (C::FAST && n_full > 0 && wave_has_rows) {
@@ -1178,7 +1213,7 @@ hipError_t dispatch_variant(int variant, const AttnParams &p, dim3 grid, hipStre
 
 extern "C" {
 
-int tva_version(void) { return 1; }
+int tva_version(void) { return 2; }
 
 size_t tva_sizeof_args(void) { return sizeof(tva_args); }
 
@@ -1222,8 +1257,8 @@ static int check_args(const tva_args *a, bool shapes_only) {
   if (shapes_only) return TVA_OK;
   if (!(a->scale > 0.f)) return TVA_INVALID_ARG;
   if (a->sum_T == 0) return TVA_OK;
-  if (!a->cu_T || !a->L || !a->q || !a->k_tree || !a->v_tree || !a->anc_mask || !a->out || !a->lse)
-    return TVA_INVALID_ARG;
+  if (!a->cu_T || !a->L || !a->q || !a->k_tree || !a->v_tree || !a->out || !a->lse) return TVA_INVALID_ARG;
+  if (!a->anc_mask && !a->parent) return TVA_INVALID_ARG;
   const bool dense = a->cu_L != nullptr, paged = a->page_table != nullptr;
   if (dense == paged) return TVA_INVALID_ARG;
   if (a->max_L > 0 && (!a->k_cache || !a->v_cache)) return TVA_INVALID_ARG;
@@ -1283,6 +1318,7 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   p.cu_L = a->cu_L;
   p.page_table = a->page_table;
   p.mask = a->anc_mask;
+  p.parent = a->parent;
   p.out = a->out;
   p.lse = a->lse;
   p.part_out = (float *)a->workspace;

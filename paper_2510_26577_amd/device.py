@@ -48,12 +48,13 @@ def build_mask(dw: DeviceWorkload, err_flag=None, stream=None):
 
 def attention(dw: DeviceWorkload, mask, num_splits: int = 0, max_L: Optional[int] = None, strides=(0, 0, 0),
               out=None, lse=None, workspace=None, stream=None):
+    """mask=None: the parent arrays are passed instead and the kernel derives the ancestor sets."""
     w = dw.w
     return binding.tree_verify_attn(
         dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, mask, dw.cu_T, dw.L,
         max_T=w.max_T, max_L=w.max_L if max_L is None else max_L, scale=w.scale, cu_L=dw.cu_L,
         page_table=dw.page_table, page_size=w.page_size, strides=strides, num_splits=num_splits,
-        out=out, lse=lse, workspace=workspace, stream=stream)
+        out=out, lse=lse, workspace=workspace, stream=stream, parent=dw.parent if mask is None else None)
 
 
 def run_path(dw: DeviceWorkload, num_splits: int = 0):

@@ -144,6 +144,39 @@ def test_every_workgroup_shape(gpu, variant, monkeypatch):
                label=f"shape {variant} paged")
     check_full(gpu, wl.random_workload(740 + variant, 2, 8, 4, 64, [300, 77], [60, 9]),
                num_splits=2, label=f"shape {variant} D=64")
+    # and with the ancestor sets derived in the kernel: bit-identical to passing the masks
+    import torch
+    dw = gpu.to_device(wl.random_workload(760 + variant, 3, 8, 2, 128, [400, 70, 0], [72, 30, 5], max_depth=12))
+    a = gpu.attention(dw, gpu.build_mask(dw), num_splits=2)
+    b = gpu.attention(dw, None, num_splits=2)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("case", ["cfg2", "cfg3_B16", "ragged", "paged", "forest_T128", "D64"])
+def test_masks_derived_in_kernel_equal_masks_passed(gpu, case):
+    """Passing the parent arrays instead of ancestor masks gives the same ancestor sets, hence the same
+    bits out (same arithmetic in the same order); the result is also checked against the oracle."""
+    import torch
+    w = {"cfg2": lambda: wl.config2(), "cfg3_B16": lambda: wl.config3(16),
+         "ragged": lambda: wl.random_workload(800, 5, 8, 2, 128, [700, 64, 0, 333, 5], [24, 5, 0, 40, 1]),
+         "paged": lambda: wl.random_workload(801, 3, 8, 2, 128, [517, 64, 130], [40, 64, 7], page_size=16),
+         "forest_T128": lambda: wl.random_workload(802, 2, 4, 2, 128, [75, 0], [128, 100], max_depth=13),
+         "D64": lambda: wl.random_workload(803, 2, 8, 4, 64, [300, 77], [60, 9])}[case]()
+    if case == "forest_T128":                      # several roots in one tree
+        w.parent[w.cu_T[0] + 5] = -1
+        w.parent[w.cu_T[1] + 50] = -1
+    say(f"[case] in-kernel masks: {case}")
+    dw = gpu.to_device(w)
+    mask = gpu.build_mask(dw)
+    for splits in (0, 1, 3):
+        out_a, lse_a = gpu.attention(dw, mask, num_splits=splits)
+        out_b, lse_b = gpu.attention(dw, None, num_splits=splits)
+        torch.cuda.synchronize()
+        assert torch.equal(out_a, out_b) and torch.equal(lse_a, lse_b)
+    ro, rl = orc.tree_verify_attn(w)
+    assert np.abs(out_b.cpu().numpy().astype(np.float64) - ro).max() <= TOL_O
+    assert np.abs(lse_b.cpu().numpy().astype(np.float64) - rl).max() <= TOL_LSE
 
 
 def test_empty_trees_in_batch_and_chain_and_star(gpu):
