@@ -1,0 +1,88 @@
+"""CPU oracle of the two steps that close a verification pass after the attention: greedy
+(temperature 0) acceptance of a root path of the draft tree, and the commit of the accepted
+nodes' K/V rows to the end of the sequence's cache.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/ (nothing in the product path).  Plain numpy /
+Python loops; shares no code with the HIP kernels.
+
+Acceptance (paper, Preliminary: "Speculative Decoding" -- a drafted token is accepted with
+probability min(1, p/q), else the target's own token is taken -- and "EAGLE": the draft is a tree
+and a rejected token leaves its siblings' subtrees in play).  At temperature 0 the target
+distribution is a point mass on its argmax, so p/q is 1/q >= 1 for the drafted token that equals
+the argmax and 0 for every other: the walk goes from the root to the child whose drafted token
+equals the target's argmax at the current node, and stops where no child does; the target's argmax
+at the last accepted node is the next (bonus) token.
+
+Readings: node 0 is the root and is always accepted (it is the token the previous step emitted);
+nodes are in topological order; when several children carry the matching token the lowest index is
+taken (a draft tree's siblings are distinct tokens, so this does not arise in practice); other roots
+of a forest are unreachable.  Commit: accepted node j of sequence b (in path order) goes to cache
+position L_b + j; nothing else in the cache changes.
+Parity unpinned: the paper prints no numeric example of either step; the pins are definitions by
+another route (all-edges-match characterisation, brute force) and invariants.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def accept_greedy(parent, cu_T, draft_token, target_token):
+    """parent, draft_token, target_token: int arrays [sum_T] (parent local to its tree, -1 = root);
+    target_token[i] = the target model's argmax for the position after node i.
+    Returns (paths: list of lists of local node indices, next_token: list)."""
+    B = len(cu_T) - 1
+    paths, nxt = [], []
+    for b in range(B):
+        t0, T = int(cu_T[b]), int(cu_T[b + 1] - cu_T[b])
+        if T == 0:
+            paths.append([])
+            nxt.append(-1)
+            continue
+        cur = 0
+        path = [0]
+        while True:
+            want = int(target_token[t0 + cur])
+            found = -1
+            for c in range(cur + 1, T):
+                if int(parent[t0 + c]) == cur and int(draft_token[t0 + c]) == want:
+                    found = c
+                    break
+            if found < 0:
+                break
+            cur = found
+            path.append(cur)
+        paths.append(path)
+        nxt.append(int(target_token[t0 + cur]))
+    return paths, nxt
+
+
+def commit_path_dense(k_cache, v_cache, cu_L, L, k_tree, v_tree, cu_T, paths):
+    """Dense ragged cache [sum_cap, Hkv, D] whose sequence b owns rows cu_L[b] .. cu_L[b+1]-1 and
+    uses the first L[b]; returns (new k_cache, new v_cache, new L).  Raises if a sequence lacks room."""
+    k, v = np.array(k_cache, copy=True), np.array(v_cache, copy=True)
+    L_new = np.array(L, copy=True)
+    for b, path in enumerate(paths):
+        cap = int(cu_L[b + 1] - cu_L[b])
+        if int(L[b]) + len(path) > cap:
+            raise ValueError("no room in the cache of sequence %d" % b)
+        for j, node in enumerate(path):
+            row = int(cu_L[b]) + int(L[b]) + j
+            k[row] = k_tree[int(cu_T[b]) + node]
+            v[row] = v_tree[int(cu_T[b]) + node]
+        L_new[b] = int(L[b]) + len(path)
+    return k, v, L_new
+
+
+def commit_path_paged(k_pool, v_pool, page_table, page_size, L, k_tree, v_tree, cu_T, paths):
+    """Paged cache [pages, page_size, Hkv, D]; position t of sequence b is slot t % page_size of page
+    page_table[b, t // page_size]."""
+    k, v = np.array(k_pool, copy=True), np.array(v_pool, copy=True)
+    L_new = np.array(L, copy=True)
+    for b, path in enumerate(paths):
+        for j, node in enumerate(path):
+            t = int(L[b]) + j
+            page = int(page_table[b, t // page_size])
+            k[page, t % page_size] = k_tree[int(cu_T[b]) + node]
+            v[page, t % page_size] = v_tree[int(cu_T[b]) + node]
+        L_new[b] = int(L[b]) + len(path)
+    return k, v, L_new

@@ -153,12 +153,13 @@ def test_every_workgroup_shape(gpu, variant, monkeypatch):
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
-@pytest.mark.parametrize("case", ["cfg2", "cfg3_B16", "ragged", "paged", "forest_T128", "D64"])
+@pytest.mark.parametrize("case", ["cfg2", "cfg3_B16", "cfg4", "cfg5", "ragged", "paged", "forest_T128", "D64"])
 def test_masks_derived_in_kernel_equal_masks_passed(gpu, case):
     """Passing the parent arrays instead of ancestor masks gives the same ancestor sets, hence the same
     bits out (same arithmetic in the same order); the result is also checked against the oracle."""
     import torch
     w = {"cfg2": lambda: wl.config2(), "cfg3_B16": lambda: wl.config3(16),
+         "cfg4": lambda: wl.config4(), "cfg5": lambda: wl.config5(),
          "ragged": lambda: wl.random_workload(800, 5, 8, 2, 128, [700, 64, 0, 333, 5], [24, 5, 0, 40, 1]),
          "paged": lambda: wl.random_workload(801, 3, 8, 2, 128, [517, 64, 130], [40, 64, 7], page_size=16),
          "forest_T128": lambda: wl.random_workload(802, 2, 4, 2, 128, [75, 0], [128, 100], max_depth=13),
@@ -174,6 +175,15 @@ def test_masks_derived_in_kernel_equal_masks_passed(gpu, case):
         out_b, lse_b = gpu.attention(dw, None, num_splits=splits)
         torch.cuda.synchronize()
         assert torch.equal(out_a, out_b) and torch.equal(lse_a, lse_b)
+    if case in ("cfg4", "cfg5"):   # full size, the benchmark's launch shape: the oracle takes sampled rows
+        rng = np.random.Generator(np.random.PCG64(5))
+        rows = [(int(b), int(rng.integers(0, w.T[b])), int(rng.integers(0, w.Hq))) for b in rng.integers(0, w.B, 24)]
+        ro, rl = orc.tree_verify_attn(w, rows=rows)
+        o, l = out_b.cpu().numpy().astype(np.float64), lse_b.cpu().numpy().astype(np.float64)
+        eo = max(np.abs(o[w.cu_T[b] + i, h] - ro[n]).max() for n, (b, i, h) in enumerate(rows))
+        el = max(abs(l[w.cu_T[b] + i, h] - rl[n]) for n, (b, i, h) in enumerate(rows))
+        assert eo <= TOL_O and el <= TOL_LSE
+        return
     ro, rl = orc.tree_verify_attn(w)
     assert np.abs(out_b.cpu().numpy().astype(np.float64) - ro).max() <= TOL_O
     assert np.abs(lse_b.cpu().numpy().astype(np.float64) - rl).max() <= TOL_LSE
