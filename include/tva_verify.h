@@ -1,0 +1,73 @@
+/*
+ * libtva -- the two steps that close a verification pass after the attention: greedy
+ * acceptance of a root path of each draft tree, and the commit of the accepted nodes' K/V rows
+ * to the end of each sequence's cache.  Same conventions as tva.h: device pointers owned by the
+ * caller, work queued on `stream` (hipStream_t as void*), nothing allocated, negative tva_status
+ * on rejected arguments (then nothing is queued).
+ */
+#ifndef TVA_VERIFY_H
+#define TVA_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Greedy (temperature 0) acceptance on draft trees (paper, Preliminary: a drafted token is accepted
+ * with probability min(1, p/q) and the target's own token replaces the first rejected one; with a
+ * tree draft a rejected token leaves its siblings in play.  At temperature 0 the target's
+ * distribution is its argmax, so exactly the child that carries that token is accepted).
+ *
+ * Per sequence b the walk starts at node 0 (always accepted) and moves to the child -- lowest index
+ * if several qualify -- whose draft_token equals target_token of the current node, until no child
+ * qualifies or max_path nodes are accepted.
+ *   parent        device int32 [cu_T[B]]  local parent index per node, -1 = root, parent[i] < i
+ *   cu_T          device int32 [B+1]
+ *   draft_token   device int32 [cu_T[B]]  token drafted at each node
+ *   target_token  device int32 [cu_T[B]]  the target model's argmax for the position after each node
+ *   max_path      row length of `path`, >= 1 (tree depth + 1 never truncates)
+ *   path          device int32 [B, max_path]: accepted local node indices in path order; entries past
+ *                 path_len[b] are not written
+ *   path_len      device int32 [B]: accepted nodes (0 for an empty tree)
+ *   next_token    device int32 [B]: target_token of the last accepted node (-1 for an empty tree)
+ */
+int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t *draft_token,
+                      const int32_t *target_token, int32_t B, int32_t max_path, int32_t *path,
+                      int32_t *path_len, int32_t *next_token, void *stream);
+
+/*
+ * Commit of the accepted path: accepted node j of sequence b (path order) has its K and V rows copied
+ * from the tree tensors to cache position L[b] + j.  Cache forms and strides as in tva_args (tva.h):
+ *   dense : cu_L != NULL; sequence b owns rows cu_L[b] .. cu_L[b+1]-1 of which the first L[b] are in use
+ *   paged : page_table != NULL; position t is slot t % page_size of page page_table[b*max_pages + t/page_size]
+ * A position outside the sequence's room (dense: beyond cu_L[b+1]; paged: beyond max_pages pages), or a
+ * path entry that is not a node of the sequence's tree, is not written and, if err_flag is given (zero
+ * on entry), stores 1 + b there.  The lengths, offsets and page numbers themselves are trusted.
+ * L_out[b] = L[b] + path_len[b] is written when L_out is not NULL; it must not alias L.
+ */
+typedef struct tva_commit_args {
+  int32_t B, Hkv, D;   /* D * Hkv * 2 bytes per row must be a multiple of 16 */
+  int32_t max_path;    /* row length of `path` */
+  const int32_t *cu_T; /* device [B+1] */
+  const int32_t *L;    /* device [B] */
+  const int32_t *path, *path_len;  /* device [B, max_path], [B] (tva_accept_greedy's outputs) */
+  const void *k_tree, *v_tree;     /* device bf16 [cu_T[B], Hkv, D] */
+  void *k_cache, *v_cache;         /* device bf16, dense or paged */
+  const int32_t *cu_L;             /* device [B+1] or NULL */
+  const int32_t *page_table;       /* device [B, max_pages] or NULL */
+  int32_t page_size, max_pages;
+  int64_t stride_page, stride_tok, stride_head; /* elements; 0 = packed default as in tva_args */
+  int32_t *L_out;      /* device [B] or NULL */
+  int32_t *err_flag;   /* device int32[1] or NULL */
+} tva_commit_args;
+
+int tva_commit_path(const tva_commit_args *a, void *stream);
+size_t tva_sizeof_commit_args(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TVA_VERIFY_H */

@@ -26,10 +26,11 @@ from __future__ import annotations
 import numpy as np
 
 
-def accept_greedy(parent, cu_T, draft_token, target_token):
+def accept_greedy(parent, cu_T, draft_token, target_token, max_path=None):
     """parent, draft_token, target_token: int arrays [sum_T] (parent local to its tree, -1 = root);
     target_token[i] = the target model's argmax for the position after node i.
-    Returns (paths: list of lists of local node indices, next_token: list)."""
+    Returns (paths: list of lists of local node indices, next_token: list).  With max_path the walk
+    also ends once that many nodes are accepted (an interface limit, not part of the method)."""
     B = len(cu_T) - 1
     paths, nxt = [], []
     for b in range(B):
@@ -40,7 +41,7 @@ def accept_greedy(parent, cu_T, draft_token, target_token):
             continue
         cur = 0
         path = [0]
-        while True:
+        while max_path is None or len(path) < max_path:
             want = int(target_token[t0 + cur])
             found = -1
             for c in range(cur + 1, T):

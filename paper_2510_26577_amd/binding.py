@@ -17,6 +17,7 @@ _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libtva.so")
 SRC_PATH = os.path.join(_HERE, "csrc", "tva.hip")
 CAST_SRC_PATH = os.path.join(_HERE, "csrc", "cast.cpp")  # host part: tree-size selection
+VERIFY_SRC_PATH = os.path.join(_HERE, "csrc", "verify.hip")  # acceptance + commit kernels
 INCLUDE_DIR = os.path.join(_ROOT, "include")
 
 TVA_OK = 0
@@ -28,10 +29,10 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile csrc/tva.hip (gfx950 kernels + their C ABI) and csrc/cast.cpp (host logic) into
-    libtva.so (in-tree)."""
+    """Compile csrc/tva.hip and csrc/verify.hip (gfx950 kernels + their C ABI) and csrc/cast.cpp
+    (host logic) into libtva.so (in-tree)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-shared", "-fPIC", "-o", LIB_PATH, SRC_PATH, CAST_SRC_PATH]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-shared", "-fPIC", "-o", LIB_PATH, SRC_PATH, VERIFY_SRC_PATH, CAST_SRC_PATH]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     lines = [l for l in res.stdout.splitlines() if "is not a recognized feature" not in l]
     if verbose or res.returncode:
@@ -63,6 +64,8 @@ class TvaArgs(ctypes.Structure):
 
 EXPORTS = ("tva_build_ancestor_mask", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys",
            "tva_tree_verify_attn", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
+# entry points of include/tva_verify.h (bound in verify.py)
+VERIFY_EXPORTS = ("tva_accept_greedy", "tva_commit_path", "tva_sizeof_commit_args")
 # host entry points of include/tva_cast.h (bound in cast.py)
 CAST_EXPORTS = ("tva_cast_select_context", "tva_cast_select_max_valid_index", "tva_cast_layer_utility",
                 "tva_cast_layer_cost", "tva_cast_breadth_prune", "tva_cast_depth_bytes", "tva_cast_depth_init",
@@ -170,6 +173,8 @@ def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: 
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     a.num_splits = int(num_splits)
     a.parent = _p(parent)
+    # the struct holds raw addresses: keep the tensors alive as long as it lives
+    a._keep = (q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, cu_L, page_table, out, lse, workspace, parent)
     return a
 
 

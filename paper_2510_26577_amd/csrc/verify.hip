@@ -1,0 +1,155 @@
+// libtva: greedy tree acceptance and commit of the accepted path's K/V rows (gfx950).
+// Entry points and their meaning: include/tva_verify.h.
+//
+//   accept_kernel   one wave per sequence.  The walk from the root is a chain of dependent steps; each
+//                   step's search for the matching child is the parallel part: the 64 lanes test 64
+//                   candidate nodes at once and a ballot picks the lowest index.  Integer work,
+//                   latency-bound (a few L2 round trips per accepted node).
+//   commit_kernel   one workgroup per (path position, sequence): a row of K and a row of V, 16 bytes
+//                   per lane, straight from the tree tensors to the cache.  HBM-bound in principle
+//                   (read + write of 2 * Hkv * D * 2 bytes per accepted node), launch-bound at the
+//                   sizes a decode step has.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tva.h"
+#include "tva_verify.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(64) accept_kernel(const int32_t *__restrict__ parent, const int32_t *__restrict__ cu_T,
+                                                    const int32_t *__restrict__ draft, const int32_t *__restrict__ target,
+                                                    int max_path, int32_t *__restrict__ path,
+                                                    int32_t *__restrict__ path_len, int32_t *__restrict__ next_token) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int t0 = cu_T[b];
+  const int T = cu_T[b + 1] - t0;
+  if (T <= 0) {
+    if (lane == 0) {
+      path_len[b] = 0;
+      next_token[b] = -1;
+    }
+    return;
+  }
+  int cur = 0, len = 1;
+  if (lane == 0) path[(size_t)b * max_path] = 0;
+  // every accepted node has a larger index than the one before, so at most T - 1 steps
+  while (len < max_path) {
+    const int want = target[t0 + cur];
+    int found = -1;
+    for (int base = cur + 1; base < T && found < 0; base += 64) {
+      const int c = base + lane;
+      const bool hit = c < T && parent[t0 + c] == cur && draft[t0 + c] == want;
+      const uint64_t votes = __ballot(hit);
+      if (votes) found = base + __builtin_ctzll(votes);
+    }
+    if (found < 0) break;
+    cur = found;
+    if (lane == 0) path[(size_t)b * max_path + len] = cur;
+    ++len;
+  }
+  if (lane == 0) {
+    path_len[b] = len;
+    next_token[b] = target[t0 + cur];
+  }
+}
+
+struct CommitParams {
+  const int32_t *cu_T, *L, *path, *path_len, *cu_L, *page_table;
+  const char *k_tree, *v_tree;
+  char *k_cache, *v_cache;
+  int32_t *L_out, *err_flag;
+  int Hkv, D, max_path, page_size, max_pages;
+  int64_t stride_page, stride_tok, stride_head;  // elements
+};
+
+__global__ void __launch_bounds__(256) commit_kernel(const CommitParams p) {
+  const int j = blockIdx.x, b = blockIdx.y;
+  const int n = p.path_len[b];
+  const int Lb = p.L[b];
+  if (j == 0 && threadIdx.x == 0 && p.L_out) p.L_out[b] = Lb + (n < p.max_path ? n : p.max_path);
+  if (j >= n || Lb < 0) return;
+  const int node = p.path[(size_t)b * p.max_path + j];
+  if (node < 0 || node >= p.cu_T[b + 1] - p.cu_T[b]) {  // not a node of this tree: nothing is copied
+    if (threadIdx.x == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+    return;
+  }
+  const int64_t src_row = (int64_t)p.cu_T[b] + node;
+  const int pos = Lb + j;
+  int64_t dst;  // element offset of (position, head 0, d 0)
+  bool room;
+  if (p.page_table) {
+    const int pi = pos / p.page_size;
+    room = pi < p.max_pages;
+    const int page = room ? p.page_table[(int64_t)b * p.max_pages + pi] : 0;
+    dst = (int64_t)page * p.stride_page + (int64_t)(pos - pi * p.page_size) * p.stride_tok;
+  } else {
+    room = (int64_t)p.cu_L[b] + pos < p.cu_L[b + 1];
+    dst = ((int64_t)p.cu_L[b] + pos) * p.stride_tok;
+  }
+  if (!room) {
+    if (threadIdx.x == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+    return;
+  }
+  // 16-byte pieces: piece q of head g; the tree tensors are packed [node, Hkv, D]
+  const int per_head = p.D / 8;
+  const int pieces = p.Hkv * per_head;
+  for (int q = threadIdx.x; q < 2 * pieces; q += blockDim.x) {
+    const bool is_v = q >= pieces;
+    const int r = is_v ? q - pieces : q;
+    const int g = r / per_head, e = (r - g * per_head) * 8;
+    const char *src = (is_v ? p.v_tree : p.k_tree) + ((src_row * p.Hkv + g) * p.D + e) * 2;
+    char *out = (is_v ? p.v_cache : p.k_cache) + (dst + (int64_t)g * p.stride_head + e) * 2;
+    *reinterpret_cast<u32x4 *>(out) = *reinterpret_cast<const u32x4 *>(src);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t *draft_token,
+                      const int32_t *target_token, int32_t B, int32_t max_path, int32_t *path, int32_t *path_len,
+                      int32_t *next_token, void *stream) {
+  if (B < 0 || max_path < 1) return TVA_INVALID_ARG;
+  if (B == 0) return TVA_OK;
+  if (!parent || !cu_T || !draft_token || !target_token || !path || !path_len || !next_token) return TVA_INVALID_ARG;
+  (void)hipGetLastError();  // the status below is this launch's
+  hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(64), 0, (hipStream_t)stream, parent, cu_T, draft_token, target_token,
+                     max_path, path, path_len, next_token);
+  return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+int tva_commit_path(const tva_commit_args *a, void *stream) {
+  if (!a || a->B < 0 || a->Hkv < 1 || a->D < 8 || a->D % 8 || a->max_path < 1) return TVA_INVALID_ARG;
+  if (a->B == 0) return TVA_OK;
+  if (!a->cu_T || !a->L || !a->path || !a->path_len || !a->k_tree || !a->v_tree || !a->k_cache || !a->v_cache)
+    return TVA_INVALID_ARG;
+  const bool dense = a->cu_L != nullptr, paged = a->page_table != nullptr;
+  if (dense == paged) return TVA_INVALID_ARG;
+  if (paged && (a->page_size <= 0 || a->max_pages <= 0)) return TVA_INVALID_ARG;
+  if ((a->stride_page | a->stride_tok | a->stride_head) % 8) return TVA_INVALID_ARG;
+  if (a->stride_page < 0 || a->stride_tok < 0 || a->stride_head < 0) return TVA_INVALID_ARG;
+  if (a->L_out == a->L) return TVA_INVALID_ARG;
+  if (a->B > 65535) return TVA_UNSUPPORTED;
+  CommitParams p;
+  p.cu_T = a->cu_T; p.L = a->L; p.path = a->path; p.path_len = a->path_len;
+  p.cu_L = a->cu_L; p.page_table = a->page_table;
+  p.k_tree = (const char *)a->k_tree; p.v_tree = (const char *)a->v_tree;
+  p.k_cache = (char *)a->k_cache; p.v_cache = (char *)a->v_cache;
+  p.L_out = a->L_out; p.err_flag = a->err_flag;
+  p.Hkv = a->Hkv; p.D = a->D; p.max_path = a->max_path;
+  p.page_size = paged ? a->page_size : 1; p.max_pages = a->max_pages;
+  p.stride_head = a->stride_head ? a->stride_head : a->D;
+  p.stride_tok = a->stride_tok ? a->stride_tok : (int64_t)a->Hkv * a->D;
+  p.stride_page = a->stride_page ? a->stride_page : (int64_t)p.page_size * p.stride_tok;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(commit_kernel, dim3(a->max_path, a->B), dim3(256), 0, (hipStream_t)stream, p);
+  return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+size_t tva_sizeof_commit_args(void) { return sizeof(tva_commit_args); }
+
+}  // extern "C"

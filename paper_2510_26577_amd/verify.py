@@ -1,0 +1,173 @@
+"""Thin ctypes binding of include/tva_verify.h (argument marshalling only): greedy acceptance of a
+root path per draft tree and commit of the accepted nodes' K/V rows to the cache.  Both run as HIP
+kernels in libtva.so; a missing library raises (no fallback)."""
+from __future__ import annotations
+
+import ctypes
+
+from . import binding
+from .binding import _check, _p, _stream_ptr
+
+_ready = False
+
+
+class CommitArgs(ctypes.Structure):
+    """Mirror of `struct tva_commit_args`."""
+    _fields_ = [
+        ("B", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32), ("max_path", ctypes.c_int32),
+        ("cu_T", ctypes.c_void_p), ("L", ctypes.c_void_p), ("path", ctypes.c_void_p), ("path_len", ctypes.c_void_p),
+        ("k_tree", ctypes.c_void_p), ("v_tree", ctypes.c_void_p), ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+        ("cu_L", ctypes.c_void_p), ("page_table", ctypes.c_void_p),
+        ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
+        ("stride_page", ctypes.c_int64), ("stride_tok", ctypes.c_int64), ("stride_head", ctypes.c_int64),
+        ("L_out", ctypes.c_void_p), ("err_flag", ctypes.c_void_p),
+    ]
+
+
+def _lib():
+    global _ready
+    lib = binding.load_library()
+    if not _ready:
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        lib.tva_accept_greedy.restype = ctypes.c_int
+        lib.tva_accept_greedy.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        lib.tva_commit_path.restype = ctypes.c_int
+        lib.tva_commit_path.argtypes = [ctypes.POINTER(CommitArgs), vp]
+        lib.tva_sizeof_commit_args.restype = ctypes.c_size_t
+        if lib.tva_sizeof_commit_args() != ctypes.sizeof(CommitArgs):
+            raise RuntimeError("libtva.so is stale: rebuild it")
+        _ready = True
+    return lib
+
+
+def accept_greedy(parent, cu_T, draft_token, target_token, max_path: int, path=None, path_len=None, next_token=None,
+                  stream=None):
+    """Device int32 tensors in; returns (path [B, max_path], path_len [B], next_token [B])."""
+    import torch
+    B = cu_T.numel() - 1
+    dev = cu_T.device
+    if path is None:
+        path = torch.full((B, max_path), -1, dtype=torch.int32, device=dev)
+    if path_len is None:
+        path_len = torch.empty(B, dtype=torch.int32, device=dev)
+    if next_token is None:
+        next_token = torch.empty(B, dtype=torch.int32, device=dev)
+    _check(_lib().tva_accept_greedy(_p(parent), _p(cu_T), _p(draft_token), _p(target_token), B, int(max_path),
+                                    _p(path), _p(path_len), _p(next_token), _stream_ptr(stream)))
+    return path, path_len, next_token
+
+
+def make_commit_args(*, cu_T, L, path, path_len, k_tree, v_tree, k_cache, v_cache, cu_L=None, page_table=None,
+                     page_size: int = 0, strides=(0, 0, 0), L_out=None, err_flag=None) -> CommitArgs:
+    a = CommitArgs()
+    a.B = cu_T.numel() - 1
+    a.Hkv, a.D = int(k_tree.shape[1]), int(k_tree.shape[2])
+    a.max_path = int(path.shape[1])
+    a.cu_T, a.L, a.path, a.path_len = _p(cu_T), _p(L), _p(path), _p(path_len)
+    a.k_tree, a.v_tree, a.k_cache, a.v_cache = _p(k_tree), _p(v_tree), _p(k_cache), _p(v_cache)
+    a.cu_L, a.page_table = _p(cu_L), _p(page_table)
+    a.page_size = int(page_size)
+    a.max_pages = int(page_table.shape[1]) if page_table is not None else 0
+    a.stride_page, a.stride_tok, a.stride_head = (int(s) for s in strides)
+    a.L_out, a.err_flag = _p(L_out), _p(err_flag)
+    # the struct holds raw addresses: keep the tensors alive as long as it lives
+    a._keep = (cu_T, L, path, path_len, k_tree, v_tree, k_cache, v_cache, cu_L, page_table, L_out, err_flag)
+    return a
+
+
+def commit_path_raw(args: CommitArgs, stream=None) -> None:
+    _check(_lib().tva_commit_path(ctypes.byref(args), _stream_ptr(stream)))
+
+
+def commit_path(**kw):
+    """Keyword arguments of make_commit_args plus stream; writes the caches in place."""
+    stream = kw.pop("stream", None)
+    commit_path_raw(make_commit_args(**kw), stream)
+
+
+def _bench(argv=None) -> int:
+    """Times the two kernels on seeded synthetic steps of the benchmark's shapes (HIP-graph replay over
+    rotating copies) and prints one JSON line per shape.  Plumbing only; the kernels do the work."""
+    import argparse
+    import json
+    import numpy as np
+    import torch
+    from . import workloads as wl
+
+    ap = argparse.ArgumentParser(description="time tva_accept_greedy and tva_commit_path")
+    ap.add_argument("--steps", type=int, default=64)
+    a = ap.parse_args(argv)
+    assert torch.cuda.is_available(), "needs a GPU"
+    rng = np.random.Generator(np.random.PCG64(77))
+    stream = torch.cuda.Stream()
+    for name, B, T, Hkv, D, depth in (("B=1 T=60", 1, 60, 8, 128, 6), ("B=8 T=32", 8, 32, 8, 128, 6),
+                                      ("B=64 T=8", 64, 8, 8, 128, 8), ("B=64 T=72", 64, 72, 8, 128, 13)):
+        copies = 8
+        cases = []
+        accepted = 0
+        for c in range(copies):
+            trees = [wl.tree_uniform(rng, T, depth) for _ in range(B)]
+            parent = np.concatenate(trees).astype(np.int32)
+            cu_T = (np.arange(B + 1) * T).astype(np.int32)
+            draft = rng.integers(0, 1 << 15, B * T).astype(np.int32)
+            target = rng.integers(0, 1 << 15, B * T).astype(np.int32)
+            for b in range(B):                       # plant a matching child under most nodes: long accepted paths
+                for i in range(T):
+                    kids = np.nonzero(trees[b] == i)[0]
+                    if len(kids) and rng.random() < 0.85:
+                        target[b * T + i] = draft[b * T + int(kids[0])]
+            L = np.full(B, 1024, np.int32)
+            cap = L + T
+            cu_L = np.concatenate([[0], np.cumsum(cap)]).astype(np.int32)
+            d = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+            kt = torch.randint(-30000, 30000, (B * T, Hkv, D), dtype=torch.int16, device="cuda")
+            vt = torch.randint(-30000, 30000, (B * T, Hkv, D), dtype=torch.int16, device="cuda")
+            kc = torch.zeros((int(cap.sum()), Hkv, D), dtype=torch.int16, device="cuda")
+            vc = torch.zeros_like(kc)
+            path = torch.full((B, depth + 1), -1, dtype=torch.int32, device="cuda")
+            plen = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
+            acc = (d(parent), d(cu_T), d(draft), d(target), path, plen, nxt)
+            cargs = make_commit_args(cu_T=acc[1], L=d(L), path=path, path_len=plen, k_tree=kt, v_tree=vt, k_cache=kc,
+                                     v_cache=vc, cu_L=d(cu_L))
+            cases.append((acc, cargs, (kt, vt, kc, vc)))
+
+        def run(which):
+            for acc, cargs, _ in cases:
+                if which in ("accept", "both"):
+                    accept_greedy(acc[0], acc[1], acc[2], acc[3], depth + 1, path=acc[4], path_len=acc[5],
+                                  next_token=acc[6], stream=stream)
+                if which in ("commit", "both"):
+                    commit_path_raw(cargs, stream)
+
+        times = {}
+        with torch.cuda.stream(stream):
+            run("both")
+            stream.synchronize()
+            accepted = sum(int(c[0][5].sum().item()) for c in cases) / copies
+            for which in ("accept", "commit", "both"):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for _ in range(a.steps // copies):
+                        run(which)
+                g.replay()
+                stream.synchronize()
+                best = 1e30
+                for _ in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    g.replay()
+                    e1.record(stream)
+                    e1.synchronize()
+                    best = min(best, e0.elapsed_time(e1) * 1e3 / (a.steps // copies * copies))
+                times[which] = best
+        moved = accepted * Hkv * D * 2 * 2 * 2      # K and V rows, read + write
+        print(json.dumps({"shape": name, "accepted_nodes_per_step": accepted, "accept_us": times["accept"],
+                          "commit_us": times["commit"], "both_us": times["both"], "commit_bytes": moved,
+                          "commit_GBps": moved / (times["commit"] * 1e-6) / 1e9}), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    import sys
+    sys.exit(_bench())

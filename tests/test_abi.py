@@ -32,6 +32,15 @@ def test_exports_match_header(lib):
         assert getattr(lib, s) is not None
 
 
+def test_verify_exports_match_header(lib):
+    from paper_2510_26577_amd import verify
+    syms = declared_symbols("tva_verify.h")
+    assert set(syms) == set(binding.VERIFY_EXPORTS)
+    for s in syms:
+        assert getattr(lib, s) is not None
+    assert lib.tva_sizeof_commit_args() == ctypes.sizeof(verify.CommitArgs)
+
+
 def test_host_exports_match_header(lib):
     syms = declared_symbols("tva_cast.h")
     assert set(syms) == set(binding.CAST_EXPORTS)

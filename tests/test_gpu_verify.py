@@ -1,0 +1,214 @@
+"""GPU parity of greedy tree acceptance and the K/V commit (through the C ABI) against the CPU
+oracle on the same seeded inputs: integer and byte work, compared exactly."""
+import numpy as np
+import pytest
+
+from oracle import verify_oracle as vo
+from paper_2510_26577_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_dev():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2510_26577_amd import binding
+    binding.load_library()
+    return torch
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def make_tokens(rng, parent, cu_T, vocab, plant):
+    """Draft tokens with distinct siblings, target tokens random with `plant` of them set to a child's token."""
+    sum_T = int(cu_T[-1])
+    draft = np.zeros(sum_T, np.int32)
+    target = rng.integers(0, vocab, sum_T).astype(np.int32)
+    for b in range(len(cu_T) - 1):
+        t0, T = int(cu_T[b]), int(cu_T[b + 1] - cu_T[b])
+        used = {}
+        kids = {}
+        for i in range(T):
+            p = int(parent[t0 + i])
+            kids.setdefault(p, []).append(i)
+            while True:
+                t = int(rng.integers(0, vocab))
+                if t not in used.setdefault(p, set()):
+                    used[p].add(t)
+                    draft[t0 + i] = t
+                    break
+        for i in range(T):
+            if i in kids and rng.random() < plant:
+                target[t0 + i] = draft[t0 + kids[i][int(rng.integers(0, len(kids[i])))]]
+    return draft, target
+
+
+def run_accept(torch, parent, cu_T, draft, target, max_path):
+    from paper_2510_26577_amd import verify
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    path, n, nxt = verify.accept_greedy(d(parent), d(cu_T), d(draft), d(target), max_path)
+    torch.cuda.synchronize()
+    return path.cpu().numpy(), n.cpu().numpy(), nxt.cpu().numpy()
+
+
+@pytest.mark.parametrize("B,T_hi,plant", [(1, 8, 0.9), (4, 60, 0.8), (64, 72, 0.7), (16, 300, 0.95), (7, 1, 0.5)])
+def test_accept_greedy_matches_oracle(torch_dev, B, T_hi, plant):
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(31 + B + T_hi))
+    T = rng.integers(0 if B > 4 else 1, T_hi + 1, B)
+    T[0] = T_hi
+    cu_T = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    parent = np.concatenate([wl.tree_uniform(rng, int(t), 40) if t > 0 else np.zeros(0, np.int32) for t in T]).astype(np.int32)
+    draft, target = make_tokens(rng, parent, cu_T, vocab=100, plant=plant)
+    say(f"[case] accept B={B} T<={T_hi} plant={plant}")
+    for max_path in (int(T.max()) + 1, 3, 1):
+        ref_paths, ref_next = vo.accept_greedy(parent, cu_T, draft, target, max_path=max_path)
+        path, n, nxt = run_accept(torch, parent, cu_T, draft, target, max_path)
+        assert list(n) == [len(p) for p in ref_paths]
+        assert list(nxt) == ref_next
+        for b, p in enumerate(ref_paths):
+            assert list(path[b, :len(p)]) == p
+    assert max(len(p) for p in vo.accept_greedy(parent, cu_T, draft, target)[0]) >= (3 if T_hi >= 8 else 1)
+
+
+def test_accept_duplicate_sibling_tokens_take_the_lowest_index(torch_dev):
+    torch = torch_dev
+    parent = np.array([-1, 0, 0, 0, 2, 2], np.int32)
+    draft = np.array([0, 5, 5, 5, 9, 9], np.int32)
+    target = np.array([5, 1, 9, 1, 1, 1], np.int32)      # root -> first child with token 5 = node 1, which has no children
+    path, n, nxt = run_accept(torch, parent, np.array([0, 6], np.int32), draft, target, 6)
+    assert list(path[0, :n[0]]) == [0, 1] and nxt[0] == 1
+    draft[1] = 4                                          # now node 2 is the first match, then node 4
+    path, n, nxt = run_accept(torch, parent, np.array([0, 6], np.int32), draft, target, 6)
+    assert list(path[0, :n[0]]) == [0, 2, 4] and nxt[0] == 1
+
+
+def _commit_case(torch, w, paths, paged_capacity_tokens=None, strides_head_major=False):
+    """Runs the commit on the GPU for workload w (dense or paged) and returns what the oracle needs to compare."""
+    from paper_2510_26577_amd import verify
+    B = w.B
+    max_path = max(1, max(len(p) for p in paths))
+    path = np.full((B, max_path), -1, np.int32)
+    for b, p in enumerate(paths):
+        path[b, :len(p)] = p
+    plen = np.array([len(p) for p in paths], np.int32)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    as_i16 = lambda a: a.view(np.int16)
+    return verify, dev, as_i16, path, plen
+
+
+@pytest.mark.parametrize("B,Hkv,D", [(3, 2, 64), (8, 8, 128), (64, 8, 128)])
+def test_commit_dense_matches_oracle(torch_dev, B, Hkv, D):
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(41 + B))
+    T = rng.integers(1, 40, B)
+    L = rng.integers(0, 300, B).astype(np.int32)
+    w = wl.random_workload(900 + B, B, Hkv * 2, Hkv, D, L, T)
+    # capacity: room for a few more tokens per sequence; sequence 0 gets too little on purpose
+    cap = L + rng.integers(6, 20, B)
+    paths = []
+    for b in range(B):
+        n = int(rng.integers(1, min(int(T[b]), 6) + 1))
+        paths.append(sorted(rng.choice(int(T[b]), size=n, replace=False).tolist()))
+    cu_cap = np.concatenate([[0], np.cumsum(cap)]).astype(np.int32)
+    kc = rng.integers(0, 2 ** 16, (int(cap.sum()), Hkv, D)).astype(np.uint16)
+    vc = rng.integers(0, 2 ** 16, (int(cap.sum()), Hkv, D)).astype(np.uint16)
+    verify, dev, as_i16, path, plen = _commit_case(torch, w, paths)
+    say(f"[case] commit dense B={B} Hkv={Hkv} D={D}")
+    k_d, v_d = dev(as_i16(kc)), dev(as_i16(vc))
+    L_out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    verify.commit_path(cu_T=dev(w.cu_T), L=dev(L), path=dev(path), path_len=dev(plen), k_tree=dev(as_i16(w.k_tree)),
+                       v_tree=dev(as_i16(w.v_tree)), k_cache=k_d, v_cache=v_d, cu_L=dev(cu_cap), L_out=L_out, err_flag=err)
+    torch.cuda.synchronize()
+    k_ref, v_ref, L_ref = vo.commit_path_dense(kc, vc, cu_cap, L, w.k_tree, w.v_tree, w.cu_T, paths)
+    assert int(err.item()) == 0
+    assert np.array_equal(k_d.cpu().numpy().view(np.uint16), k_ref) and np.array_equal(v_d.cpu().numpy().view(np.uint16), v_ref)
+    assert np.array_equal(L_out.cpu().numpy(), L_ref)
+    # no room: the flag names the sequence, rows inside the room are still written, nothing outside it is
+    tight = cap.copy()
+    tight[B - 1] = L[B - 1] + len(paths[B - 1]) - 1
+    cu_tight = np.concatenate([[0], np.cumsum(tight)]).astype(np.int32)
+    kc2 = rng.integers(0, 2 ** 16, (int(tight.sum()) + 1, Hkv, D)).astype(np.uint16)   # one guard row at the end
+    k2, v2 = dev(as_i16(kc2)), dev(as_i16(kc2.copy()))
+    err.zero_()
+    verify.commit_path(cu_T=dev(w.cu_T), L=dev(L), path=dev(path), path_len=dev(plen), k_tree=dev(as_i16(w.k_tree)),
+                       v_tree=dev(as_i16(w.v_tree)), k_cache=k2, v_cache=v2, cu_L=dev(cu_tight), err_flag=err)
+    torch.cuda.synchronize()
+    assert int(err.item()) == B
+    assert np.array_equal(k2.cpu().numpy().view(np.uint16)[-1], kc2[-1])
+
+
+@pytest.mark.parametrize("page_size", [16, 1, 5])
+def test_commit_paged_matches_oracle(torch_dev, page_size):
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(51 + page_size))
+    B, Hkv, D = 6, 4, 128
+    T = rng.integers(1, 30, B)
+    L = rng.integers(0, 100, B).astype(np.int32)
+    w = wl.random_workload(950 + page_size, B, Hkv, Hkv, D, L, T)
+    paths = [sorted(rng.choice(int(T[b]), size=int(rng.integers(1, min(int(T[b]), 8) + 1)), replace=False).tolist()) for b in range(B)]
+    max_pages = int((L.max() + 8 + page_size - 1) // page_size) + 1
+    perm = rng.permutation(B * max_pages).reshape(B, max_pages).astype(np.int32)
+    kp = rng.integers(0, 2 ** 16, (B * max_pages, page_size, Hkv, D)).astype(np.uint16)
+    vp = rng.integers(0, 2 ** 16, (B * max_pages, page_size, Hkv, D)).astype(np.uint16)
+    verify, dev, as_i16, path, plen = _commit_case(torch, w, paths)
+    say(f"[case] commit paged page_size={page_size}")
+    k_d, v_d = dev(as_i16(kp)), dev(as_i16(vp))
+    L_out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    verify.commit_path(cu_T=dev(w.cu_T), L=dev(L), path=dev(path), path_len=dev(plen), k_tree=dev(as_i16(w.k_tree)),
+                       v_tree=dev(as_i16(w.v_tree)), k_cache=k_d, v_cache=v_d, page_table=dev(perm), page_size=page_size,
+                       L_out=L_out)
+    torch.cuda.synchronize()
+    k_ref, v_ref, L_ref = vo.commit_path_paged(kp, vp, perm, page_size, L, w.k_tree, w.v_tree, w.cu_T, paths)
+    assert np.array_equal(k_d.cpu().numpy().view(np.uint16), k_ref) and np.array_equal(v_d.cpu().numpy().view(np.uint16), v_ref)
+    assert np.array_equal(L_out.cpu().numpy(), L_ref)
+
+
+def test_accept_then_commit_then_attend(torch_dev):
+    """The committed rows are what the next step's attention reads: after commit, attention over the longer cache
+    (with a one-node tree) equals the oracle on the host-side committed cache."""
+    torch = torch_dev
+    from oracle import tva_oracle as orc
+    from paper_2510_26577_amd import device, verify
+    rng = np.random.Generator(np.random.PCG64(61))
+    B, Hq, Hkv, D = 3, 8, 2, 128
+    L = np.array([40, 0, 129], np.int32)
+    T = np.array([12, 5, 30])
+    w = wl.random_workload(990, B, Hq, Hkv, D, L, T)
+    draft, target = make_tokens(rng, w.parent, w.cu_T, vocab=30, plant=0.9)
+    paths, _ = vo.accept_greedy(w.parent, w.cu_T, draft, target)
+    cap = L + T
+    cu_cap = np.concatenate([[0], np.cumsum(cap)]).astype(np.int32)
+    kc = np.zeros((int(cap.sum()), Hkv, D), np.uint16)
+    vc = np.zeros_like(kc)
+    for b in range(B):
+        kc[cu_cap[b]:cu_cap[b] + L[b]] = w.k_cache[w.cu_L[b]:w.cu_L[b] + L[b]]
+        vc[cu_cap[b]:cu_cap[b] + L[b]] = w.v_cache[w.cu_L[b]:w.cu_L[b] + L[b]]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    i16 = lambda a: a.view(np.int16)
+    dp, dcu = dev(w.parent), dev(w.cu_T)
+    path, plen, nxt = verify.accept_greedy(dp, dcu, dev(draft), dev(target), int(T.max()))
+    k_d, v_d = dev(i16(kc)), dev(i16(vc))
+    L_new = torch.zeros(B, dtype=torch.int32, device="cuda")
+    verify.commit_path(cu_T=dcu, L=dev(L), path=path, path_len=plen, k_tree=dev(i16(w.k_tree)), v_tree=dev(i16(w.v_tree)),
+                       k_cache=k_d, v_cache=v_d, cu_L=dev(cu_cap), L_out=L_new)
+    torch.cuda.synchronize()
+    assert [list(path[b, :plen[b]].cpu().numpy()) for b in range(B)] == paths
+    k_ref, v_ref, L_ref = vo.commit_path_dense(kc, vc, cu_cap, L, w.k_tree, w.v_tree, w.cu_T, paths)
+    assert np.array_equal(L_new.cpu().numpy(), L_ref)
+    # next step: one new token per sequence attends to the committed cache
+    import dataclasses
+    w2 = wl.random_workload(991, B, Hq, Hkv, D, L_ref, [1] * B)
+    w2 = dataclasses.replace(w2, k_cache=k_ref, v_cache=v_ref, cu_L=cu_cap)
+    dw2 = device.to_device(w2)
+    dw2.k_cache, dw2.v_cache = k_d, v_d                     # the GPU reads what the commit kernel wrote
+    out, lse = device.attention(dw2, None)
+    torch.cuda.synchronize()
+    ro, rl = orc.tree_verify_attn(w2)
+    assert np.abs(out.cpu().numpy().astype(np.float64) - ro).max() <= 2e-3
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - rl).max() <= 1e-4
