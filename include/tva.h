@@ -38,6 +38,7 @@ typedef enum {
   TVA_INVALID_ARG = -1,         /* null pointer, bad sizes, both / neither cache form */
   TVA_UNSUPPORTED = -2,         /* D not in {64,128}, max_T > 128, ... */
   TVA_WORKSPACE_TOO_SMALL = -3, /* see tva_workspace_bytes() */
+  TVA_BAD_TREE = -5,            /* tva_build_ancestor_mask_host only: a parent index outside [-1, i-1] */
   TVA_HIP_ERROR = -4            /* a launch failed: the error is left for hipGetLastError (an older
                                    error of the process is cleared before each launch, so the status
                                    is this launch's); TVA_VERBOSE=1 in the environment names it on stderr */
@@ -123,6 +124,17 @@ typedef struct tva_args {
  */
 int tva_build_ancestor_mask(const int32_t *parent, const int32_t *cu_T, int32_t B, int32_t max_T,
                             int32_t mask_words, uint64_t *mask, int32_t *err_flag, void *stream);
+
+/*
+ * The same masks on the host, with synchronous validation: every pointer here is HOST memory.
+ * Meant for validating trees where they are built (the device variant reports a malformed tree
+ * only through err_flag, asynchronously) and for tests; the attention never goes through it.
+ * Returns TVA_BAD_TREE if some parent[i] lies outside [-1, i-1] (bad_node, if not NULL, receives the
+ * smallest such global node index; mask contents are then unspecified), TVA_INVALID_ARG for
+ * malformed arguments, else TVA_OK with mask [cu_T[B], mask_words] fully written.
+ */
+int tva_build_ancestor_mask_host(const int32_t *parent, const int32_t *cu_T, int32_t B, int32_t max_T,
+                                 int32_t mask_words, uint64_t *mask, int32_t *bad_node);
 
 /*
  * Scratch bytes tva_tree_verify_attn needs for these shapes.  Only the shape

@@ -62,7 +62,7 @@ class TvaArgs(ctypes.Structure):
     ]
 
 
-EXPORTS = ("tva_build_ancestor_mask", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys",
+EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys",
            "tva_tree_verify_attn", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
 # entry points of include/tva_verify.h (bound in verify.py)
 VERIFY_EXPORTS = ("tva_accept_greedy", "tva_commit_path", "tva_sizeof_commit_args")
@@ -92,6 +92,9 @@ def load_library():
     lib.tva_build_ancestor_mask.restype = ctypes.c_int
     lib.tva_build_ancestor_mask.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                             ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.tva_build_ancestor_mask_host.restype = ctypes.c_int
+    lib.tva_build_ancestor_mask_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                                 ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
     lib.tva_workspace_bytes.restype = ctypes.c_size_t
     lib.tva_workspace_bytes.argtypes = [ctypes.POINTER(TvaArgs)]
     lib.tva_plan_splits.restype = ctypes.c_int32
@@ -131,6 +134,23 @@ def _stream_ptr(stream) -> Optional[int]:
 
 def _p(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
+
+
+def build_ancestor_mask_host(parent, cu_T, max_T: int):
+    """numpy int32 arrays on the host -> (uint64 mask [sum_T, W], status, bad_node).  Validation variant:
+    status is TVA_OK or TVA_BAD_TREE (-5), bad_node the first offending global node index or -1."""
+    import numpy as np
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    cu_T = np.ascontiguousarray(cu_T, dtype=np.int32)
+    B = len(cu_T) - 1
+    W = max(1, (int(max_T) + 63) // 64)
+    mask = np.zeros((int(cu_T[-1]), W), np.uint64)
+    bad = ctypes.c_int32(-1)
+    rc = load_library().tva_build_ancestor_mask_host(parent.ctypes.data, cu_T.ctypes.data, B, int(max_T), W,
+                                                     mask.ctypes.data, ctypes.byref(bad))
+    if rc not in (TVA_OK, -5):
+        raise TvaError(rc)
+    return mask, rc, bad.value
 
 
 def build_ancestor_mask(parent, cu_T, max_T: int, mask=None, err_flag=None, stream=None):

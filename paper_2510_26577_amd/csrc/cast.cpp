@@ -1,6 +1,7 @@
-// Host part of libtva: the cost-aware choice of draft-tree sizes (paper, section "Method").
-// Plain C++ on host memory; the caller owns every buffer.  Entry points and their meaning are
-// declared in include/tva_cast.h.
+// Host part of libtva: the cost-aware choice of draft-tree sizes (paper, section "Method";
+// declared in include/tva_cast.h) and the host variant of the ancestor-mask builder with its
+// synchronous tree validation (include/tva.h).  Plain C++ on host memory; the caller owns every
+// buffer.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -35,6 +36,31 @@ inline int32_t table_row(int32_t c, int32_t L, int32_t M) { return std::min(c / 
 }  // namespace
 
 extern "C" {
+
+// Host variant of the ancestor-mask builder: one pass per tree, a node's mask is its own bit OR its
+// parent's mask (parents come first in the order the interface requires).
+int tva_build_ancestor_mask_host(const int32_t *parent, const int32_t *cu_T, int32_t B, int32_t max_T,
+                                 int32_t mask_words, uint64_t *mask, int32_t *bad_node) {
+  if (B < 0 || max_T < 0 || mask_words < 1 || (int64_t)mask_words * 64 < max_T) return TVA_INVALID_ARG;
+  if (B == 0) return TVA_OK;
+  if (!parent || !cu_T || !mask) return TVA_INVALID_ARG;
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t t0 = cu_T[b], T = cu_T[b + 1] - t0;
+    if (T < 0 || T > (int64_t)mask_words * 64) return TVA_INVALID_ARG;
+    for (int32_t i = 0; i < T; ++i) {
+      const int32_t p = parent[t0 + i];
+      if (p < -1 || p >= i) {
+        if (bad_node) *bad_node = t0 + i;
+        return TVA_BAD_TREE;
+      }
+      uint64_t *row = mask + (size_t)(t0 + i) * mask_words;
+      if (p < 0) std::memset(row, 0, sizeof(uint64_t) * mask_words);
+      else std::memcpy(row, mask + (size_t)(t0 + p) * mask_words, sizeof(uint64_t) * mask_words);
+      row[i / 64] |= 1ull << (i % 64);
+    }
+  }
+  return TVA_OK;
+}
 
 int32_t tva_cast_select_context(int32_t c, int32_t L, int32_t M) {
   if (c < 0 || L < 1 || M < 1) return TVA_INVALID_ARG;

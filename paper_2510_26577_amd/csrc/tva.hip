@@ -1230,6 +1230,7 @@ const char *tva_strerror(int code) {
     case TVA_UNSUPPORTED: return "unsupported shape";
     case TVA_WORKSPACE_TOO_SMALL: return "workspace too small";
     case TVA_HIP_ERROR: return "HIP launch error";
+    case TVA_BAD_TREE: return "malformed tree (parent index outside [-1, i-1])";
     default: return "unknown status";
   }
 }

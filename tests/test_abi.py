@@ -134,3 +134,26 @@ def test_no_oracle_in_product_path():
         if f.endswith((".py", ".c")):
             txt = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2510_26577_amd" not in txt and "libtva.so" not in txt and "tva.h" not in txt
+
+
+def test_host_mask_builder_matches_oracle_and_validates(lib):
+    """The host variant of the mask builder against the oracle's masks, and its synchronous tree check."""
+    import numpy as np
+    from oracle import tva_oracle as orc
+    from paper_2510_26577_amd import workloads as wl
+    rng = np.random.Generator(np.random.PCG64(5))
+    T = [1, 9, 64, 65, 128, 0, 33]
+    parent = np.concatenate([wl.tree_uniform(rng, t, 13) if t else np.zeros(0, np.int32) for t in T]).astype(np.int32)
+    cu_T = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    parent[cu_T[4] + 40] = -1                                   # a second root
+    mask, rc, bad = binding.build_ancestor_mask_host(parent, cu_T, 128)
+    assert rc == 0 and bad == -1
+    assert np.array_equal(mask, orc.ancestor_mask(parent, cu_T, words=2))
+    broken = parent.copy()
+    broken[cu_T[2] + 7] = 7                                     # points at itself
+    broken[cu_T[3] + 3] = 50                                    # points forward (a later node is also broken)
+    _, rc, bad = binding.build_ancestor_mask_host(broken, cu_T, 128)
+    assert rc == -5 and bad == cu_T[2] + 7
+    assert lib.tva_strerror(-5).startswith(b"malformed tree")
+    with pytest.raises(binding.TvaError):
+        binding.build_ancestor_mask_host(parent, cu_T, 64)      # max_T below the largest tree
