@@ -80,7 +80,11 @@ typedef struct tva_args {
   const int32_t *L;    /* device [B], each >= 0 */
   const void *q;       /* device bf16 [sum_T, Hq, D] */
   const void *k_tree;  /* device bf16 [sum_T, Hkv, D]: keys of the tree tokens */
-  const void *v_tree;  /* device bf16 [sum_T, Hkv, D] */
+  const void *v_tree;  /* device bf16 [sum_T, Hkv, D]
+                          Both NULL: the tree tokens' K/V are in the cache, token i of sequence b at
+                          position L[b] + i (dense: row cu_L[b] + L[b] + i, so cu_L leaves that room;
+                          paged: through the page table, which then covers L[b] + T_b positions).
+                          max_L must then not be below any L[b]. */
   const uint64_t *anc_mask; /* device [sum_T, mask_words]: bit j of row i set iff node j
                                is node i or one of its ancestors (tva_build_ancestor_mask);
                                or NULL, then `parent` below is used */

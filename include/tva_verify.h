@@ -47,6 +47,10 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
  * path entry that is not a node of the sequence's tree, is not written and, if err_flag is given (zero
  * on entry), stores 1 + b there.  The lengths, offsets and page numbers themselves are trusted.
  * L_out[b] = L[b] + path_len[b] is written when L_out is not NULL; it must not alias L.
+ *
+ * k_tree = v_tree = NULL selects the in-cache form: tree node i of sequence b already sits at cache
+ * position L[b] + i (the layout tva_tree_verify_attn reads when its k_tree is NULL), and the accepted
+ * nodes are moved down in place to L[b], L[b]+1, ...; everything behind them is left as it is.
  */
 typedef struct tva_commit_args {
   int32_t B, Hkv, D;   /* D * Hkv * 2 bytes per row must be a multiple of 16 */
@@ -54,7 +58,7 @@ typedef struct tva_commit_args {
   const int32_t *cu_T; /* device [B+1] */
   const int32_t *L;    /* device [B] */
   const int32_t *path, *path_len;  /* device [B, max_path], [B] (tva_accept_greedy's outputs) */
-  const void *k_tree, *v_tree;     /* device bf16 [cu_T[B], Hkv, D] */
+  const void *k_tree, *v_tree;     /* device bf16 [cu_T[B], Hkv, D]; both NULL = tree rows are in the cache */
   void *k_cache, *v_cache;         /* device bf16, dense or paged */
   const int32_t *cu_L;             /* device [B+1] or NULL */
   const int32_t *page_table;       /* device [B, max_pages] or NULL */

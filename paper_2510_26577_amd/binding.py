@@ -177,7 +177,7 @@ def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: 
     a = TvaArgs()
     a.B = cu_T.numel() - 1
     a.sum_T, a.Hq, a.D = int(q.shape[0]), int(q.shape[1]), int(q.shape[2])
-    a.Hkv = int(k_tree.shape[1])
+    a.Hkv = int(k_tree.shape[1]) if k_tree is not None else int(k_cache.shape[-2])
     a.max_T, a.max_L = int(max_T), int(max_L)
     a.mask_words = int(anc_mask.shape[1]) if anc_mask is not None else max(1, (int(max_T) + 63) // 64)
     a.scale = float(scale)

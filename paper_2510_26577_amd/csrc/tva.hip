@@ -372,15 +372,19 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   lds_byte *const pg_lds = lds + C::RING_BYTES + wave * (NLDK * 256);
   auto request_pages = [&](int t) __attribute__((always_inline)) {
     if (!PAGED) return;
-    const int base = k0 + t * TK;
+    // a tree tile whose keys live in the cache (no separate tree tensors): positions L_b + node
+    const bool tree_in_cache = t >= n_ct && p.k_tree == nullptr;
+    const int base = tree_in_cache ? Lb0 + (t - n_ct) * TK : k0 + t * TK;
+    const int last = tree_in_cache ? Lb0 + Tb - 1 : k1 - 1;
 #pragma unroll
     for (int j = 0; j < NLDK; ++j) {
       const int n = wave * NLDK + j;
       const int blk = n / IPB, part = n % IPB;
       int key = base + blk + NBLK * (part * RPI + lsub);
-      key = key < k1 ? key : k1 - 1;
+      key = key < last ? key : last;
       key = key < 0 ? 0 : key;
-      const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
+      int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
+      pidx = pidx < p.max_pages ? pidx : p.max_pages - 1;  // never past the sequence's row of the table
       const int32_t *src = p.page_table + (int64_t)b * p.max_pages + pidx;
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), pg_lds + (t & 1) * C::PG_SLOT + j * 256, 4, 0, 0);
     }
@@ -409,12 +413,28 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
       const int n = wave * NLDK + j;
       const int blk = n / IPB, part = n % IPB;
       const __bf16 *ksrc, *vsrc;
-      if (tree) {
+      if (tree && p.k_tree != nullptr) {
         int key = base + blk + NBLK * (part * RPI + lsub);
         key = key < limit ? key : limit - 1;
         const int64_t off = ((int64_t)(t0 + key) * p.Hkv + kvh) * D + lpos * 8;
         ksrc = p.k_tree + off;
         vsrc = p.v_tree + off;
+      } else if (tree) {
+        // tree keys stored in the cache behind the sequence's L_b committed tokens
+        int key = base + blk + NBLK * (part * RPI + lsub);
+        key = key < limit ? key : limit - 1;
+        const int pos = Lb0 + key;
+        int64_t off;
+        if (PAGED) {
+          const int pidx = p.page_shift >= 0 ? (pos >> p.page_shift) : (pos / p.page_size);
+          const int page = *reinterpret_cast<const __attribute__((address_space(3))) int *>(pg_lds + (t & 1) * C::PG_SLOT + j * 256 + lane * 4);
+          off = (int64_t)page * p.stride_page + (int64_t)(pos - pidx * p.page_size) * p.stride_tok +
+                (int64_t)kvh * p.stride_head + lpos * 8;
+        } else {
+          off = cache_base + (int64_t)pos * p.stride_tok + lpos * 8;
+        }
+        ksrc = p.k_cache + off;
+        vsrc = p.v_cache + off;
       } else if (PAGED) {
         int key = base + blk + NBLK * (part * RPI + lsub);
         key = key < limit ? key : limit - 1;
@@ -1258,13 +1278,18 @@ static int check_args(const tva_args *a, bool shapes_only) {
   if (shapes_only) return TVA_OK;
   if (!(a->scale > 0.f)) return TVA_INVALID_ARG;
   if (a->sum_T == 0) return TVA_OK;
-  if (!a->cu_T || !a->L || !a->q || !a->k_tree || !a->v_tree || !a->out || !a->lse) return TVA_INVALID_ARG;
+  if (!a->cu_T || !a->L || !a->q || !a->out || !a->lse) return TVA_INVALID_ARG;
+  if ((a->k_tree == nullptr) != (a->v_tree == nullptr)) return TVA_INVALID_ARG;
   if (!a->anc_mask && !a->parent) return TVA_INVALID_ARG;
   const bool dense = a->cu_L != nullptr, paged = a->page_table != nullptr;
   if (dense == paged) return TVA_INVALID_ARG;
-  if (a->max_L > 0 && (!a->k_cache || !a->v_cache)) return TVA_INVALID_ARG;
+  const bool tree_in_cache = a->k_tree == nullptr;
+  if ((a->max_L > 0 || tree_in_cache) && (!a->k_cache || !a->v_cache)) return TVA_INVALID_ARG;
   if (paged && (a->page_size <= 0 || a->max_pages <= 0)) return TVA_INVALID_ARG;
-  if (paged && (int64_t)a->max_pages * a->page_size < a->max_L) return TVA_INVALID_ARG;
+  // (with tree rows in the cache the table must cover L[b] + T_b positions of every sequence; only the two
+  // bounds are known here, and the longest cache need not belong to the largest tree)
+  if (paged && (int64_t)a->max_pages * a->page_size < (tree_in_cache && a->max_T > a->max_L ? a->max_T : a->max_L))
+    return TVA_INVALID_ARG;
   if ((a->stride_page | a->stride_tok | a->stride_head) % 8) return TVA_INVALID_ARG;
   if (a->stride_page < 0 || a->stride_tok < 0 || a->stride_head < 0) return TVA_INVALID_ARG;
   if (a->stride_tok >= (1 << 24)) return TVA_UNSUPPORTED;  // lane offsets inside a tile are 32-bit

@@ -9,6 +9,8 @@
 //                   per lane, straight from the tree tensors to the cache.  HBM-bound in principle
 //                   (read + write of 2 * Hkv * D * 2 bytes per accepted node), launch-bound at the
 //                   sizes a decode step has.
+//   compact_kernel  the same commit when the tree's K/V already sit in the cache behind the committed
+//                   tokens: the accepted rows move down in place, one workgroup per sequence.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -106,6 +108,48 @@ __global__ void __launch_bounds__(256) commit_kernel(const CommitParams p) {
   }
 }
 
+// Tree K/V already in the cache behind the L_b committed tokens (tree node i at position L_b + i):
+// the accepted nodes are moved down to positions L_b, L_b + 1, ...  One workgroup per sequence; a
+// thread owns the same 16-byte pieces of every row and takes the path in order.  Step j reads
+// position L_b + path[j] >= L_b + j and writes L_b + j, so a later step never reads what an earlier
+// one wrote, and a read that a later step overwrites comes first in the same thread's program order.
+__global__ void __launch_bounds__(256) compact_kernel(const CommitParams p) {
+  const int b = blockIdx.x;
+  const int n = p.path_len[b] < p.max_path ? p.path_len[b] : p.max_path;
+  const int Lb = p.L[b];
+  const int T = p.cu_T[b + 1] - p.cu_T[b];
+  if (threadIdx.x == 0 && p.L_out) p.L_out[b] = Lb + n;
+  if (Lb < 0) return;
+  const int per_head = p.D / 8;
+  const int pieces = p.Hkv * per_head;
+  auto row_offset = [&](int pos) -> int64_t {  // element offset of (position, head 0, d 0)
+    if (p.page_table) {
+      const int pi = pos / p.page_size;
+      const int page = p.page_table[(int64_t)b * p.max_pages + pi];
+      return (int64_t)page * p.stride_page + (int64_t)(pos - pi * p.page_size) * p.stride_tok;
+    }
+    return ((int64_t)p.cu_L[b] + pos) * p.stride_tok;
+  };
+  for (int j = 0; j < n; ++j) {
+    const int node = p.path[(size_t)b * p.max_path + j];
+    if (node < j || node >= T || (p.page_table && (Lb + node) / p.page_size >= p.max_pages)) {
+      // not a path of this tree (entries rise at least as fast as their position): stop here
+      if (threadIdx.x == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+      return;
+    }
+    if (node == j) continue;  // already in place
+    const int64_t src = row_offset(Lb + node), dst = row_offset(Lb + j);
+    for (int q = threadIdx.x; q < 2 * pieces; q += blockDim.x) {
+      const bool is_v = q >= pieces;
+      const int r = is_v ? q - pieces : q;
+      const int g = r / per_head, e = (r - g * per_head) * 8;
+      char *base = is_v ? p.v_cache : p.k_cache;
+      const int64_t inner = (int64_t)g * p.stride_head + e;
+      *reinterpret_cast<u32x4 *>(base + (dst + inner) * 2) = *reinterpret_cast<const u32x4 *>(base + (src + inner) * 2);
+    }
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -125,8 +169,9 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
 int tva_commit_path(const tva_commit_args *a, void *stream) {
   if (!a || a->B < 0 || a->Hkv < 1 || a->D < 8 || a->D % 8 || a->max_path < 1) return TVA_INVALID_ARG;
   if (a->B == 0) return TVA_OK;
-  if (!a->cu_T || !a->L || !a->path || !a->path_len || !a->k_tree || !a->v_tree || !a->k_cache || !a->v_cache)
-    return TVA_INVALID_ARG;
+  if (!a->cu_T || !a->L || !a->path || !a->path_len || !a->k_cache || !a->v_cache) return TVA_INVALID_ARG;
+  if ((a->k_tree == nullptr) != (a->v_tree == nullptr)) return TVA_INVALID_ARG;
+  const bool in_cache = a->k_tree == nullptr;
   const bool dense = a->cu_L != nullptr, paged = a->page_table != nullptr;
   if (dense == paged) return TVA_INVALID_ARG;
   if (paged && (a->page_size <= 0 || a->max_pages <= 0)) return TVA_INVALID_ARG;
@@ -146,7 +191,8 @@ int tva_commit_path(const tva_commit_args *a, void *stream) {
   p.stride_tok = a->stride_tok ? a->stride_tok : (int64_t)a->Hkv * a->D;
   p.stride_page = a->stride_page ? a->stride_page : (int64_t)p.page_size * p.stride_tok;
   (void)hipGetLastError();
-  hipLaunchKernelGGL(commit_kernel, dim3(a->max_path, a->B), dim3(256), 0, (hipStream_t)stream, p);
+  if (in_cache) hipLaunchKernelGGL(compact_kernel, dim3(a->B), dim3(256), 0, (hipStream_t)stream, p);
+  else hipLaunchKernelGGL(commit_kernel, dim3(a->max_path, a->B), dim3(256), 0, (hipStream_t)stream, p);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 

@@ -61,7 +61,7 @@ def make_commit_args(*, cu_T, L, path, path_len, k_tree, v_tree, k_cache, v_cach
                      page_size: int = 0, strides=(0, 0, 0), L_out=None, err_flag=None) -> CommitArgs:
     a = CommitArgs()
     a.B = cu_T.numel() - 1
-    a.Hkv, a.D = int(k_tree.shape[1]), int(k_tree.shape[2])
+    a.Hkv, a.D = int(k_cache.shape[-2]), int(k_cache.shape[-1])
     a.max_path = int(path.shape[1])
     a.cu_T, a.L, a.path, a.path_len = _p(cu_T), _p(L), _p(path), _p(path_len)
     a.k_tree, a.v_tree, a.k_cache, a.v_cache = _p(k_tree), _p(v_tree), _p(k_cache), _p(v_cache)

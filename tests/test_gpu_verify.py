@@ -212,3 +212,121 @@ def test_accept_then_commit_then_attend(torch_dev):
     ro, rl = orc.tree_verify_attn(w2)
     assert np.abs(out.cpu().numpy().astype(np.float64) - ro).max() <= 2e-3
     assert np.abs(lse.cpu().numpy().astype(np.float64) - rl).max() <= 1e-4
+
+
+def _in_cache_layout(w, rng, page_size=0):
+    """Re-stores a workload with its tree K/V appended to each sequence's cache: returns the host arrays
+    (k, v, cu_L or page_table).  Position t < L_b is cached token t, position L_b + i is tree node i."""
+    B, Hkv, D = w.B, w.Hkv, w.D
+    tot = w.L.astype(np.int64) + w.T.astype(np.int64)
+
+    def rows_of(b, cache, tree):
+        if w.paged:
+            src = np.stack([cache[w.page_table[b, t // w.page_size], t % w.page_size] for t in range(int(w.L[b]))]) \
+                if w.L[b] else np.zeros((0, Hkv, D), np.uint16)
+        else:
+            src = cache[w.cu_L[b]:w.cu_L[b] + w.L[b]]
+        return np.concatenate([src, tree[w.cu_T[b]:w.cu_T[b + 1]]])
+
+    if page_size == 0:
+        cu = np.concatenate([[0], np.cumsum(tot)]).astype(np.int32)
+        k = np.concatenate([rows_of(b, w.k_cache, w.k_tree) for b in range(B)])
+        v = np.concatenate([rows_of(b, w.v_cache, w.v_tree) for b in range(B)])
+        return k, v, cu, None
+    max_pages = int((tot.max() + page_size - 1) // page_size) + 1
+    table = rng.permutation(B * max_pages).reshape(B, max_pages).astype(np.int32)
+    k = rng.integers(0, 2 ** 16, (B * max_pages, page_size, Hkv, D)).astype(np.uint16) | np.uint16(0x7F80)  # NaN/inf filler
+    v = k.copy()
+    for b in range(B):
+        kr, vr = rows_of(b, w.k_cache, w.k_tree), rows_of(b, w.v_cache, w.v_tree)
+        for t in range(int(tot[b])):
+            k[table[b, t // page_size], t % page_size] = kr[t]
+            v[table[b, t // page_size], t % page_size] = vr[t]
+    return k, v, None, table
+
+
+@pytest.mark.parametrize("page_size", [0, 16, 3])
+@pytest.mark.parametrize("variant", [None, 4, 5, 6])
+def test_attention_with_tree_rows_in_the_cache(torch_dev, page_size, variant, monkeypatch):
+    """k_tree = v_tree = NULL: the kernel reads the tree tokens' K/V from cache positions L_b + i; the
+    result must equal the oracle's on the same values held in separate tree tensors."""
+    torch = torch_dev
+    from oracle import tva_oracle as orc
+    from paper_2510_26577_amd import binding
+    if variant is not None:
+        monkeypatch.setenv("TVA_FORCE_VARIANT", str(variant))
+    rng = np.random.Generator(np.random.PCG64(71 + page_size))
+    w = wl.random_workload(1000 + page_size, 4, 8, 2, 128, [300, 64, 0, 129], [70, 33, 8, 128], max_depth=12)
+    k, v, cu, table = _in_cache_layout(w, rng, page_size)
+    say(f"[case] in-cache tree rows, page_size={page_size} variant={variant}")
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    i16 = lambda a: a.view(np.int16)
+    q, cu_T, L, parent = dev(i16(w.q)), dev(w.cu_T), dev(w.L.astype(np.int32)), dev(w.parent)
+    for splits in (0, 3):
+        out, lse = binding.tree_verify_attn(q, None, None, dev(i16(k)), dev(i16(v)), None, cu_T, L, max_T=w.max_T,
+                                            max_L=w.max_L, scale=w.scale, cu_L=dev(cu), page_table=dev(table),
+                                            page_size=page_size, num_splits=splits, parent=parent)
+        torch.cuda.synchronize()
+        ro, rl = orc.tree_verify_attn(w)
+        assert np.isfinite(out.cpu().numpy()).all()
+        assert np.abs(out.cpu().numpy().astype(np.float64) - ro).max() <= 2e-3
+        assert np.abs(lse.cpu().numpy().astype(np.float64) - rl).max() <= 1e-4
+
+
+@pytest.mark.parametrize("page_size", [0, 16, 5])
+def test_commit_in_place_for_tree_rows_in_the_cache(torch_dev, page_size):
+    torch = torch_dev
+    from paper_2510_26577_amd import verify
+    rng = np.random.Generator(np.random.PCG64(81 + page_size))
+    B = 5
+    T = np.array([40, 1, 9, 72, 17])
+    L = np.array([100, 0, 31, 5, 64], np.int32)
+    w = wl.random_workload(1100 + page_size, B, 4, 4, 128, L, T, max_depth=13)
+    k, v, cu, table = _in_cache_layout(w, rng, page_size)
+    # deep trees (each parent among the two previous nodes) so that accepted paths get long
+    deep = np.concatenate([np.array([-1] + [int(rng.integers(max(0, i - 2), i)) for i in range(1, int(t))], np.int32)
+                           for t in T])
+    draft, target = make_tokens(rng, deep, w.cu_T, vocab=40, plant=0.95)
+    paths, _ = vo.accept_greedy(deep, w.cu_T, draft, target, max_path=16)
+    assert max(len(p) for p in paths) >= 6 and any(p != list(range(len(p))) for p in paths)
+    max_path = 16
+    path = np.full((B, max_path), -1, np.int32)
+    for b, p in enumerate(paths):
+        path[b, :len(p)] = p
+    plen = np.array([len(p) for p in paths], np.int32)
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    i16 = lambda a: a.view(np.int16)
+    k_d, v_d = dev(i16(k)), dev(i16(v))
+    L_out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    say(f"[case] in-place commit, page_size={page_size}")
+    verify.commit_path(cu_T=dev(w.cu_T), L=dev(L), path=dev(path), path_len=dev(plen), k_tree=None, v_tree=None,
+                       k_cache=k_d, v_cache=v_d, cu_L=dev(cu), page_table=dev(table), page_size=page_size,
+                       L_out=L_out, err_flag=err)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    # expected: position L_b + j holds the old row of position L_b + path[j]; every other position is unchanged
+    k_ref, v_ref = k.copy(), v.copy()
+
+    def at(arr, b, t):
+        return arr[cu[b] + t] if page_size == 0 else arr[table[b, t // page_size], t % page_size]
+
+    for b, p in enumerate(paths):
+        for j, node in enumerate(p):
+            if page_size == 0:
+                k_ref[cu[b] + L[b] + j], v_ref[cu[b] + L[b] + j] = at(k, b, L[b] + node), at(v, b, L[b] + node)
+            else:
+                t = L[b] + j
+                k_ref[table[b, t // page_size], t % page_size] = at(k, b, L[b] + node)
+                v_ref[table[b, t // page_size], t % page_size] = at(v, b, L[b] + node)
+    assert np.array_equal(k_d.cpu().numpy().view(np.uint16), k_ref) and np.array_equal(v_d.cpu().numpy().view(np.uint16), v_ref)
+    assert np.array_equal(L_out.cpu().numpy(), L + plen)
+    # a row that is not a rising path is refused
+    bad = path.copy()
+    b_long = int(np.argmax(plen))
+    bad[b_long, 1] = 0
+    err.zero_()
+    verify.commit_path(cu_T=dev(w.cu_T), L=dev(L), path=dev(bad), path_len=dev(plen), k_tree=None, v_tree=None,
+                       k_cache=k_d, v_cache=v_d, cu_L=dev(cu), page_table=dev(table), page_size=page_size, err_flag=err)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 1 + b_long
