@@ -95,7 +95,7 @@ typedef struct tva_args {
   int32_t page_size, max_pages;  /* paged form only */
   int64_t stride_page, stride_tok, stride_head; /* elements; 0 = packed default */
 
-  float *out; /* device fp32 [sum_T, Hq, D] */
+  float *out; /* device fp32 [sum_T, Hq, D]  (sum_Q rows with cu_Q, below) */
   float *lse; /* device fp32 [sum_T, Hq]: natural-log sum-exp of the scaled scores */
 
   void *workspace;        /* device scratch for the KV splits, may be NULL if 0 bytes */
@@ -108,6 +108,16 @@ typedef struct tva_args {
                              tva_build_ancestor_mask; no separate launch, nothing written).  A link
                              that does not point backwards is not reported here: it just ends that
                              node's walk -- validate with tva_build_ancestor_mask's err_flag. */
+
+  const int32_t *cu_Q;    /* device int32 [B+1] or NULL.  NULL: every tree node is a query (q, out, lse have
+                             sum_T rows).  Else only the LAST cu_Q[b+1]-cu_Q[b] nodes of sequence b's tree
+                             are queries -- the keys are still all T_b nodes under the ancestor mask -- and
+                             q / out / lse have sum_Q = cu_Q[B] rows, row cu_Q[b] + i being node
+                             T_b - Tq_b + i.  This is the draft model's attention while the tree is being
+                             grown: the nodes of the newest layer attend to the context and to their
+                             ancestors in the layers before (paper, Tree Expansion Phase). */
+  int32_t sum_Q, max_Q;   /* with cu_Q: cu_Q[B] and a host-side upper bound of the per-sequence count
+                             (<= max_T); ignored otherwise */
 } tva_args;
 
 /*

@@ -22,7 +22,7 @@ INCLUDE_DIR = os.path.join(_ROOT, "include")
 
 TVA_OK = 0
 TVA_MAX_TREE = 128
-EXPECTED_VERSION = 2
+EXPECTED_VERSION = 3
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -59,6 +59,7 @@ class TvaArgs(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("num_splits", ctypes.c_int32),
         ("parent", ctypes.c_void_p),
+        ("cu_Q", ctypes.c_void_p), ("sum_Q", ctypes.c_int32), ("max_Q", ctypes.c_int32),
     ]
 
 
@@ -172,11 +173,17 @@ def build_ancestor_mask(parent, cu_T, max_T: int, mask=None, err_flag=None, stre
 
 def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: int, max_L: int,
               scale: float, cu_L=None, page_table=None, page_size: int = 0, strides=(0, 0, 0),
-              num_splits: int = 0, out=None, lse=None, workspace=None, parent=None) -> TvaArgs:
-    """Fill `tva_args` from tensors (q [sum_T,Hq,D], k_tree [sum_T,Hkv,D], ...)."""
+              num_splits: int = 0, out=None, lse=None, workspace=None, parent=None, cu_Q=None, max_Q: int = 0,
+              sum_T: Optional[int] = None) -> TvaArgs:
+    """Fill `tva_args` from tensors (q [sum_T,Hq,D], k_tree [sum_T,Hkv,D], ...).  With cu_Q (queries =
+    the last nodes of each tree) q has sum_Q rows and sum_T comes from k_tree or the sum_T argument."""
     a = TvaArgs()
     a.B = cu_T.numel() - 1
     a.sum_T, a.Hq, a.D = int(q.shape[0]), int(q.shape[1]), int(q.shape[2])
+    if cu_Q is not None:
+        a.sum_Q, a.max_Q = int(q.shape[0]), int(max_Q)
+        a.sum_T = int(sum_T) if sum_T is not None else int(k_tree.shape[0])
+    a.cu_Q = _p(cu_Q)
     a.Hkv = int(k_tree.shape[1]) if k_tree is not None else int(k_cache.shape[-2])
     a.max_T, a.max_L = int(max_T), int(max_L)
     a.mask_words = int(anc_mask.shape[1]) if anc_mask is not None else max(1, (int(max_T) + 63) // 64)
@@ -194,7 +201,7 @@ def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: 
     a.num_splits = int(num_splits)
     a.parent = _p(parent)
     # the struct holds raw addresses: keep the tensors alive as long as it lives
-    a._keep = (q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, cu_L, page_table, out, lse, workspace, parent)
+    a._keep = (q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, cu_L, page_table, out, lse, workspace, parent, cu_Q)
     return a
 
 
@@ -231,7 +238,8 @@ def tree_verify_attn_splits_raw(args: TvaArgs, stream=None) -> None:
 
 def tree_verify_attn(q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, *, max_T: int, max_L: int,
                      scale: float, cu_L=None, page_table=None, page_size: int = 0, strides=(0, 0, 0),
-                     num_splits: int = 0, out=None, lse=None, workspace=None, stream=None, parent=None):
+                     num_splits: int = 0, out=None, lse=None, workspace=None, stream=None, parent=None, cu_Q=None,
+                     max_Q: int = 0, sum_T: Optional[int] = None):
     """Tree-masked verification attention.  Returns (out fp32 [sum_T,Hq,D], lse fp32 [sum_T,Hq]).
     bf16 tensors may be torch.bfloat16 or int16/uint16 bit patterns.  anc_mask may be None when the
     trees' parent array (int32 [sum_T]) is passed instead: the kernel then derives the masks itself."""
@@ -242,7 +250,8 @@ def tree_verify_attn(q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, *, 
         lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
     args = make_args(q=q, k_tree=k_tree, v_tree=v_tree, k_cache=k_cache, v_cache=v_cache, anc_mask=anc_mask,
                      cu_T=cu_T, L=L, max_T=max_T, max_L=max_L, scale=scale, cu_L=cu_L, page_table=page_table,
-                     page_size=page_size, strides=strides, num_splits=num_splits, out=out, lse=lse, parent=parent)
+                     page_size=page_size, strides=strides, num_splits=num_splits, out=out, lse=lse, parent=parent,
+                     cu_Q=cu_Q, max_Q=max_Q, sum_T=sum_T)
     need = workspace_bytes(args)
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty((need + 3) // 4, dtype=torch.float32, device=q.device)

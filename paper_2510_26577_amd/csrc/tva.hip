@@ -106,11 +106,12 @@ __global__ void anc_mask_kernel(const int32_t *__restrict__ parent, const int32_
 struct AttnParams {
   const __bf16 *q, *k_tree, *v_tree, *k_cache, *v_cache;
   const int32_t *cu_T, *L, *cu_L, *page_table;
+  const int32_t *cu_Q;  // null: every tree node is a query; else the last cu_Q[b+1]-cu_Q[b] nodes are
   const uint64_t *mask;
   const int32_t *parent;  // used when mask is null: ancestor masks are derived in the kernel
   float *out, *lse;            // final results
-  float *part_out, *part_lse;  // [S, sum_T, Hq, D], [S, sum_T, Hq] when S > 1
-  int B, Hq, Hkv, G, g_shift, sum_T, W;
+  float *part_out, *part_lse;  // [S, sum_Q, Hq, D], [S, sum_Q, Hq] when S > 1
+  int B, Hq, Hkv, G, g_shift, sum_Q, W;  // sum_Q: query rows of the whole batch (= sum_T without cu_Q)
   int chunk_keys, n_chunks, n_row_blocks, max_L;
   int page_size, page_shift, max_pages;
   int64_t stride_page, stride_tok, stride_head;
@@ -285,9 +286,16 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   int cuL = PAGED ? 0 : ((const_i32 *)(uintptr_t)p.cu_L)[b];
   // (an empty statement that ties them together: keeps the compiler from moving one of the loads
   // down to its first use, where the wave would wait for it alone)
-  asm("" : "+s"(t0), "+s"(t1), "+s"(Lb0), "+s"(cuL));
+  int q0 = p.cu_Q ? ((const_i32 *)(uintptr_t)p.cu_Q)[b] : 0;
+  int q1 = p.cu_Q ? ((const_i32 *)(uintptr_t)p.cu_Q)[b + 1] : 0;
+  asm("" : "+s"(t0), "+s"(t1), "+s"(Lb0), "+s"(cuL), "+s"(q0), "+s"(q1));
   const int Tb = t1 - t0;
-  const int R = Tb * p.G;
+  // query nodes: all T_b of the tree, or (draft-stage use: one expansion layer attends to the layers
+  // before it) only its last Tq; tq0 is the first query row of the sequence in q / out / lse
+  const int Tq = p.cu_Q ? (q1 - q0 < Tb ? q1 - q0 : Tb) : Tb;
+  const int tq0 = p.cu_Q ? q0 : t0;
+  const int node_off = Tb - Tq;
+  const int R = Tq * p.G;
   if (rblk * BM >= R) return;
   const int Lb = Lb0 < p.max_L ? Lb0 : p.max_L;
   int nc = (Lb + p.chunk_keys - 1) / p.chunk_keys;
@@ -296,7 +304,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     // this sequence has fewer chunks than the launch provides: mark the slot empty for the merge
     for (int row = rblk * BM + (int)threadIdx.x; row < R && row < (rblk + 1) * BM; row += blockDim.x) {
       const int t = p.g_shift >= 0 ? (row >> p.g_shift) : row / p.G, g = row - t * p.G;
-      p.part_lse[(size_t)chunk * p.sum_T * p.Hq + (size_t)(t0 + t) * p.Hq + kvh * p.G + g] = -INFINITY;
+      p.part_lse[(size_t)chunk * p.sum_Q * p.Hq + (size_t)(tq0 + t) * p.Hq + kvh * p.G + g] = -INFINITY;
     }
     return;
   }
@@ -328,7 +336,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     const int rowc = rvalid[r] ? row : R - 1;
     const int t = p.g_shift >= 0 ? (rowc >> p.g_shift) : rowc / p.G;
     const int g = rowc - t * p.G;
-    orow[r] = (int64_t)(t0 + t) * p.Hq + kvh * p.G + g;
+    orow[r] = (int64_t)(tq0 + t) * p.Hq + kvh * p.G + g;
     const __bf16 *qp = p.q + orow[r] * D + 8 * hh;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -338,7 +346,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     // is in the tree tiles, so nothing waits for them before the key loads have been queued
     mrow[r][0] = mrow[r][1] = 0;
     if (has_tree && p.mask != nullptr) {
-      const auto *mp = (const __attribute__((address_space(1))) uint64_t *)(uintptr_t)(p.mask + (size_t)(t0 + t) * p.W);
+      const auto *mp = (const __attribute__((address_space(1))) uint64_t *)(uintptr_t)(p.mask + (size_t)(t0 + node_off + t) * p.W);
       mrow[r][0] = mp[0];
       if (p.W > 1) mrow[r][1] = mp[1];
     }
@@ -881,7 +889,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     for (int r = 0; r < RB; ++r) {
       const int row = rblk * BM + (wm * RB + r) * 32 + l32;
       const int rowc = row < R ? row : R - 1;
-      int node = p.g_shift >= 0 ? (rowc >> p.g_shift) : rowc / p.G;
+      int node = node_off + (p.g_shift >= 0 ? (rowc >> p.g_shift) : rowc / p.G);
       uint64_t b0 = 0, b1 = 0;
       for (int step = 0; step < Tb && node >= 0; ++step) {
         if (node < 64) b0 |= 1ull << node;
@@ -1043,8 +1051,8 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   // wave transposes one 32-row block at a time through its own LDS patch so that global stores
   // are whole contiguous rows (of the half of the head dimension the wave holds, when paired).
   const bool final_out = (p.n_chunks == 1);
-  float *obase = final_out ? p.out : p.part_out + (size_t)chunk * p.sum_T * p.Hq * D;
-  float *lbase = final_out ? p.lse : p.part_lse + (size_t)chunk * p.sum_T * p.Hq;
+  float *obase = final_out ? p.out : p.part_out + (size_t)chunk * p.sum_Q * p.Hq * D;
+  float *lbase = final_out ? p.lse : p.part_lse + (size_t)chunk * p.sum_Q * p.Hq;
   constexpr int NDW = C::NDW;       // 32-wide d blocks this wave writes
   constexpr int TP = C::TP;         // patch row pitch in floats: 16 rows x 16 B apart in bank position
   constexpr int LPR = NDW * 8;      // lanes that cover one row piece with 16 bytes each
@@ -1070,7 +1078,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
         const int rl = i * RPP + lane / LPR;
         const int row = row0 + rl;
         const int t = p.g_shift >= 0 ? (row >> p.g_shift) : row / p.G;
-        const int64_t og = (int64_t)(t0 + t) * p.Hq + kvh * p.G + (row - t * p.G);
+        const int64_t og = (int64_t)(tq0 + t) * p.Hq + kvh * p.G + (row - t * p.G);
         const f32x4 v = *reinterpret_cast<const f32x4 *>(tbuf + rl * TP + (lane % LPR) * 4);
         if (row < R) *reinterpret_cast<f32x4 *>(obase + og * D + 32 * d0 + (lane % LPR) * 4) = v;
       }
@@ -1143,11 +1151,14 @@ struct Plan {
 
 enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5, V_K2 = 6, V_K2R2 = 7, V_M2K2 = 8, V_W4D = 9, V_M2K2_3 = 10, V_M2K2_4 = 11 };
 
+// query rows of the whole batch: every tree node, or only the nodes cu_Q selects
+inline int64_t query_rows(const tva_args *a) { return a->cu_Q ? a->sum_Q : a->sum_T; }
+
 bool make_plan(const tva_args *a, Plan *pl) {
   if (!a || a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv) return false;
   if (a->sum_T < 0 || a->max_T < 0 || a->max_L < 0 || a->num_splits < 0) return false;
   const int G = a->Hq / a->Hkv;
-  const int rows = a->max_T * G;
+  const int rows = (a->cu_Q ? a->max_Q : a->max_T) * G;
   // Workgroup shape, from sweeps over the benchmark shapes.  Up to 32 rows per KV head: 32-row
   // workgroups of two waves that split the keys of 64-key tiles.  Up to 128 rows, or more rows
   // but few (sequence, KV head) pairs: 64-row workgroups of 2 x 2 waves (two row groups x two key
@@ -1233,7 +1244,7 @@ hipError_t dispatch_variant(int variant, const AttnParams &p, dim3 grid, hipStre
 
 extern "C" {
 
-int tva_version(void) { return 2; }
+int tva_version(void) { return 3; }
 
 size_t tva_sizeof_args(void) { return sizeof(tva_args); }
 
@@ -1277,6 +1288,7 @@ static int check_args(const tva_args *a, bool shapes_only) {
   if (a->mask_words < 1 || a->mask_words > 2 || a->mask_words * 64 < a->max_T) return TVA_UNSUPPORTED;
   if (shapes_only) return TVA_OK;
   if (!(a->scale > 0.f)) return TVA_INVALID_ARG;
+  if (a->cu_Q && (a->sum_Q < 0 || a->max_Q < 0 || a->max_Q > a->max_T || a->sum_Q > a->sum_T)) return TVA_INVALID_ARG;
   if (a->sum_T == 0) return TVA_OK;
   if (!a->cu_T || !a->L || !a->q || !a->out || !a->lse) return TVA_INVALID_ARG;
   if ((a->k_tree == nullptr) != (a->v_tree == nullptr)) return TVA_INVALID_ARG;
@@ -1315,7 +1327,7 @@ size_t tva_workspace_bytes(const tva_args *a) {
   Plan pl;
   if (!make_plan(a, &pl)) return (size_t)-1;
   if (pl.n_chunks <= 1) return 0;
-  return (size_t)pl.n_chunks * a->sum_T * a->Hq * (a->D + 1) * sizeof(float);
+  return (size_t)pl.n_chunks * query_rows(a) * a->Hq * (a->D + 1) * sizeof(float);
 }
 
 static int run_attention(const tva_args *a, void *stream, bool merge);
@@ -1327,10 +1339,10 @@ int tva_tree_verify_attn_splits(const tva_args *a, void *stream) { return run_at
 static int run_attention(const tva_args *a, void *stream, bool merge) {
   int rc = check_args(a, false);
   if (rc != TVA_OK) return rc;
-  if (a->sum_T == 0 || a->max_T == 0) return TVA_OK;
+  if (a->sum_T == 0 || a->max_T == 0 || query_rows(a) == 0) return TVA_OK;
   Plan pl;
   if (!make_plan(a, &pl)) return TVA_INVALID_ARG;
-  const size_t need = pl.n_chunks > 1 ? (size_t)pl.n_chunks * a->sum_T * a->Hq * (a->D + 1) * sizeof(float) : 0;
+  const size_t need = pl.n_chunks > 1 ? (size_t)pl.n_chunks * query_rows(a) * a->Hq * (a->D + 1) * sizeof(float) : 0;
   if (need > 0 && (!a->workspace || a->workspace_bytes < need)) return TVA_WORKSPACE_TOO_SMALL;
 
   AttnParams p;
@@ -1348,7 +1360,7 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   p.out = a->out;
   p.lse = a->lse;
   p.part_out = (float *)a->workspace;
-  p.part_lse = p.part_out ? p.part_out + (size_t)pl.n_chunks * a->sum_T * a->Hq * a->D : nullptr;
+  p.part_lse = p.part_out ? p.part_out + (size_t)pl.n_chunks * query_rows(a) * a->Hq * a->D : nullptr;
   p.B = a->B;
   p.Hq = a->Hq;
   p.Hkv = a->Hkv;
@@ -1356,7 +1368,8 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   p.g_shift = -1;
   for (int sft = 0; sft < 31; ++sft)
     if ((1 << sft) == p.G) p.g_shift = sft;
-  p.sum_T = a->sum_T;
+  p.sum_Q = (int)query_rows(a);
+  p.cu_Q = a->cu_Q;
   p.W = a->mask_words;
   p.chunk_keys = pl.chunk_keys;
   p.n_chunks = pl.n_chunks;
@@ -1384,7 +1397,7 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   if (e != hipSuccess) return TVA_HIP_ERROR;
 
   if (merge && pl.n_chunks > 1) {
-    const int64_t n_rows = (int64_t)a->sum_T * a->Hq;
+    const int64_t n_rows = (int64_t)query_rows(a) * a->Hq;
     const int mgrid = (int)((n_rows + 3) / 4);
     clear_stale_hip_error();
     if (a->D == 128)

@@ -189,6 +189,39 @@ def test_masks_derived_in_kernel_equal_masks_passed(gpu, case):
     assert np.abs(lse_b.cpu().numpy().astype(np.float64) - rl).max() <= TOL_LSE
 
 
+@pytest.mark.parametrize("variant", [None, 4, 5, 6, 8])
+@pytest.mark.parametrize("page_size", [0, 16])
+def test_queries_are_the_last_nodes_of_each_tree(gpu, page_size, variant, monkeypatch):
+    """cu_Q: only the last Tq_b nodes of each tree are queries (the draft model's attention for the newest
+    expansion layer); keys stay all T_b nodes.  Rows must equal the oracle's rows of those nodes."""
+    import torch
+    from paper_2510_26577_amd import binding
+    if variant is not None:
+        monkeypatch.setenv("TVA_FORCE_VARIANT", str(variant))
+    w = wl.random_workload(1200 + page_size, 5, 8, 2, 128, [400, 70, 0, 33, 129], [72, 30, 5, 12, 128], max_depth=13,
+                           page_size=page_size)
+    Tq = np.array([12, 30, 1, 0, 60])                    # newest layer sizes (whole tree, one node, none, ...)
+    cu_Q = np.concatenate([[0], np.cumsum(Tq)]).astype(np.int32)
+    sel = np.concatenate([np.arange(w.cu_T[b + 1] - Tq[b], w.cu_T[b + 1]) for b in range(w.B)]).astype(np.int64)
+    say(f"[case] query subset page_size={page_size} variant={variant} Tq={list(Tq)}")
+    dw = gpu.to_device(w)
+    q_sub = dw.q[torch.from_numpy(sel).to(dw.q.device)].contiguous()
+    ro, rl = orc.tree_verify_attn(w)
+    mask = gpu.build_mask(dw)
+    for use_mask in (True, False):
+        for splits in (0, 3):
+            out, lse = binding.tree_verify_attn(
+                q_sub, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, mask if use_mask else None, dw.cu_T, dw.L,
+                max_T=w.max_T, max_L=w.max_L, scale=w.scale, cu_L=dw.cu_L, page_table=dw.page_table,
+                page_size=w.page_size, num_splits=splits, parent=None if use_mask else dw.parent,
+                cu_Q=torch.from_numpy(cu_Q).to(dw.q.device), max_Q=int(Tq.max()))
+            torch.cuda.synchronize()
+            assert out.shape[0] == len(sel)
+            eo = np.abs(out.cpu().numpy().astype(np.float64) - ro[sel]).max()
+            el = np.abs(lse.cpu().numpy().astype(np.float64) - rl[sel]).max()
+            assert eo <= TOL_O and el <= TOL_LSE
+
+
 def test_empty_trees_in_batch_and_chain_and_star(gpu):
     rng = np.random.Generator(np.random.PCG64(500))
     trees = [wl.tree_chain(13), np.zeros(0, np.int32), wl.tree_star(30), wl.tree_chain(1)]
