@@ -18,7 +18,18 @@
 // stays in its natural [key][d] layout.  Waves of a workgroup are arranged
 // WM x WK: WM groups own different query rows, WK groups own different keys of
 // each tile and are merged through LDS at the end (used when few rows share a
-// KV head, so that the workgroup still has four waves streaming keys).
+// KV head, so that the workgroup still has several waves streaming keys).
+//
+// Every load on the key path is an LDS-writing load the compiler does not track
+// (tiles, page-table entries, the tree's parent array), and every wait on them
+// is written by hand as a count of the operations queued behind the one waited
+// for: left to the compiler, any register it believes pending costs a
+// vmcnt(0), which drains the prefetched tiles.
+//
+// Variants of the inputs handled by the same kernel: dense or paged cache;
+// tree K/V in their own tensors or in the cache behind the committed tokens;
+// ancestor sets passed as bitmasks or derived here from the parent array; all
+// tree nodes as queries or only the last ones of each tree.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -1166,7 +1177,7 @@ bool make_plan(const tva_args *a, Plan *pl) {
   // each other's start-up and drain.  Otherwise eight waves of 32 rows each (256 rows, two waves
   // per SIMD), which fill the chip with few KV splits.
   int variant = rows <= 32 ? V_K2 : (rows > 128 && a->B * a->Hkv >= 32) ? V_W8 : V_M2K2;
-  // benchmarking aid: TVA_FORCE_VARIANT=0..9 picks the workgroup shape
+  // benchmarking and test aid: TVA_FORCE_VARIANT=0..11 picks the workgroup shape
   if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
     const int v = atoi(fv);
     if (v >= V_R256 && v <= V_M2K2_4) variant = v;
