@@ -118,7 +118,7 @@ def test_tree_size_edges(gpu, T):
     check_full(gpu, wl.random_workload(200 + T, 1, 4, 2, 128, [75], [T], max_depth=13), label=f"T={T}")
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 4), (8, 2), (8, 1), (16, 1)])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 4), (8, 2), (8, 1), (16, 1), (6, 2), (12, 4), (10, 2), (14, 2), (7, 1)])
 @pytest.mark.parametrize("D", [64, 128])
 def test_gqa_groups_and_head_dims(gpu, Hq, Hkv, D):
     check_full(gpu, wl.random_workload(300 + Hq + Hkv + D, 2, Hq, Hkv, D, [150, 33], [20, 11]),
