@@ -1170,17 +1170,23 @@ bool make_plan(const tva_args *a, Plan *pl) {
   if (a->sum_T < 0 || a->max_T < 0 || a->max_L < 0 || a->num_splits < 0) return false;
   const int G = a->Hq / a->Hkv;
   const int rows = (a->cu_Q ? a->max_Q : a->max_T) * G;
-  // Workgroup shape, from sweeps over the benchmark shapes.  Up to 32 rows per KV head: 32-row
-  // workgroups of two waves that split the keys of 64-key tiles.  Up to 128 rows, or more rows
-  // but few (sequence, KV head) pairs: 64-row workgroups of 2 x 2 waves (two row groups x two key
-  // groups).  Both keep a two-stage ring, small enough that two workgroups share a CU and hide
-  // each other's start-up and drain.  Otherwise eight waves of 32 rows each (256 rows, two waves
-  // per SIMD), which fill the chip with few KV splits.
-  int variant = rows <= 32 ? V_K2 : (rows > 128 && a->B * a->Hkv >= 32) ? V_W8 : V_M2K2;
+  // Workgroup shape, from sweeps over the benchmark shapes and batch / length variations of them.
+  // Up to 32 rows per KV head: 32-row workgroups of two waves that split the keys of 64-key tiles.
+  // More rows: 64-row workgroups of 2 x 2 waves (two row groups x two key groups).  Both keep a
+  // two-stage ring, small enough that two workgroups share a CU and hide each other's start-up
+  // and drain.  128 rows or more AND enough keys in all that re-reading them per 64 rows costs
+  // more than the splits and idle start-up of a larger workgroup -- half a million keys over the
+  // (sequence, KV head) pairs, or half of that when the caches are long -- : eight waves of 32 rows
+  // each (256 rows, two waves per SIMD), which read every key once per pair.
+  const int pairs = a->B * a->Hkv;
+  const int64_t keys = (int64_t)pairs * a->max_L;
+  const bool eight_waves = rows >= 128 && (keys >= (512 << 10) || (keys >= (256 << 10) && a->max_L >= 4096));
+  int variant = rows <= 32 ? V_K2 : eight_waves ? V_W8 : V_M2K2;
   // benchmarking and test aid: TVA_FORCE_VARIANT=0..11 picks the workgroup shape
+  bool forced = false;
   if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
     const int v = atoi(fv);
-    if (v >= V_R256 && v <= V_M2K2_4) variant = v;
+    if (v >= V_R256 && v <= V_M2K2_4) variant = v, forced = true;
   }
   pl->variant = variant;
   pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4 || variant == V_W4D) ? 128 : (variant == V_R64 || variant == V_M2K2 || variant == V_M2K2_3 || variant == V_M2K2_4) ? 64 : 32;
@@ -1192,9 +1198,16 @@ bool make_plan(const tva_args *a, Plan *pl) {
     // one workgroup per CU (256) if the batch allows, but no split shorter than two tiles:
     // every split costs a partial O of the size of the output, written and read back
     const int natural = a->B * a->Hkv * pl->n_row_blocks;
-    S = (256 + natural - 1) / natural;
+    S = natural * 3 >= 512 ? 1 : (256 + natural - 1) / natural;  // two thirds of the CUs busy beats a merge pass
     const int cap = a->max_L > 0 ? (a->max_L + 2 * pl->TK - 1) / (2 * pl->TK) : 1;
     if (S > cap) S = cap;
+    if (variant == V_M2K2) {
+      // two of these workgroups fit a CU: go on to 512 of them while a split keeps 16 tiles or more
+      int s2 = (512 + natural - 1) / natural;
+      const int by_len = a->max_L / (16 * pl->TK);
+      s2 = s2 < by_len ? s2 : by_len;
+      if (s2 > S) S = s2;
+    }
   }
   if (S > max_by_len) S = max_by_len;
   if (S < 1) S = 1;
@@ -1202,6 +1215,10 @@ bool make_plan(const tva_args *a, Plan *pl) {
   ck = (ck + pl->TK - 1) / pl->TK * pl->TK;
   pl->chunk_keys = ck;
   pl->n_chunks = a->max_L > 0 ? (a->max_L + ck - 1) / ck : 1;
+  // one 2 x 2 workgroup per CU at most and long splits: a third ring stage (two tiles in flight)
+  // pays; with more workgroups the second one on the CU hides more than the deeper ring would
+  if (pl->variant == V_M2K2 && !forced && (int64_t)pairs * pl->n_row_blocks * pl->n_chunks <= 256 && ck >= 12 * pl->TK)
+    pl->variant = V_M2K2_3;
   return true;
 }
 
