@@ -330,3 +330,78 @@ def test_commit_in_place_for_tree_rows_in_the_cache(torch_dev, page_size):
                        k_cache=k_d, v_cache=v_d, cu_L=dev(cu), page_table=dev(table), page_size=page_size, err_flag=err)
     torch.cuda.synchronize()
     assert int(err.item()) == 1 + b_long
+
+
+@pytest.mark.parametrize("page_size", [0, 16])
+def test_whole_pass_replayed_from_a_graph(torch_dev, page_size):
+    """Attention on tree rows held in the cache, acceptance and in-place commit captured in one HIP graph:
+    every replay (cache restored by eager work in between) must reproduce the eager pass bit for bit."""
+    torch = torch_dev
+    from paper_2510_26577_amd import binding, verify
+    rng = np.random.Generator(np.random.PCG64(91 + page_size))
+    B, Hq, Hkv, D = 6, 8, 2, 128
+    L = np.array([700, 0, 129, 64, 2048, 33], np.int32)
+    T = np.array([60, 7, 33, 1, 48, 72])
+    w = wl.random_workload(1200 + page_size, B, Hq, Hkv, D, L, T, max_depth=10)
+    k, v, cu, table = _in_cache_layout(w, rng, page_size)
+    draft, target = make_tokens(rng, w.parent, w.cu_T, vocab=25, plant=0.9)
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    i16 = lambda a: a.view(np.int16)
+    q, cu_T, L_d, parent = dev(i16(w.q)), dev(w.cu_T), dev(L), dev(w.parent)
+    k0, v0 = dev(i16(k)), dev(i16(v))
+    k_d, v_d = k0.clone(), v0.clone()
+    cu_d, table_d = dev(cu), dev(table)
+    draft_d, target_d = dev(draft), dev(target)
+    max_path = 12
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    lse = torch.empty(q.shape[:2], dtype=torch.float32, device="cuda")
+    path = torch.full((B, max_path), -1, dtype=torch.int32, device="cuda")
+    plen = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
+    L_out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    args = binding.make_args(q=q, k_tree=None, v_tree=None, k_cache=k_d, v_cache=v_d, anc_mask=None, cu_T=cu_T, L=L_d,
+                             max_T=w.max_T, max_L=w.max_L, scale=w.scale, cu_L=cu_d, page_table=table_d,
+                             page_size=page_size, num_splits=3, out=out, lse=lse, parent=parent)
+    ws = torch.empty((binding.workspace_bytes(args) + 3) // 4, dtype=torch.float32, device="cuda")
+    args.workspace, args.workspace_bytes = ws.data_ptr(), ws.numel() * 4
+    cargs = verify.make_commit_args(cu_T=cu_T, L=L_d, path=path, path_len=plen, k_tree=None, v_tree=None, k_cache=k_d,
+                                    v_cache=v_d, cu_L=cu_d, page_table=table_d, page_size=page_size, L_out=L_out,
+                                    err_flag=err)
+
+    def one_pass(stream=None):
+        binding.tree_verify_attn_raw(args, stream)
+        verify.accept_greedy(parent, cu_T, draft_d, target_d, max_path, path=path, path_len=plen, next_token=nxt,
+                             stream=stream)
+        verify.commit_path_raw(cargs, stream)
+
+    say(f"[case] whole pass eager, page_size={page_size}")
+    one_pass()
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    outputs = (out, lse, path, plen, nxt, L_out, k_d, v_d)
+    eager = [t.clone() for t in outputs]
+    paths, nxt_ref = vo.accept_greedy(w.parent, w.cu_T, draft, target, max_path=max_path)
+    assert [list(path[b, :plen[b]].cpu().numpy()) for b in range(B)] == paths and nxt.cpu().tolist() == nxt_ref
+
+    def reset():
+        k_d.copy_(k0), v_d.copy_(v0)
+        for t in (out, lse, plen, nxt, L_out):
+            t.zero_()
+        path.fill_(-1)
+
+    reset()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        one_pass(side)
+    for replay in range(3):
+        say(f"[case] whole pass, graph replay {replay}")
+        reset()                                  # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert int(err.item()) == 0
+        for name, got, want in zip("out lse path path_len next L_out k v".split(), outputs, eager):
+            assert torch.equal(got, want), (name, replay)
