@@ -1160,7 +1160,7 @@ struct Plan {
   int n_row_blocks, n_chunks, chunk_keys;
 };
 
-enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5, V_K2 = 6, V_K2R2 = 7, V_M2K2 = 8, V_W4D = 9, V_M2K2_3 = 10, V_M2K2_4 = 11 };
+enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5, V_K2 = 6, V_K2R2 = 7, V_M2K2 = 8, V_W4D = 9, V_M2K2_3 = 10, V_M2K2_4 = 11, V_M4K2 = 12, V_LAST = V_M4K2 };
 
 // query rows of the whole batch: every tree node, or only the nodes cu_Q selects
 inline int64_t query_rows(const tva_args *a) { return a->cu_Q ? a->sum_Q : a->sum_T; }
@@ -1174,22 +1174,32 @@ bool make_plan(const tva_args *a, Plan *pl) {
   // Up to 32 rows per KV head: 32-row workgroups of two waves that split the keys of 64-key tiles.
   // More rows: 64-row workgroups of 2 x 2 waves (two row groups x two key groups).  Both keep a
   // two-stage ring, small enough that two workgroups share a CU and hide each other's start-up
-  // and drain.  128 rows or more AND enough keys in all that re-reading them per 64 rows costs
-  // more than the splits and idle start-up of a larger workgroup -- half a million keys over the
-  // (sequence, KV head) pairs, or half of that when the caches are long -- : eight waves of 32 rows
-  // each (256 rows, two waves per SIMD), which read every key once per pair.
+  // and drain.  From 128 rows on, larger workgroups that read each key fewer times take over
+  // where the launch can feed them:
+  //  - 128-row workgroups of 4 x 2 waves when 96 .. 256 of them exist (one per CU; with two KV
+  //    splits at most, and those 16 tiles or longer);
+  //  - 256-row workgroups of eight waves (32 rows each, two waves per SIMD) when there would be more
+  //    than 256 of the former, or when there are fewer than 96 but the keys are many: half a million
+  //    over the (sequence, KV head) pairs, or half of that with long caches, which splits then
+  //    spread over the chip.
   const int pairs = a->B * a->Hkv;
   const int64_t keys = (int64_t)pairs * a->max_L;
-  const bool eight_waves = rows >= 128 && (keys >= (512 << 10) || (keys >= (256 << 10) && a->max_L >= 4096));
-  int variant = rows <= 32 ? V_K2 : eight_waves ? V_W8 : V_M2K2;
-  // benchmarking and test aid: TVA_FORCE_VARIANT=0..11 picks the workgroup shape
+  const int n128 = pairs * ((rows + 127) / 128);
+  const int s128 = n128 * 3 >= 512 ? 1 : 256 / (n128 > 0 ? n128 : 1);
+  int variant = V_M2K2;
+  if (rows <= 32) variant = V_K2;
+  else if (rows >= 128) {
+    if (n128 >= 96 && n128 <= 256 && (s128 == 1 || a->max_L / s128 >= 16 * 64)) variant = V_M4K2;
+    else if (n128 > 256 || keys >= (512 << 10) || (keys >= (256 << 10) && a->max_L >= 4096)) variant = V_W8;
+  }
+  // benchmarking and test aid: TVA_FORCE_VARIANT=0..12 picks the workgroup shape
   bool forced = false;
   if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
     const int v = atoi(fv);
-    if (v >= V_R256 && v <= V_M2K2_4) variant = v, forced = true;
+    if (v >= V_R256 && v <= V_LAST) variant = v, forced = true;
   }
   pl->variant = variant;
-  pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4 || variant == V_W4D) ? 128 : (variant == V_R64 || variant == V_M2K2 || variant == V_M2K2_3 || variant == V_M2K2_4) ? 64 : 32;
+  pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4 || variant == V_W4D || variant == V_M4K2) ? 128 : (variant == V_R64 || variant == V_M2K2 || variant == V_M2K2_3 || variant == V_M2K2_4) ? 64 : 32;
   pl->TK = (variant == V_R64 || variant == V_R32) ? 128 : (variant == V_W8 ? 32 * TVA_W8_KBW : 64);
   pl->n_row_blocks = rows > 0 ? (rows + pl->BM - 1) / pl->BM : 1;
   int S = a->num_splits;
@@ -1199,11 +1209,13 @@ bool make_plan(const tva_args *a, Plan *pl) {
     // every split costs a partial O of the size of the output, written and read back
     const int natural = a->B * a->Hkv * pl->n_row_blocks;
     S = natural * 3 >= 512 ? 1 : (256 + natural - 1) / natural;  // two thirds of the CUs busy beats a merge pass
+    const bool two_per_cu = variant == V_K2 || variant == V_M2K2 || variant == V_W4D;
+    if (!two_per_cu && S > 1 && natural * S > 256) --S;  // one workgroup per CU: no second round for a few
     const int cap = a->max_L > 0 ? (a->max_L + 2 * pl->TK - 1) / (2 * pl->TK) : 1;
     if (S > cap) S = cap;
     if (variant == V_M2K2) {
       // two of these workgroups fit a CU: go on to 512 of them while a split keeps 16 tiles or more
-      int s2 = (512 + natural - 1) / natural;
+      int s2 = 512 / natural;
       const int by_len = a->max_L / (16 * pl->TK);
       s2 = s2 < by_len ? s2 : by_len;
       if (s2 > S) S = s2;
@@ -1264,6 +1276,7 @@ hipError_t dispatch_variant(int variant, const AttnParams &p, dim3 grid, hipStre
     case V_W4D: return launch_attn<D, 4, 1, 1, PAGED, 2>(p, grid, st);
     case V_M2K2_3: return launch_attn<D, 2, 2, 1, PAGED, 3>(p, grid, st);
     case V_M2K2_4: return launch_attn<D, 2, 2, 1, PAGED, 4>(p, grid, st);
+    case V_M4K2: return launch_attn<D, 4, 2, 1, PAGED, 4>(p, grid, st);
     default: return launch_attn<D, 1, 4, 1, PAGED>(p, grid, st);
   }
 }

@@ -132,7 +132,7 @@ def test_split_counts_ragged(gpu, splits):
     check_full(gpu, w, num_splits=splits, label=f"splits={splits}")
 
 
-@pytest.mark.parametrize("variant", list(range(12)))
+@pytest.mark.parametrize("variant", list(range(13)))
 def test_every_workgroup_shape(gpu, variant, monkeypatch):
     """The launch plan picks three of the kernel's workgroup shapes; the others (64-row-per-wave shapes,
     four-wave shapes, deeper rings) stay selectable through TVA_FORCE_VARIANT and must agree with the
