@@ -171,6 +171,14 @@ int32_t tva_plan_splits(const tva_args *a);
 int32_t tva_plan_chunk_keys(const tva_args *a);
 
 /*
+ * Query rows (tree nodes x query heads of one KV head) one workgroup of the attention kernel
+ * covers for these shapes: 32, 64, 128 or 256.  With tva_plan_splits it names the launch
+ * (workgroups = B * Hkv * ceil(max_T * Hq / Hkv / rows) * splits); meant for tools that tune
+ * or report it.  -1 on invalid arguments.
+ */
+int32_t tva_plan_workgroup_rows(const tva_args *a);
+
+/*
  * The attention itself.  For sequence b, tree node i, query head h (KV head
  * g = h / (Hq/Hkv)) with keys k = the L[b] cached tokens followed by the tree
  * tokens j for which bit j of anc_mask row i is set:

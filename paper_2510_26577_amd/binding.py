@@ -63,7 +63,7 @@ class TvaArgs(ctypes.Structure):
     ]
 
 
-EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys",
+EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys", "tva_plan_workgroup_rows",
            "tva_tree_verify_attn", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
 # entry points of include/tva_verify.h (bound in verify.py)
 VERIFY_EXPORTS = ("tva_accept_greedy", "tva_commit_path", "tva_sizeof_commit_args")
@@ -102,6 +102,8 @@ def load_library():
     lib.tva_plan_splits.argtypes = [ctypes.POINTER(TvaArgs)]
     lib.tva_plan_chunk_keys.restype = ctypes.c_int32
     lib.tva_plan_chunk_keys.argtypes = [ctypes.POINTER(TvaArgs)]
+    lib.tva_plan_workgroup_rows.restype = ctypes.c_int32
+    lib.tva_plan_workgroup_rows.argtypes = [ctypes.POINTER(TvaArgs)]
     lib.tva_tree_verify_attn.restype = ctypes.c_int
     lib.tva_tree_verify_attn.argtypes = [ctypes.POINTER(TvaArgs), ctypes.c_void_p]
     lib.tva_tree_verify_attn_splits.restype = ctypes.c_int
@@ -221,6 +223,13 @@ def plan_splits(args: TvaArgs) -> int:
 
 def plan_chunk_keys(args: TvaArgs) -> int:
     n = load_library().tva_plan_chunk_keys(ctypes.byref(args))
+    if n < 0:
+        raise TvaError(-1)
+    return int(n)
+
+
+def plan_workgroup_rows(args: TvaArgs) -> int:
+    n = load_library().tva_plan_workgroup_rows(ctypes.byref(args))
     if n < 0:
         raise TvaError(-1)
     return int(n)

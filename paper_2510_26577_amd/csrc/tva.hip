@@ -1195,7 +1195,7 @@ bool make_plan(const tva_args *a, Plan *pl) {
   // benchmarking and test aid: TVA_FORCE_VARIANT=0..12 picks the workgroup shape
   bool forced = false;
   if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
-    const int v = atoi(fv);
+    const int v = (*fv >= '0' && *fv <= '9') ? atoi(fv) : -1;  // unset or empty: the planner decides
     if (v >= V_R256 && v <= V_LAST) variant = v, forced = true;
   }
   pl->variant = variant;
@@ -1361,6 +1361,13 @@ int32_t tva_plan_chunk_keys(const tva_args *a) {
   Plan pl;
   if (!make_plan(a, &pl)) return -1;
   return pl.chunk_keys;
+}
+
+int32_t tva_plan_workgroup_rows(const tva_args *a) {
+  if (check_args(a, true) != TVA_OK) return -1;
+  Plan pl;
+  if (!make_plan(a, &pl)) return -1;
+  return pl.BM;
 }
 
 size_t tva_workspace_bytes(const tva_args *a) {

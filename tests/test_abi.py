@@ -79,6 +79,29 @@ def test_plan_and_workspace(lib):
     assert binding.plan_splits(a) == 1
 
 
+@pytest.mark.parametrize("B,L,T,rows,splits", [
+    (1, 2048, 60, 64, 8),      # the headline shape: 32 natural workgroups of 64 rows, split to one per CU
+    (4, 2048, 60, 64, 2),      # 128 natural: two per CU would allow 4 splits, but those would be 8 tiles
+    (4, 4096, 60, 64, 4),      # ... and here they keep 16 tiles
+    (8, 2048, 60, 128, 2),     # 128 workgroups of 128 rows, two splits of 16 tiles
+    (16, 2048, 60, 128, 1),    # 256 of them
+    (8, 1024, 40, 64, 1),      # 128 of 128 rows would need splits of 8 tiles: 192 of 64 rows instead
+    (20, 2048, 60, 256, 1),    # more than 256 of 128 rows: 160 of 256 rows, not split into a second round
+    (32, 2048, 60, 256, 1),
+    (4, 8192, 60, 256, 8),     # few sequences, many keys
+    (8, 4096, 32, 256, 4),     # exactly 128 rows
+    (16, 2048, 16, 64, 2),     # 64 rows: never the large shapes
+    (64, 2048, 8, 32, 1),      # 32 rows
+    (2, 300, 8, 32, 3),        # no split shorter than two tiles
+])
+def test_launch_plan_bands(lib, B, L, T, rows, splits):
+    """The launch planner is host arithmetic on the shapes: one case per band of its rules (Hq 32, Hkv 8)."""
+    a = shape_args(B=B, max_L=L, max_T=T, sum_T=B * T)
+    assert (binding.plan_workgroup_rows(a), binding.plan_splits(a)) == (rows, splits)
+    ck = binding.plan_chunk_keys(a)
+    assert ck % 32 == 0 and ck * splits >= L > ck * (splits - 1)
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(D=96), -2), (dict(max_T=129, mask_words=3), -2), (dict(mask_words=0), -2),
     (dict(Hq=30), -1), (dict(B=0), -1), (dict(max_L=-1), -1), (dict(max_T=100, mask_words=1), -2),

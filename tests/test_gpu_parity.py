@@ -153,6 +153,26 @@ def test_every_workgroup_shape(gpu, variant, monkeypatch):
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
+@pytest.mark.parametrize("B,L,T,page,rows,splits", [
+    (8, 2048, 60, 0, 128, 2), (16, 2048, 60, 0, 128, 1), (20, 1024, 60, 0, 256, 1), (4, 8192, 60, 0, 256, 8),
+    (4, 4096, 60, 0, 64, 4), (32, 1024, 16, 0, 64, 1), (8, 4096, 32, 0, 256, 4),
+    (8, 2048, 60, 16, 128, 2), (20, 1024, 60, 16, 256, 1), (4, 4096, 60, 16, 64, 4),
+])
+def test_every_band_of_the_launch_planner(gpu, B, L, T, page, rows, splits):
+    """Batch / length shapes that land in each band of the launch planner (workgroup rows and split count
+    asserted), with ragged lengths and tree sizes below the maxima, planner left to itself."""
+    from paper_2510_26577_amd import binding
+    rng = np.random.Generator(np.random.PCG64(B * 131 + L + T))
+    Ls = rng.integers(L // 2, L + 1, B)
+    Ts = rng.integers(max(1, T - 8), T + 1, B)
+    Ls[int(rng.integers(0, B))], Ts[int(rng.integers(0, B))] = L, T
+    w = wl.random_workload(900 + B + L + T, B, 32, 8, 128, Ls, Ts, max_depth=8, page_size=page)
+    a = binding.TvaArgs()
+    a.B, a.Hq, a.Hkv, a.D, a.sum_T, a.max_T, a.mask_words, a.max_L, a.scale = B, 32, 8, 128, w.sum_T, T, 1, L, w.scale
+    assert (binding.plan_workgroup_rows(a), binding.plan_splits(a)) == (rows, splits)
+    check_full(gpu, w, label=f"planner band rows={rows} splits={splits} page={page}")
+
+
 @pytest.mark.parametrize("case", ["cfg2", "cfg3_B16", "cfg4", "cfg5", "ragged", "paged", "forest_T128", "D64"])
 def test_masks_derived_in_kernel_equal_masks_passed(gpu, case):
     """Passing the parent arrays instead of ancestor masks gives the same ancestor sets, hence the same
