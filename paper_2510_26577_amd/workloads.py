@@ -42,6 +42,49 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << 16).view(np.float32)
 
 
+# ----------------------------------------------------------------------------
+# 8-bit floating point (OCP E4M3) storage of K/V: input preparation only
+# ----------------------------------------------------------------------------
+def _e4m3_magnitudes() -> np.ndarray:
+    """The 127 finite magnitudes in code order (code c -> value), float32."""
+    c = np.arange(127)
+    e, m = c >> 3, c & 7
+    return np.where(e == 0, m * 2.0 ** -9, (8 + m) * 2.0 ** (e - 10.0)).astype(np.float32)
+
+
+def f32_to_e4m3(x: np.ndarray) -> np.ndarray:
+    """Nearest finite E4M3 code of every element (ties to the even code, saturating at +-448), uint8."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    mags = _e4m3_magnitudes()
+    out = np.empty(x.shape, np.uint8)
+    flat_in, flat_out = x.reshape(-1), out.reshape(-1)
+    step = 1 << 22
+    for s in range(0, flat_in.size, step):
+        v = flat_in[s:s + step]
+        a = np.minimum(np.abs(v), mags[-1])
+        hi = np.clip(np.searchsorted(mags, a), 1, 126)
+        lo = hi - 1
+        d_lo, d_hi = a - mags[lo], mags[hi] - a
+        pick_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))
+        code = np.where(pick_hi, hi, lo).astype(np.uint8)
+        flat_out[s:s + step] = code | (np.signbit(v).astype(np.uint8) << 7)
+    return out
+
+
+def to_fp8_kv(w: "Workload"):
+    """The same workload with K and V (cache and tree) stored as E4M3 bytes, each tensor pair scaled so
+    that its largest magnitude maps to 448.  Returns (workload with uint8 K/V, k_scale, v_scale)."""
+    def amax(*arrs):
+        m = max((float(np.abs(bf16_bits_to_f32(a)).max()) for a in arrs if a.size), default=1.0)
+        return m if m > 0 else 1.0
+    k_scale = amax(w.k_cache, w.k_tree) / 448.0
+    v_scale = amax(w.v_cache, w.v_tree) / 448.0
+    q8 = lambda a, sc: f32_to_e4m3(bf16_bits_to_f32(a) / np.float32(sc))
+    w8 = dataclasses.replace(w, name=w.name + "_fp8kv", k_cache=q8(w.k_cache, k_scale), v_cache=q8(w.v_cache, v_scale),
+                             k_tree=q8(w.k_tree, k_scale), v_tree=q8(w.v_tree, v_scale))
+    return w8, k_scale, v_scale
+
+
 def _normal_bf16(rng: np.random.Generator, shape) -> np.ndarray:
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.uint16)
