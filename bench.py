@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--head-major", action="store_true",
                     help="store the dense cache as [Hkv, sum_L, D] (passed through the stride arguments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kv-fp8", action="store_true",
+                    help="K/V stored as 8-bit floating point (E4M3) bytes: half the K/V bytes per step")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -80,6 +82,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = get_workload(a.workload)
+    k_scale = v_scale = 1.0
+    if a.kv_fp8:
+        from paper_2510_26577_amd import workloads as wl
+        w, k_scale, v_scale = wl.to_fp8_kv(w)
     kv_bytes, alg_bytes, flops = w.kv_bytes(), w.algorithmic_bytes(), w.algorithmic_flops()
     R = a.rotate or max(2, min(64, -(-640 * 2 ** 20 // alg_bytes)))
 
@@ -103,7 +109,8 @@ def main():
         args = binding.make_args(q=dw.q, k_tree=dw.k_tree, v_tree=dw.v_tree, k_cache=dw.k_cache, v_cache=dw.v_cache,
                                  anc_mask=m, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale,
                                  cu_L=dw.cu_L, page_table=dw.page_table, page_size=w.page_size,
-                                 strides=strides, num_splits=a.splits, out=o, lse=l)
+                                 strides=strides, num_splits=a.splits, out=o, lse=l, kv_fp8=a.kv_fp8, k_scale=k_scale,
+                                 v_scale=v_scale)
         argv.append(args)
     # the same calls with the parent arrays in place of ancestor masks (the kernel derives the masks)
     argv_parent = []
@@ -111,7 +118,8 @@ def main():
         argv_parent.append(binding.make_args(
             q=dw.q, k_tree=dw.k_tree, v_tree=dw.v_tree, k_cache=dw.k_cache, v_cache=dw.v_cache, anc_mask=None,
             parent=dw.parent, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale, cu_L=dw.cu_L,
-            page_table=dw.page_table, page_size=w.page_size, strides=strides, num_splits=a.splits, out=o, lse=l))
+            page_table=dw.page_table, page_size=w.page_size, strides=strides, num_splits=a.splits, out=o, lse=l,
+            kv_fp8=a.kv_fp8, k_scale=k_scale, v_scale=v_scale))
     n_splits = binding.plan_splits(argv[0])
     ws_bytes = binding.workspace_bytes(argv[0])
     wss = []
@@ -196,10 +204,16 @@ def main():
 
     # ---- correctness spot check of what was just timed (first set, oracle rows) ----
     from oracle import tva_oracle
+    if a.kv_fp8:
+        from oracle import fp8_oracle
+        oracle_attn = lambda rows=None: fp8_oracle.tree_verify_attn_fp8(w, k_scale, v_scale, rows=rows)
+    else:
+        oracle_attn = lambda rows=None: tva_oracle.tree_verify_attn(w, rows=rows) if rows is not None \
+            else tva_oracle.tree_verify_attn(w)
     rng = np.random.Generator(np.random.PCG64(7))
     rows = [(int(rng.integers(0, w.B)), 0, 0)]
     rows = [(b, int(rng.integers(0, w.T[b])), int(rng.integers(0, w.Hq))) for b in rng.integers(0, w.B, size=8)]
-    ro, rl = tva_oracle.tree_verify_attn(w, rows=rows)
+    ro, rl = oracle_attn(rows)
     o0, l0 = outs[0].cpu().numpy(), lses[0].cpu().numpy()
     err_o = max(float(np.abs(o0[w.cu_T[b] + i, h] - ro[n]).max()) for n, (b, i, h) in enumerate(rows))
     err_l = max(float(abs(l0[w.cu_T[b] + i, h] - rl[n])) for n, (b, i, h) in enumerate(rows))
@@ -216,7 +230,7 @@ def main():
             best = 1e30
             for _ in range(3):
                 t1 = time.perf_counter()
-                tva_oracle.tree_verify_attn(w)
+                oracle_attn()
                 best = min(best, time.perf_counter() - t1)
                 if time.perf_counter() - t0 > 20:
                     break
@@ -227,7 +241,7 @@ def main():
             srows = [(b, int(rng.integers(0, w.T[b])), int(rng.integers(0, w.Hq)))
                      for b in rng.integers(0, w.B, size=n_s)]
             t1 = time.perf_counter()
-            tva_oracle.tree_verify_attn(w, rows=srows)
+            oracle_attn(srows)
             dt = time.perf_counter() - t1
             f_s = sum(4 * w.D * (int(w.L[b]) + int(w.T[b])) for b, _, _ in srows)
             full_s, sample = dt * flops / f_s, f"{n_s} random output rows of {n_rows_total}, time scaled by flops"
@@ -254,7 +268,7 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
-                   "L": [int(w.L.min()), int(w.L.max())], "T": int(w.max_T), "paged": bool(w.paged),
+                   "L": [int(w.L.min()), int(w.L.max())], "T": int(w.max_T), "paged": bool(w.paged), "kv_storage": "e4m3" if a.kv_fp8 else "bf16",
                    "kv_splits": n_splits, "rotating_input_copies": R, "launch": "eager" if a.no_graph else "hip-graph",
                    "step": "one tva_tree_verify_attn call on parent arrays (ancestor sets derived in the kernel) "
                            "incl. merge of the KV splits; ms_per_step_two_calls = mask kernel + attention on masks"},

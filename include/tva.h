@@ -118,6 +118,15 @@ typedef struct tva_args {
                              ancestors in the layers before (paper, Tree Expansion Phase). */
   int32_t sum_Q, max_Q;   /* with cu_Q: cu_Q[B] and a host-side upper bound of the per-sequence count
                              (<= max_T); ignored otherwise */
+
+  /* 8-bit K/V (a widening of the kernel; the paper keeps the cache in 16 bits).  kv_fp8 = 1: k_cache,
+     v_cache and, if given, k_tree, v_tree hold one byte per element in the OCP 8-bit floating point
+     format E4M3 (1 sign, 4 exponent, 3 mantissa bits, bias 7, no infinities; the NaN codes 0x7F / 0xFF
+     must not occur), with the same shapes, and strides counted in elements (= bytes, multiples of 16).
+     K = k_scale * value, V = v_scale * value, one scale per tensor (0 is read as 1).  q, out and lse
+     are unchanged; the arithmetic is the bf16 path's on the exactly widened values.  D = 128 only. */
+  int32_t kv_fp8;
+  float k_scale, v_scale;
 } tva_args;
 
 /*

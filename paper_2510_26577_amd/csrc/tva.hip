@@ -126,7 +126,8 @@ struct AttnParams {
   int chunk_keys, n_chunks, n_row_blocks, max_L;
   int page_size, page_shift, max_pages;
   int64_t stride_page, stride_tok, stride_head;
-  float scale_log2;  // scale * log2(e)
+  float scale_log2;  // scale * log2(e) (times the K scale of an fp8 cache)
+  float v_scale;     // 1, or the V scale of an fp8 cache
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -161,7 +162,7 @@ __device__ __forceinline__ float half_sum(float x) {
 #define TVA_FAST_PATH 1
 #endif
 
-template <int D, int WM, int WK, int RB, bool PAGED, int NST>
+template <int D, int WM, int WK, int RB, bool PAGED, int NST, bool KV8 = false>
 struct AttnCfg {
   static constexpr int NW = WM * WK;
   static constexpr int NT = NW * 64;
@@ -171,7 +172,9 @@ struct AttnCfg {
   static constexpr int DC = D / 8;               // 16-byte chunks per K/V row
   static constexpr int ROWB = D * 2;             // bytes per K/V row
   static constexpr int RPI = 64 / DC;            // rows one wave-wide 16-byte-per-lane load covers
-  static constexpr int NLDK = TK / RPI / NW;     // such loads per wave per tile, for K (same for V)
+  // 8-bit K/V: a row is D bytes, a wave-wide load covers twice the rows
+  static constexpr int DC8 = D / 16, RPI8 = 64 / DC8;
+  static constexpr int NLDK = KV8 ? TK / RPI8 / NW : TK / RPI / NW;  // such loads per wave per tile, for K (same for V)
   static constexpr int NLD = 2 * NLDK;
   // LDS tile layout: NBLK blocks; block n holds rows n, n+NBLK, n+2*NBLK, ... back to back, and
   // blocks are PAD bytes further apart than their size.  Rows that are read together (16
@@ -194,10 +197,21 @@ struct AttnCfg {
   // hence one stage more than tiles in flight + 1) and for the eight-wave shape (three in flight:
   // its LDS footprint is set by the output patches anyway), else three (TK = 64) or two (TK = 128).
   // Two stages keep the footprint small enough for two workgroups per CU.
-  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4) && (NST == 0);
-  static constexpr int NSTAGE = NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
-  static constexpr int PD = FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed
-  static constexpr int WG_PER_CU = (NSTAGE == 2 && TK == 64) ? 2 : 1;
+  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4) && (NST == 0) && !KV8;
+  // 8-bit K/V: the loads land in per-wave zones of NL landing slots (a tile of bytes each); the wave that
+  // loaded a piece widens it to bf16 into one of two tiles of the layout above, one tile ahead of
+  // the arithmetic.  NL tiles are in flight or being widened.
+  // Workgroups of up to four waves keep ONE widened tile and two landing slots, so that two of them
+  // fit a CU (the other workgroup covers the two barriers per tile this costs); where a wave only ever
+  // reads the rows it loaded itself (one row group: the key groups' rows are disjoint) no barrier is
+  // needed at all.
+  static constexpr bool KV8_SINGLE = KV8 && NW <= 4;
+  static constexpr bool KV8_PRIV = KV8 && WM == 1;
+  static constexpr int NL = KV8 ? (KV8_SINGLE ? 2 : (NST ? NST : 3)) : 0;
+  static constexpr int LAND_SLOT = KV8 ? 2 * TK * D : 0;
+  static constexpr int NSTAGE = KV8 ? (KV8_SINGLE ? 1 : 2) : NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
+  static constexpr int PD = KV8 ? NL : FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed (widened)
+  static constexpr int WG_PER_CU = KV8 ? (KV8_SINGLE ? 2 : 1) : (NSTAGE == 2 && TK == 64) ? 2 : 1;
   // after the key loop the ring is reused: exchange area of the key-group merge, then (behind it,
   // when the groups are paired; else on top of it, after a barrier) the output transpose patches
   static constexpr bool PAIR = (WK == 2);
@@ -207,7 +221,8 @@ struct AttnCfg {
                                      : (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
   static constexpr int PATCH_OFF = PAIR ? MERGE_BYTES : 0;
   static constexpr int PATCH_BYTES = (PAIR ? NW : WM) * 32 * TP * 4;
-  static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
+  static constexpr int LAND_OFF = NSTAGE * STAGE_BYTES;
+  static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES + NL * LAND_SLOT;
   // paged cache: table entries of the next two tiles, fetched by the same LDS-writing loads as the
   // tiles themselves: [2 slots][wave][load instruction of a tile][lane], behind the ring
   static constexpr int NPG = PAGED ? NLDK : 0;   // table-entry loads per wave and tile
@@ -219,9 +234,12 @@ struct AttnCfg {
   static constexpr int PARENT_BYTES = TVA_MAX_TREE * 4;
   static constexpr int TAIL_BYTES = PAIR ? MERGE_BYTES + PATCH_BYTES : (MERGE_BYTES > PATCH_BYTES ? MERGE_BYTES : PATCH_BYTES);
   static constexpr int SMEM = PARENT_OFF + PARENT_BYTES > TAIL_BYTES ? PARENT_OFF + PARENT_BYTES : TAIL_BYTES;
+  // load instruction n of a tile (n = wave * NLDK + j): the first tile row it covers
+  static constexpr int load_row0(int n) { return KV8 ? n * RPI8 : n / IPB + NBLK * ((n % IPB) * RPI); }
   static_assert(SMEM * WG_PER_CU <= 160 * 1024, "LDS of the workgroups that share a CU");
   static_assert(PD <= 3 && TILE_OPS * (PD > 1 ? PD - 1 : 1) < 64, "the wait counter holds 6 bits");
-  static_assert(TK % (RPI * NW) == 0, "tile must divide evenly over the waves");
+  static_assert(TK % ((KV8 ? RPI8 : RPI) * NW) == 0, "tile must divide evenly over the waves");
+  static_assert(!KV8 || (D == 128 && NLDK >= 1), "8-bit K/V: head dimension 128");
   static_assert(BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
 };
 
@@ -247,6 +265,32 @@ __device__ __forceinline__ void lds_wait(s16x4 &a, s16x4 &b, s16x4 &c, s16x4 &d)
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
+// 16-byte LDS read from a landing zone of the 8-bit K/V path (inline assembly for the same reason),
+// and its wait.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
+  return v;
+}
+__device__ __forceinline__ void lds_wait(u32x4 &a, u32x4 &b) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b));
+}
+// 16 E4M3 bytes -> 16 bf16 (exact: every E4M3 value is a bf16 value)
+__device__ __forceinline__ void widen_e4m3(const u32x4 raw, bf16x8 &lo, bf16x8 &hi) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], false);
+    const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], true);
+    bf16x8 &dst = w < 2 ? lo : hi;
+    const int o = (w & 1) * 4;
+    dst[o + 0] = (__bf16)a[0];
+    dst[o + 1] = (__bf16)a[1];
+    dst[o + 2] = (__bf16)b[0];
+    dst[o + 3] = (__bf16)b[1];
+  }
+}
+
 #ifdef TVA_TIMING
 #define TVA_PHASE_DECL long long ph_acc[7] = {0, 0, 0, 0, 0, 0, 0}; long long ph_t = clock64();
 #define TVA_PHASE(i) do { const long long ph_n = clock64(); ph_acc[i] += ph_n - ph_t; ph_t = ph_n; } while (0)
@@ -260,10 +304,10 @@ __device__ long long tva_dbg[64];
 #define TVA_PHASE_DUMP do { } while (0)
 #endif
 
-template <int D, int WM, int WK, int RB, bool PAGED, int NST>
-__global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
+template <int D, int WM, int WK, int RB, bool PAGED, int NST, bool KV8>
+__global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NST, KV8>::WG_PER_CU))
     attn_kernel(const AttnParams p_in) {
-  using C = AttnCfg<D, WM, WK, RB, PAGED, NST>;
+  using C = AttnCfg<D, WM, WK, RB, PAGED, NST, KV8>;
   // The arguments the prologue needs, tied together by an empty statement so that they are fetched
   // in one batch at the top rather than one by one, each with its own wait, at their first uses.
   AttnParams p = p_in;
@@ -380,7 +424,24 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   // Instruction n of a tile fills part n%IPB of block n/IPB; lane l lands at sub-row
   // (n%IPB)*RPI + l/DC of that block, chunk l%DC.  Rows past the tile's limit re-read the last
   // valid row (finite data; their scores are masked to -inf), so LDS never holds stale values.
-  const int lsub = lane / DC, lpos = lane % DC;
+  // (8-bit K/V: a row is D bytes, instruction n covers rows n*RPI8 .. n*RPI8 + RPI8 - 1 of the tile and
+  // lands in the wave's own zone of a landing slot, from where the same lanes widen it to bf16 into
+  // the layout above.)
+  constexpr int EB = KV8 ? 1 : 2;                 // bytes per K/V element
+  constexpr int LDC = KV8 ? C::DC8 : DC;          // lanes (16-byte chunks) per row of a wave-wide load
+  const int lsub = lane / LDC, lpos = lane % LDC;
+  const int lrow = KV8 ? lsub : NBLK * lsub;      // the lane's row within its load instruction's rows
+  // tile row of (load instruction j of this wave, lane 0), and the LDS byte offsets of that
+  // instruction's K and V destinations inside a stage (8-bit: inside the wave's zone of a landing
+  // slot): wave-uniform.  (Plain expressions: with calls in their place the host pass of the compiler
+  // silently drops the kernel's launch stub.)
+  auto row0_of = [&](int j) __attribute__((always_inline)) { return C::load_row0(wave * NLDK + j); };
+#define kdst_of(j) (KV8 ? (wave * 2 * NLDK + (j)) * 1024 : ((wave * NLDK + (j)) / IPB) * PK + ((wave * NLDK + (j)) % IPB) * 1024)
+#define vdst_of(j) (KV8 ? (wave * 2 * NLDK + NLDK + (j)) * 1024 : KTILE + ((wave * NLDK + (j)) / IPB) * PV + ((wave * NLDK + (j)) % IPB) * 1024)
+  const char *const kc_bytes = reinterpret_cast<const char *>(p.k_cache);
+  const char *const vc_bytes = reinterpret_cast<const char *>(p.v_cache);
+  const char *const kt_bytes = reinterpret_cast<const char *>(p.k_tree);
+  const char *const vt_bytes = reinterpret_cast<const char *>(p.v_tree);
   const int64_t cache_base = PAGED ? 0 : (int64_t)cuL * p.stride_tok + (int64_t)kvh * p.stride_head;
   // paged cache: each lane needs the page of the row it loads, one table entry per load
   // instruction of a cache tile.  The entries of tile t + 2 are requested right after the loads of
@@ -397,9 +458,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     const int last = tree_in_cache ? Lb0 + Tb - 1 : k1 - 1;
 #pragma unroll
     for (int j = 0; j < NLDK; ++j) {
-      const int n = wave * NLDK + j;
-      const int blk = n / IPB, part = n % IPB;
-      int key = base + blk + NBLK * (part * RPI + lsub);
+      int key = base + row0_of(j) + lrow;
       key = key < last ? key : last;
       key = key < 0 ? 0 : key;
       int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
@@ -409,69 +468,60 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     }
   };
   // full tiles of a dense cache: a wave-uniform row pointer plus one tile-independent lane offset
-  const uint32_t lane_off = (uint32_t)(NBLK * lsub) * (uint32_t)p.stride_tok * 2u + (uint32_t)lpos * 16u;
+  const uint32_t lane_off = (uint32_t)lrow * (uint32_t)p.stride_tok * (uint32_t)EB + (uint32_t)lpos * 16u;
   auto issue_impl = [&](int t, auto tree_tag) __attribute__((always_inline)) {
     constexpr bool tree = decltype(tree_tag)::value;
     const int base = tree ? (t - n_ct) * TK : k0 + t * TK;
     const int limit = tree ? Tb : k1;
-    lds_byte *stage = lds + (t % NSTAGE) * STAGE_BYTES;
+    lds_byte *stage = KV8 ? lds + C::LAND_OFF + (t % (KV8 ? C::NL : 1)) * C::LAND_SLOT : lds + (t % NSTAGE) * STAGE_BYTES;
     if (!PAGED && t < n_full) {
 #pragma unroll
       for (int j = 0; j < NLDK; ++j) {
-        const int n = wave * NLDK + j;
-        const int blk = n / IPB, part = n % IPB;
-        const int64_t urow = cache_base + (int64_t)(base + blk + NBLK * part * RPI) * p.stride_tok;
-        const char *ksrc = reinterpret_cast<const char *>(p.k_cache + urow) + lane_off;
-        const char *vsrc = reinterpret_cast<const char *>(p.v_cache + urow) + lane_off;
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + blk * PK + part * 1024, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + KTILE + blk * PV + part * 1024, 16, 0, 0);
+        const int64_t urow = cache_base + (int64_t)(base + row0_of(j)) * p.stride_tok;
+        const char *ksrc = kc_bytes + urow * EB + lane_off;
+        const char *vsrc = vc_bytes + urow * EB + lane_off;
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + kdst_of(j), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + vdst_of(j), 16, 0, 0);
       }
     } else {
 #pragma unroll
     for (int j = 0; j < NLDK; ++j) {
-      const int n = wave * NLDK + j;
-      const int blk = n / IPB, part = n % IPB;
-      const __bf16 *ksrc, *vsrc;
+      const char *ksrc, *vsrc;
+      int key = base + row0_of(j) + lrow;
+      key = key < limit ? key : limit - 1;
+      const int eoff = lpos * (16 / EB);  // first element of the lane's 16-byte chunk
       if (tree && p.k_tree != nullptr) {
-        int key = base + blk + NBLK * (part * RPI + lsub);
-        key = key < limit ? key : limit - 1;
-        const int64_t off = ((int64_t)(t0 + key) * p.Hkv + kvh) * D + lpos * 8;
-        ksrc = p.k_tree + off;
-        vsrc = p.v_tree + off;
+        const int64_t off = ((int64_t)(t0 + key) * p.Hkv + kvh) * D + eoff;
+        ksrc = kt_bytes + off * EB;
+        vsrc = vt_bytes + off * EB;
       } else if (tree) {
         // tree keys stored in the cache behind the sequence's L_b committed tokens
-        int key = base + blk + NBLK * (part * RPI + lsub);
-        key = key < limit ? key : limit - 1;
         const int pos = Lb0 + key;
         int64_t off;
         if (PAGED) {
           const int pidx = p.page_shift >= 0 ? (pos >> p.page_shift) : (pos / p.page_size);
           const int page = *reinterpret_cast<const __attribute__((address_space(3))) int *>(pg_lds + (t & 1) * C::PG_SLOT + j * 256 + lane * 4);
           off = (int64_t)page * p.stride_page + (int64_t)(pos - pidx * p.page_size) * p.stride_tok +
-                (int64_t)kvh * p.stride_head + lpos * 8;
+                (int64_t)kvh * p.stride_head + eoff;
         } else {
-          off = cache_base + (int64_t)pos * p.stride_tok + lpos * 8;
+          off = cache_base + (int64_t)pos * p.stride_tok + eoff;
         }
-        ksrc = p.k_cache + off;
-        vsrc = p.v_cache + off;
+        ksrc = kc_bytes + off * EB;
+        vsrc = vc_bytes + off * EB;
       } else if (PAGED) {
-        int key = base + blk + NBLK * (part * RPI + lsub);
-        key = key < limit ? key : limit - 1;
         const int pidx = p.page_shift >= 0 ? (key >> p.page_shift) : (key / p.page_size);
         const int page = *reinterpret_cast<const __attribute__((address_space(3))) int *>(pg_lds + (t & 1) * C::PG_SLOT + j * 256 + lane * 4);
         const int64_t off = (int64_t)page * p.stride_page + (int64_t)(key - pidx * p.page_size) * p.stride_tok +
-                            (int64_t)kvh * p.stride_head + lpos * 8;
-        ksrc = p.k_cache + off;
-        vsrc = p.v_cache + off;
+                            (int64_t)kvh * p.stride_head + eoff;
+        ksrc = kc_bytes + off * EB;
+        vsrc = vc_bytes + off * EB;
       } else {
-        int key = base + blk + NBLK * (part * RPI + lsub);
-        key = key < limit ? key : limit - 1;
-        const int64_t off = cache_base + (int64_t)key * p.stride_tok + lpos * 8;
-        ksrc = p.k_cache + off;
-        vsrc = p.v_cache + off;
+        const int64_t off = cache_base + (int64_t)key * p.stride_tok + eoff;
+        ksrc = kc_bytes + off * EB;
+        vsrc = vc_bytes + off * EB;
       }
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + blk * PK + part * 1024, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + KTILE + blk * PV + part * 1024, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + kdst_of(j), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + vdst_of(j), 16, 0, 0);
     }
     }
   };
@@ -829,13 +879,59 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   };
 
   // ---- one pipeline step: wait for tile `it`, refill the stage tile it-1 used, compute ----
+  // ---- 8-bit K/V: this wave's pieces of tile j, once landed, are widened to bf16 into stage j % 2,
+  // and the landing slot they leave takes the loads of tile j + NL.  A lane widens the 16 bytes it
+  // loaded itself (row row0_of(jj) + lsub, 16 head-dimension elements from 16 * lpos): 32 bytes of bf16 ----
+  auto land_tile = [&](int j) __attribute__((always_inline)) {
+    if constexpr (KV8) {
+      wait_tile(j);
+      const uint32_t land = (uint32_t)(uintptr_t)(lds + C::LAND_OFF + (j % C::NL) * C::LAND_SLOT) + lane * 16;
+      lds_byte *stage = lds + (j % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+      for (int jj = 0; jj < NLDK; ++jj) {
+        u32x4 kraw = lds_read_b128(land + kdst_of(jj));
+        u32x4 vraw = lds_read_b128(land + vdst_of(jj));
+        lds_wait(kraw, vraw);
+        const int r = row0_of(jj) + lsub;
+        const int at = (r / NBLK) * ROWB + lpos * 32;
+        bf16x8 lo, hi;
+        widen_e4m3(kraw, lo, hi);
+        auto *kd = reinterpret_cast<__attribute__((address_space(3))) bf16x8 *>(stage + (r % NBLK) * PK + at);
+        kd[0] = lo;
+        kd[1] = hi;
+        widen_e4m3(vraw, lo, hi);
+        auto *vd = reinterpret_cast<__attribute__((address_space(3))) bf16x8 *>(stage + KTILE + (r % NBLK) * PV + at);
+        vd[0] = lo;
+        vd[1] = hi;
+      }
+      asm volatile("" ::: "memory");  // the slot is refilled below this line, not above
+      if (j + PD < n_tiles) issue_tile(j + PD);
+    }
+  };
+
   auto step = [&](int it, auto masked_tag, auto tree_tag) __attribute__((always_inline)) {
+    if constexpr (C::KV8_SINGLE) {
+      // one widened tile: everyone is done with tile it-1; this wave's pieces of tile `it` are widened
+      // into its place; everyone's are (the wait covers this wave's LDS writes).  Without the barriers
+      // where every wave reads only what it widened itself.
+      if (!C::KV8_PRIV) __builtin_amdgcn_s_barrier();
+      land_tile(it);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (!C::KV8_PRIV) __builtin_amdgcn_s_barrier();
+    } else if constexpr (KV8) {
+      // everyone's widened part of tile `it` is in LDS (the wait covers this wave's LDS writes);
+      // everyone is done with tile it-1, whose stage tile it+1 is widened into next
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      if (it + 1 < n_tiles) land_tile(it + 1);
+    } else {
     // this wave's loads of tile `it` have landed once at most the later tiles' loads are outstanding
     wait_tile(it);
     TVA_PHASE(5);
     __builtin_amdgcn_s_barrier();  // everyone's part of tile `it` is in LDS; everyone is done with tile it-1
     TVA_PHASE(6);
     if (it + PD < n_tiles) issue_tile(it + PD);
+    }
     constexpr bool tree = decltype(tree_tag)::value;
     const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
     const int limit = tree ? Tb : k1;
@@ -912,6 +1008,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
       mrow[r][1] = b1;
     }
   }
+  if constexpr (KV8 && !C::KV8_SINGLE) land_tile(0);
   TVA_STAMP(2);
   int it = 0;
   if (C::FAST && n_full > 0 && wave_has_rows) {
@@ -1073,7 +1170,7 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
     constexpr int d0 = decltype(d0_tag)::value;  // first d block of this wave's share
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-      const float inv = l_tot[r] > 0.f ? 1.f / l_tot[r] : 0.f;
+      const float inv = l_tot[r] > 0.f ? p.v_scale / l_tot[r] : 0.f;
 #pragma unroll
       for (int d = 0; d < NDW; ++d)
 #pragma unroll
@@ -1102,6 +1199,8 @@ __global__ void __launch_bounds__(WM *WK * 64, NST == 2 ? 2 : 1)
   TVA_STAMP(5);
   TVA_PHASE_DUMP;
 }
+#undef kdst_of
+#undef vdst_of
 
 // ---------------------------------------------------------------------------------------
 // merge of the KV splits
@@ -1198,6 +1297,11 @@ bool make_plan(const tva_args *a, Plan *pl) {
     const int v = (*fv >= '0' && *fv <= '9') ? atoi(fv) : -1;  // unset or empty: the planner decides
     if (v >= V_R256 && v <= V_LAST) variant = v, forced = true;
   }
+  if (a->kv_fp8) {
+    // 8-bit K/V: four shapes exist
+    if (variant != V_K2 && variant != V_W8 && variant != V_M4K2) variant = V_M2K2;
+    forced = true;  // (no three-stage variant of the 2 x 2 shape either)
+  }
   pl->variant = variant;
   pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4 || variant == V_W4D || variant == V_M4K2) ? 128 : (variant == V_R64 || variant == V_M2K2 || variant == V_M2K2_3 || variant == V_M2K2_4) ? 64 : 32;
   pl->TK = (variant == V_R64 || variant == V_R32) ? 128 : (variant == V_W8 ? 32 * TVA_W8_KBW : 64);
@@ -1213,7 +1317,7 @@ bool make_plan(const tva_args *a, Plan *pl) {
     if (!two_per_cu && S > 1 && natural * S > 256) --S;  // one workgroup per CU: no second round for a few
     const int cap = a->max_L > 0 ? (a->max_L + 2 * pl->TK - 1) / (2 * pl->TK) : 1;
     if (S > cap) S = cap;
-    if (variant == V_M2K2) {
+    if (variant == V_M2K2 && two_per_cu) {
       // two of these workgroups fit a CU: go on to 512 of them while a split keeps 16 tiles or more
       int s2 = 512 / natural;
       const int by_len = a->max_L / (16 * pl->TK);
@@ -1246,11 +1350,11 @@ inline hipError_t launch_status(const char *what) {
   return e;
 }
 
-template <int D, int WM, int WK, int RB, bool PAGED, int NST = 0>
+template <int D, int WM, int WK, int RB, bool PAGED, int NST = 0, bool KV8 = false>
 hipError_t launch_attn(const AttnParams &p, dim3 grid, hipStream_t st) {
-  using C = AttnCfg<D, WM, WK, RB, PAGED, NST>;
+  using C = AttnCfg<D, WM, WK, RB, PAGED, NST, KV8>;
   static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent
-  auto kfn = attn_kernel<D, WM, WK, RB, PAGED, NST>;
+  auto kfn = attn_kernel<D, WM, WK, RB, PAGED, NST, KV8>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kfn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
@@ -1281,11 +1385,22 @@ hipError_t dispatch_variant(int variant, const AttnParams &p, dim3 grid, hipStre
   }
 }
 
+// 8-bit K/V: the planner's shapes only (three landing slots each)
+template <bool PAGED>
+hipError_t dispatch_variant_fp8(int variant, const AttnParams &p, dim3 grid, hipStream_t st) {
+  switch (variant) {
+    case V_W8: return launch_attn<128, 8, 1, 1, PAGED, 3, true>(p, grid, st);
+    case V_M4K2: return launch_attn<128, 4, 2, 1, PAGED, 3, true>(p, grid, st);
+    case V_K2: return launch_attn<128, 1, 2, 1, PAGED, 3, true>(p, grid, st);
+    default: return launch_attn<128, 2, 2, 1, PAGED, 3, true>(p, grid, st);  // V_M2K2
+  }
+}
+
 }  // namespace
 
 extern "C" {
 
-int tva_version(void) { return 3; }
+int tva_version(void) { return 4; }
 
 size_t tva_sizeof_args(void) { return sizeof(tva_args); }
 
@@ -1327,6 +1442,8 @@ static int check_args(const tva_args *a, bool shapes_only) {
   if (a->D != 64 && a->D != 128) return TVA_UNSUPPORTED;
   if (a->max_T > TVA_MAX_TREE) return TVA_UNSUPPORTED;
   if (a->mask_words < 1 || a->mask_words > 2 || a->mask_words * 64 < a->max_T) return TVA_UNSUPPORTED;
+  if (a->kv_fp8 != 0 && a->kv_fp8 != 1) return TVA_INVALID_ARG;
+  if (a->kv_fp8 && a->D != 128) return TVA_UNSUPPORTED;
   if (shapes_only) return TVA_OK;
   if (!(a->scale > 0.f)) return TVA_INVALID_ARG;
   if (a->cu_Q && (a->sum_Q < 0 || a->max_Q < 0 || a->max_Q > a->max_T || a->sum_Q > a->sum_T)) return TVA_INVALID_ARG;
@@ -1343,9 +1460,10 @@ static int check_args(const tva_args *a, bool shapes_only) {
   // bounds are known here, and the longest cache need not belong to the largest tree)
   if (paged && (int64_t)a->max_pages * a->page_size < (tree_in_cache && a->max_T > a->max_L ? a->max_T : a->max_L))
     return TVA_INVALID_ARG;
-  if ((a->stride_page | a->stride_tok | a->stride_head) % 8) return TVA_INVALID_ARG;
+  if ((a->stride_page | a->stride_tok | a->stride_head) % (a->kv_fp8 ? 16 : 8)) return TVA_INVALID_ARG;  // 16-byte pieces
   if (a->stride_page < 0 || a->stride_tok < 0 || a->stride_head < 0) return TVA_INVALID_ARG;
   if (a->stride_tok >= (1 << 24)) return TVA_UNSUPPORTED;  // lane offsets inside a tile are 32-bit
+  if (a->kv_fp8 && (!(a->k_scale >= 0.f) || !(a->v_scale >= 0.f))) return TVA_INVALID_ARG;
   return TVA_OK;
 }
 
@@ -1431,14 +1549,17 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   p.stride_head = a->stride_head ? a->stride_head : a->D;
   p.stride_tok = a->stride_tok ? a->stride_tok : (int64_t)a->Hkv * a->D;
   p.stride_page = a->stride_page ? a->stride_page : (int64_t)p.page_size * p.stride_tok;
-  p.scale_log2 = a->scale * kLog2e;
+  p.scale_log2 = a->scale * kLog2e * ((a->kv_fp8 && a->k_scale > 0.f) ? a->k_scale : 1.f);
+  p.v_scale = (a->kv_fp8 && a->v_scale > 0.f) ? a->v_scale : 1.f;
 
   if ((int64_t)a->B * pl.n_chunks > 65535 || pl.n_row_blocks > 65535) return TVA_UNSUPPORTED;
   const dim3 grid(a->Hkv, pl.n_row_blocks, a->B * pl.n_chunks);
   const bool paged = a->page_table != nullptr;
   hipStream_t st = (hipStream_t)stream;
   hipError_t e;
-  if (a->D == 128)
+  if (a->kv_fp8)
+    e = paged ? dispatch_variant_fp8<true>(pl.variant, p, grid, st) : dispatch_variant_fp8<false>(pl.variant, p, grid, st);
+  else if (a->D == 128)
     e = paged ? dispatch_variant<128, true>(pl.variant, p, grid, st) : dispatch_variant<128, false>(pl.variant, p, grid, st);
   else
     e = paged ? dispatch_variant<64, true>(pl.variant, p, grid, st) : dispatch_variant<64, false>(pl.variant, p, grid, st);

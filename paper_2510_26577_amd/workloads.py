@@ -230,7 +230,7 @@ class Workload:
 
     # --- byte / flop accounting used by the benchmark (definitions only) ---
     def kv_bytes(self) -> int:
-        per_tok = 2 * self.Hkv * self.D * 2
+        per_tok = 2 * self.Hkv * self.D * self.k_cache.dtype.itemsize   # 2 bytes per element (bf16), 1 for E4M3
         return int((int(self.L.sum()) + self.sum_T) * per_tok)
 
     def algorithmic_bytes(self) -> int:

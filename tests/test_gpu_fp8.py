@@ -1,0 +1,96 @@
+"""GPU parity of the attention on an 8-bit floating point (E4M3) KV cache against the CPU oracle that
+decodes the same bytes: same tolerances as the bf16 path (the kernel widens the bytes exactly and then
+runs the bf16 arithmetic)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import fp8_oracle as f8
+from paper_2510_26577_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL_O = 2e-3
+TOL_LSE = 1e-4
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2510_26577_amd import binding, device
+    binding.load_library()
+    return device
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def check(gpu, w8, ks, vs, num_splits=0, derive=False, label=""):
+    import torch
+    say(f"[case] fp8 {label} B={w8.B} T={list(w8.T[:6])} L={list(w8.L[:6])} paged={w8.paged} splits={num_splits}")
+    dw = gpu.to_device(w8)
+    mask = None if derive else gpu.build_mask(dw)
+    out, lse = gpu.attention(dw, mask, num_splits=num_splits, k_scale=ks, v_scale=vs)
+    torch.cuda.synchronize()
+    ro, rl = f8.tree_verify_attn_fp8(w8, ks, vs)
+    o, l = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    assert np.isfinite(o).all() and np.isfinite(l).all()
+    eo = np.abs(o - ro).max() if o.size else 0.0
+    el = np.abs(l - rl).max() if l.size else 0.0
+    say(f"        max|dO|={eo:.3e} max|dLSE|={el:.3e}")
+    assert eo <= TOL_O and el <= TOL_LSE
+    return eo, el
+
+
+@pytest.mark.parametrize("variant", [None, 4, 6, 8, 12])
+@pytest.mark.parametrize("page", [0, 16])
+def test_fp8_shapes_dense_and_paged(gpu, variant, page, monkeypatch):
+    if variant is not None:
+        monkeypatch.setenv("TVA_FORCE_VARIANT", str(variant))
+    w = wl.random_workload(1300 + page, 4, 8, 2, 128, [900, 130, 0, 517], [70, 33, 8, 64], max_depth=10, page_size=page)
+    w8, ks, vs = wl.to_fp8_kv(w)
+    for splits in (0, 3):
+        check(gpu, w8, ks, vs, num_splits=splits, label=f"shape {variant}")
+    check(gpu, w8, ks, vs, num_splits=2, derive=True, label=f"shape {variant}, masks derived")
+
+
+def test_every_code_is_widened_exactly(gpu):
+    """K and V made of all 254 non-NaN codes (each head-dimension lane sees each code): a wrong exponent bias,
+    a mishandled subnormal or a swapped byte order inside a dword shows here."""
+    w = wl.random_workload(1310, 1, 4, 1, 128, [254], [5], max_depth=3)
+    codes = np.array([c for c in range(256) if c not in (0x7F, 0xFF)], np.uint8)
+    k8 = np.empty((254, 1, 128), np.uint8)
+    v8 = np.empty((254, 1, 128), np.uint8)
+    for d in range(128):
+        k8[:, 0, d] = np.roll(codes, 7 * d)
+        v8[:, 0, d] = np.roll(codes, 11 * d + 3)
+    rng = np.random.Generator(np.random.PCG64(5))
+    kt = codes[rng.integers(0, 254, (5, 1, 128))]
+    vt = codes[rng.integers(0, 254, (5, 1, 128))]
+    w8 = dataclasses.replace(w, k_cache=k8, v_cache=v8, k_tree=kt, v_tree=vt)
+    # scales small enough that the scores stay moderate: |k| <= 448
+    check(gpu, w8, 1.0 / 4096, 1.0 / 128, label="all codes")
+
+
+@pytest.mark.parametrize("B,L,T", [(1, 2048, 60), (16, 2048, 16), (8, 2048, 60), (40, 700, 8)])
+def test_fp8_benchmark_like_shapes(gpu, B, L, T):
+    rng = np.random.Generator(np.random.PCG64(B + L + T))
+    Ls = rng.integers(L // 2, L + 1, B)
+    Ls[0] = L
+    w = wl.random_workload(1320 + B, B, 32, 8, 128, Ls, T, max_depth=8)
+    w8, ks, vs = wl.to_fp8_kv(w)
+    check(gpu, w8, ks, vs, label="benchmark-like")
+
+
+def test_fp8_rejects_head_dimension_64(gpu):
+    import torch
+    from paper_2510_26577_amd import binding
+    w = wl.random_workload(1330, 1, 4, 2, 64, [40], [5])
+    w8, ks, vs = wl.to_fp8_kv(w)
+    dw = gpu.to_device(w8)
+    with pytest.raises(binding.TvaError):
+        gpu.attention(dw, None, k_scale=ks, v_scale=vs)
