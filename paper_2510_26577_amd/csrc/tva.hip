@@ -29,7 +29,9 @@
 // Variants of the inputs handled by the same kernel: dense or paged cache;
 // tree K/V in their own tensors or in the cache behind the committed tokens;
 // ancestor sets passed as bitmasks or derived here from the parent array; all
-// tree nodes as queries or only the last ones of each tree.
+// tree nodes as queries or only the last ones of each tree; K/V stored as bf16
+// or as 8-bit floating point (E4M3) bytes, which the wave that loaded them
+// widens exactly to bf16 inside LDS before the same arithmetic runs.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>

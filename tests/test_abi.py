@@ -112,6 +112,17 @@ def test_invalid_shapes_rejected_before_launch(lib, kw, code):
     assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == code
 
 
+def test_fp8_arguments_checked_on_the_host(lib):
+    assert binding.plan_splits(shape_args(kv_fp8=1)) >= 1                         # D = 128: fine
+    a = shape_args(kv_fp8=1, D=64)
+    assert lib.tva_plan_splits(ctypes.byref(a)) == -1 and lib.tva_tree_verify_attn(ctypes.byref(a), None) == -2
+    a = shape_args(kv_fp8=2)
+    assert lib.tva_plan_splits(ctypes.byref(a)) == -1 and lib.tva_tree_verify_attn(ctypes.byref(a), None) == -1
+    # the four shapes the 8-bit path has: 32, 64, 128 or 256 rows, like the 16-bit planner's bands
+    for B, T, rows in [(1, 60, 64), (16, 60, 128), (32, 60, 256), (64, 8, 32)]:
+        assert binding.plan_workgroup_rows(shape_args(kv_fp8=1, B=B, max_T=T, sum_T=B * T)) == rows
+
+
 def test_null_pointers_and_cache_form_rejected(lib):
     a = shape_args()
     assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == -1      # null tensors
