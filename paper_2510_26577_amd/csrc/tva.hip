@@ -184,16 +184,22 @@ struct AttnCfg {
   // 16-lane group of the V transpose load) then sit in different blocks, PAD apart in bank
   // position, and every read address is one per-lane base plus a compile-time offset.
   static constexpr int NBLK = DC;                // 16 (D=128) or 8 (D=64)
-  static constexpr int SUBS = TK / NBLK;         // rows per block
+  // 8-bit K/V (see NL below): workgroups of up to four waves keep ONE widened tile; with one row group
+  // every wave reads only the rows it loaded itself, and its widened K and V then take turns in one
+  // private region of 32 rows laid out like a tile (KTILE = 0: V sits where K was)
+  static constexpr bool KV8_SINGLE = KV8 && NW <= 4;
+  static constexpr bool KV8_PRIV = KV8 && WM == 1;
+  static constexpr int SUBS = KV8_PRIV ? 32 / NBLK : TK / NBLK;  // rows per block
   static constexpr int BLKB = SUBS * ROWB;       // 1 KiB (TK=64) or 2 KiB (TK=128)
-  static constexpr int IPB = BLKB / 1024;        // load instructions per block
+  static constexpr int IPB = BLKB >= 1024 ? BLKB / 1024 : 1;  // load instructions per block (16-bit K/V)
   static constexpr int PK = BLKB + 16;           // block pitch of the K tile
 #ifndef TVA_PV_PAD
 #define TVA_PV_PAD 32
 #endif
   static constexpr int PV = BLKB + TVA_PV_PAD;   // block pitch of the V tile
-  static constexpr int KTILE = NBLK * PK, VTILE = NBLK * PV;
-  static constexpr int STAGE_BYTES = (KTILE + VTILE + 1023) / 1024 * 1024;
+  static constexpr int KTILE = KV8_PRIV ? 0 : NBLK * PK, VTILE = NBLK * PV;
+  static constexpr int PRIV_REGION = NBLK * PV;  // one wave's 32 widened rows (KV8_PRIV)
+  static constexpr int STAGE_BYTES = KV8_PRIV ? (NW * PRIV_REGION + 1023) / 1024 * 1024 : (KTILE + VTILE + 1023) / 1024 * 1024;
   // NST = stages of the ring, 0 for the shape's default: four for the software-pipelined loop
   // (two tiles in flight; it still reads the V operands of tile t-1 after tile t has been entered,
   // hence one stage more than tiles in flight + 1) and for the eight-wave shape (three in flight:
@@ -207,9 +213,7 @@ struct AttnCfg {
   // fit a CU (the other workgroup covers the two barriers per tile this costs); where a wave only ever
   // reads the rows it loaded itself (one row group: the key groups' rows are disjoint) no barrier is
   // needed at all.
-  static constexpr bool KV8_SINGLE = KV8 && NW <= 4;
-  static constexpr bool KV8_PRIV = KV8 && WM == 1;
-  static constexpr int NL = KV8 ? (KV8_SINGLE ? 2 : (NST ? NST : 3)) : 0;
+  static constexpr int NL = KV8 ? (KV8_PRIV ? 3 : KV8_SINGLE ? 2 : (NST ? NST : 3)) : 0;
   static constexpr int LAND_SLOT = KV8 ? 2 * TK * D : 0;
   static constexpr int NSTAGE = KV8 ? (KV8_SINGLE ? 1 : 2) : NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
   static constexpr int PD = KV8 ? NL : FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed (widened)
@@ -242,7 +246,7 @@ struct AttnCfg {
   static_assert(PD <= 3 && TILE_OPS * (PD > 1 ? PD - 1 : 1) < 64, "the wait counter holds 6 bits");
   static_assert(TK % ((KV8 ? RPI8 : RPI) * NW) == 0, "tile must divide evenly over the waves");
   static_assert(!KV8 || (D == 128 && NLDK >= 1), "8-bit K/V: head dimension 128");
-  static_assert(BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
+  static_assert(KV8 || BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
 };
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
@@ -539,10 +543,30 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
 
   // per-lane LDS read bases (row r of a tile: block r % NBLK, sub-row r / NBLK)
   const int L16 = lane & 15, grp1 = (lane >> 4) & 1;
-  const int wave_sub = wk * KBW * (32 / NBLK);  // first sub-row of this wave's keys
-  const int kbase_off = (l32 % NBLK) * PK + (wave_sub + l32 / NBLK) * ROWB + hh * 16;
-  const int vbase_off = KTILE + (4 * hh + (L16 >> 2)) * PV + wave_sub * ROWB + (2 * grp1 + ((L16 & 3) >> 1)) * 16 +
+  const int wave_sub = C::KV8_PRIV ? 0 : wk * KBW * (32 / NBLK);  // first sub-row of this wave's keys
+  const int priv_base = C::KV8_PRIV ? wave * C::PRIV_REGION : 0;  // (8-bit K/V, one row group: the wave's own region)
+  const int kbase_off = priv_base + (l32 % NBLK) * PK + (wave_sub + l32 / NBLK) * ROWB + hh * 16;
+  const int vbase_off = priv_base + KTILE + (4 * hh + (L16 >> 2)) * PV + wave_sub * ROWB + (2 * grp1 + ((L16 & 3) >> 1)) * 16 +
                         ((L16 & 1) << 3);
+
+  // 8-bit K/V, one row group: the raw V bytes of the tile at hand stay in registers until the wave has
+  // read its K operands; only then are they widened, into the region K occupied
+  u32x4 vraw_keep[C::KV8_PRIV ? NLDK : 1];
+  auto widen_v_private = [&]() __attribute__((always_inline)) {
+    if constexpr (C::KV8_PRIV) {
+#pragma unroll
+      for (int jj = 0; jj < NLDK; ++jj) {
+        const int r = jj * C::RPI8 + lsub;  // row among the wave's 32
+        bf16x8 lo, hi;
+        widen_e4m3(vraw_keep[jj], lo, hi);
+        auto *vd = reinterpret_cast<__attribute__((address_space(3))) bf16x8 *>(lds + priv_base + (r % NBLK) * PV +
+                                                                                 (r / NBLK) * ROWB + lpos * 32);
+        vd[0] = lo;
+        vd[1] = hi;
+      }
+      asm volatile("" ::: "memory");  // the transposed reads below come after these stores
+    }
+  };
 
   // ---- one 32-key block of one tile: S^T = K Q^T, online softmax, O^T += V^T P^T ----
   auto compute_block = [&](const lds_byte *stage, auto kb_tag, int base, int limit, bool tree, auto masked_tag) __attribute__((always_inline)) {
@@ -567,6 +591,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
         sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
     }
     TVA_PHASE(1);
+    widen_v_private();
     // V^T operands of the first 16 keys: in flight during the softmax arithmetic
     s16x4 vlo[2][ND], vhi[2][ND];
 #pragma unroll
@@ -885,7 +910,33 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   // and the landing slot they leave takes the loads of tile j + NL.  A lane widens the 16 bytes it
   // loaded itself (row row0_of(jj) + lsub, 16 head-dimension elements from 16 * lpos): 32 bytes of bf16 ----
   auto land_tile = [&](int j) __attribute__((always_inline)) {
-    if constexpr (KV8) {
+    if constexpr (C::KV8_PRIV) {
+      // one row group: K is widened now, V after the K operands have been read (widen_v_private);
+      // both raw pieces are in registers first, so the landing slot is refilled at once
+      wait_tile(j);
+      const uint32_t land = (uint32_t)(uintptr_t)(lds + C::LAND_OFF + (j % C::NL) * C::LAND_SLOT) + lane * 16;
+      u32x4 kraw[NLDK];
+#pragma unroll
+      for (int jj = 0; jj < NLDK; ++jj) {
+        kraw[jj] = lds_read_b128(land + kdst_of(jj));
+        vraw_keep[jj] = lds_read_b128(land + vdst_of(jj));
+      }
+#pragma unroll
+      for (int jj = 0; jj < NLDK; ++jj) lds_wait(kraw[jj], vraw_keep[jj]);
+      asm volatile("" ::: "memory");  // the slot is refilled below this line, not above
+      if (j + PD < n_tiles) issue_tile(j + PD);
+#pragma unroll
+      for (int jj = 0; jj < NLDK; ++jj) {
+        const int r = jj * C::RPI8 + lsub;
+        bf16x8 lo, hi;
+        widen_e4m3(kraw[jj], lo, hi);
+        auto *kd = reinterpret_cast<__attribute__((address_space(3))) bf16x8 *>(lds + priv_base + (r % NBLK) * PK +
+                                                                                 (r / NBLK) * ROWB + lpos * 32);
+        kd[0] = lo;
+        kd[1] = hi;
+      }
+      asm volatile("" ::: "memory");
+    } else if constexpr (KV8) {
       wait_tile(j);
       const uint32_t land = (uint32_t)(uintptr_t)(lds + C::LAND_OFF + (j % C::NL) * C::LAND_SLOT) + lane * 16;
       lds_byte *stage = lds + (j % NSTAGE) * STAGE_BYTES;
@@ -918,8 +969,10 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       // where every wave reads only what it widened itself.
       if (!C::KV8_PRIV) __builtin_amdgcn_s_barrier();
       land_tile(it);
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      if (!C::KV8_PRIV) __builtin_amdgcn_s_barrier();
+      if (!C::KV8_PRIV) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+      }
     } else if constexpr (KV8) {
       // everyone's widened part of tile `it` is in LDS (the wait covers this wave's LDS writes);
       // everyone is done with tile it-1, whose stage tile it+1 is widened into next
