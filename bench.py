@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--head-major", action="store_true",
                     help="store the dense cache as [Hkv, sum_L, D] (passed through the stride arguments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-length-hint", action="store_true",
+                    help="do not pass the host-known sum of the cache lengths to the launch planner")
     ap.add_argument("--kv-fp8", action="store_true",
                     help="K/V stored as 8-bit floating point (E4M3) bytes: half the K/V bytes per step")
     a = ap.parse_args()
@@ -86,6 +88,7 @@ def main():
     if a.kv_fp8:
         from paper_2510_26577_amd import workloads as wl
         w, k_scale, v_scale = wl.to_fp8_kv(w)
+    sum_L = 0 if a.no_length_hint else int(w.L.sum())   # the serving side knows its sequence lengths
     kv_bytes, alg_bytes, flops = w.kv_bytes(), w.algorithmic_bytes(), w.algorithmic_flops()
     R = a.rotate or max(2, min(64, -(-640 * 2 ** 20 // alg_bytes)))
 
@@ -110,7 +113,7 @@ def main():
                                  anc_mask=m, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale,
                                  cu_L=dw.cu_L, page_table=dw.page_table, page_size=w.page_size,
                                  strides=strides, num_splits=a.splits, out=o, lse=l, kv_fp8=a.kv_fp8, k_scale=k_scale,
-                                 v_scale=v_scale)
+                                 v_scale=v_scale, sum_L=sum_L)
         argv.append(args)
     # the same calls with the parent arrays in place of ancestor masks (the kernel derives the masks)
     argv_parent = []
@@ -119,7 +122,7 @@ def main():
             q=dw.q, k_tree=dw.k_tree, v_tree=dw.v_tree, k_cache=dw.k_cache, v_cache=dw.v_cache, anc_mask=None,
             parent=dw.parent, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale, cu_L=dw.cu_L,
             page_table=dw.page_table, page_size=w.page_size, strides=strides, num_splits=a.splits, out=o, lse=l,
-            kv_fp8=a.kv_fp8, k_scale=k_scale, v_scale=v_scale))
+            kv_fp8=a.kv_fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L))
     n_splits = binding.plan_splits(argv[0])
     ws_bytes = binding.workspace_bytes(argv[0])
     wss = []

@@ -127,6 +127,14 @@ typedef struct tva_args {
      are unchanged; the arithmetic is the bf16 path's on the exactly widened values.  D = 128 only. */
   int32_t kv_fp8;
   float k_scale, v_scale;
+
+  /* Optional planning hint: the sum over the batch of min(L[b], max_L), as the host knows it, or 0.
+     The launch plan sizes the KV splits for max_L; with cache lengths that differ a lot some splits
+     of the shorter sequences are empty and their workgroups idle.  Given the sum, long splits are
+     shortened so that the non-empty ones still fit one round of workgroups.  Results do not depend
+     on the value (any number gives a valid plan); tva_workspace_bytes and the tva_plan_* queries
+     use it the same way, so pass the same value to them. */
+  int64_t sum_L;
 } tva_args;
 
 /*

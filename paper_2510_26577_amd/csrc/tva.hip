@@ -1384,6 +1384,18 @@ bool make_plan(const tva_args *a, Plan *pl) {
   if (S < 1) S = 1;
   int ck = a->max_L > 0 ? (a->max_L + S - 1) / S : pl->TK;
   ck = (ck + pl->TK - 1) / pl->TK * pl->TK;
+  if (a->num_splits == 0 && S > 1 && a->sum_L > 0 && a->B > 1) {
+    // Cache lengths known to differ (their sum is given): the plan above aims at natural * S
+    // workgroups, but the splits a shorter sequence does not reach are empty.  Sequence b needs
+    // ceil(L_b / c) <= L_b / c + 1 splits of c keys, so with c >= sum_L / (S * B - B) the non-empty
+    // ones of the whole batch still number at most S * B per (KV head, row block): one round as
+    // planned, of shorter splits.  Only where splits stay long (16 tiles), so that their length and
+    // not the fixed cost per workgroup is what the time follows.
+    const int64_t slots = (int64_t)S * a->B - a->B;
+    int64_t c = (a->sum_L + slots - 1) / slots;
+    c = (c + pl->TK - 1) / pl->TK * pl->TK;
+    if (c >= 16 * pl->TK && c < ck) ck = (int)c;
+  }
   pl->chunk_keys = ck;
   pl->n_chunks = a->max_L > 0 ? (a->max_L + ck - 1) / ck : 1;
   // one 2 x 2 workgroup per CU at most and long splits: a third ring stage (two tiles in flight)
@@ -1519,6 +1531,7 @@ static int check_args(const tva_args *a, bool shapes_only) {
   if (a->stride_page < 0 || a->stride_tok < 0 || a->stride_head < 0) return TVA_INVALID_ARG;
   if (a->stride_tok >= (1 << 24)) return TVA_UNSUPPORTED;  // lane offsets inside a tile are 32-bit
   if (a->kv_fp8 && (!(a->k_scale >= 0.f) || !(a->v_scale >= 0.f))) return TVA_INVALID_ARG;
+  if (a->sum_L < 0) return TVA_INVALID_ARG;
   return TVA_OK;
 }
 

@@ -112,6 +112,26 @@ def test_invalid_shapes_rejected_before_launch(lib, kw, code):
     assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == code
 
 
+def test_length_hint_shortens_long_splits_of_ragged_batches(lib):
+    """Four sequences of up to 32768 cached tokens, 96000 in all: 8 splits of 4096 keys would leave a quarter of
+    the workgroups without keys; with the sum known the splits shrink so that the non-empty ones still fit one
+    round (ceil(L_b / c) summed over the batch <= 8 * 4 per KV head)."""
+    a = shape_args(B=4, max_L=32768, max_T=48, sum_T=4 * 48)
+    assert (binding.plan_splits(a), binding.plan_chunk_keys(a)) == (8, 4096)
+    a = shape_args(B=4, max_L=32768, max_T=48, sum_T=4 * 48, sum_L=96000)
+    c = binding.plan_chunk_keys(a)
+    assert c == 3456 and binding.plan_splits(a) == 10 and c % 64 == 0
+    assert 96000 / c + 4 <= 8 * 4                        # the bound the planner relies on
+    assert binding.workspace_bytes(a) == 10 * 4 * 48 * 32 * 129 * 4
+    # equal lengths (sum = B * max_L), short splits, one sequence, forced splits: the hint changes nothing
+    for kw in (dict(B=4, max_L=32768, sum_L=4 * 32768), dict(B=4, max_L=2048, sum_L=5000),
+               dict(B=1, max_L=32768, sum_L=20000), dict(B=4, max_L=32768, sum_L=96000, num_splits=8)):
+        b = shape_args(max_T=48, sum_T=kw["B"] * 48, **kw)
+        kw.pop("sum_L")
+        assert binding.plan_chunk_keys(b) == binding.plan_chunk_keys(shape_args(max_T=48, sum_T=kw["B"] * 48, **kw))
+    assert lib.tva_plan_splits(ctypes.byref(shape_args(sum_L=-1))) == 8      # shapes only: not looked at
+    
+
 def test_fp8_arguments_checked_on_the_host(lib):
     assert binding.plan_splits(shape_args(kv_fp8=1)) >= 1                         # D = 128: fine
     a = shape_args(kv_fp8=1, D=64)

@@ -173,6 +173,30 @@ def test_every_band_of_the_launch_planner(gpu, B, L, T, page, rows, splits):
     check_full(gpu, w, label=f"planner band rows={rows} splits={splits} page={page}")
 
 
+@pytest.mark.parametrize("page", [0, 16])
+def test_length_hint_changes_the_plan_not_the_result(gpu, page):
+    """Long ragged caches with their sum passed as the planning hint: shorter splits (asserted), same result."""
+    import torch
+    from paper_2510_26577_amd import binding
+    L = [6000, 11900, 7100, 12000]
+    w = wl.random_workload(950 + page, 4, 32, 8, 128, L, [48, 40, 48, 33], max_depth=7, page_size=page)
+    a = binding.TvaArgs()
+    a.B, a.Hq, a.Hkv, a.D, a.sum_T, a.max_T, a.mask_words, a.max_L, a.scale = 4, 32, 8, 128, w.sum_T, 48, 1, 12000, w.scale
+    plain = binding.plan_chunk_keys(a)
+    a.sum_L = sum(L)
+    hinted = binding.plan_chunk_keys(a)
+    say(f"[case] length hint page={page}: split {plain} -> {hinted} keys")
+    assert hinted < plain
+    dw = gpu.to_device(w)
+    out, lse = gpu.attention(dw, None, sum_L=sum(L))
+    out0, lse0 = gpu.attention(dw, None)
+    torch.cuda.synchronize()
+    ro, rl = orc.tree_verify_attn(w)
+    for o, l in ((out, lse), (out0, lse0)):
+        assert np.abs(o.cpu().numpy().astype(np.float64) - ro).max() <= TOL_O
+        assert np.abs(l.cpu().numpy().astype(np.float64) - rl).max() <= TOL_LSE
+
+
 @pytest.mark.parametrize("case", ["cfg2", "cfg3_B16", "cfg4", "cfg5", "ragged", "paged", "forest_T128", "D64"])
 def test_masks_derived_in_kernel_equal_masks_passed(gpu, case):
     """Passing the parent arrays instead of ancestor masks gives the same ancestor sets, hence the same
