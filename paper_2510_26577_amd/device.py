@@ -62,8 +62,8 @@ def attention(dw: DeviceWorkload, mask, num_splits: int = 0, max_L: Optional[int
         kv_fp8=fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L)
 
 
-def run_path(dw: DeviceWorkload, num_splits: int = 0):
+def run_path(dw: DeviceWorkload, num_splits: int = 0, sum_L: int = 0):
     """The whole hot path once: ancestor masks, split-KV attention, merge."""
     mask = build_mask(dw)
-    out, lse = attention(dw, mask, num_splits=num_splits)
+    out, lse = attention(dw, mask, num_splits=num_splits, sum_L=sum_L)
     return mask, out, lse

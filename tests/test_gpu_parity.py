@@ -81,7 +81,7 @@ def test_config5_paged_full_size_sampled(gpu):
     w = wl.config5()
     say(f"[case] cfg5 full L={list(w.L)}")
     dw = gpu.to_device(w)
-    mask, out, lse = gpu.run_path(dw)
+    mask, out, lse = gpu.run_path(dw, sum_L=int(w.L.sum()))   # the benchmark passes the length hint too
     torch.cuda.synchronize()
     assert np.array_equal(mask.cpu().numpy().view(np.uint64), orc.ancestor_mask(w.parent, w.cu_T))
     rng = np.random.Generator(np.random.PCG64(99))
