@@ -1260,49 +1260,81 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
 // ---------------------------------------------------------------------------------------
 // merge of the KV splits
 // ---------------------------------------------------------------------------------------
-// One wave per output row (token, head).  The two 32-lane halves take the even and the odd
-// splits, 16 bytes of the row per lane (D = 128; one half-wave covers two splits' worth at
-// D = 64), and are added at the end.  Splits whose LSE is -inf (empty, or never computed because
-// the sequence is shorter than the launch's split count) get weight zero.
-template <int D>
+// One wave per output row (token, head).  The lanes form GROUPS groups of D/4 lanes (16 bytes of
+// the row per lane); group g takes the splits g, g + GROUPS, ...  Every load of a block of NI
+// splits per group -- the partial rows and their log-sum-exps, clamped to a split that exists --
+// is issued before anything is computed from them, so a row costs one memory round trip however
+// many splits it has (NI is chosen on the host to cover S where it can).  The groups keep a
+// running maximum each and are combined at the end.  Splits whose LSE is -inf (empty, or never
+// computed because the sequence is shorter than the launch's split count) get weight zero; their
+// O may be uninitialised memory and is dropped by selection, never by multiplication.
+template <int D, int NI>
 __global__ void __launch_bounds__(256) merge_kernel(const float *__restrict__ part_out,
                                                     const float *__restrict__ part_lse, int S, int64_t n_rows,
                                                     float *__restrict__ out, float *__restrict__ lse) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= n_rows) return;
-  constexpr int LPR = D / 4;      // lanes covering one row with 16 bytes each
+  constexpr int LPR = D / 4;        // lanes covering one row with 16 bytes each
   constexpr int GROUPS = 64 / LPR;  // splits processed side by side in one wave
   const int grp = lane / LPR, col = (lane % LPR) * 4;
-  float mx = -INFINITY;
-  for (int s = lane; s < S; s += 64) mx = fmaxf(mx, part_lse[(size_t)s * n_rows + row]);
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-  if (mx == -INFINITY) {
-    if (grp == 0) *reinterpret_cast<f32x4 *>(out + row * D + col) = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (lane == 0) lse[row] = -INFINITY;
-    return;
-  }
+  float m = -INFINITY, z = 0.f;     // running maximum of the LSEs, sum of weights relative to it
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  float z = 0.f;
-#pragma unroll 8
-  for (int s = grp; s < S; s += GROUPS) {
-    // O of an empty split may be uninitialised memory: read it anyway (so that the loads of all
-    // splits are in flight together) and drop it by selection, never by multiplication
-    const float w = __expf(part_lse[(size_t)s * n_rows + row] - mx);
-    const f32x4 v = *reinterpret_cast<const f32x4 *>(part_out + ((size_t)s * n_rows + row) * D + col);
-    z += w;
+  for (int s0 = grp; s0 < S; s0 += GROUPS * NI) {
+    float l[NI];
+    f32x4 v[NI];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) acc[e] += (w != 0.f) ? v[e] * w : 0.f;
+    for (int i = 0; i < NI; ++i) {
+      const int s = s0 + i * GROUPS;
+      const int sc = s < S ? s : s0;
+      l[i] = part_lse[(size_t)sc * n_rows + row];
+      v[i] = *reinterpret_cast<const f32x4 *>(part_out + ((size_t)sc * n_rows + row) * D + col);
+      if (s >= S) l[i] = -INFINITY;
+    }
+    float mb = m;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) mb = fmaxf(mb, l[i]);
+    if (mb > -INFINITY) {
+      const float keep = __expf(m - mb);  // 0 while nothing has been accumulated (m = -inf)
+      z *= keep;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] *= keep;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const float w = __expf(l[i] - mb);
+        z += w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += (w != 0.f) ? v[i][e] * w : 0.f;
+      }
+      m = mb;
+    }
   }
 #pragma unroll
   for (int o = 32; o >= LPR; o >>= 1) {
-    z += __shfl_xor(z, o);
+    const float m2 = __shfl_xor(m, o), z2 = __shfl_xor(z, o);
+    const float mn = fmaxf(m, m2);
+    const float k1 = (m > -INFINITY) ? __expf(m - mn) : 0.f, k2 = (m2 > -INFINITY) ? __expf(m2 - mn) : 0.f;
+    z = z * k1 + z2 * k2;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], o);
+    for (int e = 0; e < 4; ++e) acc[e] = acc[e] * k1 + __shfl_xor(acc[e], o) * k2;
+    m = mn;
   }
-  if (grp == 0) *reinterpret_cast<f32x4 *>(out + row * D + col) = acc * (1.f / z);
-  if (lane == 0) lse[row] = mx + __logf(z);
+  const bool any = z > 0.f;
+  if (grp == 0) *reinterpret_cast<f32x4 *>(out + row * D + col) = any ? acc * (1.f / z) : f32x4{0.f, 0.f, 0.f, 0.f};
+  if (lane == 0) lse[row] = any ? m + __logf(z) : -INFINITY;
+}
+
+// NI = splits per lane group and block: the smallest of 1, 2, 4, 8 that covers S in one block
+template <int D>
+void launch_merge(const float *part_out, const float *part_lse, int S, int64_t n_rows, float *out, float *lse,
+                  hipStream_t st) {
+  constexpr int GROUPS = 64 / (D / 4);
+  const dim3 grid((unsigned)((n_rows + 3) / 4)), block(256);
+  const int per_group = (S + GROUPS - 1) / GROUPS;
+  if (per_group <= 1) hipLaunchKernelGGL((merge_kernel<D, 1>), grid, block, 0, st, part_out, part_lse, S, n_rows, out, lse);
+  else if (per_group <= 2) hipLaunchKernelGGL((merge_kernel<D, 2>), grid, block, 0, st, part_out, part_lse, S, n_rows, out, lse);
+  else if (per_group <= 4) hipLaunchKernelGGL((merge_kernel<D, 4>), grid, block, 0, st, part_out, part_lse, S, n_rows, out, lse);
+  else hipLaunchKernelGGL((merge_kernel<D, 8>), grid, block, 0, st, part_out, part_lse, S, n_rows, out, lse);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1635,14 +1667,9 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
 
   if (merge && pl.n_chunks > 1) {
     const int64_t n_rows = (int64_t)query_rows(a) * a->Hq;
-    const int mgrid = (int)((n_rows + 3) / 4);
     clear_stale_hip_error();
-    if (a->D == 128)
-      hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, p.part_out, p.part_lse, pl.n_chunks,
-                         n_rows, a->out, a->lse);
-    else
-      hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, p.part_out, p.part_lse, pl.n_chunks,
-                         n_rows, a->out, a->lse);
+    if (a->D == 128) launch_merge<128>(p.part_out, p.part_lse, pl.n_chunks, n_rows, a->out, a->lse, st);
+    else launch_merge<64>(p.part_out, p.part_lse, pl.n_chunks, n_rows, a->out, a->lse, st);
     if (launch_status("merge kernel launch") != hipSuccess) return TVA_HIP_ERROR;
   }
   return TVA_OK;
@@ -1655,13 +1682,10 @@ int tva_merge_splits(const float *part_out, const float *part_lse, int32_t S, in
   if (n_rows == 0) return TVA_OK;
   if (!part_out || !part_lse || !out || !lse) return TVA_INVALID_ARG;
   if ((n_rows + 3) / 4 > 0x7fffffff) return TVA_UNSUPPORTED;
-  const int mgrid = (int)((n_rows + 3) / 4);
   hipStream_t st = (hipStream_t)stream;
   clear_stale_hip_error();
-  if (D == 128)
-    hipLaunchKernelGGL(merge_kernel<128>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse);
-  else
-    hipLaunchKernelGGL(merge_kernel<64>, dim3(mgrid), dim3(256), 0, st, part_out, part_lse, S, n_rows, out, lse);
+  if (D == 128) launch_merge<128>(part_out, part_lse, S, n_rows, out, lse, st);
+  else launch_merge<64>(part_out, part_lse, S, n_rows, out, lse, st);
   return launch_status("merge kernel launch") == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 
