@@ -1056,7 +1056,10 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       for (int step = 0; step < Tb && node >= 0; ++step) {
         if (node < 64) b0 |= 1ull << node;
         else b1 |= 1ull << (node - 64);
-        const int up = par[node];
+        // (read through inline assembly: an ordinary LDS load of memory an LDS-writing load filled
+        // makes the compiler drain every outstanding load first, the prefetched tiles included)
+        int up;
+        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(up) : "v"((uint32_t)(uintptr_t)(par + node)));
         node = up < node ? up : -1;  // a link that does not point backwards ends the walk
       }
       mrow[r][0] = b0;
