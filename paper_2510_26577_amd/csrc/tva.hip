@@ -144,19 +144,11 @@ __device__ __forceinline__ float half_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-#ifndef TVA_PRIO_MODE
-#define TVA_PRIO_MODE 0
-#endif
-#if TVA_PRIO_MODE == 1
-#define TVA_PRIO_MFMA() __builtin_amdgcn_s_setprio(1)
-#define TVA_PRIO_VALU() __builtin_amdgcn_s_setprio(0)
-#elif TVA_PRIO_MODE == 2
-#define TVA_PRIO_MFMA() __builtin_amdgcn_s_setprio(0)
-#define TVA_PRIO_VALU() __builtin_amdgcn_s_setprio(1)
-#else
-#define TVA_PRIO_MFMA() do { } while (0)
-#define TVA_PRIO_VALU() do { } while (0)
-#endif
+// Build-time switches, all off or at their shipped value by default.  They exist for one-off
+// measurement builds: TVA_W8_KBW (32-key blocks per tile of the eight-wave shape), TVA_FAST_PATH
+// (software-pipelined loop of the four-wave shape), TVA_PV_PAD (V tile block padding),
+// TVA_EXP_NOCOMPUTE / TVA_EXP_NOLOAD (the kernel's load skeleton / its arithmetic alone: results are
+// wrong on purpose), TVA_TIMING (cycle stamps of one workgroup).
 #ifndef TVA_W8_KBW
 #define TVA_W8_KBW 2
 #endif
