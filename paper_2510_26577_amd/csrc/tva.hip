@@ -156,6 +156,7 @@ __device__ __forceinline__ float half_sum(float x) {
 #define TVA_FAST_PATH 1
 #endif
 
+
 template <int D, int WM, int WK, int RB, bool PAGED, int NST, bool KV8 = false>
 struct AttnCfg {
   static constexpr int NW = WM * WK;
@@ -176,22 +177,23 @@ struct AttnCfg {
   // 16-lane group of the V transpose load) then sit in different blocks, PAD apart in bank
   // position, and every read address is one per-lane base plus a compile-time offset.
   static constexpr int NBLK = DC;                // 16 (D=128) or 8 (D=64)
-  // 8-bit K/V (see NL below): workgroups of up to four waves keep ONE widened tile; with one row group
-  // every wave reads only the rows it loaded itself, and its widened K and V then take turns in one
-  // private region of 32 rows laid out like a tile (KTILE = 0: V sits where K was)
-  static constexpr bool KV8_SINGLE = KV8 && NW <= 4;
-  static constexpr bool KV8_PRIV = KV8 && WM == 1;
-  static constexpr int SUBS = KV8_PRIV ? 32 / NBLK : TK / NBLK;  // rows per block
+  // 8-bit K/V (see NL below).  One row group (WM = 1): every wave reads only the rows it loaded itself,
+  // and it widens nothing in LDS -- its operand reads take the bytes straight from where they landed
+  // (8 bytes per lane for K, the 8-bit LDS transpose read for V) and widen them in registers; the
+  // ring is four byte tiles and there is no barrier.  Other workgroups of up to four waves keep ONE
+  // widened tile and two landing slots, so that two of them fit a CU.
+  static constexpr bool KV8_REG = KV8 && WM == 1;
+  static constexpr bool KV8_SINGLE = KV8 && NW <= 4 && !KV8_REG;
+  static constexpr int SUBS = TK / NBLK;         // rows per block
   static constexpr int BLKB = SUBS * ROWB;       // 1 KiB (TK=64) or 2 KiB (TK=128)
-  static constexpr int IPB = BLKB >= 1024 ? BLKB / 1024 : 1;  // load instructions per block (16-bit K/V)
+  static constexpr int IPB = BLKB / 1024;        // load instructions per block (16-bit K/V)
   static constexpr int PK = BLKB + 16;           // block pitch of the K tile
 #ifndef TVA_PV_PAD
 #define TVA_PV_PAD 32
 #endif
   static constexpr int PV = BLKB + TVA_PV_PAD;   // block pitch of the V tile
-  static constexpr int KTILE = KV8_PRIV ? 0 : NBLK * PK, VTILE = NBLK * PV;
-  static constexpr int PRIV_REGION = NBLK * PV;  // one wave's 32 widened rows (KV8_PRIV)
-  static constexpr int STAGE_BYTES = KV8_PRIV ? (NW * PRIV_REGION + 1023) / 1024 * 1024 : (KTILE + VTILE + 1023) / 1024 * 1024;
+  static constexpr int KTILE = NBLK * PK, VTILE = NBLK * PV;
+  static constexpr int STAGE_BYTES = KV8_REG ? 2 * TK * D : (KTILE + VTILE + 1023) / 1024 * 1024;
   // NST = stages of the ring, 0 for the shape's default: four for the software-pipelined loop
   // (two tiles in flight; it still reads the V operands of tile t-1 after tile t has been entered,
   // hence one stage more than tiles in flight + 1) and for the eight-wave shape (three in flight:
@@ -201,15 +203,11 @@ struct AttnCfg {
   // 8-bit K/V: the loads land in per-wave zones of NL landing slots (a tile of bytes each); the wave that
   // loaded a piece widens it to bf16 into one of two tiles of the layout above, one tile ahead of
   // the arithmetic.  NL tiles are in flight or being widened.
-  // Workgroups of up to four waves keep ONE widened tile and two landing slots, so that two of them
-  // fit a CU (the other workgroup covers the two barriers per tile this costs); where a wave only ever
-  // reads the rows it loaded itself (one row group: the key groups' rows are disjoint) no barrier is
-  // needed at all.
-  static constexpr int NL = KV8 ? (KV8_PRIV ? 3 : KV8_SINGLE ? 2 : (NST ? NST : 3)) : 0;
+  static constexpr int NL = KV8_REG ? 0 : KV8 ? (KV8_SINGLE ? 2 : (NST ? NST : 3)) : 0;
   static constexpr int LAND_SLOT = KV8 ? 2 * TK * D : 0;
-  static constexpr int NSTAGE = KV8 ? (KV8_SINGLE ? 1 : 2) : NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
-  static constexpr int PD = KV8 ? NL : FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed (widened)
-  static constexpr int WG_PER_CU = KV8 ? (KV8_SINGLE ? 2 : 1) : (NSTAGE == 2 && TK == 64) ? 2 : 1;
+  static constexpr int NSTAGE = KV8_REG ? 4 : KV8 ? (KV8_SINGLE ? 1 : 2) : NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
+  static constexpr int PD = KV8_REG ? NSTAGE - 1 : KV8 ? NL : FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed (widened)
+  static constexpr int WG_PER_CU = KV8 ? ((KV8_SINGLE || KV8_REG) ? 2 : 1) : (NSTAGE == 2 && TK == 64) ? 2 : 1;
   // after the key loop the ring is reused: exchange area of the key-group merge, then (behind it,
   // when the groups are paired; else on top of it, after a barrier) the output transpose patches
   static constexpr bool PAIR = (WK == 2);
@@ -238,7 +236,7 @@ struct AttnCfg {
   static_assert(PD <= 3 && TILE_OPS * (PD > 1 ? PD - 1 : 1) < 64, "the wait counter holds 6 bits");
   static_assert(TK % ((KV8 ? RPI8 : RPI) * NW) == 0, "tile must divide evenly over the waves");
   static_assert(!KV8 || (D == 128 && NLDK >= 1), "8-bit K/V: head dimension 128");
-  static_assert(KV8 || BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
+  static_assert(BLKB % 1024 == 0, "a block is a whole number of wave-wide loads");
 };
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
@@ -273,6 +271,37 @@ __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) {
 }
 __device__ __forceinline__ void lds_wait(u32x4 &a, u32x4 &b) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b));
+}
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x2 lds_read_b64(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64 %0, %1" : "=v"(v) : "v"(addr));
+  return v;
+}
+// LDS transpose read of bytes: the 16 lanes of a group pass the addresses of 8 bytes each, rows
+// (lane >> 1) of an 8 x 16 byte matrix, columns 8 * (lane & 1) ...; lane j of the group receives
+// column j, rows 0 .. 7.
+__device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64_tr_b8 %0, %1" : "=v"(v) : "v"(addr));
+  return v;
+}
+__device__ __forceinline__ void lds_wait(u32x2 &a, u32x2 &b, u32x2 &c, u32x2 &d) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+// 8 E4M3 bytes -> 8 bf16
+__device__ __forceinline__ bf16x8 widen_e4m3(const u32x2 raw) {
+  bf16x8 out;
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], false);
+    const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[w], true);
+    out[4 * w + 0] = (__bf16)a[0];
+    out[4 * w + 1] = (__bf16)a[1];
+    out[4 * w + 2] = (__bf16)b[0];
+    out[4 * w + 3] = (__bf16)b[1];
+  }
+  return out;
 }
 // 16 E4M3 bytes -> 16 bf16 (exact: every E4M3 value is a bf16 value)
 __device__ __forceinline__ void widen_e4m3(const u32x4 raw, bf16x8 &lo, bf16x8 &hi) {
@@ -466,18 +495,24 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     }
   };
   // full tiles of a dense cache: a wave-uniform row pointer plus one tile-independent lane offset
-  const uint32_t lane_off = (uint32_t)lrow * (uint32_t)p.stride_tok * (uint32_t)EB + (uint32_t)lpos * 16u;
+  // (8-bit K/V read in place: inside each 1 KiB piece -- 8 rows of 8 chunks -- the lane that lands in
+  // slot (row, c) fetches chunk c ^ row ^ (j & 1) of that row, j the piece's index: the 8-byte operand
+  // reads and the byte transpose reads then spread over the LDS banks)
+  auto chunk_of = [&](int j) __attribute__((always_inline)) { return C::KV8_REG ? (lpos ^ lsub ^ (j & 1)) : lpos; };
+  const uint32_t lane_off2[2] = {(uint32_t)lrow * (uint32_t)p.stride_tok * (uint32_t)EB + (uint32_t)chunk_of(0) * 16u,
+                                 (uint32_t)lrow * (uint32_t)p.stride_tok * (uint32_t)EB + (uint32_t)chunk_of(1) * 16u};
   auto issue_impl = [&](int t, auto tree_tag) __attribute__((always_inline)) {
     constexpr bool tree = decltype(tree_tag)::value;
     const int base = tree ? (t - n_ct) * TK : k0 + t * TK;
     const int limit = tree ? Tb : k1;
-    lds_byte *stage = KV8 ? lds + C::LAND_OFF + (t % (KV8 ? C::NL : 1)) * C::LAND_SLOT : lds + (t % NSTAGE) * STAGE_BYTES;
+    lds_byte *stage = (KV8 && !C::KV8_REG) ? lds + C::LAND_OFF + (t % (C::NL > 0 ? C::NL : 1)) * C::LAND_SLOT
+                                           : lds + (t % NSTAGE) * STAGE_BYTES;
     if (!PAGED && t < n_full) {
 #pragma unroll
       for (int j = 0; j < NLDK; ++j) {
         const int64_t urow = cache_base + (int64_t)(base + row0_of(j)) * p.stride_tok;
-        const char *ksrc = kc_bytes + urow * EB + lane_off;
-        const char *vsrc = vc_bytes + urow * EB + lane_off;
+        const char *ksrc = kc_bytes + urow * EB + lane_off2[j & 1];
+        const char *vsrc = vc_bytes + urow * EB + lane_off2[j & 1];
         __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + kdst_of(j), 16, 0, 0);
         __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + vdst_of(j), 16, 0, 0);
       }
@@ -487,7 +522,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       const char *ksrc, *vsrc;
       int key = base + row0_of(j) + lrow;
       key = key < limit ? key : limit - 1;
-      const int eoff = lpos * (16 / EB);  // first element of the lane's 16-byte chunk
+      const int eoff = chunk_of(j) * (16 / EB);  // first element of the lane's 16-byte chunk
       if (tree && p.k_tree != nullptr) {
         const int64_t off = ((int64_t)(t0 + key) * p.Hkv + kvh) * D + eoff;
         ksrc = kt_bytes + off * EB;
@@ -535,30 +570,27 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
 
   // per-lane LDS read bases (row r of a tile: block r % NBLK, sub-row r / NBLK)
   const int L16 = lane & 15, grp1 = (lane >> 4) & 1;
-  const int wave_sub = C::KV8_PRIV ? 0 : wk * KBW * (32 / NBLK);  // first sub-row of this wave's keys
-  const int priv_base = C::KV8_PRIV ? wave * C::PRIV_REGION : 0;  // (8-bit K/V, one row group: the wave's own region)
-  const int kbase_off = priv_base + (l32 % NBLK) * PK + (wave_sub + l32 / NBLK) * ROWB + hh * 16;
-  const int vbase_off = priv_base + KTILE + (4 * hh + (L16 >> 2)) * PV + wave_sub * ROWB + (2 * grp1 + ((L16 & 3) >> 1)) * 16 +
+  const int wave_sub = wk * KBW * (32 / NBLK);  // first sub-row of this wave's keys
+  const int kbase_off = (l32 % NBLK) * PK + (wave_sub + l32 / NBLK) * ROWB + hh * 16;
+  const int vbase_off = KTILE + (4 * hh + (L16 >> 2)) * PV + wave_sub * ROWB + (2 * grp1 + ((L16 & 3) >> 1)) * 16 +
                         ((L16 & 1) << 3);
 
-  // 8-bit K/V, one row group: the raw V bytes of the tile at hand stay in registers until the wave has
-  // read its K operands; only then are they widened, into the region K occupied
-  u32x4 vraw_keep[C::KV8_PRIV ? NLDK : 1];
-  auto widen_v_private = [&]() __attribute__((always_inline)) {
-    if constexpr (C::KV8_PRIV) {
+  // 8-bit K/V read in place: byte offsets, inside a stage, of the lane's K operand of k-step s (key l32
+  // of the wave's 32, bytes 16 s + 8 hh of its row) and of its share of the byte transpose read for
+  // d block d (row = L16 >> 1 of the 8 x 16 byte matrix is key 4 hh + (row & 3) + 8 (row >> 2), as the
+  // probabilities' operand layout pairs them; columns are bytes 32 d + 16 grp1 ...), with the slot
+  // permutation the loads apply inside each 1 KiB piece
+  int koff8[NS], voff8[ND];
+  if constexpr (C::KV8_REG) {
+    const int zone = wave * (2 * NLDK * 1024);
+    const int kj = l32 >> 3, kr = l32 & 7;
 #pragma unroll
-      for (int jj = 0; jj < NLDK; ++jj) {
-        const int r = jj * C::RPI8 + lsub;  // row among the wave's 32
-        bf16x8 lo, hi;
-        widen_e4m3(vraw_keep[jj], lo, hi);
-        auto *vd = reinterpret_cast<__attribute__((address_space(3))) bf16x8 *>(lds + priv_base + (r % NBLK) * PV +
-                                                                                 (r / NBLK) * ROWB + lpos * 32);
-        vd[0] = lo;
-        vd[1] = hi;
-      }
-      asm volatile("" ::: "memory");  // the transposed reads below come after these stores
-    }
-  };
+    for (int s2 = 0; s2 < NS; ++s2) koff8[s2] = zone + kj * 1024 + ((kr * 8 + (s2 ^ kr ^ (kj & 1))) << 4) + 8 * hh;
+    const int row = L16 >> 1, vj = row >> 2, vr = 4 * hh + (row & 3);
+#pragma unroll
+    for (int d = 0; d < ND; ++d)
+      voff8[d] = zone + NLDK * 1024 + vj * 1024 + ((vr * 8 + ((2 * d + grp1) ^ vr ^ (vj & 1))) << 4) + 8 * (L16 & 1);
+  }
 
   // ---- one 32-key block of one tile: S^T = K Q^T, online softmax, O^T += V^T P^T ----
   auto compute_block = [&](const lds_byte *stage, auto kb_tag, int base, int limit, bool tree, auto masked_tag) __attribute__((always_inline)) {
@@ -575,6 +607,22 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[r][i] = 0.f;
     TVA_PHASE(0);
+    const uint32_t sb8 = (uint32_t)(uintptr_t)stage;  // (8-bit K/V read in place)
+    if constexpr (C::KV8_REG) {
+      static_assert(!C::KV8_REG || (NS == 8 && ND == 4 && KBW == 1), "8-bit K/V in place: D = 128, one block per wave and tile");
+      u32x2 kraw[NS];
+#pragma unroll
+      for (int s = 0; s < NS; ++s) kraw[s] = lds_read_b64(sb8 + koff8[s]);
+      lds_wait(kraw[0], kraw[1], kraw[2], kraw[3]);
+      lds_wait(kraw[NS - 4], kraw[NS - 3], kraw[NS - 2], kraw[NS - 1]);
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const bf16x8 ka = widen_e4m3(kraw[s]);
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+          sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
+      }
+    } else {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(kp + s * 32);
@@ -582,15 +630,25 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       for (int r = 0; r < RB; ++r)
         sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
     }
+    }
     TVA_PHASE(1);
-    widen_v_private();
     // V^T operands of the first 16 keys: in flight during the softmax arithmetic
     s16x4 vlo[2][ND], vhi[2][ND];
+    u32x2 vraw[2][ND];  // (8-bit K/V read in place: one byte transpose read per operand)
 #pragma unroll
     for (int d = 0; d < ND; ++d) {
-      vlo[0][d] = lds_read_tr<KBOFF + 0>(va + d * 64);
-      vhi[0][d] = lds_read_tr<KBOFF + V8>(va + d * 64);
+      if constexpr (C::KV8_REG) {
+        vraw[0][d] = lds_read_tr8(sb8 + voff8[d]);
+      } else {
+        vlo[0][d] = lds_read_tr<KBOFF + 0>(va + d * 64);
+        vhi[0][d] = lds_read_tr<KBOFF + V8>(va + d * 64);
+      }
     }
+    // the V^T operand of the PV product over keys 16 s2 .. 16 s2 + 15, d block d
+    auto v_operand = [&](int s2, int d) __attribute__((always_inline)) {
+      if constexpr (C::KV8_REG) return widen_e4m3(vraw[s2][d]);
+      else return __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[s2][d], vhi[s2][d], 0, 1, 2, 3, 4, 5, 6, 7));
+    };
     // bit i of ok[r]: element i of this lane (key base+kofs+8*(i/4)+4*hh+i%4) may be attended
     unsigned ok[RB];
 #pragma unroll
@@ -657,25 +715,31 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     TVA_PHASE(2);
     constexpr int S2OFF = (16 / NBLK) * ROWB;
     static_assert(ND == 4 || ND == 2, "head dimension 128 or 64");
-    if constexpr (ND == 4) lds_wait(vlo[0][0], vlo[0][1], vlo[0][2], vlo[0][3]), lds_wait(vhi[0][0], vhi[0][1], vhi[0][2], vhi[0][3]);
+    if constexpr (C::KV8_REG) lds_wait(vraw[0][0], vraw[0][1], vraw[0][ND - 2], vraw[0][ND - 1]);
+    else if constexpr (ND == 4) lds_wait(vlo[0][0], vlo[0][1], vlo[0][2], vlo[0][3]), lds_wait(vhi[0][0], vhi[0][1], vhi[0][2], vhi[0][3]);
     else lds_wait(vlo[0][0], vlo[0][1], vhi[0][0], vhi[0][1]);
 #pragma unroll
     for (int d = 0; d < ND; ++d) {
-      vlo[1][d] = lds_read_tr<KBOFF + S2OFF>(va + d * 64);
-      vhi[1][d] = lds_read_tr<KBOFF + S2OFF + V8>(va + d * 64);
+      if constexpr (C::KV8_REG) {
+        vraw[1][d] = lds_read_tr8(sb8 + voff8[d] + 2048);  // keys 16 .. 31: two 1 KiB pieces further
+      } else {
+        vlo[1][d] = lds_read_tr<KBOFF + S2OFF>(va + d * 64);
+        vhi[1][d] = lds_read_tr<KBOFF + S2OFF + V8>(va + d * 64);
+      }
     }
 #pragma unroll
     for (int d = 0; d < ND; ++d) {
-      const bf16x8 vop = __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[0][d], vhi[0][d], 0, 1, 2, 3, 4, 5, 6, 7));
+      const bf16x8 vop = v_operand(0, d);
 #pragma unroll
       for (int r = 0; r < RB; ++r)
         oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pb[0][r], oacc[r][d], 0, 0, 0);
     }
-    if constexpr (ND == 4) lds_wait(vlo[1][0], vlo[1][1], vlo[1][2], vlo[1][3]), lds_wait(vhi[1][0], vhi[1][1], vhi[1][2], vhi[1][3]);
+    if constexpr (C::KV8_REG) lds_wait(vraw[1][0], vraw[1][1], vraw[1][ND - 2], vraw[1][ND - 1]);
+    else if constexpr (ND == 4) lds_wait(vlo[1][0], vlo[1][1], vlo[1][2], vlo[1][3]), lds_wait(vhi[1][0], vhi[1][1], vhi[1][2], vhi[1][3]);
     else lds_wait(vlo[1][0], vlo[1][1], vhi[1][0], vhi[1][1]);
 #pragma unroll
     for (int d = 0; d < ND; ++d) {
-      const bf16x8 vop = __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[1][d], vhi[1][d], 0, 1, 2, 3, 4, 5, 6, 7));
+      const bf16x8 vop = v_operand(1, d);
 #pragma unroll
       for (int r = 0; r < RB; ++r)
         oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pb[1][r], oacc[r][d], 0, 0, 0);
@@ -697,8 +761,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
         for (int d = 0; d < ND; ++d) {
-          const bf16x8 vop =
-              __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[s2][d], vhi[s2][d], 0, 1, 2, 3, 4, 5, 6, 7));
+          const bf16x8 vop = v_operand(s2, d);
 #pragma unroll
           for (int r = 0; r < RB; ++r)
             oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[s2][r], oacc[r][d], 0, 0, 0);
@@ -897,38 +960,11 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     return false;
   };
 
-  // ---- one pipeline step: wait for tile `it`, refill the stage tile it-1 used, compute ----
-  // ---- 8-bit K/V: this wave's pieces of tile j, once landed, are widened to bf16 into stage j % 2,
-  // and the landing slot they leave takes the loads of tile j + NL.  A lane widens the 16 bytes it
+  // ---- 8-bit K/V widened through LDS: this wave's pieces of tile j, once landed, are widened to bf16 into
+  // stage j % NSTAGE, and the landing slot they leave takes the loads of tile j + NL.  A lane widens the 16 bytes it
   // loaded itself (row row0_of(jj) + lsub, 16 head-dimension elements from 16 * lpos): 32 bytes of bf16 ----
   auto land_tile = [&](int j) __attribute__((always_inline)) {
-    if constexpr (C::KV8_PRIV) {
-      // one row group: K is widened now, V after the K operands have been read (widen_v_private);
-      // both raw pieces are in registers first, so the landing slot is refilled at once
-      wait_tile(j);
-      const uint32_t land = (uint32_t)(uintptr_t)(lds + C::LAND_OFF + (j % C::NL) * C::LAND_SLOT) + lane * 16;
-      u32x4 kraw[NLDK];
-#pragma unroll
-      for (int jj = 0; jj < NLDK; ++jj) {
-        kraw[jj] = lds_read_b128(land + kdst_of(jj));
-        vraw_keep[jj] = lds_read_b128(land + vdst_of(jj));
-      }
-#pragma unroll
-      for (int jj = 0; jj < NLDK; ++jj) lds_wait(kraw[jj], vraw_keep[jj]);
-      asm volatile("" ::: "memory");  // the slot is refilled below this line, not above
-      if (j + PD < n_tiles) issue_tile(j + PD);
-#pragma unroll
-      for (int jj = 0; jj < NLDK; ++jj) {
-        const int r = jj * C::RPI8 + lsub;
-        bf16x8 lo, hi;
-        widen_e4m3(kraw[jj], lo, hi);
-        auto *kd = reinterpret_cast<__attribute__((address_space(3))) bf16x8 *>(lds + priv_base + (r % NBLK) * PK +
-                                                                                 (r / NBLK) * ROWB + lpos * 32);
-        kd[0] = lo;
-        kd[1] = hi;
-      }
-      asm volatile("" ::: "memory");
-    } else if constexpr (KV8) {
+    if constexpr (KV8 && !C::KV8_REG) {
       wait_tile(j);
       const uint32_t land = (uint32_t)(uintptr_t)(lds + C::LAND_OFF + (j % C::NL) * C::LAND_SLOT) + lane * 16;
       lds_byte *stage = lds + (j % NSTAGE) * STAGE_BYTES;
@@ -954,18 +990,16 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     }
   };
 
+  // ---- one pipeline step: wait for tile `it`, refill the stage tile it-1 used, compute ----
   auto step = [&](int it, auto masked_tag, auto tree_tag) __attribute__((always_inline)) {
     if constexpr (C::KV8_SINGLE) {
       // one widened tile: everyone is done with tile it-1; this wave's pieces of tile `it` are widened
-      // into its place; everyone's are (the wait covers this wave's LDS writes).  Without the barriers
-      // where every wave reads only what it widened itself.
-      if (!C::KV8_PRIV) __builtin_amdgcn_s_barrier();
+      // into its place; everyone's are (the wait covers this wave's LDS writes)
+      __builtin_amdgcn_s_barrier();
       land_tile(it);
-      if (!C::KV8_PRIV) {
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-      }
-    } else if constexpr (KV8) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+    } else if constexpr (KV8 && !C::KV8_REG) {
       // everyone's widened part of tile `it` is in LDS (the wait covers this wave's LDS writes);
       // everyone is done with tile it-1, whose stage tile it+1 is widened into next
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -975,7 +1009,9 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     // this wave's loads of tile `it` have landed once at most the later tiles' loads are outstanding
     wait_tile(it);
     TVA_PHASE(5);
-    __builtin_amdgcn_s_barrier();  // everyone's part of tile `it` is in LDS; everyone is done with tile it-1
+    // everyone's part of tile `it` is in LDS; everyone is done with tile it-1 (no barrier where a wave
+    // reads only the bytes it loaded itself)
+    if (!C::KV8_REG) __builtin_amdgcn_s_barrier();
     TVA_PHASE(6);
     if (it + PD < n_tiles) issue_tile(it + PD);
     }
@@ -1058,7 +1094,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       mrow[r][1] = b1;
     }
   }
-  if constexpr (KV8 && !C::KV8_SINGLE) land_tile(0);
+  if constexpr (KV8 && !C::KV8_SINGLE && !C::KV8_REG) land_tile(0);
   TVA_STAMP(2);
   int it = 0;
   if (C::FAST && n_full > 0 && wave_has_rows) {
