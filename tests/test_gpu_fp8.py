@@ -94,3 +94,62 @@ def test_fp8_rejects_head_dimension_64(gpu):
     dw = gpu.to_device(w8)
     with pytest.raises(binding.TvaError):
         gpu.attention(dw, None, k_scale=ks, v_scale=vs)
+
+
+def _rows_in_cache(w8, page_size, rng):
+    """Re-stores an fp8 workload with the tree's K/V bytes behind each sequence's committed tokens."""
+    B, Hkv, D = w8.B, w8.Hkv, w8.D
+    tot = w8.L.astype(np.int64) + w8.T.astype(np.int64)
+    rows = lambda b, cache, tree: np.concatenate([cache[w8.cu_L[b]:w8.cu_L[b] + w8.L[b]], tree[w8.cu_T[b]:w8.cu_T[b + 1]]])
+    if page_size == 0:
+        cu = np.concatenate([[0], np.cumsum(tot)]).astype(np.int32)
+        return (np.concatenate([rows(b, w8.k_cache, w8.k_tree) for b in range(B)]),
+                np.concatenate([rows(b, w8.v_cache, w8.v_tree) for b in range(B)]), cu, None)
+    max_pages = int((tot.max() + page_size - 1) // page_size) + 1
+    table = rng.permutation(B * max_pages).reshape(B, max_pages).astype(np.int32)
+    k = np.full((B * max_pages, page_size, Hkv, D), 0x7E, np.uint8)      # 448 everywhere a stray read would land
+    v = k.copy()
+    for b in range(B):
+        kr, vr = rows(b, w8.k_cache, w8.k_tree), rows(b, w8.v_cache, w8.v_tree)
+        for t in range(int(tot[b])):
+            k[table[b, t // page_size], t % page_size] = kr[t]
+            v[table[b, t // page_size], t % page_size] = vr[t]
+    return k, v, None, table
+
+
+@pytest.mark.parametrize("page_size", [0, 16])
+@pytest.mark.parametrize("variant", [None, 4, 6, 12])
+def test_fp8_tree_rows_in_the_cache_and_query_subsets(gpu, page_size, variant, monkeypatch):
+    """The other input variants on the 8-bit path: tree K/V stored in the cache (k_tree = NULL), and only the
+    newest nodes of each tree as queries (cu_Q); both against the oracle on the same bytes."""
+    import torch
+    from paper_2510_26577_amd import binding
+    if variant is not None:
+        monkeypatch.setenv("TVA_FORCE_VARIANT", str(variant))
+    rng = np.random.Generator(np.random.PCG64(1400 + page_size))
+    w = wl.random_workload(1400 + page_size, 4, 8, 2, 128, [300, 64, 0, 129], [70, 33, 8, 128], max_depth=12)
+    w8, ks, vs = wl.to_fp8_kv(w)
+    ro, rl = f8.tree_verify_attn_fp8(w8, ks, vs)
+    k, v, cu, table = _rows_in_cache(w8, page_size, rng)
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    q, cu_T, L, parent = dev(w8.q.view(np.int16)), dev(w8.cu_T), dev(w8.L.astype(np.int32)), dev(w8.parent)
+    kd, vd, cud, tabd = dev(k), dev(v), dev(cu), dev(table)
+    say(f"[case] fp8 tree rows in cache, page_size={page_size} variant={variant}")
+    for splits in (0, 3):
+        out, lse = binding.tree_verify_attn(q, None, None, kd, vd, None, cu_T, L, max_T=w8.max_T, max_L=w8.max_L,
+                                            scale=w8.scale, cu_L=cud, page_table=tabd, page_size=page_size,
+                                            num_splits=splits, parent=parent, kv_fp8=True, k_scale=ks, v_scale=vs)
+        torch.cuda.synchronize()
+        assert np.abs(out.cpu().numpy().astype(np.float64) - ro).max() <= TOL_O
+        assert np.abs(lse.cpu().numpy().astype(np.float64) - rl).max() <= TOL_LSE
+    Tq = np.array([12, 33, 1, 60])
+    cu_Q = np.concatenate([[0], np.cumsum(Tq)]).astype(np.int32)
+    sel = np.concatenate([np.arange(w8.cu_T[b + 1] - Tq[b], w8.cu_T[b + 1]) for b in range(w8.B)]).astype(np.int64)
+    say(f"[case] fp8 query subset, page_size={page_size} variant={variant}")
+    out, lse = binding.tree_verify_attn(q[torch.from_numpy(sel).cuda()].contiguous(), None, None, kd, vd, None, cu_T, L,
+                                        max_T=w8.max_T, max_L=w8.max_L, scale=w8.scale, cu_L=cud, page_table=tabd,
+                                        page_size=page_size, parent=parent, cu_Q=dev(cu_Q), max_Q=int(Tq.max()),
+                                        sum_T=w8.sum_T, kv_fp8=True, k_scale=ks, v_scale=vs)
+    torch.cuda.synchronize()
+    assert np.abs(out.cpu().numpy().astype(np.float64) - ro[sel]).max() <= TOL_O
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - rl[sel]).max() <= TOL_LSE
