@@ -48,6 +48,9 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
  * on entry), stores 1 + b there.  The lengths, offsets and page numbers themselves are trusted.
  * L_out[b] = L[b] + path_len[b] is written when L_out is not NULL; it must not alias L.
  *
+ * An 8-bit cache (tva_args.kv_fp8) is committed by the same call: only bytes are moved, so pass D / 2 for D
+ * and strides counted in two-byte units.
+ *
  * k_tree = v_tree = NULL selects the in-cache form: tree node i of sequence b already sits at cache
  * position L[b] + i (the layout tva_tree_verify_attn reads when its k_tree is NULL), and the accepted
  * nodes are moved down in place to L[b], L[b]+1, ...; everything behind them is left as it is.

@@ -69,6 +69,11 @@ def make_commit_args(*, cu_T, L, path, path_len, k_tree, v_tree, k_cache, v_cach
     a.page_size = int(page_size)
     a.max_pages = int(page_table.shape[1]) if page_table is not None else 0
     a.stride_page, a.stride_tok, a.stride_head = (int(s) for s in strides)
+    if k_cache.element_size() == 1:
+        # 8-bit K/V: the kernels only move bytes, so a row of D bytes is passed as D/2 two-byte elements
+        assert a.D % 2 == 0 and all(int(s) % 2 == 0 for s in strides)
+        a.D //= 2
+        a.stride_page, a.stride_tok, a.stride_head = (int(s) // 2 for s in strides)
     a.L_out, a.err_flag = _p(L_out), _p(err_flag)
     # the struct holds raw addresses: keep the tensors alive as long as it lives
     a._keep = (cu_T, L, path, path_len, k_tree, v_tree, k_cache, v_cache, cu_L, page_table, L_out, err_flag)

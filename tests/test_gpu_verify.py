@@ -405,3 +405,54 @@ def test_whole_pass_replayed_from_a_graph(torch_dev, page_size):
         assert int(err.item()) == 0
         for name, got, want in zip("out lse path path_len next L_out k v".split(), outputs, eager):
             assert torch.equal(got, want), (name, replay)
+
+
+@pytest.mark.parametrize("page_size", [0, 16])
+def test_commit_of_an_8bit_cache(torch_dev, page_size):
+    """One byte per element (the attention's kv_fp8 layout): copy commit and in-place commit move the same rows."""
+    torch = torch_dev
+    from paper_2510_26577_amd import verify
+    rng = np.random.Generator(np.random.PCG64(95 + page_size))
+    B, Hkv, D = 4, 2, 128
+    T = np.array([30, 1, 9, 64])
+    L = np.array([100, 0, 31, 5], np.int32)
+    w = wl.random_workload(1500 + page_size, B, 4, Hkv, D, L, T, max_depth=9)
+    w8, _, _ = wl.to_fp8_kv(w)
+    k, v, cu, table = _in_cache_layout(w8, rng, page_size)
+    k, v = k.astype(np.uint8), v.astype(np.uint8)
+    paths = [sorted(rng.choice(int(t), size=int(min(t, 5)), replace=False).tolist()) for t in T]
+    max_path = 8
+    path = np.full((B, max_path), -1, np.int32)
+    for b, pth in enumerate(paths):
+        path[b, :len(pth)] = pth
+    plen = np.array([len(pth) for pth in paths], np.int32)
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    at = lambda arr, b, t: arr[cu[b] + t] if page_size == 0 else arr[table[b, t // page_size], t % page_size]
+
+    def expected(src_k, src_v, tree_k=None, tree_v=None):
+        ek, ev = src_k.copy(), src_v.copy()
+        for b, pth in enumerate(paths):
+            for j, node in enumerate(pth):
+                rk = at(src_k, b, L[b] + node) if tree_k is None else tree_k[w8.cu_T[b] + node]
+                rv = at(src_v, b, L[b] + node) if tree_v is None else tree_v[w8.cu_T[b] + node]
+                if page_size == 0:
+                    ek[cu[b] + L[b] + j], ev[cu[b] + L[b] + j] = rk, rv
+                else:
+                    t = L[b] + j
+                    ek[table[b, t // page_size], t % page_size], ev[table[b, t // page_size], t % page_size] = rk, rv
+        return ek, ev
+
+    for in_place in (True, False):
+        say(f"[case] 8-bit commit page_size={page_size} in_place={in_place}")
+        k_d, v_d = dev(k), dev(v)
+        err = torch.zeros(1, dtype=torch.int32, device="cuda")
+        L_out = torch.zeros(B, dtype=torch.int32, device="cuda")
+        verify.commit_path(cu_T=dev(w8.cu_T), L=dev(L), path=dev(path), path_len=dev(plen),
+                           k_tree=None if in_place else dev(w8.k_tree), v_tree=None if in_place else dev(w8.v_tree),
+                           k_cache=k_d, v_cache=v_d, cu_L=dev(cu), page_table=dev(table), page_size=page_size,
+                           L_out=L_out, err_flag=err)
+        torch.cuda.synchronize()
+        ek, ev = expected(k, v) if in_place else expected(k, v, w8.k_tree, w8.v_tree)
+        assert int(err.item()) == 0
+        assert np.array_equal(k_d.cpu().numpy(), ek) and np.array_equal(v_d.cpu().numpy(), ev)
+        assert np.array_equal(L_out.cpu().numpy(), L + plen)
