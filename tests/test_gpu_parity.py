@@ -60,6 +60,11 @@ def test_config2_8b(gpu, splits):
     check_full(gpu, wl.config2(), num_splits=splits)
 
 
+def test_config2_shape_at_batch_32(gpu):
+    """The benchmark's saturating-batch extra (config 2's shape, 32 sequences): every output compared."""
+    check_full(gpu, wl.config2(32))
+
+
 @pytest.mark.parametrize("B", [1, 4, 16, 64])
 def test_config3_sweep(gpu, B):
     check_full(gpu, wl.config3(B))
