@@ -177,13 +177,13 @@ struct AttnCfg {
   // 16-lane group of the V transpose load) then sit in different blocks, PAD apart in bank
   // position, and every read address is one per-lane base plus a compile-time offset.
   static constexpr int NBLK = DC;                // 16 (D=128) or 8 (D=64)
-  // 8-bit K/V (see NL below).  One row group (WM = 1): every wave reads only the rows it loaded itself,
-  // and it widens nothing in LDS -- its operand reads take the bytes straight from where they landed
-  // (8 bytes per lane for K, the 8-bit LDS transpose read for V) and widen them in registers; the
-  // ring is four byte tiles and there is no barrier.  Other workgroups of up to four waves keep ONE
-  // widened tile and two landing slots, so that two of them fit a CU.
-  static constexpr bool KV8_REG = KV8 && WM == 1;
-  static constexpr bool KV8_SINGLE = KV8 && NW <= 4 && !KV8_REG;
+  // 8-bit K/V (see NL below).  Workgroups of up to four waves widen nothing in LDS: the operand reads
+  // take the bytes straight from where they landed (8 bytes per lane for K, the 8-bit LDS transpose read
+  // for V) and widen them in registers; the ring is four byte tiles, two workgroups fit a CU.  With one
+  // row group (WM = 1) every wave reads only the rows it loaded itself and there is no barrier either.
+  // (With two row groups each key is widened twice, with eight waves it would be up to eight times:
+  // those widen once, cooperatively, through LDS.)
+  static constexpr bool KV8_REG = KV8 && NW <= 4;
   static constexpr int SUBS = TK / NBLK;         // rows per block
   static constexpr int BLKB = SUBS * ROWB;       // 1 KiB (TK=64) or 2 KiB (TK=128)
   static constexpr int IPB = BLKB / 1024;        // load instructions per block (16-bit K/V)
@@ -203,11 +203,11 @@ struct AttnCfg {
   // 8-bit K/V: the loads land in per-wave zones of NL landing slots (a tile of bytes each); the wave that
   // loaded a piece widens it to bf16 into one of two tiles of the layout above, one tile ahead of
   // the arithmetic.  NL tiles are in flight or being widened.
-  static constexpr int NL = KV8_REG ? 0 : KV8 ? (KV8_SINGLE ? 2 : (NST ? NST : 3)) : 0;
+  static constexpr int NL = KV8_REG ? 0 : KV8 ? (NST ? NST : 3) : 0;
   static constexpr int LAND_SLOT = KV8 ? 2 * TK * D : 0;
-  static constexpr int NSTAGE = KV8_REG ? 4 : KV8 ? (KV8_SINGLE ? 1 : 2) : NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
+  static constexpr int NSTAGE = KV8_REG ? 4 : KV8 ? 2 : NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
   static constexpr int PD = KV8_REG ? NSTAGE - 1 : KV8 ? NL : FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed (widened)
-  static constexpr int WG_PER_CU = KV8 ? ((KV8_SINGLE || KV8_REG) ? 2 : 1) : (NSTAGE == 2 && TK == 64) ? 2 : 1;
+  static constexpr int WG_PER_CU = KV8 ? (KV8_REG ? 2 : 1) : (NSTAGE == 2 && TK == 64) ? 2 : 1;
   // after the key loop the ring is reused: exchange area of the key-group merge, then (behind it,
   // when the groups are paired; else on top of it, after a barrier) the output transpose patches
   static constexpr bool PAIR = (WK == 2);
@@ -582,15 +582,19 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   // permutation the loads apply inside each 1 KiB piece
   int koff8[NS], voff8[ND];
   if constexpr (C::KV8_REG) {
-    const int zone = wave * (2 * NLDK * 1024);
-    const int kj = l32 >> 3, kr = l32 & 7;
+    // piece n of the tile (keys 8 n .. 8 n + 7) was loaded by wave n / NLDK as its piece n % NLDK: its K bytes
+    // sit in that wave's zone, its V bytes NLDK pieces further on
+    static_assert(!C::KV8_REG || (NLDK % 2 == 0), "the slot permutation's parity bit is the piece's index in its wave's zone");
+    auto piece_off = [&](int n) __attribute__((always_inline)) { return ((n / NLDK) * 2 * NLDK + n % NLDK) * 1024; };
+    const int kn = wk * 4 + (l32 >> 3), kr = l32 & 7;
 #pragma unroll
-    for (int s2 = 0; s2 < NS; ++s2) koff8[s2] = zone + kj * 1024 + ((kr * 8 + (s2 ^ kr ^ (kj & 1))) << 4) + 8 * hh;
-    const int row = L16 >> 1, vj = row >> 2, vr = 4 * hh + (row & 3);
+    for (int s2 = 0; s2 < NS; ++s2) koff8[s2] = piece_off(kn) + ((kr * 8 + (s2 ^ kr ^ (kn & 1))) << 4) + 8 * hh;
+    const int row = L16 >> 1, vn = wk * 4 + (row >> 2), vr = 4 * hh + (row & 3);
 #pragma unroll
     for (int d = 0; d < ND; ++d)
-      voff8[d] = zone + NLDK * 1024 + vj * 1024 + ((vr * 8 + ((2 * d + grp1) ^ vr ^ (vj & 1))) << 4) + 8 * (L16 & 1);
+      voff8[d] = piece_off(vn) + NLDK * 1024 + ((vr * 8 + ((2 * d + grp1) ^ vr ^ (vn & 1))) << 4) + 8 * (L16 & 1);
   }
+  constexpr int V8_SECOND = (NLDK >= 4 ? 2 : 2 * NLDK) * 1024;  // keys 16 .. 31 of the wave: two pieces further on
 
   // ---- one 32-key block of one tile: S^T = K Q^T, online softmax, O^T += V^T P^T ----
   auto compute_block = [&](const lds_byte *stage, auto kb_tag, int base, int limit, bool tree, auto masked_tag) __attribute__((always_inline)) {
@@ -721,7 +725,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
 #pragma unroll
     for (int d = 0; d < ND; ++d) {
       if constexpr (C::KV8_REG) {
-        vraw[1][d] = lds_read_tr8(sb8 + voff8[d] + 2048);  // keys 16 .. 31: two 1 KiB pieces further
+        vraw[1][d] = lds_read_tr8(sb8 + voff8[d] + V8_SECOND);
       } else {
         vlo[1][d] = lds_read_tr<KBOFF + S2OFF>(va + d * 64);
         vhi[1][d] = lds_read_tr<KBOFF + S2OFF + V8>(va + d * 64);
@@ -992,14 +996,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
 
   // ---- one pipeline step: wait for tile `it`, refill the stage tile it-1 used, compute ----
   auto step = [&](int it, auto masked_tag, auto tree_tag) __attribute__((always_inline)) {
-    if constexpr (C::KV8_SINGLE) {
-      // one widened tile: everyone is done with tile it-1; this wave's pieces of tile `it` are widened
-      // into its place; everyone's are (the wait covers this wave's LDS writes)
-      __builtin_amdgcn_s_barrier();
-      land_tile(it);
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      __builtin_amdgcn_s_barrier();
-    } else if constexpr (KV8 && !C::KV8_REG) {
+    if constexpr (KV8 && !C::KV8_REG) {
       // everyone's widened part of tile `it` is in LDS (the wait covers this wave's LDS writes);
       // everyone is done with tile it-1, whose stage tile it+1 is widened into next
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -1011,7 +1008,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     TVA_PHASE(5);
     // everyone's part of tile `it` is in LDS; everyone is done with tile it-1 (no barrier where a wave
     // reads only the bytes it loaded itself)
-    if (!C::KV8_REG) __builtin_amdgcn_s_barrier();
+    if (!(C::KV8_REG && WM == 1)) __builtin_amdgcn_s_barrier();
     TVA_PHASE(6);
     if (it + PD < n_tiles) issue_tile(it + PD);
     }
@@ -1094,7 +1091,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       mrow[r][1] = b1;
     }
   }
-  if constexpr (KV8 && !C::KV8_SINGLE && !C::KV8_REG) land_tile(0);
+  if constexpr (KV8 && !C::KV8_REG) land_tile(0);
   TVA_STAMP(2);
   int it = 0;
   if (C::FAST && n_full > 0 && wave_has_rows) {
