@@ -1438,6 +1438,13 @@ bool make_plan(const tva_args *a, Plan *pl) {
       const int by_len = a->max_L / (16 * pl->TK);
       s2 = s2 < by_len ? s2 : by_len;
       if (s2 > S) S = s2;
+      // A count well between 256 and 512 leaves some CUs with two full workgroups and the rest with
+      // one, and the launch lasts as long as the former: from there go on to (nearly) 512 even with
+      // shorter splits, down to 6 tiles.
+      int s3 = 512 / natural;
+      const int by_len3 = a->max_L / (6 * pl->TK);
+      s3 = s3 < by_len3 ? s3 : by_len3;
+      if (natural * S > 256 && s3 > S && natural * s3 >= 448) S = s3;
     }
   }
   if (S > max_by_len) S = max_by_len;

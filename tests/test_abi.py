@@ -83,6 +83,8 @@ def test_plan_and_workspace(lib):
     (1, 2048, 60, 64, 8),      # the headline shape: 32 natural workgroups of 64 rows, split to one per CU
     (4, 2048, 60, 64, 2),      # 128 natural: two per CU would allow 4 splits, but those would be 8 tiles
     (4, 4096, 60, 64, 4),      # ... and here they keep 16 tiles
+    (3, 2048, 60, 64, 5),      # 96 natural: 3 splits would be 288 workgroups, uneven over 256 CUs: on to 480
+    (5, 2048, 60, 64, 3),      # 160 natural: 320 -> 480
     (8, 2048, 60, 128, 2),     # 128 workgroups of 128 rows, two splits of 16 tiles
     (16, 2048, 60, 128, 1),    # 256 of them
     (8, 1024, 40, 64, 1),      # 128 of 128 rows would need splits of 8 tiles: 192 of 64 rows instead
