@@ -1438,6 +1438,8 @@ bool make_plan(const tva_args *a, Plan *pl) {
       const int by_len = a->max_L / (16 * pl->TK);
       s2 = s2 < by_len ? s2 : by_len;
       if (s2 > S) S = s2;
+    }
+    if ((variant == V_M2K2 || variant == V_K2) && two_per_cu) {
       // A count well between 256 and 512 leaves some CUs with two full workgroups and the rest with
       // one, and the launch lasts as long as the former: from there go on to (nearly) 512 even with
       // shorter splits, down to 6 tiles.

@@ -85,6 +85,7 @@ def test_plan_and_workspace(lib):
     (4, 4096, 60, 64, 4),      # ... and here they keep 16 tiles
     (3, 2048, 60, 64, 5),      # 96 natural: 3 splits would be 288 workgroups, uneven over 256 CUs: on to 480
     (5, 2048, 60, 64, 3),      # 160 natural: 320 -> 480
+    (12, 2048, 8, 32, 5),      # the same for the 32-row shape: 96 natural, 288 -> 480
     (8, 2048, 60, 128, 2),     # 128 workgroups of 128 rows, two splits of 16 tiles
     (16, 2048, 60, 128, 1),    # 256 of them
     (8, 1024, 40, 64, 1),      # 128 of 128 rows would need splits of 8 tiles: 192 of 64 rows instead
