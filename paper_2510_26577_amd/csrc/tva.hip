@@ -37,6 +37,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "tva.h"
@@ -1489,13 +1490,17 @@ inline hipError_t launch_status(const char *what) {
 template <int D, int WM, int WK, int RB, bool PAGED, int NST = 0, bool KV8 = false>
 hipError_t launch_attn(const AttnParams &p, dim3 grid, hipStream_t st) {
   using C = AttnCfg<D, WM, WK, RB, PAGED, NST, KV8>;
-  static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent
+  // raising the dynamic-LDS limit is idempotent and needed once per device (and per instantiation)
+  static std::atomic<uint64_t> attr_done{0};
   auto kfn = attn_kernel<D, WM, WK, RB, PAGED, NST, KV8>;
-  if (!attr_done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+  const uint64_t bit = (dev >= 0 && dev < 64) ? 1ull << dev : 0;
+  if (!(attr_done.load(std::memory_order_relaxed) & bit)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kfn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.fetch_or(bit, std::memory_order_relaxed);
   }
   clear_stale_hip_error();
   hipLaunchKernelGGL(kfn, grid, dim3(C::NT), C::SMEM, st, p);
