@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2510_26577_amd import binding
@@ -113,6 +114,34 @@ def test_invalid_shapes_rejected_before_launch(lib, kw, code):
     a = shape_args(**kw)
     assert lib.tva_plan_splits(ctypes.byref(a)) == -1
     assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == code
+
+
+def test_launch_plan_invariants_over_random_shapes(lib):
+    """Whatever the shapes: the splits cover max_L, are whole tiles of at least two tiles unless the cache is
+    shorter, the workspace matches the split count, the workgroup size is one of the four, the length hint never
+    lengthens a split, and a forced split count is honoured up to the tile limit."""
+    rng = np.random.Generator(np.random.PCG64(20251026))
+    for _ in range(3000):
+        Hkv = int(rng.choice([1, 2, 4, 8, 16]))
+        G = int(rng.choice([1, 2, 4, 7, 8, 16]))
+        B = int(rng.choice([1, 2, 3, 5, 8, 13, 32, 64, 200]))
+        T = int(rng.integers(1, 129))
+        L = int(rng.choice([0, 1, 63, 64, 65, 500, 2048, 4097, 20000, 100000]))
+        kw = dict(B=B, Hq=Hkv * G, Hkv=Hkv, D=int(rng.choice([64, 128])), max_T=T, sum_T=B * T,
+                  mask_words=(T + 63) // 64, max_L=L)
+        fp8 = bool(rng.integers(0, 2)) and kw["D"] == 128
+        a = shape_args(kv_fp8=int(fp8), **kw)
+        S, ck, rows = binding.plan_splits(a), binding.plan_chunk_keys(a), binding.plan_workgroup_rows(a)
+        assert rows in (32, 64, 128, 256) and S >= 1 and ck % 32 == 0 and ck >= 32
+        assert S * ck >= L and (S - 1) * ck < max(L, 1)
+        if S > 1:
+            assert ck >= 64            # no split shorter than two 32-key blocks
+        n_rows = B * T * kw["Hq"]
+        assert binding.workspace_bytes(a) == (0 if S == 1 else S * n_rows * (kw["D"] + 1) * 4)
+        hinted = shape_args(kv_fp8=int(fp8), sum_L=max(1, (B * L) // 2), **kw)
+        assert binding.plan_chunk_keys(hinted) <= ck
+        forced = shape_args(kv_fp8=int(fp8), num_splits=3, **kw)
+        assert binding.plan_splits(forced) == min(3, max(1, -(-L // binding.plan_chunk_keys(forced)))) or L == 0
 
 
 def test_length_hint_shortens_long_splits_of_ragged_batches(lib):
