@@ -444,3 +444,33 @@ def test_splits_entry_point_partials_match_oracle_key_ranges(gpu, splits):
     torch.cuda.synchronize()
     fo, fl = orc.tree_verify_attn(w)
     assert np.abs(out.cpu().numpy() - fo).max() <= TOL_O and np.abs(lse.cpu().numpy() - fl).max() <= TOL_LSE
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_seeded_random_shapes(gpu, seed):
+    """Valid shapes drawn at random (fixed seeds): head counts and group sizes, head dimension, ragged cache and
+    tree sizes including empty ones, dense or paged with odd page sizes, automatic or forced splits, masks
+    passed or derived in the kernel -- each against the oracle."""
+    import torch
+    rng = np.random.Generator(np.random.PCG64(7000 + seed))
+    B = int(rng.integers(1, 7))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 3, 4, 7, 8]))
+    D = int(rng.choice([64, 128]))
+    L = rng.integers(0, int(rng.choice([40, 300, 900])) + 1, B)
+    T = rng.integers(0, int(rng.choice([8, 40, 128])) + 1, B)
+    T[int(rng.integers(0, B))] = max(1, int(T.max()))
+    page = int(rng.choice([0, 0, 1, 5, 16, 64]))
+    splits = int(rng.choice([0, 0, 1, 2, 5]))
+    w = wl.random_workload(7100 + seed, B, Hkv * G, Hkv, D, L, T, max_depth=int(rng.integers(1, 14)), page_size=page)
+    say(f"[case] random seed={seed} B={B} Hkv={Hkv} G={G} D={D} L={list(L)} T={list(T)} page={page} splits={splits}")
+    check_full(gpu, w, num_splits=splits, label=f"random {seed}")
+    dw = gpu.to_device(w)
+    out, lse = gpu.attention(dw, None, num_splits=splits, sum_L=int(L.sum()))
+    torch.cuda.synchronize()
+    ro, rl = orc.tree_verify_attn(w)
+    if ro.size:
+        assert np.abs(out.cpu().numpy().astype(np.float64) - ro).max() <= TOL_O
+        fin = np.isfinite(rl)
+        assert np.array_equal(np.isfinite(lse.cpu().numpy()), fin)
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[fin] - rl[fin]).max() <= TOL_LSE if fin.any() else True
