@@ -138,8 +138,9 @@ typedef struct tva_args {
 } tva_args;
 
 /*
- * Ancestor masks from parent arrays (paper: Tree Reranking Phase -- after the
- * subtree is linearised "each token attends only to its ancestors").
+ * Ancestor masks from parent arrays (paper: Tree Reranking Phase, last
+ * paragraph: the attention mask of the linearised subtree; read here as
+ * "a node sees itself and the nodes on its path to the root").
  *   parent   device int32 [cu_T[B]]  local parent index per node, -1 = root
  *   cu_T     device int32 [B+1]
  *   max_T    host upper bound of the tree sizes (any value >= 1)

@@ -1,7 +1,7 @@
 """CPU oracle of the cost-aware tree-size selection (CAST) host logic.
 
 TEST INFRASTRUCTURE ONLY: imported by tests/ (and nothing in the product path).  Plain
-Python loops in double precision that take the paper's steps in the paper's order and
+Python in double precision, each function written from what the paper defines, in the paper's
 notation; no blocking, no shortcuts.  Shares no code with the native implementation.
 
 What is written out here (paper, section "Method"):
@@ -35,16 +35,16 @@ def select_context(c: int, L: int, M: int) -> int:
 
 
 def select_max_valid_index(u: Sequence[float], c: Sequence[float], C: float) -> int:
-    """Algorithm 1.  u, c of equal length n >= 1, c strictly increasing.  Returns the largest
-    1-based index j whose mark survived: j is unmarked as soon as some earlier i has a chord
-    (u[j]-u[i]) / (c[j]-c[i]) below C."""
-    n = len(u)
-    mark = [1] * n
-    for i in range(n):
-        for j in range(i + 1, n):
-            if (float(u[j]) - float(u[i])) / (float(c[j]) - float(c[i])) < C:
-                mark[j] = 0
-    return max(j + 1 for j in range(n) if mark[j] == 1)
+    """Algorithm 1, from what it defines.  u, c of equal length n >= 1, c strictly increasing.
+    Index j (1-based) is valid iff no chord that ends in it is too flat: the smallest slope
+    (u[j]-u[i]) / (c[j]-c[i]) over the earlier indices i < j is at least C (index 1 has no
+    chord and is always valid).  The result is the largest valid index."""
+    def flattest_chord_into(j: int) -> float:
+        slopes = [(float(u[j]) - float(u[i])) / (float(c[j]) - float(c[i])) for i in range(j)]
+        return min(slopes) if slopes else float("inf")
+
+    valid = [j + 1 for j in range(len(u)) if not flattest_chord_into(j) < C]
+    return valid[-1]
 
 
 def layer_utility(scores: Sequence[Sequence[float]]) -> List[float]:

@@ -3,8 +3,8 @@
  *
  * This file is the plain definition of what the attention of the target
  * model's verification pass computes (paper: Tree Reranking Phase, last
- * paragraph -- the selected subtree is linearised and "each token attends only
- * to its ancestors"; Method, first paragraphs -- a batch of B samples, each
+ * paragraph -- the selected subtree is flattened and its attention mask lets a
+ * node see the nodes on its path to the root; Method, first paragraphs -- a batch of B samples, each
  * with a context of length c, verifying n tree tokens).  It is slow on
  * purpose: the full (L+T) boolean mask of every sequence is materialised, all
  * scores of a row are stored, and the softmax is the naive three-pass one.

@@ -1,8 +1,8 @@
 // libtva: tree-masked verification attention for gfx950 (MI355X).
 //
 // Kernels
-//   anc_mask_kernel   parent arrays -> ancestor-or-self bitmasks (Tree Reranking Phase:
-//                     each linearised tree token attends only to its ancestors)
+//   anc_mask_kernel   parent arrays -> ancestor-or-self bitmasks (the attention mask of the
+//                     linearised subtree; paper, Tree Reranking Phase, last paragraph)
 //   attn_kernel       split-KV attention of all tree tokens of one (sequence, KV head)
 //                     against one chunk of that sequence's cache (+ the tree's own
 //                     keys under the ancestor mask, folded into the last chunk)

@@ -159,3 +159,27 @@ def test_expansion_plan_stops_when_gain_drops():
                              pruner=co.DepthPruner(R=4, C2=1.0))
     # layer 3's utility at its kept size is far below C2 * cost: layer 4 is never generated
     assert len(kept) == 3 and all(1 <= k <= 4 for k in kept)
+
+
+def test_expansion_plan_hand_worked_three_layers_two_steps():
+    """The context of Eq. 2 grows with the nodes kept so far (the table row changes from layer to
+    layer), phi_i goes into the buffer of layer i (not i+1), buffers persist from one decode step to
+    the next and drop their oldest value: all worked out by hand in tests/cast_cases.py."""
+    import cast_cases as cc
+    pr = co.DepthPruner(R=cc.R, C2=cc.C2)
+    kept = co.expansion_plan(cc.STEP1, cc.S_D, cc.S_T, n0=cc.N0, L=cc.L, M=cc.M, C1=cc.C1, pruner=pr)
+    assert kept == cc.KEPT1
+    for layer, a in cc.ALPHA_AFTER_1.items():
+        assert pr.alpha(layer) == pytest.approx(a, rel=1e-12)
+    for layer, buf in cc.BUFFERS_AFTER_1.items():
+        assert list(pr.A[layer]) == pytest.approx(buf, rel=1e-12)
+    kept = co.expansion_plan(cc.STEP2, cc.S_D, cc.S_T, n0=cc.N0, L=cc.L, M=cc.M, C1=cc.C1, pruner=pr)
+    assert kept == cc.KEPT2
+    for layer, a in cc.ALPHA_AFTER_2.items():
+        assert pr.alpha(layer) == pytest.approx(a, rel=1e-12)
+    for layer, buf in cc.BUFFERS_AFTER_2.items():
+        assert list(pr.A[layer]) == pytest.approx(buf, rel=1e-12)
+    # the same second step on fresh buffers goes one layer further: the stop came from A_2's content
+    fresh = co.expansion_plan(cc.STEP2, cc.S_D, cc.S_T, n0=cc.N0, L=cc.L, M=cc.M, C1=cc.C1,
+                              pruner=co.DepthPruner(R=cc.R, C2=cc.C2))
+    assert fresh == [3, 2, 2]

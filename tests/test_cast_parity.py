@@ -135,6 +135,21 @@ def test_expansion_plan_matches_oracle():
     assert agree == 40
 
 
+def test_expansion_plan_hand_worked_case_through_the_native_path():
+    """The hand-worked two-step case of tests/cast_cases.py (expected values from paper arithmetic,
+    not from the oracle): kept counts and every buffer average, exactly."""
+    import cast_cases as cc
+    pr = cast.DepthPruner(max_layers=4, R=cc.R, C2=cc.C2)
+    assert cast.expansion_plan(cc.STEP1, cc.S_D, cc.S_T, n0=cc.N0, L=cc.L, C1=cc.C1, pruner=pr) == cc.KEPT1
+    for layer, a in cc.ALPHA_AFTER_1.items():
+        assert pr.alpha(layer) == pytest.approx(a, rel=1e-7)   # the native scores are float32
+    assert cast.expansion_plan(cc.STEP2, cc.S_D, cc.S_T, n0=cc.N0, L=cc.L, C1=cc.C1, pruner=pr) == cc.KEPT2
+    for layer, a in cc.ALPHA_AFTER_2.items():
+        assert pr.alpha(layer) == pytest.approx(a, rel=1e-7)
+    fresh = cast.DepthPruner(max_layers=4, R=cc.R, C2=cc.C2)
+    assert cast.expansion_plan(cc.STEP2, cc.S_D, cc.S_T, n0=cc.N0, L=cc.L, C1=cc.C1, pruner=fresh) == [3, 2, 2]
+
+
 def test_rerank_count_and_subtree_selection():
     rng = np.random.Generator(np.random.PCG64(16))
     L, M = 128, 8

@@ -4,8 +4,8 @@ Every check below compares `oracle.tva_oracle` with an independent statement of
 the same fact: a textbook routine (scipy softmax / logsumexp on explicitly
 gathered keys), a closed form, an invariant or brute force.  The paper prints
 no numeric example of the attention path, so these pins fix the semantics
-(Tree Reranking Phase: a linearised subtree in which each token attends only to
-its ancestors; Method: batch B, context c, n verified tokens).
+(Tree Reranking Phase: the mask of the linearised subtree admits a node's path to
+the root; Method: batch B, context c, n verified tokens).
 """
 import itertools
 
@@ -173,13 +173,14 @@ def pack(masks, W):
 
 
 def test_ancestor_mask_exhaustive_small_trees():
-    """All topological parent arrays with one root for T <= 8 ((T-1)! of them), in one batch per T."""
-    for T in range(1, 9):
+    """All topological parent arrays with one root for T <= 9 ((T-1)! of them: 40,320 at T = 9), in one
+    batch per T."""
+    for T in range(1, 10):
         trees = [(-1,) + t for t in itertools.product(*[range(i) for i in range(1, T)])]
         parent = np.array(trees, dtype=np.int32).reshape(-1)
         cu_T = np.arange(len(trees) + 1, dtype=np.int32) * T
         got = orc.ancestor_mask(parent, cu_T)
-        want = np.concatenate([pack(dp_masks(t), 1) for t in trees])
+        want = np.array([m for t in trees for m in dp_masks(t)], dtype=np.uint64).reshape(-1, 1)
         assert np.array_equal(got, want), T
 
 
