@@ -63,6 +63,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--splits", type=int, default=0, help="KV splits (0 = library chooses)")
+    ap.add_argument("--shape", type=int, default=0, help="workgroup shape (tva_shape 1..5; 0 = library chooses)")
     ap.add_argument("--rotate", type=int, default=0, help="distinct input copies (0 = enough to exceed 640 MB)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--head-major", action="store_true",
@@ -80,7 +81,7 @@ def main():
               file=sys.stderr)
         raise SystemExit(2)
     line = measure(a)
-    if a.workload == "cfg2" and not (a.kv_fp8 or a.head_major or a.no_graph or a.splits or a.no_saturated):
+    if a.workload == "cfg2" and not (a.kv_fp8 or a.head_major or a.no_graph or a.splits or a.shape or a.no_saturated):
         # The headline shape at B = 1 is ~1 us of HBM time: its roofline fraction mostly measures launch
         # latency.  The same shape at a batch that fills the chip is measured beside it (kernel-level figures
         # only; `value` stays the B = 1 step).
@@ -134,7 +135,7 @@ def measure(a):
                                  anc_mask=m, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale,
                                  cu_L=dw.cu_L, page_table=dw.page_table, page_size=w.page_size,
                                  strides=strides, num_splits=a.splits, out=o, lse=l, kv_fp8=a.kv_fp8, k_scale=k_scale,
-                                 v_scale=v_scale, sum_L=sum_L)
+                                 v_scale=v_scale, sum_L=sum_L, plan_shape=a.shape)
         argv.append(args)
     # the same calls with the parent arrays in place of ancestor masks (the kernel derives the masks)
     argv_parent = []
@@ -143,7 +144,7 @@ def measure(a):
             q=dw.q, k_tree=dw.k_tree, v_tree=dw.v_tree, k_cache=dw.k_cache, v_cache=dw.v_cache, anc_mask=None,
             parent=dw.parent, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale, cu_L=dw.cu_L,
             page_table=dw.page_table, page_size=w.page_size, strides=strides, num_splits=a.splits, out=o, lse=l,
-            kv_fp8=a.kv_fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L))
+            kv_fp8=a.kv_fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L, plan_shape=a.shape))
     n_splits = binding.plan_splits(argv[0])
     ws_bytes = binding.workspace_bytes(argv[0])
     wss = []

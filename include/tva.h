@@ -47,6 +47,21 @@ typedef enum {
 #define TVA_MAX_TREE 128 /* nodes per tree supported by the attention kernels (2 mask words) */
 
 /*
+ * Workgroup shapes of the attention kernel, for tva_args.plan_shape: query rows per workgroup
+ * (tree nodes x query heads of one KV head) and waves.  TVA_SHAPE_AUTO lets the library choose
+ * from the sizes; naming one is a tuning and testing aid (every shape computes the same result
+ * for every input; only the speed differs).
+ */
+typedef enum {
+  TVA_SHAPE_AUTO = 0,
+  TVA_SHAPE_R32_W2 = 1,       /*  32 rows, 1 x 2 waves (the two waves split each tile's keys) */
+  TVA_SHAPE_R64_W4 = 2,       /*  64 rows, 2 x 2 waves, two workgroups per CU */
+  TVA_SHAPE_R64_W4_DEEP = 3,  /*  the same with one more tile in flight, one workgroup per CU */
+  TVA_SHAPE_R128_W8 = 4,      /* 128 rows, 4 x 2 waves */
+  TVA_SHAPE_R256_W8 = 5       /* 256 rows, 8 x 1 waves */
+} tva_shape;
+
+/*
  * Arguments of tva_tree_verify_attn.
  *
  * Shapes: B sequences; sequence b verifies T_b = cu_T[b+1]-cu_T[b] tree tokens
@@ -135,6 +150,8 @@ typedef struct tva_args {
      on the value (any number gives a valid plan); tva_workspace_bytes and the tva_plan_* queries
      use it the same way, so pass the same value to them. */
   int64_t sum_L;
+
+  int32_t plan_shape; /* a tva_shape; TVA_SHAPE_AUTO (0) = the library chooses */
 } tva_args;
 
 /*

@@ -145,24 +145,11 @@ __device__ __forceinline__ float half_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Build-time switches, all off or at their shipped value by default.  They exist for one-off
-// measurement builds: TVA_W8_KBW (32-key blocks per tile of the eight-wave shape), TVA_FAST_PATH
-// (software-pipelined loop of the four-wave shape), TVA_PV_PAD (V tile block padding),
-// TVA_EXP_NOCOMPUTE / TVA_EXP_NOLOAD (the kernel's load skeleton / its arithmetic alone: results are
-// wrong on purpose), TVA_TIMING (cycle stamps of one workgroup).
-#ifndef TVA_W8_KBW
-#define TVA_W8_KBW 2
-#endif
-#ifndef TVA_FAST_PATH
-#define TVA_FAST_PATH 1
-#endif
-
-
 template <int D, int WM, int WK, int RB, bool PAGED, int NST, bool KV8 = false>
 struct AttnCfg {
   static constexpr int NW = WM * WK;
   static constexpr int NT = NW * 64;
-  static constexpr int KBW = (WK == 1) ? ((WM == 8 && RB == 1) ? TVA_W8_KBW : 2) : 1;  // 32-key blocks each wave owns in a tile
+  static constexpr int KBW = (WK == 1) ? (2) : 1;  // 32-key blocks each wave owns in a tile
   static constexpr int TK = WK * KBW * 32;       // keys per tile
   static constexpr int BM = WM * RB * 32;        // query rows per workgroup
   static constexpr int DC = D / 8;               // 16-byte chunks per K/V row
@@ -189,33 +176,26 @@ struct AttnCfg {
   static constexpr int BLKB = SUBS * ROWB;       // 1 KiB (TK=64) or 2 KiB (TK=128)
   static constexpr int IPB = BLKB / 1024;        // load instructions per block (16-bit K/V)
   static constexpr int PK = BLKB + 16;           // block pitch of the K tile
-#ifndef TVA_PV_PAD
-#define TVA_PV_PAD 32
-#endif
-  static constexpr int PV = BLKB + TVA_PV_PAD;   // block pitch of the V tile
+  static constexpr int PV = BLKB + 32;           // block pitch of the V tile
   static constexpr int KTILE = NBLK * PK, VTILE = NBLK * PV;
   static constexpr int STAGE_BYTES = KV8_REG ? 2 * TK * D : (KTILE + VTILE + 1023) / 1024 * 1024;
-  // NST = stages of the ring, 0 for the shape's default: four for the software-pipelined loop
-  // (two tiles in flight; it still reads the V operands of tile t-1 after tile t has been entered,
-  // hence one stage more than tiles in flight + 1) and for the eight-wave shape (three in flight:
-  // its LDS footprint is set by the output patches anyway), else three (TK = 64) or two (TK = 128).
-  // Two stages keep the footprint small enough for two workgroups per CU.
-  static constexpr bool FAST = TVA_FAST_PATH && (TK == 64) && (RB == 1) && (WM == 4) && (NST == 0) && !KV8;
+  // NST = stages of the ring (16-bit K/V): NST - 1 tiles are in flight ahead of the one being computed.
+  // Two stages of 64-key tiles keep the footprint small enough for two workgroups per CU.
   // 8-bit K/V: the loads land in per-wave zones of NL landing slots (a tile of bytes each); the wave that
   // loaded a piece widens it to bf16 into one of two tiles of the layout above, one tile ahead of
   // the arithmetic.  NL tiles are in flight or being widened.
-  static constexpr int NL = KV8_REG ? 0 : KV8 ? (NST ? NST : 3) : 0;
+  static constexpr int NL = KV8_REG ? 0 : KV8 ? NST : 0;
   static constexpr int LAND_SLOT = KV8 ? 2 * TK * D : 0;
-  static constexpr int NSTAGE = KV8_REG ? 4 : KV8 ? 2 : NST ? NST : (FAST || WM == 8) ? 4 : (TK == 64 ? 3 : 2);
-  static constexpr int PD = KV8_REG ? NSTAGE - 1 : KV8 ? NL : FAST ? NSTAGE - 2 : NSTAGE - 1;  // tiles in flight ahead of the one being computed (widened)
+  static constexpr int NSTAGE = KV8_REG ? 4 : KV8 ? 2 : NST;
+  static constexpr int PD = KV8_REG ? NSTAGE - 1 : KV8 ? NL : NSTAGE - 1;  // tiles in flight ahead of the one being computed (widened)
   static constexpr int WG_PER_CU = KV8 ? (KV8_REG ? 2 : 1) : (NSTAGE == 2 && TK == 64) ? 2 : 1;
   // after the key loop the ring is reused: exchange area of the key-group merge, then (behind it,
   // when the groups are paired; else on top of it, after a barrier) the output transpose patches
   static constexpr bool PAIR = (WK == 2);
   static constexpr int NDW = PAIR ? D / 64 : D / 32;  // 32-wide d blocks of the result each wave writes
   static constexpr int TP = NDW * 32 + 4;             // patch row pitch, floats
-  static constexpr int MERGE_BYTES = PAIR ? (2 * WK * WM * RB * 32 * 4 + WM * WK * RB * (D / 64) * 16 * 64 * 4)
-                                     : (WK > 1) ? (WK * WM * RB * 32 * 4 + WM * (RB * (D / 32) * 16 + RB) * 64 * 4) : 0;
+  static_assert(WK == 1 || WK == 2, "one key group, or two that are merged pairwise");
+  static constexpr int MERGE_BYTES = PAIR ? (2 * WK * WM * RB * 32 * 4 + WM * WK * RB * (D / 64) * 16 * 64 * 4) : 0;
   static constexpr int PATCH_OFF = PAIR ? MERGE_BYTES : 0;
   static constexpr int PATCH_BYTES = (PAIR ? NW : WM) * 32 * TP * 4;
   static constexpr int LAND_OFF = NSTAGE * STAGE_BYTES;
@@ -319,19 +299,6 @@ __device__ __forceinline__ void widen_e4m3(const u32x4 raw, bf16x8 &lo, bf16x8 &
   }
 }
 
-#ifdef TVA_TIMING
-#define TVA_PHASE_DECL long long ph_acc[7] = {0, 0, 0, 0, 0, 0, 0}; long long ph_t = clock64();
-#define TVA_PHASE(i) do { const long long ph_n = clock64(); ph_acc[i] += ph_n - ph_t; ph_t = ph_n; } while (0)
-#define TVA_PHASE_DUMP do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == gridDim.z / 2 && (threadIdx.x & 63) == 0) for (int i = 0; i < 7; ++i) tva_dbg[8 + (threadIdx.x >> 6) * 7 + i] = ph_acc[i]; } while (0)
-__device__ long long tva_dbg[64];
-#define TVA_STAMP(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == gridDim.z / 2 && threadIdx.x == 0) tva_dbg[i] = clock64(); } while (0)
-#else
-#define TVA_STAMP(i) do { } while (0)
-#define TVA_PHASE_DECL
-#define TVA_PHASE(i) do { } while (0)
-#define TVA_PHASE_DUMP do { } while (0)
-#endif
-
 template <int D, int WM, int WK, int RB, bool PAGED, int NST, bool KV8>
 __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NST, KV8>::WG_PER_CU))
     attn_kernel(const AttnParams p_in) {
@@ -349,8 +316,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   constexpr int ND = D / 32;  // 32-wide d blocks of the PV product
   extern __shared__ __align__(1024) unsigned char smem[];
   lds_byte *const lds = (lds_byte *)smem;
-  TVA_STAMP(0);
-  TVA_PHASE_DECL
 
   // ---- which (sequence, KV head, row block, chunk) ----
   // grid = (Hkv, row blocks, B * splits): the KV head varies fastest in dispatch order
@@ -394,7 +359,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   const int k0 = chunk * p.chunk_keys;
   const int k1 = (k0 + p.chunk_keys < Lb) ? k0 + p.chunk_keys : Lb;
   const bool has_tree = (chunk == nc - 1);
-  TVA_STAMP(6);
   const int n_full = (k1 - k0) / TK;               // cache tiles that need no masking
   const int n_ct = (k1 - k0 + TK - 1) / TK;
   const int n_tt = has_tree ? (Tb + TK - 1) / TK : 0;
@@ -561,9 +525,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   };
 
   auto issue_tile = [&](int t) __attribute__((always_inline)) {
-#ifdef TVA_EXP_NOLOAD
-    if (t >= 0) return;
-#endif
     if (t >= n_ct) issue_impl(t, std::true_type{});
     else issue_impl(t, std::false_type{});
     request_pages(t + 2);
@@ -611,7 +572,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     for (int r = 0; r < RB; ++r)
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[r][i] = 0.f;
-    TVA_PHASE(0);
     const uint32_t sb8 = (uint32_t)(uintptr_t)stage;  // (8-bit K/V read in place)
     if constexpr (C::KV8_REG) {
       static_assert(!C::KV8_REG || (NS == 8 && ND == 4 && KBW == 1), "8-bit K/V in place: D = 128, one block per wave and tile");
@@ -636,7 +596,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
         sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
     }
     }
-    TVA_PHASE(1);
     // V^T operands of the first 16 keys: in flight during the softmax arithmetic
     s16x4 vlo[2][ND], vhi[2][ND];
     u32x2 vraw[2][ND];  // (8-bit K/V read in place: one byte transpose read per operand)
@@ -717,7 +676,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       need_lo = need_lo || (pmax > kLoThreshold * l_run[r]);
     }
     // O^T += V^T P^T: first 16 keys while the operands of the second 16 arrive
-    TVA_PHASE(2);
     constexpr int S2OFF = (16 / NBLK) * ROWB;
     static_assert(ND == 4 || ND == 2, "head dimension 128 or 64");
     if constexpr (C::KV8_REG) lds_wait(vraw[0][0], vraw[0][1], vraw[0][ND - 2], vraw[0][ND - 1]);
@@ -749,7 +707,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       for (int r = 0; r < RB; ++r)
         oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pb[1][r], oacc[r][d], 0, 0, 0);
     }
-    TVA_PHASE(3);
     // low-order pass (rare): the bf16 rounding remainder of P, recomputed from the scores
     if (__builtin_amdgcn_ballot_w64(need_lo) != 0) {
       bf16x8 plo[2][RB];
@@ -790,179 +747,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
       else if (PD >= 2 && later >= 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD * 1));
       else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     }
-  };
-
-  // ---- software-pipelined path for runs of full (unmasked) tiles ----
-  // One wave has a single instruction stream per SIMD, so the matrix pipe and the vector ALU only
-  // overlap if independent MFMA and VALU work alternates in program order.  Each pass of
-  // fast_body therefore computes the QK^T product of the NEXT 32-key block next to the
-  // exponentials of the CURRENT one, then the PV product of the current block next to reading
-  // back the next block's scores.  The reference maximum is an integer (log2 domain) and is only
-  // moved between passes, when the next block's maximum calls for it, so a pass is branch-free;
-  // moving it multiplies O and l by an exact power of two.
-  struct Scores {
-    float sv[RB][16];  // scores of a block (this lane's 16 keys per row block)
-    float mx[RB];      // block maximum per row, scaled to the log2 domain
-  };
-
-  auto tile_enter = [&](int t) __attribute__((always_inline)) {
-    wait_tile(t);
-    __builtin_amdgcn_s_barrier();
-    if (t + PD < n_tiles) issue_tile(t + PD);
-  };
-
-  // S^T of block (tile t, kb): MFMAs only; fast_readback turns the accumulators into Scores
-  auto fast_qk = [&](int t, auto kb_tag, f32x16 (&sacc)[RB]) {
-    constexpr int kb = decltype(kb_tag)::value;
-    constexpr int KBOFF = kb * (32 / NBLK) * ROWB;
-    const lds_byte *kp = lds + (t % NSTAGE) * STAGE_BYTES + kbase_off + KBOFF;
-#pragma unroll
-    for (int r = 0; r < RB; ++r)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[r][i] = 0.f;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(kp + s * 32);
-#pragma unroll
-      for (int r = 0; r < RB; ++r)
-        sacc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[r][s], sacc[r], 0, 0, 0);
-    }
-  };
-  auto fast_readback = [&](const f32x16 (&sacc)[RB], Scores &x) {
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        x.sv[r][i] = sacc[r][i];
-        mx = fmaxf(mx, x.sv[r][i]);
-      }
-      x.mx[r] = half_max(mx) * p.scale_log2;
-    }
-  };
-  // moves the reference of rows whose next block exceeds it (nothing is pending between passes)
-  auto fast_reference = [&](const Scores &nx) __attribute__((always_inline)) {
-    bool move = false;
-#pragma unroll
-    for (int r = 0; r < RB; ++r) move = move || (nx.mx[r] > m_run[r] + kLazy);
-    if (__builtin_amdgcn_ballot_w64(move) != 0) {
-#pragma unroll
-      for (int r = 0; r < RB; ++r) {
-        const float m_new = ceilf(fmaxf(m_run[r], nx.mx[r]));
-        const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_run[r] - m_new);  // exact power of two
-        m_run[r] = m_new;
-        l_run[r] *= alpha;
-#pragma unroll
-        for (int d = 0; d < ND; ++d)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[r][d][i] *= alpha;
-      }
-    }
-  };
-  // Does block n need the low-order P pass?  Decided before its exponentials, from its maximum
-  // and the running sum so far: the block's largest probability p adds at least p to the sum, so
-  // p > thr * (l + p) is the (slightly conservative) form of the test the plain path applies.
-  auto fast_needs_lo = [&](const Scores &n) __attribute__((always_inline)) {
-    bool need = false;
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      const float m_use = (m_run[r] == -INFINITY) ? 0.f : m_run[r];
-      const float pmax = fast_exp2(n.mx[r] - m_use);
-      need = need || (pmax * (1.f - kLoThreshold) > kLoThreshold * l_run[r]);
-    }
-    return __builtin_amdgcn_ballot_w64(need) != 0;
-  };
-  // exponentials of block c; with LO also the bf16 rounding remainder of P (second MFMA pass)
-  auto fast_exps = [&](const Scores &c, bf16x8 (&pb)[2][RB], bf16x8 (&plo)[2][RB], auto lo_tag) {
-    constexpr bool LO = decltype(lo_tag)::value;
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      const float m_use = (m_run[r] == -INFINITY) ? 0.f : m_run[r];
-      float ls = 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pv = fast_exp2(fmaf(c.sv[r][i], p.scale_log2, -m_use));
-        ls += pv;
-        pb[i / 8][r][i % 8] = (__bf16)pv;
-        if (LO) plo[i / 8][r][i % 8] = (__bf16)(pv - (float)pb[i / 8][r][i % 8]);
-      }
-      l_run[r] += ls;
-    }
-  };
-  struct VOps {
-    s16x4 lo[2][ND], hi[2][ND];
-  };
-  auto fast_vread = [&](int t, auto kb_tag, VOps &v) __attribute__((always_inline)) {
-    constexpr int kb = decltype(kb_tag)::value;
-    constexpr int KBOFF = kb * (32 / NBLK) * ROWB;
-    constexpr int V8 = (NBLK == 16) ? 8 * PV : ROWB;
-    constexpr int S2OFF = (16 / NBLK) * ROWB;
-    const uint32_t va = (uint32_t)(uintptr_t)(lds + (t % NSTAGE) * STAGE_BYTES + vbase_off);
-#pragma unroll
-    for (int d = 0; d < ND; ++d) {
-      v.lo[0][d] = lds_read_tr<KBOFF>(va + d * 64);
-      v.hi[0][d] = lds_read_tr<KBOFF + V8>(va + d * 64);
-    }
-#pragma unroll
-    for (int d = 0; d < ND; ++d) {
-      v.lo[1][d] = lds_read_tr<KBOFF + S2OFF>(va + d * 64);
-      v.hi[1][d] = lds_read_tr<KBOFF + S2OFF + V8>(va + d * 64);
-    }
-  };
-  auto fast_vwait = [&](VOps &v) __attribute__((always_inline)) {
-    static_assert(ND == 4 || ND == 2, "head dimension 128 or 64");
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) {
-      if constexpr (ND == 4) {
-        lds_wait(v.lo[s2][0], v.lo[s2][1], v.lo[s2][2], v.lo[s2][3]);
-        lds_wait(v.hi[s2][0], v.hi[s2][1], v.hi[s2][2], v.hi[s2][3]);
-      } else {
-        lds_wait(v.lo[s2][0], v.lo[s2][1], v.hi[s2][0], v.hi[s2][1]);
-      }
-    }
-  };
-  auto fast_pv = [&](const bf16x8 (&pbx)[2][RB], const VOps &v) {
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-      for (int d = 0; d < ND; ++d) {
-        const bf16x8 vop =
-            __builtin_bit_cast(bf16x8, __builtin_shufflevector(v.lo[s2][d], v.hi[s2][d], 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-        for (int r = 0; r < RB; ++r)
-          oacc[r][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pbx[s2][r], oacc[r][d], 0, 0, 0);
-      }
-  };
-  // One pass.  In: scores of the current block (tc, kbc) in `sc`, with the reference valid for
-  // them, and whether that block takes the low-order pass.  Out: `sc` holds the scores of the
-  // next block (tn, kbn), the reference is valid for those, and the return value says whether
-  // that block takes the low-order pass.  HAS_NEXT = false drains the pipeline.
-  auto fast_body = [&](int tc, auto kbc_tag, int tn, auto kbn_tag, Scores &sc, bool lo, auto has_next_tag) __attribute__((always_inline)) {
-    constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
-    constexpr int kbn = decltype(kbn_tag)::value;
-    if (HAS_NEXT && kbn == 0) tile_enter(tn);
-    VOps v;
-    fast_vread(tc, kbc_tag, v);
-    f32x16 sacc[RB];
-    bf16x8 pb[2][RB], plo[2][RB];
-    if (lo) {  // rare: few effective keys so far
-      fast_exps(sc, pb, plo, std::true_type{});
-      if (HAS_NEXT) fast_qk(tn, kbn_tag, sacc);
-      fast_vwait(v);
-      fast_pv(pb, v);
-      fast_pv(plo, v);
-    } else {
-      if (HAS_NEXT) fast_qk(tn, kbn_tag, sacc);
-      fast_exps(sc, pb, plo, std::false_type{});
-      fast_vwait(v);
-      fast_pv(pb, v);
-    }
-    if (HAS_NEXT) {
-      fast_readback(sacc, sc);
-      fast_reference(sc);
-      return fast_needs_lo(sc);
-    }
-    return false;
   };
 
   // ---- 8-bit K/V widened through LDS: this wave's pieces of tile j, once landed, are widened to bf16 into
@@ -1006,21 +790,15 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     } else {
     // this wave's loads of tile `it` have landed once at most the later tiles' loads are outstanding
     wait_tile(it);
-    TVA_PHASE(5);
     // everyone's part of tile `it` is in LDS; everyone is done with tile it-1 (no barrier where a wave
     // reads only the bytes it loaded itself)
     if (!(C::KV8_REG && WM == 1)) __builtin_amdgcn_s_barrier();
-    TVA_PHASE(6);
     if (it + PD < n_tiles) issue_tile(it + PD);
     }
     constexpr bool tree = decltype(tree_tag)::value;
     const int base = tree ? (it - n_ct) * TK : k0 + it * TK;
     const int limit = tree ? Tb : k1;
     const lds_byte *stage = lds + (it % NSTAGE) * STAGE_BYTES;
-    TVA_PHASE(4);
-#ifdef TVA_EXP_NOCOMPUTE
-    if (threadIdx.x > 100000)
-#endif
     {
     // wave-uniform: a block is skipped when none of its keys exists, and all of them by a wave
     // none of whose query rows exists (it still loads its share of every tile)
@@ -1035,7 +813,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     }
   };
 
-  TVA_STAMP(1);
   // No ancestor masks passed: the tree's parent array goes to LDS (by the first two waves, with the
   // same LDS-writing loads as everything else here, so it is covered by the counted wait below).
   const bool derive_masks = has_tree && p.mask == nullptr;
@@ -1093,33 +870,10 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     }
   }
   if constexpr (KV8 && !C::KV8_REG) land_tile(0);
-  TVA_STAMP(2);
   int it = 0;
-  if (C::FAST && n_full > 0 && wave_has_rows) {
-    using kb0 = std::integral_constant<int, 0>;
-    using kb1 = std::integral_constant<int, KBW - 1>;
-    Scores sc;
-    {
-      f32x16 sacc[RB];
-      tile_enter(0);
-      fast_qk(0, kb0{}, sacc);
-      fast_readback(sacc, sc);
-      fast_reference(sc);
-    }
-    bool lo = fast_needs_lo(sc);
-    for (int t = 0; t < n_full; ++t) {
-      if constexpr (KBW == 2) lo = fast_body(t, kb0{}, t, kb1{}, sc, lo, std::true_type{});
-      if (t + 1 < n_full) lo = fast_body(t, kb1{}, t + 1, kb0{}, sc, lo, std::true_type{});
-      else fast_body(t, kb1{}, t + 1, kb0{}, sc, lo, std::false_type{});
-      
-    }
-    it = n_full;
-  }
   for (; it < n_full; ++it) step(it, std::false_type{}, std::false_type{});
-  TVA_STAMP(3);
   for (; it < n_ct; ++it) step(it, std::true_type{}, std::false_type{});   // the partial cache tile
   for (; it < n_tiles; ++it) step(it, std::true_type{}, std::true_type{});  // the tree's own keys
-  TVA_STAMP(4);
   if constexpr (PAGED) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the last (unused) table entries have landed
   __builtin_amdgcn_s_barrier();  // all waves are done reading the ring before it is reused below
 
@@ -1130,8 +884,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
 
   // ---- merge the WK key groups through LDS ----
   // Two key groups: each wave keeps one half of the head dimension and hands the other half to
-  // its partner, so both take part in the reduction and in writing the result.  More than two:
-  // the groups are folded into group 0 one after the other, which then writes alone.
+  // its partner, so both take part in the reduction and in writing the result.
   constexpr bool PAIR = C::PAIR;
   if constexpr (PAIR) {
     constexpr int H = ND / 2;
@@ -1185,59 +938,8 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
     };
     if (wk == 0) swap_halves(std::integral_constant<int, 0>{});
     else swap_halves(std::integral_constant<int, 1>{});
-  } else if constexpr (WK > 1) {
-    float *sm = reinterpret_cast<float *>(smem);                      // [WK][WM][RB][32]
-    float *so = sm + WK * WM * RB * 32;                               // [WM][RB*ND*16 + RB][64]
-    constexpr int OSTRIDE = (RB * ND * 16 + RB) * 64;
-    if (hh == 0) {
-#pragma unroll
-      for (int r = 0; r < RB; ++r) sm[((wk * WM + wm) * RB + r) * 32 + l32] = m_run[r];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      float mf = -INFINITY;
-#pragma unroll
-      for (int w = 0; w < WK; ++w) mf = fmaxf(mf, sm[((w * WM + wm) * RB + r) * 32 + l32]);
-      const float m_use = (mf == -INFINITY) ? 0.f : mf;
-      const float a = fast_exp2(m_run[r] - m_use);
-      m_run[r] = mf;
-      l_tot[r] *= a;
-#pragma unroll
-      for (int d = 0; d < ND; ++d)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[r][d][i] *= a;
-    }
-    __syncthreads();
-    for (int w = WK - 1; w >= 1; --w) {
-      float *dst = so + wm * OSTRIDE;
-      if (wk == w) {
-#pragma unroll
-        for (int r = 0; r < RB; ++r) {
-#pragma unroll
-          for (int d = 0; d < ND; ++d)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dst[((r * ND + d) * 16 + i) * 64 + lane] = oacc[r][d][i];
-          dst[(RB * ND * 16 + r) * 64 + lane] = l_tot[r];
-        }
-      }
-      __syncthreads();
-      if (wk == 0) {
-#pragma unroll
-        for (int r = 0; r < RB; ++r) {
-#pragma unroll
-          for (int d = 0; d < ND; ++d)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[r][d][i] += dst[((r * ND + d) * 16 + i) * 64 + lane];
-          l_tot[r] += dst[(RB * ND * 16 + r) * 64 + lane];
-        }
-      }
-      __syncthreads();
-    }
-    if (wk != 0) return;
   }
 
-  TVA_STAMP(7);
   // ---- write (normalised) result: final when there is one split, else the partial ----
   // The accumulators hold O^T (lane = row, registers = 16 scattered d per 32-wide block); each
   // wave transposes one 32-row block at a time through its own LDS patch so that global stores
@@ -1280,8 +982,6 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   };
   if (PAIR && wk == 1) write_out(std::integral_constant<int, PAIR ? ND / 2 : 0>{});
   else write_out(std::integral_constant<int, 0>{});
-  TVA_STAMP(5);
-  TVA_PHASE_DUMP;
 }
 #undef kdst_of
 #undef vdst_of
@@ -1375,7 +1075,9 @@ struct Plan {
   int n_row_blocks, n_chunks, chunk_keys;
 };
 
-enum { V_R256 = 0, V_R128 = 1, V_R64 = 2, V_R32 = 3, V_W8 = 4, V_W4 = 5, V_K2 = 6, V_K2R2 = 7, V_M2K2 = 8, V_W4D = 9, V_M2K2_3 = 10, V_M2K2_4 = 11, V_M4K2 = 12, V_LAST = V_M4K2 };
+// workgroup shapes (values of tva_shape in tva.h, minus one)
+enum { V_K2 = TVA_SHAPE_R32_W2 - 1, V_M2K2 = TVA_SHAPE_R64_W4 - 1, V_M2K2_3 = TVA_SHAPE_R64_W4_DEEP - 1,
+       V_M4K2 = TVA_SHAPE_R128_W8 - 1, V_W8 = TVA_SHAPE_R256_W8 - 1, V_LAST = V_W8 };
 
 // query rows of the whole batch: every tree node, or only the nodes cu_Q selects
 inline int64_t query_rows(const tva_args *a) { return a->cu_Q ? a->sum_Q : a->sum_T; }
@@ -1383,6 +1085,7 @@ inline int64_t query_rows(const tva_args *a) { return a->cu_Q ? a->sum_Q : a->su
 bool make_plan(const tva_args *a, Plan *pl) {
   if (!a || a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv) return false;
   if (a->sum_T < 0 || a->max_T < 0 || a->max_L < 0 || a->num_splits < 0) return false;
+  if (a->plan_shape < TVA_SHAPE_AUTO || a->plan_shape > V_LAST + 1) return false;
   const int G = a->Hq / a->Hkv;
   const int rows = (a->cu_Q ? a->max_Q : a->max_T) * G;
   // Workgroup shape, from sweeps over the benchmark shapes and batch / length variations of them.
@@ -1407,20 +1110,13 @@ bool make_plan(const tva_args *a, Plan *pl) {
     if (n128 >= 96 && n128 <= 256 && (s128 == 1 || a->max_L / s128 >= 16 * 64)) variant = V_M4K2;
     else if (n128 > 256 || keys >= (512 << 10) || (keys >= (256 << 10) && a->max_L >= 4096)) variant = V_W8;
   }
-  // benchmarking and test aid: TVA_FORCE_VARIANT=0..12 picks the workgroup shape
-  bool forced = false;
-  if (const char *fv = getenv("TVA_FORCE_VARIANT")) {
-    const int v = (*fv >= '0' && *fv <= '9') ? atoi(fv) : -1;  // unset or empty: the planner decides
-    if (v >= V_R256 && v <= V_LAST) variant = v, forced = true;
-  }
-  if (a->kv_fp8) {
-    // 8-bit K/V: four shapes exist
-    if (variant != V_K2 && variant != V_W8 && variant != V_M4K2) variant = V_M2K2;
-    forced = true;  // (no three-stage variant of the 2 x 2 shape either)
-  }
+  // tuning and test aid: the caller names the workgroup shape
+  const bool forced = a->plan_shape != TVA_SHAPE_AUTO;
+  if (forced) variant = a->plan_shape - 1;
+  if (a->kv_fp8 && variant == V_M2K2_3) variant = V_M2K2;  // (8-bit K/V: no deep variant of the 2 x 2 shape)
   pl->variant = variant;
-  pl->BM = (variant == V_R256 || variant == V_W8) ? 256 : (variant == V_R128 || variant == V_W4 || variant == V_W4D || variant == V_M4K2) ? 128 : (variant == V_R64 || variant == V_M2K2 || variant == V_M2K2_3 || variant == V_M2K2_4) ? 64 : 32;
-  pl->TK = (variant == V_R64 || variant == V_R32) ? 128 : (variant == V_W8 ? 32 * TVA_W8_KBW : 64);
+  pl->BM = variant == V_W8 ? 256 : variant == V_M4K2 ? 128 : variant == V_K2 ? 32 : 64;
+  pl->TK = 64;
   pl->n_row_blocks = rows > 0 ? (rows + pl->BM - 1) / pl->BM : 1;
   int S = a->num_splits;
   const int max_by_len = a->max_L > 0 ? (a->max_L + pl->TK - 1) / pl->TK : 1;
@@ -1429,7 +1125,7 @@ bool make_plan(const tva_args *a, Plan *pl) {
     // every split costs a partial O of the size of the output, written and read back
     const int natural = a->B * a->Hkv * pl->n_row_blocks;
     S = natural * 3 >= 512 ? 1 : (256 + natural - 1) / natural;  // two thirds of the CUs busy beats a merge pass
-    const bool two_per_cu = variant == V_K2 || variant == V_M2K2 || variant == V_W4D;
+    const bool two_per_cu = variant == V_K2 || variant == V_M2K2;
     if (!two_per_cu && S > 1 && natural * S > 256) --S;  // one workgroup per CU: no second round for a few
     const int cap = a->max_L > 0 ? (a->max_L + 2 * pl->TK - 1) / (2 * pl->TK) : 1;
     if (S > cap) S = cap;
@@ -1470,7 +1166,7 @@ bool make_plan(const tva_args *a, Plan *pl) {
   pl->n_chunks = a->max_L > 0 ? (a->max_L + ck - 1) / ck : 1;
   // one 2 x 2 workgroup per CU at most and long splits: a third ring stage (two tiles in flight)
   // pays; with more workgroups the second one on the CU hides more than the deeper ring would
-  if (pl->variant == V_M2K2 && !forced && (int64_t)pairs * pl->n_row_blocks * pl->n_chunks <= 256 && ck >= 12 * pl->TK)
+  if (pl->variant == V_M2K2 && !forced && !a->kv_fp8 && (int64_t)pairs * pl->n_row_blocks * pl->n_chunks <= 256 && ck >= 12 * pl->TK)
     pl->variant = V_M2K2_3;
   return true;
 }
@@ -1487,7 +1183,7 @@ inline hipError_t launch_status(const char *what) {
   return e;
 }
 
-template <int D, int WM, int WK, int RB, bool PAGED, int NST = 0, bool KV8 = false>
+template <int D, int WM, int WK, int RB, bool PAGED, int NST, bool KV8 = false>
 hipError_t launch_attn(const AttnParams &p, dim3 grid, hipStream_t st) {
   using C = AttnCfg<D, WM, WK, RB, PAGED, NST, KV8>;
   // raising the dynamic-LDS limit is idempotent and needed once per device (and per instantiation)
@@ -1510,23 +1206,15 @@ hipError_t launch_attn(const AttnParams &p, dim3 grid, hipStream_t st) {
 template <int D, bool PAGED>
 hipError_t dispatch_variant(int variant, const AttnParams &p, dim3 grid, hipStream_t st) {
   switch (variant) {
-    case V_R256: return launch_attn<D, 4, 1, 2, PAGED>(p, grid, st);
-    case V_R128: return launch_attn<D, 2, 2, 2, PAGED>(p, grid, st);
-    case V_R64: return launch_attn<D, 1, 4, 2, PAGED>(p, grid, st);
-    case V_W8: return launch_attn<D, 8, 1, 1, PAGED>(p, grid, st);
-    case V_W4: return launch_attn<D, 4, 1, 1, PAGED>(p, grid, st);
-    case V_K2: return launch_attn<D, 1, 2, 1, PAGED, 2>(p, grid, st);
-    case V_K2R2: return launch_attn<D, 1, 2, 1, PAGED, 4>(p, grid, st);   // (slot reused: deep 2-wave shape)
-    case V_M2K2: return launch_attn<D, 2, 2, 1, PAGED, 2>(p, grid, st);
-    case V_W4D: return launch_attn<D, 4, 1, 1, PAGED, 2>(p, grid, st);
-    case V_M2K2_3: return launch_attn<D, 2, 2, 1, PAGED, 3>(p, grid, st);
-    case V_M2K2_4: return launch_attn<D, 2, 2, 1, PAGED, 4>(p, grid, st);
+    case V_W8: return launch_attn<D, 8, 1, 1, PAGED, 4>(p, grid, st);
     case V_M4K2: return launch_attn<D, 4, 2, 1, PAGED, 4>(p, grid, st);
-    default: return launch_attn<D, 1, 4, 1, PAGED>(p, grid, st);
+    case V_M2K2_3: return launch_attn<D, 2, 2, 1, PAGED, 3>(p, grid, st);
+    case V_K2: return launch_attn<D, 1, 2, 1, PAGED, 2>(p, grid, st);
+    default: return launch_attn<D, 2, 2, 1, PAGED, 2>(p, grid, st);  // V_M2K2
   }
 }
 
-// 8-bit K/V: the planner's shapes only (three landing slots each)
+// 8-bit K/V (three landing slots each)
 template <bool PAGED>
 hipError_t dispatch_variant_fp8(int variant, const AttnParams &p, dim3 grid, hipStream_t st) {
   switch (variant) {
@@ -1541,15 +1229,9 @@ hipError_t dispatch_variant_fp8(int variant, const AttnParams &p, dim3 grid, hip
 
 extern "C" {
 
-int tva_version(void) { return 4; }
+int tva_version(void) { return 5; }
 
 size_t tva_sizeof_args(void) { return sizeof(tva_args); }
-
-#ifdef TVA_TIMING
-int tva_debug_stamps(long long *host64) {
-  return hipMemcpyFromSymbol(host64, HIP_SYMBOL(tva_dbg), sizeof(long long) * 64) == hipSuccess ? 0 : -4;
-}
-#endif
 
 const char *tva_strerror(int code) {
   switch (code) {
@@ -1585,9 +1267,11 @@ static int check_args(const tva_args *a, bool shapes_only) {
   if (a->mask_words < 1 || a->mask_words > 2 || a->mask_words * 64 < a->max_T) return TVA_UNSUPPORTED;
   if (a->kv_fp8 != 0 && a->kv_fp8 != 1) return TVA_INVALID_ARG;
   if (a->kv_fp8 && a->D != 128) return TVA_UNSUPPORTED;
+  if (a->cu_Q && (a->sum_Q < 0 || a->max_Q < 0 || a->max_Q > a->max_T || a->sum_Q > a->sum_T)) return TVA_INVALID_ARG;
+  if (a->plan_shape < TVA_SHAPE_AUTO || a->plan_shape > TVA_SHAPE_R256_W8) return TVA_INVALID_ARG;
+  if (a->sum_L < 0) return TVA_INVALID_ARG;
   if (shapes_only) return TVA_OK;
   if (!(a->scale > 0.f)) return TVA_INVALID_ARG;
-  if (a->cu_Q && (a->sum_Q < 0 || a->max_Q < 0 || a->max_Q > a->max_T || a->sum_Q > a->sum_T)) return TVA_INVALID_ARG;
   if (a->sum_T == 0) return TVA_OK;
   if (!a->cu_T || !a->L || !a->q || !a->out || !a->lse) return TVA_INVALID_ARG;
   if ((a->k_tree == nullptr) != (a->v_tree == nullptr)) return TVA_INVALID_ARG;
@@ -1605,7 +1289,6 @@ static int check_args(const tva_args *a, bool shapes_only) {
   if (a->stride_page < 0 || a->stride_tok < 0 || a->stride_head < 0) return TVA_INVALID_ARG;
   if (a->stride_tok >= (1 << 24)) return TVA_UNSUPPORTED;  // lane offsets inside a tile are 32-bit
   if (a->kv_fp8 && (!(a->k_scale >= 0.f) || !(a->v_scale >= 0.f))) return TVA_INVALID_ARG;
-  if (a->sum_L < 0) return TVA_INVALID_ARG;
   return TVA_OK;
 }
 
@@ -1638,20 +1321,24 @@ size_t tva_workspace_bytes(const tva_args *a) {
   return (size_t)pl.n_chunks * query_rows(a) * a->Hq * (a->D + 1) * sizeof(float);
 }
 
-static int run_attention(const tva_args *a, void *stream, bool merge);
+static int run_attention(const tva_args *a, void *workspace, size_t workspace_bytes, void *stream, bool merge);
 
-int tva_tree_verify_attn(const tva_args *a, void *stream) { return run_attention(a, stream, true); }
+int tva_tree_verify_attn(const tva_args *a, void *stream) {
+  return a ? run_attention(a, a->workspace, a->workspace_bytes, stream, true) : TVA_INVALID_ARG;
+}
 
-int tva_tree_verify_attn_splits(const tva_args *a, void *stream) { return run_attention(a, stream, false); }
+int tva_tree_verify_attn_splits(const tva_args *a, void *stream) {
+  return a ? run_attention(a, a->workspace, a->workspace_bytes, stream, false) : TVA_INVALID_ARG;
+}
 
-static int run_attention(const tva_args *a, void *stream, bool merge) {
+static int run_attention(const tva_args *a, void *workspace, size_t workspace_bytes, void *stream, bool merge) {
   int rc = check_args(a, false);
   if (rc != TVA_OK) return rc;
   if (a->sum_T == 0 || a->max_T == 0 || query_rows(a) == 0) return TVA_OK;
   Plan pl;
   if (!make_plan(a, &pl)) return TVA_INVALID_ARG;
   const size_t need = pl.n_chunks > 1 ? (size_t)pl.n_chunks * query_rows(a) * a->Hq * (a->D + 1) * sizeof(float) : 0;
-  if (need > 0 && (!a->workspace || a->workspace_bytes < need)) return TVA_WORKSPACE_TOO_SMALL;
+  if (need > 0 && (!workspace || workspace_bytes < need)) return TVA_WORKSPACE_TOO_SMALL;
 
   AttnParams p;
   p.q = (const __bf16 *)a->q;
@@ -1667,7 +1354,7 @@ static int run_attention(const tva_args *a, void *stream, bool merge) {
   p.parent = a->parent;
   p.out = a->out;
   p.lse = a->lse;
-  p.part_out = (float *)a->workspace;
+  p.part_out = need > 0 ? (float *)workspace : nullptr;
   p.part_lse = p.part_out ? p.part_out + (size_t)pl.n_chunks * query_rows(a) * a->Hq * a->D : nullptr;
   p.B = a->B;
   p.Hq = a->Hq;

@@ -109,11 +109,22 @@ def test_launch_plan_bands(lib, B, L, T, rows, splits):
 @pytest.mark.parametrize("kw,code", [
     (dict(D=96), -2), (dict(max_T=129, mask_words=3), -2), (dict(mask_words=0), -2),
     (dict(Hq=30), -1), (dict(B=0), -1), (dict(max_L=-1), -1), (dict(max_T=100, mask_words=1), -2),
+    (dict(plan_shape=6), -1), (dict(plan_shape=-1), -1), (dict(sum_L=-5), -1),
+    # query subsets: the plan and the workspace size are computed from sum_Q / max_Q, so they are checked
+    # wherever those are (cu_Q is only tested for being set here, never read)
+    (dict(cu_Q=8, sum_Q=-1, max_Q=4), -1), (dict(cu_Q=8, sum_Q=61, max_Q=4), -1), (dict(cu_Q=8, sum_Q=10, max_Q=61), -1),
 ])
 def test_invalid_shapes_rejected_before_launch(lib, kw, code):
     a = shape_args(**kw)
     assert lib.tva_plan_splits(ctypes.byref(a)) == -1
+    assert lib.tva_workspace_bytes(ctypes.byref(a)) == ctypes.c_size_t(-1).value
     assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == code
+
+
+def test_named_shapes(lib):
+    """plan_shape names the workgroup shape (rows per workgroup follow)."""
+    for shape, rows in ((1, 32), (2, 64), (3, 64), (4, 128), (5, 256)):
+        assert binding.plan_workgroup_rows(shape_args(plan_shape=shape)) == rows
 
 
 def test_launch_plan_invariants_over_random_shapes(lib):
@@ -161,7 +172,7 @@ def test_length_hint_shortens_long_splits_of_ragged_batches(lib):
         b = shape_args(max_T=48, sum_T=kw["B"] * 48, **kw)
         kw.pop("sum_L")
         assert binding.plan_chunk_keys(b) == binding.plan_chunk_keys(shape_args(max_T=48, sum_T=kw["B"] * 48, **kw))
-    assert lib.tva_plan_splits(ctypes.byref(shape_args(sum_L=-1))) == 8      # shapes only: not looked at
+    assert lib.tva_plan_splits(ctypes.byref(shape_args(sum_L=-1))) == -1     # the plan reads it: refused
     
 
 def test_fp8_arguments_checked_on_the_host(lib):

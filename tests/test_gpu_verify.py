@@ -246,15 +246,13 @@ def _in_cache_layout(w, rng, page_size=0):
 
 
 @pytest.mark.parametrize("page_size", [0, 16, 3])
-@pytest.mark.parametrize("variant", [None, 4, 5, 6])
-def test_attention_with_tree_rows_in_the_cache(torch_dev, page_size, variant, monkeypatch):
+@pytest.mark.parametrize("variant", [0, 1, 3, 5])
+def test_attention_with_tree_rows_in_the_cache(torch_dev, page_size, variant):
     """k_tree = v_tree = NULL: the kernel reads the tree tokens' K/V from cache positions L_b + i; the
     result must equal the oracle's on the same values held in separate tree tensors."""
     torch = torch_dev
     from oracle import tva_oracle as orc
     from paper_2510_26577_amd import binding
-    if variant is not None:
-        monkeypatch.setenv("TVA_FORCE_VARIANT", str(variant))
     rng = np.random.Generator(np.random.PCG64(71 + page_size))
     w = wl.random_workload(1000 + page_size, 4, 8, 2, 128, [300, 64, 0, 129], [70, 33, 8, 128], max_depth=12)
     k, v, cu, table = _in_cache_layout(w, rng, page_size)
@@ -265,12 +263,13 @@ def test_attention_with_tree_rows_in_the_cache(torch_dev, page_size, variant, mo
     for splits in (0, 3):
         out, lse = binding.tree_verify_attn(q, None, None, dev(i16(k)), dev(i16(v)), None, cu_T, L, max_T=w.max_T,
                                             max_L=w.max_L, scale=w.scale, cu_L=dev(cu), page_table=dev(table),
-                                            page_size=page_size, num_splits=splits, parent=parent)
+                                            page_size=page_size, num_splits=splits, parent=parent,
+                                            plan_shape=variant)
         torch.cuda.synchronize()
         ro, rl = orc.tree_verify_attn(w)
         assert np.isfinite(out.cpu().numpy()).all()
         assert np.abs(out.cpu().numpy().astype(np.float64) - ro).max() <= 2e-3
-        assert np.abs(lse.cpu().numpy().astype(np.float64) - rl).max() <= 1e-4
+        assert np.abs(lse.cpu().numpy().astype(np.float64) - rl).max() <= 1e-4 <= 1e-4
 
 
 @pytest.mark.parametrize("page_size", [0, 16, 5])
