@@ -46,6 +46,9 @@ typedef enum {
 
 #define TVA_MAX_TREE 128 /* nodes per tree supported by the attention kernels (2 mask words) */
 
+/* Bytes of scratch memory tva_tree_verify_attn_static owns on every GPU (see there). */
+#define TVA_STATIC_SCRATCH_BYTES (32u << 20)
+
 /*
  * Workgroup shapes of the attention kernel, for tva_args.plan_shape: query rows per workgroup
  * (tree nodes x query heads of one KV head) and waves.  TVA_SHAPE_AUTO lets the library choose
@@ -225,6 +228,25 @@ int32_t tva_plan_workgroup_rows(const tva_args *a);
  * get out = 0, lse = -inf.
  */
 int tva_tree_verify_attn(const tva_args *a, void *stream);
+
+/*
+ * tva_tree_verify_attn for callers that cannot allocate device memory or have none to hand over
+ * for the KV splits: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels, same result as tva_tree_verify_attn, except that
+ * a->workspace / a->workspace_bytes are ignored: the partial results of the KV splits go to a
+ * device array of TVA_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU
+ * the library runs on holds its own copy until the process ends).  The call allocates and frees
+ * nothing; the first call on a device looks up the array's address there (hipGetSymbolAddress).
+ *   - Shapes whose plan needs more (tva_workspace_bytes(a) > TVA_STATIC_SCRATCH_BYTES) are
+ *     refused with TVA_WORKSPACE_TOO_SMALL and nothing is queued; a smaller num_splits, or
+ *     tva_tree_verify_attn with a caller-owned workspace, serves them.
+ *   - All calls on one GPU share that GPU's array.  The array keeps whatever the last call
+ *     left; nothing in it needs to start at zero (each call writes every slot it later reads).
+ *     Calls that overlap on one GPU (different streams, or threads) race on it: serialise them,
+ *     or use tva_tree_verify_attn with one workspace per stream.
+ */
+int tva_tree_verify_attn_static(const tva_args *a, void *stream);
+size_t tva_static_scratch_bytes(void); /* = TVA_STATIC_SCRATCH_BYTES */
 
 /*
  * The split-KV part of tva_tree_verify_attn alone: same arguments, but the merge of the KV

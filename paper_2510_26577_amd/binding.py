@@ -26,6 +26,7 @@ EXPECTED_VERSION = 5
 # tva_shape (include/tva.h): workgroup shapes a caller may name in tva_args.plan_shape
 SHAPE_AUTO, SHAPE_R32_W2, SHAPE_R64_W4, SHAPE_R64_W4_DEEP, SHAPE_R128_W8, SHAPE_R256_W8 = range(6)
 SHAPES = (SHAPE_R32_W2, SHAPE_R64_W4, SHAPE_R64_W4_DEEP, SHAPE_R128_W8, SHAPE_R256_W8)
+STATIC_SCRATCH_BYTES = 32 << 20
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -70,7 +71,7 @@ class TvaArgs(ctypes.Structure):
 
 
 EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys", "tva_plan_workgroup_rows",
-           "tva_tree_verify_attn", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
+           "tva_tree_verify_attn", "tva_tree_verify_attn_static", "tva_static_scratch_bytes", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
 # entry points of include/tva_verify.h (bound in verify.py)
 VERIFY_EXPORTS = ("tva_accept_greedy", "tva_commit_path", "tva_sizeof_commit_args")
 # host entry points of include/tva_cast.h (bound in cast.py)
@@ -112,6 +113,9 @@ def load_library():
     lib.tva_plan_workgroup_rows.argtypes = [ctypes.POINTER(TvaArgs)]
     lib.tva_tree_verify_attn.restype = ctypes.c_int
     lib.tva_tree_verify_attn.argtypes = [ctypes.POINTER(TvaArgs), ctypes.c_void_p]
+    lib.tva_tree_verify_attn_static.restype = ctypes.c_int
+    lib.tva_tree_verify_attn_static.argtypes = [ctypes.POINTER(TvaArgs), ctypes.c_void_p]
+    lib.tva_static_scratch_bytes.restype = ctypes.c_size_t
     lib.tva_tree_verify_attn_splits.restype = ctypes.c_int
     lib.tva_tree_verify_attn_splits.argtypes = [ctypes.POINTER(TvaArgs), ctypes.c_void_p]
     lib.tva_merge_splits.restype = ctypes.c_int
@@ -248,6 +252,12 @@ def plan_workgroup_rows(args: TvaArgs) -> int:
 def tree_verify_attn_raw(args: TvaArgs, stream=None) -> None:
     """Queue the attention on `stream` with a prepared argument struct."""
     _check(load_library().tva_tree_verify_attn(ctypes.byref(args), _stream_ptr(stream)))
+
+
+def tree_verify_attn_static_raw(args: TvaArgs, stream=None) -> None:
+    """Queue the attention with the KV splits' partial results in the library's own device array
+    (tva_tree_verify_attn_static: nothing is allocated, args.workspace is ignored)."""
+    _check(load_library().tva_tree_verify_attn_static(ctypes.byref(args), _stream_ptr(stream)))
 
 
 def tree_verify_attn_splits_raw(args: TvaArgs, stream=None) -> None:

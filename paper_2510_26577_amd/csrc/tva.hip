@@ -1227,6 +1227,39 @@ hipError_t dispatch_variant_fp8(int variant, const AttnParams &p, dim3 grid, hip
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------
+// scratch memory of tva_tree_verify_attn_static (the entry point that allocates nothing)
+// ---------------------------------------------------------------------------------------
+// A device array that is part of the code object: every GPU the library runs on holds its own copy,
+// at its own address, from the moment the module is loaded there until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the address it returns for the
+// current device is what kernels, copies and fills are given.  Nothing in it has to start at zero:
+// the attention kernel writes every partial row and every partial log-sum-exp (also the "empty"
+// marks of splits a short sequence does not reach) that the merge of the same call reads.
+static __device__ __align__(256) unsigned char scratch[TVA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_addr[kMaxDevices];  // zero-initialised: not looked up yet
+
+// Address of `scratch` on the current device; looked up once per device, with that device current.
+int static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TVA_HIP_ERROR;
+  void *ptr = scratch_addr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    const hipError_t e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      if (getenv("TVA_VERBOSE")) fprintf(stderr, "libtva: hipGetSymbolAddress(scratch): %s\n", hipGetErrorString(e));
+      return TVA_HIP_ERROR;
+    }
+    scratch_addr[dev].store(ptr, std::memory_order_release);  // (two threads racing store the same value)
+  }
+  *out = ptr;
+  return TVA_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int tva_version(void) { return 5; }
@@ -1329,6 +1362,26 @@ int tva_tree_verify_attn(const tva_args *a, void *stream) {
 
 int tva_tree_verify_attn_splits(const tva_args *a, void *stream) {
   return a ? run_attention(a, a->workspace, a->workspace_bytes, stream, false) : TVA_INVALID_ARG;
+}
+
+size_t tva_static_scratch_bytes(void) { return TVA_STATIC_SCRATCH_BYTES; }
+
+int tva_tree_verify_attn_static(const tva_args *a, void *stream) {
+  if (!a) return TVA_INVALID_ARG;
+  // the size is settled from the shapes alone, before any pointer or the device is looked at
+  int rc = check_args(a, true);
+  if (rc != TVA_OK) return rc;
+  const size_t need = tva_workspace_bytes(a);
+  if (need == (size_t)-1) return TVA_INVALID_ARG;
+  if (need > TVA_STATIC_SCRATCH_BYTES) return TVA_WORKSPACE_TOO_SMALL;
+  rc = check_args(a, false);
+  if (rc != TVA_OK) return rc;
+  void *ptr = nullptr;
+  if (need > 0) {  // (a single split touches no scratch memory: no lookup either)
+    rc = static_scratch(&ptr);
+    if (rc != TVA_OK) return rc;
+  }
+  return run_attention(a, ptr, need > 0 ? TVA_STATIC_SCRATCH_BYTES : 0, stream, true);
 }
 
 static int run_attention(const tva_args *a, void *workspace, size_t workspace_bytes, void *stream, bool merge) {

@@ -119,12 +119,18 @@ def test_invalid_shapes_rejected_before_launch(lib, kw, code):
     assert lib.tva_plan_splits(ctypes.byref(a)) == -1
     assert lib.tva_workspace_bytes(ctypes.byref(a)) == ctypes.c_size_t(-1).value
     assert lib.tva_tree_verify_attn(ctypes.byref(a), None) == code
+    assert lib.tva_tree_verify_attn_static(ctypes.byref(a), None) == code
 
 
-def test_named_shapes(lib):
-    """plan_shape names the workgroup shape (rows per workgroup follow)."""
+def test_named_shapes_and_static_scratch_limit(lib):
+    """plan_shape names the workgroup shape (rows per workgroup follow); the entry point that uses the
+    library's own scratch array refuses, from the shapes alone, plans that need more than it holds."""
     for shape, rows in ((1, 32), (2, 64), (3, 64), (4, 128), (5, 256)):
         assert binding.plan_workgroup_rows(shape_args(plan_shape=shape)) == rows
+    assert lib.tva_static_scratch_bytes() == binding.STATIC_SCRATCH_BYTES == 32 << 20
+    big = shape_args(B=8, Hq=64, Hkv=8, max_T=128, mask_words=2, sum_T=8 * 128, max_L=4096, num_splits=4)
+    assert binding.workspace_bytes(big) > binding.STATIC_SCRATCH_BYTES
+    assert lib.tva_tree_verify_attn_static(ctypes.byref(big), None) == -3   # nothing queued, no pointer read
 
 
 def test_launch_plan_invariants_over_random_shapes(lib):
