@@ -73,6 +73,8 @@ def main():
                     help="default workload only: skip the extra kernel-level measurement of the same shape at B=32")
     ap.add_argument("--no-length-hint", action="store_true",
                     help="do not pass the host-known sum of the cache lengths to the launch planner")
+    ap.add_argument("--microbench", action="store_true",
+                    help="run the microbenchmarks of the machine rates (libtva_ubench) instead of a workload")
     ap.add_argument("--kv-fp8", action="store_true",
                     help="K/V stored as 8-bit floating point (E4M3) bytes: half the K/V bytes per step")
     a = ap.parse_args()
@@ -80,6 +82,10 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         raise SystemExit(2)
+    if a.microbench:
+        from paper_2510_26577_amd import ubench
+        print(json.dumps({"microbench": ubench.run_all(), "device": "MI355X (gfx950)", "n_gpus": 1}))
+        return
     line = measure(a)
     if a.workload == "cfg2" and not (a.kv_fp8 or a.head_major or a.no_graph or a.splits or a.shape or a.no_saturated):
         # The headline shape at B = 1 is ~1 us of HBM time: its roofline fraction mostly measures launch

@@ -1,0 +1,44 @@
+/*
+ * libtva_ubench -- microbenchmarks of the MI355X (gfx950) rates the attention kernels are priced
+ * against: matrix-instruction issue rate, how much vector work fits under a matrix instruction,
+ * v_exp_f32 / v_fma_f32 rates, LDS read bandwidth, streaming reads, empty launches.  A separate
+ * library from libtva (measurement aid, not on the hot path); `bench.py --microbench` runs it.
+ *
+ * Conventions: every pointer is DEVICE memory the caller owns; `stream` is a hipStream_t as void*;
+ * calls queue one kernel and return 0, -1 for bad arguments, -2 for a combination that has no
+ * instantiation.  Timed probes write, per wave, {shader-clock cycles, 100 MHz ticks} of their loop to
+ * `out` (uint64 [2 * waves], waves = workgroups * threads / 64); `sink` is a float [512] that is never
+ * written in practice (it keeps the probe's arithmetic alive).
+ */
+#ifndef TVA_UBENCH_H
+#define TVA_UBENCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Per iteration and accumulator: one v_mfma_f32_32x32x16_bf16 (nacc independent accumulators in turn; 0 = no
+ * matrix instruction), then k independent v_fma_f32 and e independent v_exp_f32.  Workgroups of
+ * 256 * waves_per_simd threads (1 or 2 waves per SIMD). */
+int tva_ubench_mfma_valu(int32_t nacc, int32_t k, int32_t e, int32_t waves_per_simd, int32_t workgroups,
+                         int32_t iters, uint64_t *out, float *sink, void *stream);
+
+/* Per iteration: 8 x ds_read_b128 (128 bytes per lane) or, with transpose_reads, 16 x ds_read_b64_tr_b16
+ * (128 bytes per lane), conflict-free addresses, then a wait for all of them. */
+int tva_ubench_lds(int32_t transpose_reads, int32_t waves_per_simd, int32_t workgroups, int32_t iters, uint64_t *out,
+                   float *sink, void *stream);
+
+/* Reads `bytes` of `src` once (16 bytes per lane, 8 loads in flight per lane) with `workgroups` workgroups
+ * of 256 threads: into registers, or with to_lds straight into LDS.  Timed by the caller. */
+int tva_ubench_stream(int32_t to_lds, const void *src, size_t bytes, int32_t workgroups, float *sink, void *stream);
+
+/* One empty kernel (one wave).  Timed by the caller, back to back. */
+int tva_ubench_empty(void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -49,6 +49,18 @@ def test_host_exports_match_header(lib):
         assert getattr(lib, s) is not None
 
 
+def test_microbenchmark_library_exports_match_header():
+    """libtva_ubench (measurement aid, include/tva_ubench.h) loads and exports what its header declares."""
+    from paper_2510_26577_amd import ubench
+    if not os.path.exists(ubench.LIB_PATH):
+        ubench.build_library()
+    ul = ubench.load_library()
+    syms = declared_symbols("tva_ubench.h")
+    assert set(syms) == set(ubench.EXPORTS)
+    for s in syms:
+        assert getattr(ul, s) is not None
+
+
 def test_struct_mirror_and_version(lib):
     assert lib.tva_sizeof_args() == ctypes.sizeof(binding.TvaArgs)
     assert lib.tva_version() == binding.EXPECTED_VERSION
