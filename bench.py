@@ -73,6 +73,11 @@ def main():
                     help="default workload only: skip the extra kernel-level measurement of the same shape at B=32")
     ap.add_argument("--no-length-hint", action="store_true",
                     help="do not pass the host-known sum of the cache lengths to the launch planner")
+    ap.add_argument("--reps", type=int, default=5, help="timed replays per figure (median and minimum are reported)")
+    ap.add_argument("--with-traffic", action="store_true",
+                    help="also measure roofline.traffic: two child runs of this command under rocprofv3 --pmc")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="(used by profile_traffic) make one plain 64 MiB device-to-device copy first: the counters' calibration")
     ap.add_argument("--microbench", action="store_true",
                     help="run the microbenchmarks of the machine rates (libtva_ubench) instead of a workload")
     ap.add_argument("--kv-fp8", action="store_true",
@@ -111,6 +116,12 @@ def measure(a):
     binding.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if a.traffic_probe:
+        cal_src = torch.ones(1 << 24, dtype=torch.int32, device="cuda:0")      # 64 MiB
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
     w = get_workload(a.workload)
     k_scale = v_scale = 1.0
     if a.kv_fp8:
@@ -176,10 +187,17 @@ def measure(a):
             binding.build_ancestor_mask(sets[j].parent, sets[j].cu_T, w.max_T, mask=masks[j], stream=stream)
         binding.tree_verify_attn_raw(argv[j], stream=stream)
 
-    def timed(n, fn):
-        """Run fn(i) for i < n on `stream`, as one graph replay unless --no-graph; ms total."""
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # a buffer four times the 256 MB last-level cache: writing it between timed regions evicts whatever the
+    # region before (or the warm-up) left in the caches, so a timed region reads its inputs from HBM
+    # however few of the rotating copies it touches
+    flush_buf = torch.empty(1 << 28, dtype=torch.int32, device="cuda:0")
+    REPS = 1 if a.no_graph else max(1, a.reps)
+
+    def timed(n, fn, cold=True):
+        """Runs fn(i) for i < n on `stream` as one HIP-graph replay (eager with --no-graph), REPS times,
+        each preceded (cold) by the cache flush; returns the REPS durations in ms per call of fn."""
         if a.no_graph:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             with torch.cuda.stream(stream):
                 e0.record(stream)
@@ -187,26 +205,36 @@ def measure(a):
                     fn(i)
                 e1.record(stream)
             torch.cuda.synchronize()
-            return e0.elapsed_time(e1)
+            return [e0.elapsed_time(e1) / n]
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=stream):
             for i in range(n):
                 fn(i)
+        out = []
         with torch.cuda.stream(stream):
             # untimed replays first (graph upload, then enough work for the clocks to settle under
             # this load: the first region timed after the host-side set-up otherwise reads ~7 % slow
-            # on the large workloads), then the timed one
+            # on the large workloads), then the timed ones
             t_warm = time.perf_counter()
             while True:
                 g.replay()
                 torch.cuda.synchronize()
                 if time.perf_counter() - t_warm > 0.1:
                     break
-            e0.record(stream)
-            g.replay()
-            e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1)
+            for _ in range(REPS):
+                if cold:
+                    flush_buf.fill_(1)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                g.replay()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                out.append(e0.elapsed_time(e1) / n)
+        return out
+
+    def med(xs):
+        xs = sorted(xs)
+        return xs[len(xs) // 2] if len(xs) % 2 else 0.5 * (xs[len(xs) // 2 - 1] + xs[len(xs) // 2])
 
     # ---- warm-up (eager: also raises the LDS limit of the kernels before any capture) ----
     with torch.cuda.stream(stream):
@@ -215,23 +243,29 @@ def measure(a):
             step_two_calls(i)
     torch.cuda.synchronize()
 
-    # ---- the timed region: exactly K steps of the whole path ----
-    ms_total = timed(a.steps, step)
-    ms_step = ms_total / a.steps
+    # ---- the timed region: exactly K steps of the whole path (one graph replay), REPS times, each
+    #      starting from flushed caches; `ms_per_step` is the median, the minimum is reported beside it ----
+    step_runs = timed(a.steps, step)
+    ms_step, ms_step_min = med(step_runs), min(step_runs)
+    # the same with every step on ONE input set and no flush (inputs cache-resident), and one isolated step
+    ms_step_warm = med(timed(a.steps, lambda i: step(0), cold=False))
+    single = timed(1, lambda i: step(0), cold=True) if not a.no_graph else [ms_step]
+    ms_single_launch = med(single)
 
     # ---- dominant kernel: K launches of the split-KV attention kernel alone (same graph replay,
     #      same rotation; the average includes the dispatch gap between back-to-back launches),
     #      and the merge kernel alone the same way ----
-    ms_kernel = timed(a.steps, lambda i: binding.tree_verify_attn_splits_raw(argv[i % R], stream=stream)) / a.steps
-    ms_attn_call = timed(a.steps, lambda i: step_two_calls(i, with_mask=False)) / a.steps
-    ms_step_two_calls = timed(a.steps, step_two_calls) / a.steps
+    kernel_runs = timed(a.steps, lambda i: binding.tree_verify_attn_splits_raw(argv[i % R], stream=stream))
+    ms_kernel, ms_kernel_min = med(kernel_runs), min(kernel_runs)
+    ms_attn_call = med(timed(a.steps, lambda i: step_two_calls(i, with_mask=False)))
+    ms_step_two_calls = med(timed(a.steps, step_two_calls))
     ms_merge = 0.0
     if n_splits > 1:
         n_rows = w.sum_T * w.Hq
         po = [ws[: n_splits * n_rows * w.D].view(n_splits, n_rows, w.D) for ws in wss]
         pl = [ws[n_splits * n_rows * w.D: n_splits * n_rows * (w.D + 1)].view(n_splits, n_rows) for ws in wss]
-        ms_merge = timed(a.steps, lambda i: binding.merge_splits(po[i % R], pl[i % R], out=outs[i % R].view(n_rows, w.D),
-                                                                 lse=lses[i % R].view(n_rows), stream=stream)) / a.steps
+        ms_merge = med(timed(a.steps, lambda i: binding.merge_splits(po[i % R], pl[i % R], out=outs[i % R].view(n_rows, w.D),
+                                                                     lse=lses[i % R].view(n_rows), stream=stream)))
 
     # ---- the CPU oracle leg (--no-cpu-baseline skips all of it; nothing else here touches the oracle):
     # first a spot check of what was just timed (first input set, sampled rows), then the oracle timed on
@@ -277,18 +311,21 @@ def measure(a):
             full_s, sample = dt * flops / f_s, f"{n_s} random output rows of {n_rows_total}, time scaled by flops"
         cpu = {"value": kv_bytes / full_s / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
                "sample": sample, "ms_per_step": full_s * 1e3}
+        if flops <= 8e9:                       # small workloads (configs 1-2): the same on one host thread
+            tva_oracle.set_num_threads(1)
+            t1 = time.perf_counter()
+            oracle_attn()
+            one_s = time.perf_counter() - t1
+            tva_oracle.set_num_threads(cores)
+            cpu["one_thread"] = {"value": kv_bytes / one_s / 1e9, "unit": "GB/s", "cores": 1, "ms_per_step": one_s * 1e3}
 
-    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary (the
-    # counters cannot be read from inside this process); only quoted for the launch shape it was taken on
+    # HBM bytes per launch of the dominant kernel: only from a counter run made for this very command
+    # (--with-traffic: two child runs of this script under rocprofv3 --pmc); otherwise null
     traffic = None
-    try:
-        for line in open(os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.txt")):
-            if line.startswith("traffic "):
-                kv = dict(item.split("=") for item in line.split()[1:])
-                if kv["workload"] == w.name and int(kv["kv_splits"]) == n_splits and not a.head_major:
-                    traffic = float(kv["attn_kernel_bytes"])
-    except (OSError, ValueError, KeyError):
-        pass
+    if a.with_traffic:
+        from paper_2510_26577_amd import profile_traffic
+        t = profile_traffic.measure(profile_traffic.bench_args_of(a))
+        traffic = t["attn_kernel_bytes"]
     value = kv_bytes / (ms_step * 1e-3) / 1e9
     achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
     tflops_kernel = flops / (ms_kernel * 1e-3) / 1e12
@@ -308,6 +345,12 @@ def measure(a):
         "kv_bytes_per_step": kv_bytes, "algorithmic_bytes_per_step": alg_bytes, "algorithmic_flops_per_step": flops,
         "max_abs_err_O": err_o, "max_abs_err_LSE": err_l,
         "ms_per_step_two_calls": ms_step_two_calls,
+        "timing": {"protocol": f"{REPS} timed replays of one HIP graph of {a.steps} steps cycling through "
+                               f"{R} input copies ({R * alg_bytes / 2**20:.0f} MiB), caches flushed by a 1 GiB fill before each; "
+                               "ms_per_step = median",
+                   "ms_per_step_median": ms_step, "ms_per_step_min": ms_step_min,
+                   "ms_per_step_warm_one_input_set": ms_step_warm, "ms_single_isolated_step": ms_single_launch,
+                   "kernel_ms_median": ms_kernel, "kernel_ms_min": ms_kernel_min, "reps": REPS},
         "roofline": {"bound": "hbm", "kernel": "attn_kernel (split-KV attention)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel_ms": ms_kernel, "attn_call_ms": ms_attn_call, "merge_ms": ms_merge,
