@@ -7,9 +7,10 @@ tva_tree_verify_attn (split-KV attention + merge of the splits) at every grid po
 synthetic inputs of the benchmark's head shapes.  The rest of a target forward (projections, MLP)
 is outside this repository; a deployment adds its own measurements of those to the table.
 
-Timing: per grid point, R rotating copies of the inputs (so that the cache of one call is not the
-next call's), their attention calls captured into one HIP graph, the graph replayed a few times;
-the cost is the best replay divided by R, in microseconds.
+Timing: per grid point, R copies of the inputs, their attention calls captured into one HIP graph,
+the graph replayed a few times with the caches flushed before each replay (every call reads its K/V
+from HBM, as a layer of a real verification pass does); the cost is the best replay divided by R,
+in microseconds.
 
     python -m paper_2510_26577_amd.cost_table --B 4 --L 256 --M 8 --N 72 --out table.txt
 
@@ -37,6 +38,9 @@ def measure(B: int, L: int, M: int, N: int, Hq: int = 32, Hkv: int = 8, D: int =
     n_values = sorted(set(n_values or range(1, N + 1)) | {1, N})
     table = np.full((M, N), np.nan)
     stream = torch.cuda.Stream()
+    # written before every timed replay: four times the 256 MB last-level cache, so every call of the replay
+    # reads its inputs from HBM, as a layer of a real verification pass does
+    flush = torch.empty(1 << 28, dtype=torch.int32, device="cuda:0")
     for r in range(1, M + 1):
         c = r * L
         # one cache and one N-node tree per copy; the n-token cases use the tree's first n nodes
@@ -75,11 +79,13 @@ def measure(B: int, L: int, M: int, N: int, Hq: int = 32, Hkv: int = 8, D: int =
                 with torch.cuda.graph(g, stream=stream):
                     for args, _ in cases:
                         binding.tree_verify_attn_raw(args, stream=stream)
-                g.replay()
+                for _ in range(3):                         # untimed: clocks and code caches settle
+                    g.replay()
                 stream.synchronize()
                 best = float("inf")
                 for _ in range(replays):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    flush.fill_(1)
                     e0.record(stream)
                     g.replay()
                     e1.record(stream)
@@ -107,13 +113,23 @@ def read_table(path: str) -> np.ndarray:
     return np.loadtxt(path, comments="#", ndmin=2)
 
 
-def make_strictly_increasing(table: np.ndarray, eps: float = 1e-3) -> np.ndarray:
-    """Conditions a measured table for Algorithm 1, which needs costs strictly increasing in n:
-    timing noise and changes of the launch plan leave small dips, so every entry is raised to at
-    least its left neighbour plus eps microseconds.  Measurement plumbing, not part of the method."""
+def make_strictly_increasing(table: np.ndarray, eps: float = 1e-3, max_raise: float = 0.05) -> np.ndarray:
+    """Conditions a measured table for Algorithm 1, which needs costs strictly increasing in n: every
+    entry is raised to at least its left neighbour plus eps microseconds.  Small dips are real: a tree
+    that opens one more row block of workgroups, or crosses to a plan with fewer KV splits, can run up to
+    about 3 % faster than the slightly smaller tree before it (the planner's model of a launch is only that
+    accurate).  A dip deeper than max_raise (relative) is refused: that would be a launch plan gone wrong,
+    which the selection would read as a property of the machine.  Measurement plumbing, not part of the
+    method."""
     t = np.array(table, dtype=np.float64, copy=True)
     for k in range(1, t.shape[1]):
-        t[:, k] = np.maximum(t[:, k], t[:, k - 1] + eps)
+        floor = t[:, k - 1] + eps
+        worst = float(np.max((floor - t[:, k]) / t[:, k]))
+        if worst > max_raise:
+            r = int(np.argmax((floor - t[:, k]) / t[:, k]))
+            raise ValueError(f"cost table row {r} dips by {100 * worst:.1f} % from n = {k} to n = {k + 1}: "
+                             f"{t[r, k - 1]:.3f} -> {t[r, k]:.3f}")
+        t[:, k] = np.maximum(t[:, k], floor)
     return t
 
 
@@ -132,7 +148,7 @@ def main(argv=None) -> int:
     cmd = "python -m paper_2510_26577_amd.cost_table " + " ".join(sys.argv[1:] if argv is None else argv)
     write_table(a.out, table, a.B, a.L, header_lines=[
         "attention slice of the target cost table S_T(B): tva_tree_verify_attn (split-KV attention + merge), MI355X",
-        "head shape Hq=32 Hkv=8 D=128, bf16, dense cache; best HIP-graph replay over 8 rotating input copies",
+        "head shape Hq=32 Hkv=8 D=128, bf16, dense cache; best of 5 HIP-graph replays over 8 input copies, caches flushed before each",
         "command: " + cmd])
     print(f"wrote {a.out} in {time.time() - t0:.0f} s", flush=True)
     return 0

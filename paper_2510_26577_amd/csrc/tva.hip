@@ -1120,31 +1120,45 @@ bool make_plan(const tva_args *a, Plan *pl) {
   pl->n_row_blocks = rows > 0 ? (rows + pl->BM - 1) / pl->BM : 1;
   int S = a->num_splits;
   const int max_by_len = a->max_L > 0 ? (a->max_L + pl->TK - 1) / pl->TK : 1;
-  if (S == 0) {
+  const int natural = a->B * a->Hkv * pl->n_row_blocks;
+  const bool two_per_cu = variant == V_K2 || variant == V_M2K2;
+  if (S == 0 && two_per_cu) {
+    // The small shapes (two workgroups fit a CU): the number of splits that minimises a model of the
+    // launch's duration, fitted to sweeps of the split count over B = 1 .. 8, caches of 256 .. 2048 keys and
+    // trees of 1 .. 72 nodes on the benchmark head shape:
+    //   (tiles of the longest split, the tree's own tiles counted with the last one) x time per tile
+    //      x 1 while every workgroup has a CU to itself (256), x 1.5 while two share one (512),
+    //   + with splits: a merge pass (second launch, 3.5 us) and the partial rows written and read back
+    //     (0.19 us per MB).
+    // Splits keep two tiles or more and together stay within 512 workgroups.
+    const int tiles = max_by_len, tree_tiles = (a->max_T + pl->TK - 1) / pl->TK;
+    const double tile_us = 1.18 * a->D / 128.0;
+    const double part_mb = 2.0 * query_rows(a) * a->Hq * (a->D + 1) * sizeof(float) * 1e-6;
+    double best = 0.0;
+    S = 1;
+    for (int s = 1; s <= (tiles / 2 > 1 ? tiles / 2 : 1); ++s) {
+      const int ckt = (tiles + s - 1) / s, nch = (tiles + ckt - 1) / ckt;
+      if (nch != s) continue;  // the same split length as a smaller count
+      const int64_t wgs = (int64_t)natural * nch;
+      if (nch > 1 && wgs > 512) break;
+      const int last = tiles - (nch - 1) * ckt + tree_tiles;
+      const int longest = nch > 1 && ckt > last ? ckt : last;
+      const double share = wgs <= 256 ? 1.0 : 1.5 * (double)((wgs + 511) / 512);
+      double cost = tile_us * longest * share;
+      if (nch > 1) cost += 3.5 + 0.19 * part_mb * nch;
+      if (s == 1 || cost < best - 1e-9) best = cost, S = nch;
+    }
+  } else if (S == 0) {
     // one workgroup per CU (256) if the batch allows, but no split shorter than two tiles:
     // every split costs a partial O of the size of the output, written and read back
-    const int natural = a->B * a->Hkv * pl->n_row_blocks;
     S = natural * 3 >= 512 ? 1 : (256 + natural - 1) / natural;  // two thirds of the CUs busy beats a merge pass
-    const bool two_per_cu = variant == V_K2 || variant == V_M2K2;
-    if (!two_per_cu && S > 1 && natural * S > 256) --S;  // one workgroup per CU: no second round for a few
+    if (S > 1 && natural * S > 256) --S;  // no second round for a few
     const int cap = a->max_L > 0 ? (a->max_L + 2 * pl->TK - 1) / (2 * pl->TK) : 1;
     if (S > cap) S = cap;
-    if (variant == V_M2K2 && two_per_cu) {
-      // two of these workgroups fit a CU: go on to 512 of them while a split keeps 16 tiles or more
-      int s2 = 512 / natural;
-      const int by_len = a->max_L / (16 * pl->TK);
-      s2 = s2 < by_len ? s2 : by_len;
-      if (s2 > S) S = s2;
-    }
-    if ((variant == V_M2K2 || variant == V_K2) && two_per_cu) {
-      // A count well between 256 and 512 leaves some CUs with two full workgroups and the rest with
-      // one, and the launch lasts as long as the former: from there go on to (nearly) 512 even with
-      // shorter splits, down to 6 tiles.
-      int s3 = 512 / natural;
-      const int by_len3 = a->max_L / (6 * pl->TK);
-      s3 = s3 < by_len3 ? s3 : by_len3;
-      if (natural * S > 256 && s3 > S && natural * s3 >= 448) S = s3;
-    }
+    if (S > max_by_len) S = max_by_len;
+    // A split has to save more tile time than its merge pass costs (a second launch and the partial rows
+    // written and read back: about six tiles' worth): short caches are split less, or not at all.
+    while (S > 1 && max_by_len - (max_by_len + S - 1) / S < 6) --S;
   }
   if (S > max_by_len) S = max_by_len;
   if (S < 1) S = 1;

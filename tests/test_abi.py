@@ -93,12 +93,13 @@ def test_plan_and_workspace(lib):
 
 
 @pytest.mark.parametrize("B,L,T,rows,splits", [
-    (1, 2048, 60, 64, 8),      # the headline shape: 32 natural workgroups of 64 rows, split to one per CU
-    (4, 2048, 60, 64, 2),      # 128 natural: two per CU would allow 4 splits, but those would be 8 tiles
-    (4, 4096, 60, 64, 4),      # ... and here they keep 16 tiles
-    (3, 2048, 60, 64, 5),      # 96 natural: 3 splits would be 288 workgroups, uneven over 256 CUs: on to 480
-    (5, 2048, 60, 64, 3),      # 160 natural: 320 -> 480
-    (12, 2048, 8, 32, 5),      # the same for the 32-row shape: 96 natural, 288 -> 480
+    (1, 2048, 60, 64, 7),      # the headline shape: 32 natural workgroups of 64 rows; 7 splits of 5 tiles (224 workgroups:
+                               # the tree's tile rides on the short last split) beat 8 of 4, whose last one has 5 as well
+    (4, 2048, 60, 64, 4),      # 128 natural: two per CU (512) with splits of 8 tiles beat one per CU with 16
+    (4, 4096, 60, 64, 4),
+    (3, 2048, 60, 64, 5),      # 96 natural: on to 480
+    (5, 2048, 60, 64, 3),      # 160 natural: 480
+    (12, 2048, 8, 32, 5),      # the same for the 32-row shape: 96 natural -> 480
     (8, 2048, 60, 128, 2),     # 128 workgroups of 128 rows, two splits of 16 tiles
     (16, 2048, 60, 128, 1),    # 256 of them
     (8, 1024, 40, 64, 1),      # 128 of 128 rows would need splits of 8 tiles: 192 of 64 rows instead
@@ -106,9 +107,12 @@ def test_plan_and_workspace(lib):
     (32, 2048, 60, 256, 1),
     (4, 8192, 60, 256, 8),     # few sequences, many keys
     (8, 4096, 32, 256, 4),     # exactly 128 rows
-    (16, 2048, 16, 64, 2),     # 64 rows: never the large shapes
+    (16, 2048, 16, 64, 4),     # 64 rows: never the large shapes
     (64, 2048, 8, 32, 1),      # 32 rows
-    (2, 300, 8, 32, 3),        # no split shorter than two tiles
+    (2, 300, 8, 32, 1),        # five tiles: no split saves what its merge pass costs
+    (8, 512, 24, 64, 1),       # 128 workgroups, eight tiles: two splits would save four, a merge pass costs more
+    (8, 768, 24, 64, 2),       # ... twelve tiles: two splits save six
+    (1, 512, 8, 32, 3),        # eight tiles in splits of 3, 3, 2 + the tree's own
 ])
 def test_launch_plan_bands(lib, B, L, T, rows, splits):
     """The launch planner is host arithmetic on the shapes: one case per band of its rules (Hq 32, Hkv 8)."""
@@ -116,6 +120,30 @@ def test_launch_plan_bands(lib, B, L, T, rows, splits):
     assert (binding.plan_workgroup_rows(a), binding.plan_splits(a)) == (rows, splits)
     ck = binding.plan_chunk_keys(a)
     assert ck % 32 == 0 and ck * splits >= L > ck * (splits - 1)
+
+
+def test_launch_plan_properties_over_the_cost_table_grid(lib):
+    """The grid the attention cost tables are measured on (paper, Method: f(B, c, n) for c = k L, n = 1..N;
+    here B = 1, 2, 4 and 8, c = 256..2048, n = 1..72, benchmark head shape).  Whatever the split count the
+    planner settles on, a split keeps two tiles or more, splits of the small shapes stay within two workgroups
+    per CU, the longest split (the tree's own tiles ride on the last one) is no longer than an unsplit pass
+    would be minus what a merge pass costs, and the rows per workgroup never shrink as the tree grows."""
+    for B in (1, 2, 4, 8):
+        for c in range(256, 2049, 256):
+            prev_rows = 0
+            for n in range(1, 73):
+                a = shape_args(B=B, max_L=c, max_T=n, sum_T=B * n, mask_words=(n + 63) // 64)
+                rows, S, ck = binding.plan_workgroup_rows(a), binding.plan_splits(a), binding.plan_chunk_keys(a)
+                assert rows >= prev_rows, (B, c, n, rows)
+                prev_rows = rows
+                if S == 1:
+                    continue
+                tiles, tree_tiles = -(-c // 64), -(-n // 64)
+                assert ck >= 128 and S == -(-c // ck), (B, c, n, S, ck)
+                if rows <= 64:
+                    assert B * 8 * -(-4 * n // rows) * S <= 512, (B, c, n, S)
+                longest = max(ck // 64, tiles - (S - 1) * (ck // 64) + tree_tiles)
+                assert tiles + tree_tiles - longest >= 3, (B, c, n, S, ck)
 
 
 @pytest.mark.parametrize("kw,code", [

@@ -44,9 +44,13 @@ def test_table_file_round_trip(tmp_path):
 
 def test_conditioning_makes_rows_strictly_increasing():
     t = np.array([[5.0, 4.0, 4.5, 7.0], [1.0, 1.0, 1.0, 0.5]])
-    m = cost_table.make_strictly_increasing(t, eps=0.25)
+    m = cost_table.make_strictly_increasing(t, eps=0.25, max_raise=10.0)
     assert np.all(np.diff(m, axis=1) > 0) and np.all(m >= t)
     assert np.allclose(m, [[5.0, 5.25, 5.5, 7.0], [1.0, 1.25, 1.5, 1.75]])
+    with pytest.raises(ValueError, match="dips by"):             # a 25 % dip is no measurement noise
+        cost_table.make_strictly_increasing(t, eps=0.25)
+    small = np.array([[10.0, 9.8, 10.3]])                        # a 2 % one is
+    assert np.allclose(cost_table.make_strictly_increasing(small), [[10.0, 10.001, 10.3]])
     inc = np.cumsum(np.ones((2, 5)), axis=1)
     assert np.array_equal(cost_table.make_strictly_increasing(inc), inc)     # already increasing: untouched
 
@@ -85,6 +89,6 @@ def test_measure_tiny_table_on_gpu():
         pytest.skip("no GPU")
     t = cost_table.measure(B=2, L=128, M=2, N=16, copies=4, replays=3, n_values=[1, 8, 16])
     assert t.shape == (2, 16) and np.isfinite(t).all() and (t > 1.0).all() and (t < 500.0).all()
-    m = cost_table.make_strictly_increasing(t)
+    m = cost_table.make_strictly_increasing(t, max_raise=1.0)   # (three replays of four copies: plumbing, not a measurement)
     k = cast.select_max_valid_index(np.cumsum(np.linspace(1.0, 0.1, 16)), m[0] / m[0, 0], 0.5)
     assert 1 <= k <= 16
