@@ -275,6 +275,16 @@ int tva_tree_verify_attn_splits(const tva_args *a, void *stream);
 int tva_merge_splits(const float *part_out, const float *part_lse, int32_t S, int64_t n_rows,
                      int32_t D, float *out, float *lse, void *stream);
 
+/* Instrumented builds only (the library compiled with -DTVA_TIMELINE; any other build returns
+ * TVA_UNSUPPORTED): for profiling tools, not for the hot path.  Copies to the HOST buffer dst the time
+ * stamps the kernels of the last tva_tree_verify_attn call left, 8 per workgroup, as counts of the
+ * GPU's constant 100 MHz clock: workgroup w (x fastest, then y, then z of the attention launch) at
+ * dst[8 w + 0..5] = entry, per-sequence scalars arrived, key loop entered, first tile done, all tiles
+ * done, result stores issued; block w of the merge launch at dst[8 w + 6..7] = entry, stores issued.
+ * Synchronous; the caller synchronises the stream first.  n_workgroups <= 8192 (workgroups beyond that
+ * leave no stamps). */
+int tva_timeline_read(uint64_t *dst, int32_t n_workgroups);
+
 const char *tva_strerror(int code);
 
 /* Library version and sizeof(tva_args), for a binding to check that it loaded

@@ -15,6 +15,7 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libtva.so")
+TIMELINE_LIB_PATH = os.path.join(_HERE, "libtva_timeline.so")  # the same sources with time stamps in the kernels
 SRC_PATH = os.path.join(_HERE, "csrc", "tva.hip")
 CAST_SRC_PATH = os.path.join(_HERE, "csrc", "cast.cpp")  # host part: tree-size selection
 VERIFY_SRC_PATH = os.path.join(_HERE, "csrc", "verify.hip")  # acceptance + commit kernels
@@ -32,18 +33,21 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, timeline: bool = False) -> str:
     """Compile csrc/tva.hip and csrc/verify.hip (gfx950 kernels + their C ABI) and csrc/cast.cpp
-    (host logic) into libtva.so (in-tree)."""
+    (host logic) into libtva.so (in-tree); timeline=True: the instrumented build libtva_timeline.so
+    (paper_2510_26577_amd/timeline.py) instead."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE_DIR, "-shared", "-fPIC", "-o", LIB_PATH, SRC_PATH, VERIFY_SRC_PATH, CAST_SRC_PATH]
+    out = TIMELINE_LIB_PATH if timeline else LIB_PATH
+    cmd = [hipcc, *HIPCC_FLAGS, *(["-DTVA_TIMELINE"] if timeline else []), "-I", INCLUDE_DIR, "-shared", "-fPIC", "-o", out,
+           SRC_PATH, VERIFY_SRC_PATH, CAST_SRC_PATH]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     lines = [l for l in res.stdout.splitlines() if "is not a recognized feature" not in l]
     if verbose or res.returncode:
         print("\n".join(lines))
     if res.returncode:
-        raise RuntimeError("hipcc failed building libtva.so")
-    return LIB_PATH
+        raise RuntimeError(f"hipcc failed building {os.path.basename(out)}")
+    return out
 
 
 class TvaArgs(ctypes.Structure):
@@ -71,7 +75,7 @@ class TvaArgs(ctypes.Structure):
 
 
 EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys", "tva_plan_workgroup_rows",
-           "tva_tree_verify_attn", "tva_tree_verify_attn_static", "tva_static_scratch_bytes", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args")
+           "tva_tree_verify_attn", "tva_tree_verify_attn_static", "tva_static_scratch_bytes", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args", "tva_timeline_read")
 # entry points of include/tva_verify.h (bound in verify.py)
 VERIFY_EXPORTS = ("tva_accept_greedy", "tva_commit_path", "tva_sizeof_commit_args")
 # host entry points of include/tva_cast.h (bound in cast.py)
@@ -81,6 +85,14 @@ CAST_EXPORTS = ("tva_cast_select_context", "tva_cast_select_max_valid_index", "t
                 "tva_cast_expansion_plan", "tva_cast_rerank_count", "tva_cast_select_subtree")
 
 _lib = None
+
+
+def use_timeline_library() -> None:
+    """Profiling tools: make this process load the instrumented build.  Before the first load only."""
+    global LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("libtva is already loaded")
+    LIB_PATH = TIMELINE_LIB_PATH
 
 
 def load_library():
@@ -122,6 +134,8 @@ def load_library():
     lib.tva_merge_splits.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
                                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.tva_sizeof_args.restype = ctypes.c_size_t
+    lib.tva_timeline_read.restype = ctypes.c_int
+    lib.tva_timeline_read.argtypes = [ctypes.c_void_p, ctypes.c_int32]
     if lib.tva_version() != EXPECTED_VERSION or lib.tva_sizeof_args() != ctypes.sizeof(TvaArgs):
         raise RuntimeError("libtva.so is stale: rebuild it")
     _lib = lib

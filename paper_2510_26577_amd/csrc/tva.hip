@@ -44,6 +44,24 @@
 
 namespace {
 
+// Instrumented build (-DTVA_TIMELINE, a library of its own): workgroup w of the attention kernel records
+// the constant 100 MHz counter at six points of its life, block w of the merge kernel at two; the stamps
+// stay in scalar registers until the end of the kernel and lane 0 stores them then, so that the kernel's
+// own memory operations are disturbed as little as possible.  tva_timeline_read copies them out.
+#ifdef TVA_TIMELINE
+constexpr int TL_MAX_WG = 8192, TL_SLOTS = 8;
+__device__ unsigned long long timeline[TL_MAX_WG * TL_SLOTS];
+#define TL_DECL unsigned long long tl_t[6] = {0, 0, 0, 0, 0, 0}
+#define TL_STAMP(i) tl_t[i] = __builtin_amdgcn_s_memrealtime()
+#define TL_STORE(wg, first, n)                                                              \
+  if (threadIdx.x == 0 && (wg) < TL_MAX_WG)                                                 \
+    for (int tl_i = 0; tl_i < (n); ++tl_i) timeline[(size_t)(wg) * TL_SLOTS + (first) + tl_i] = tl_t[tl_i]
+#else
+#define TL_DECL
+#define TL_STAMP(i)
+#define TL_STORE(wg, first, n)
+#endif
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -56,8 +74,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // A tile takes the low-order P pass when, for some row, (largest probability of the tile) >
-// kLoThreshold * (that lane half's running sum): then one weight can exceed ~1/16 of the row's
-// total and its bf16 rounding (2^-9 relative) would be visible at the 2e-3 output tolerance.
+// kLoThreshold * (the row's running sum over the keys this wave has seen: both lane halves): then one
+// weight can exceed 1/8 of the row's total and its bf16 rounding (2^-8 relative at worst) would be
+// visible at the 2e-3 output tolerance.
 constexpr float kLoThreshold = 0.125f;
 // The reference maximum of a row is only moved (and O, l rescaled) when a tile maximum exceeds it by
 // more than 2^kLazy: probabilities then stay below 2^kLazy, harmless in fp32 sums and bf16 operands.
@@ -253,6 +272,7 @@ __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) {
 __device__ __forceinline__ void lds_wait(u32x4 &a, u32x4 &b) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b));
 }
+
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ u32x2 lds_read_b64(uint32_t addr) {
   u32x2 v;
@@ -317,6 +337,8 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   extern __shared__ __align__(1024) unsigned char smem[];
   lds_byte *const lds = (lds_byte *)smem;
 
+  TL_DECL;
+  TL_STAMP(0);
   // ---- which (sequence, KV head, row block, chunk) ----
   // grid = (Hkv, row blocks, B * splits): the KV head varies fastest in dispatch order
   const int kvh = blockIdx.x;
@@ -337,6 +359,10 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   int q0 = p.cu_Q ? ((const_i32 *)(uintptr_t)p.cu_Q)[b] : 0;
   int q1 = p.cu_Q ? ((const_i32 *)(uintptr_t)p.cu_Q)[b + 1] : 0;
   asm("" : "+s"(t0), "+s"(t1), "+s"(Lb0), "+s"(cuL), "+s"(q0), "+s"(q1));
+#ifdef TVA_TIMELINE
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the scalars have arrived
+  TL_STAMP(1);
+#endif
   const int Tb = t1 - t0;
   // query nodes: all T_b of the tree, or (draft-stage use: one expansion layer attends to the layers
   // before it) only its last Tq; tq0 is the first query row of the sequence in q / out / lse
@@ -673,7 +699,7 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
         pb[i / 8][r][i % 8] = (__bf16)pv;
       }
       l_run[r] += ls;
-      need_lo = need_lo || (pmax > kLoThreshold * l_run[r]);
+      need_lo = need_lo || (pmax > kLoThreshold * half_sum(l_run[r]));
     }
     // O^T += V^T P^T: first 16 keys while the operands of the second 16 arrive
     constexpr int S2OFF = (16 / NBLK) * ROWB;
@@ -871,11 +897,20 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   }
   if constexpr (KV8 && !C::KV8_REG) land_tile(0);
   int it = 0;
+  TL_STAMP(2);  // Q and the mask rows have arrived, the first tiles are in flight
+#ifdef TVA_TIMELINE
+  if (n_full > 0) {
+    step(0, std::false_type{}, std::false_type{});
+    it = 1;
+    TL_STAMP(3);  // first tile done
+  }
+#endif
   for (; it < n_full; ++it) step(it, std::false_type{}, std::false_type{});
   for (; it < n_ct; ++it) step(it, std::true_type{}, std::false_type{});   // the partial cache tile
   for (; it < n_tiles; ++it) step(it, std::true_type{}, std::true_type{});  // the tree's own keys
   if constexpr (PAGED) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the last (unused) table entries have landed
   __builtin_amdgcn_s_barrier();  // all waves are done reading the ring before it is reused below
+  TL_STAMP(4);  // all tiles done
 
   // ---- combine the two lane halves' partial sums ----
   float l_tot[RB];
@@ -982,6 +1017,8 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   };
   if (PAIR && wk == 1) write_out(std::integral_constant<int, PAIR ? ND / 2 : 0>{});
   else write_out(std::integral_constant<int, 0>{});
+  TL_STAMP(5);  // key groups merged, result stores issued
+  TL_STORE(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), 0, 6);
 }
 #undef kdst_of
 #undef vdst_of
@@ -1002,6 +1039,8 @@ __global__ void __launch_bounds__(256) merge_kernel(const float *__restrict__ pa
                                                     const float *__restrict__ part_lse, int S, int64_t n_rows,
                                                     float *__restrict__ out, float *__restrict__ lse) {
   const int lane = threadIdx.x & 63;
+  TL_DECL;
+  TL_STAMP(0);
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= n_rows) return;
   constexpr int LPR = D / 4;        // lanes covering one row with 16 bytes each
@@ -1051,6 +1090,8 @@ __global__ void __launch_bounds__(256) merge_kernel(const float *__restrict__ pa
   const bool any = z > 0.f;
   if (grp == 0) *reinterpret_cast<f32x4 *>(out + row * D + col) = any ? acc * (1.f / z) : f32x4{0.f, 0.f, 0.f, 0.f};
   if (lane == 0) lse[row] = any ? m + __logf(z) : -INFINITY;
+  TL_STAMP(1);  // stores issued
+  TL_STORE(blockIdx.x, 6, 2);
 }
 
 // NI = splits per lane group and block: the smallest of 1, 2, 4, 8 that covers S in one block
@@ -1277,6 +1318,19 @@ int static_scratch(void **out) {
 extern "C" {
 
 int tva_version(void) { return 5; }
+
+int tva_timeline_read(uint64_t *dst, int32_t n_workgroups) {
+#ifdef TVA_TIMELINE
+  if (!dst || n_workgroups < 0 || n_workgroups > TL_MAX_WG) return TVA_INVALID_ARG;
+  const hipError_t e = hipMemcpyFromSymbol(dst, HIP_SYMBOL(timeline), (size_t)n_workgroups * TL_SLOTS * sizeof(uint64_t), 0,
+                                           hipMemcpyDeviceToHost);
+  return e == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+#else
+  (void)dst;
+  (void)n_workgroups;
+  return TVA_UNSUPPORTED;
+#endif
+}
 
 size_t tva_sizeof_args(void) { return sizeof(tva_args); }
 
