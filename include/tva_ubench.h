@@ -1,8 +1,10 @@
 /*
  * libtva_ubench -- microbenchmarks of the MI355X (gfx950) rates the attention kernels are priced
  * against: matrix-instruction issue rate, how much vector work fits under a matrix instruction,
- * v_exp_f32 / v_fma_f32 rates, LDS read bandwidth, streaming reads, empty launches.  A separate
- * library from libtva (measurement aid, not on the hot path); `bench.py --microbench` runs it.
+ * v_exp_f32 / v_fma_f32 rates, LDS read bandwidth, streaming reads, empty launches; and one alternative
+ * kernel the attention kernels are compared against (attention for very few query rows on the vector
+ * ALUs).  A separate library from libtva (measurement aid, not on the hot path); `bench.py --microbench`
+ * runs the probes, paper_2510_26577_amd/small_rows.py the comparison.
  *
  * Conventions: every pointer is DEVICE memory the caller owns; `stream` is a hipStream_t as void*;
  * calls queue one kernel and return 0, -1 for bad arguments, -2 for a combination that has no
@@ -37,6 +39,30 @@ int tva_ubench_stream(int32_t to_lds, const void *src, size_t bytes, int32_t wor
 
 /* One empty kernel (one wave).  Timed by the caller, back to back. */
 int tva_ubench_empty(void *stream);
+
+/* The alternative for very few query rows that the attention kernels of libtva are compared against:
+ * tree-verification attention on the vector ALUs only (no matrix instructions, no LDS staging of K/V).
+ * Same operation and layouts as tva_tree_verify_attn (include/tva.h; paper, "Tree Reranking Phase": a tree
+ * token attends to its sequence's cache and to its ancestors in the tree and itself), for a dense cache
+ * and explicit ancestor masks only, without KV splits.  A workgroup of four waves takes four query rows
+ * (token, head of the group) of one (sequence, KV head); a wave takes every fourth 64-key tile: lane =
+ * key for the scores (each lane reads its key's row and dots it with the rows' q, which sit in LDS),
+ * lane = pair of head dimensions for the output (each key's probability is broadcast from its lane).
+ * Cost grows with the number of rows; meant for <= 16.
+ *   q [sum_Q, Hq, D] bf16; k_cache / v_cache [sum_L, Hkv, D] bf16 at cu_L; k_tree / v_tree [sum_T, Hkv, D] bf16;
+ *   mask [sum_T, mask_words] uint64; cu_T, L, cu_L int32 [B + 1], [B], [B + 1]; cu_Q int32 [B + 1] or null
+ *   (null: all T_b nodes are queries, else the last cu_Q[b+1] - cu_Q[b]); out fp32 [sum_Q, Hq, D],
+ *   lse fp32 [sum_Q, Hq] (natural log).  D is 64 or 128, max_rows = max_b (query nodes) * Hq / Hkv.
+ * Returns 0, -1 for bad arguments. */
+typedef struct tva_ubench_attn_args {
+  const void *q, *k_cache, *v_cache, *k_tree, *v_tree;
+  const uint64_t *mask;
+  const int32_t *cu_T, *L, *cu_L, *cu_Q;
+  int32_t B, Hq, Hkv, D, mask_words, max_rows;
+  float scale;
+  float *out, *lse;
+} tva_ubench_attn_args;
+int tva_ubench_valu_attn(const tva_ubench_attn_args *args, void *stream);
 
 #ifdef __cplusplus
 }

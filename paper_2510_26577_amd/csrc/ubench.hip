@@ -13,6 +13,7 @@
 //   LDS      ds_read_b128 and ds_read_b64_tr_b16 bandwidth per CU, conflict-free addresses
 //   STREAM   read of a buffer larger than every cache: vector loads and LDS-writing loads
 //   EMPTY    an empty kernel (launch cost is measured by the caller: back-to-back launches in a graph)
+// and one alternative kernel for comparison: attention for very few query rows on the vector ALUs only.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -141,6 +142,159 @@ __global__ void __launch_bounds__(256) stream_kernel(const u32x4 *__restrict__ s
 
 __global__ void empty_kernel() {}
 
+// ---- attention for very few query rows on the vector ALUs (see tva_ubench_valu_attn in the header) ----
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+template <int D>
+__global__ void __launch_bounds__(256) valu_attn_kernel(const tva_ubench_attn_args p) {
+  constexpr int RG = 4;          // query rows per workgroup
+  constexpr int DW = D / 2;      // 32-bit words (bf16 pairs) per row
+  __shared__ float qs[RG][D];  // the rows' q, widened once
+  __shared__ float xm[4][RG], xl[4][RG];
+  __shared__ float xo[4][RG][D];
+  const int kvh = blockIdx.x, rg = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int G = p.Hq / p.Hkv;
+  const int t0 = p.cu_T[b], Tb = p.cu_T[b + 1] - t0, Lb = p.L[b], cuL = p.cu_L[b];
+  int Tq = Tb, tq0 = t0;
+  if (p.cu_Q) {
+    const int nq = p.cu_Q[b + 1] - p.cu_Q[b];
+    Tq = nq < Tb ? nq : Tb;
+    tq0 = p.cu_Q[b];
+  }
+  const int node_off = Tb - Tq, R = Tq * G;
+  if (rg * RG >= R) return;
+  const uint32_t *q32 = (const uint32_t *)p.q;
+  for (int i = threadIdx.x; i < RG * DW; i += 256) {
+    const int r = i / DW, c = i % DW;
+    const int row = rg * RG + r < R ? rg * RG + r : R - 1;
+    const uint32_t w = q32[((size_t)(tq0 + row / G) * p.Hq + kvh * G + row % G) * DW + c];
+    qs[r][2 * c] = bf16_lo(w);
+    qs[r][2 * c + 1] = bf16_hi(w);
+  }
+  __syncthreads();
+  uint64_t mk[RG][2];
+#pragma unroll
+  for (int r = 0; r < RG; ++r) {
+    const int row = rg * RG + r < R ? rg * RG + r : R - 1;
+    const uint64_t *mp = p.mask + (size_t)(t0 + node_off + row / G) * p.mask_words;
+    mk[r][0] = mp[0];
+    mk[r][1] = p.mask_words > 1 ? mp[1] : 0;
+  }
+  const float scale_log2 = p.scale * 1.4426950408889634f;
+  float m[RG], l[RG], o[RG][2];
+#pragma unroll
+  for (int r = 0; r < RG; ++r) m[r] = -INFINITY, l[r] = 0.f, o[r][0] = o[r][1] = 0.f;
+  const uint32_t *kc32 = (const uint32_t *)p.k_cache, *vc32 = (const uint32_t *)p.v_cache;
+  const uint32_t *kt32 = (const uint32_t *)p.k_tree, *vt32 = (const uint32_t *)p.v_tree;
+  const int n_keys = Lb + Tb, n_tiles = (n_keys + 63) / 64;
+  for (int tile = wave; tile < n_tiles; tile += 4) {
+    // scores: lane = key
+    const int kidx = tile * 64 + lane;
+    const bool valid = kidx < n_keys;
+    const int kc = valid ? kidx : n_keys - 1;
+    const uint32_t *kp = kc < Lb ? kc32 + ((size_t)(cuL + kc) * p.Hkv + kvh) * DW
+                                 : kt32 + ((size_t)(t0 + kc - Lb) * p.Hkv + kvh) * DW;
+    u32x4 kr[DW / 4];
+#pragma unroll
+    for (int c = 0; c < DW / 4; ++c) kr[c] = reinterpret_cast<const u32x4 *>(kp)[c];
+    float s[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int c = 0; c < DW / 4; ++c) {
+      float kf[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) kf[2 * e] = bf16_lo(kr[c][e]), kf[2 * e + 1] = bf16_hi(kr[c][e]);
+#pragma unroll
+      for (int r = 0; r < RG; ++r) {
+        // (the same address in every lane: broadcast reads)
+        const f32x4 qa = *reinterpret_cast<const f32x4 *>(&qs[r][8 * c]), qb = *reinterpret_cast<const f32x4 *>(&qs[r][8 * c + 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[r] = fmaf(kf[e], qa[e], s[r]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[r] = fmaf(kf[4 + e], qb[e], s[r]);
+      }
+    }
+    float pr[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+      bool ok = valid;
+      if (kidx >= Lb) {
+        const int n = kidx - Lb;
+        ok = ok && ((mk[r][(n >> 6) & 1] >> (n & 63)) & 1ull);
+      }
+      const float sv = ok ? s[r] * scale_log2 : -INFINITY;
+      const float m_new = fmaxf(m[r], wave_max(sv));
+      const float alpha = (m_new == -INFINITY) ? 1.f : exp2f(m[r] - m_new);
+      pr[r] = (m_new == -INFINITY) ? 0.f : exp2f(sv - m_new);
+      l[r] = l[r] * alpha + pr[r];
+      o[r][0] *= alpha;
+      o[r][1] *= alpha;
+      m[r] = m_new;
+    }
+    // output: lane = pair of head dimensions; key j's probability comes from lane j
+    // (keys past the end have probability zero and re-read the last key's row)
+    const int k0 = tile * 64;
+#pragma unroll 1
+    for (int j0 = 0; j0 < 64; j0 += 16) {
+      uint32_t vw[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int key = k0 + j0 + j < n_keys ? k0 + j0 + j : n_keys - 1;
+        const uint32_t *vp = key < Lb ? vc32 + ((size_t)(cuL + key) * p.Hkv + kvh) * DW
+                                      : vt32 + ((size_t)(t0 + key - Lb) * p.Hkv + kvh) * DW;
+        vw[j] = lane < DW ? vp[lane] : 0u;
+      }
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const float vx = bf16_lo(vw[j]), vy = bf16_hi(vw[j]);
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+          const float pj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(pr[r]), j0 + j));
+          o[r][0] = fmaf(pj, vx, o[r][0]);
+          o[r][1] = fmaf(pj, vy, o[r][1]);
+        }
+      }
+    }
+  }
+  // combine the four waves
+#pragma unroll
+  for (int r = 0; r < RG; ++r) {
+    const float ls = wave_sum(l[r]);
+    if (lane == 0) xm[wave][r] = m[r], xl[wave][r] = ls;
+    if (lane < DW) xo[wave][r][2 * lane] = o[r][0], xo[wave][r][2 * lane + 1] = o[r][1];
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < RG * D; i += 256) {
+    const int r = i / D, d = i % D;
+    const int row = rg * RG + r;
+    if (row >= R) continue;
+    float M = -INFINITY;
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, xm[w][r]);
+    float L = 0.f, O = 0.f;
+    for (int w = 0; w < 4; ++w) {
+      const float a = (xm[w][r] == -INFINITY) ? 0.f : exp2f(xm[w][r] - M);
+      L += xl[w][r] * a;
+      O += xo[w][r][d] * a;
+    }
+    const size_t og = (size_t)(tq0 + row / G) * p.Hq + kvh * G + row % G;
+    p.out[og * D + d] = L > 0.f ? O / L : 0.f;
+    if (d == 0) p.lse[og] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+  }
+}
+
 template <typename F>
 int launch_checked(F &&f) {
   (void)hipGetLastError();
@@ -185,6 +339,19 @@ int tva_ubench_stream(int32_t to_lds, const void *src, size_t bytes, int32_t wor
   const size_t n16 = bytes / 16;
   if (to_lds) return launch_checked([&] { hipLaunchKernelGGL((stream_kernel<true>), dim3(workgroups), dim3(256), 32 * 1024, st, p, n16, sink); });
   return launch_checked([&] { hipLaunchKernelGGL((stream_kernel<false>), dim3(workgroups), dim3(256), 0, st, p, n16, sink); });
+}
+
+int tva_ubench_valu_attn(const tva_ubench_attn_args *a, void *stream) {
+  if (!a || !a->q || !a->k_cache || !a->v_cache || !a->k_tree || !a->v_tree || !a->mask || !a->cu_T || !a->L || !a->cu_L ||
+      !a->out || !a->lse)
+    return -1;
+  if (a->B < 1 || a->Hkv < 1 || a->Hq < a->Hkv || a->Hq % a->Hkv || (a->D != 64 && a->D != 128) || a->mask_words < 1 ||
+      a->mask_words > 2 || a->max_rows < 1 || a->B > 65535)
+    return -1;
+  const dim3 grid(a->Hkv, (a->max_rows + 3) / 4, a->B), block(256);
+  hipStream_t st = (hipStream_t)stream;
+  if (a->D == 128) return launch_checked([&] { hipLaunchKernelGGL((valu_attn_kernel<128>), grid, block, 0, st, *a); });
+  return launch_checked([&] { hipLaunchKernelGGL((valu_attn_kernel<64>), grid, block, 0, st, *a); });
 }
 
 int tva_ubench_empty(void *stream) {

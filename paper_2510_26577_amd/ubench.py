@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtva_ubench.so")
 SRC_PATH = os.path.join(_HERE, "csrc", "ubench.hip")
 INCLUDE_DIR = os.path.join(os.path.dirname(_HERE), "include")
-EXPORTS = ("tva_ubench_mfma_valu", "tva_ubench_lds", "tva_ubench_stream", "tva_ubench_empty")
+EXPORTS = ("tva_ubench_mfma_valu", "tva_ubench_lds", "tva_ubench_stream", "tva_ubench_empty", "tva_ubench_valu_attn")
 _lib = None
 
 
@@ -40,6 +40,7 @@ def load_library():
         lib.tva_ubench_lds.argtypes = [i32, i32, i32, i32, vp, vp, vp]
         lib.tva_ubench_stream.argtypes = [i32, vp, ctypes.c_size_t, i32, vp, vp]
         lib.tva_ubench_empty.argtypes = [vp]
+        lib.tva_ubench_valu_attn.argtypes = [vp, vp]      # (tva_ubench_attn_args *, stream): paper_2510_26577_amd/small_rows.py
         _lib = lib
     return _lib
 
