@@ -902,8 +902,8 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   if (n_full > 0) {
     step(0, std::false_type{}, std::false_type{});
     it = 1;
-    TL_STAMP(3);  // first tile done
   }
+  TL_STAMP(3);  // first full tile done (a split without one: the same moment as the stamp before)
 #endif
   for (; it < n_full; ++it) step(it, std::false_type{}, std::false_type{});
   for (; it < n_ct; ++it) step(it, std::true_type{}, std::false_type{});   // the partial cache tile
