@@ -37,6 +37,12 @@ int tva_ubench_lds(int32_t transpose_reads, int32_t waves_per_simd, int32_t work
  * of 256 threads: into registers, or with to_lds straight into LDS.  Timed by the caller. */
 int tva_ubench_stream(int32_t to_lds, const void *src, size_t bytes, int32_t workgroups, float *sink, void *stream);
 
+/* Every one of `workgroups` workgroups of 256 threads reads the first `bytes` of `src` (a multiple of 32 KiB, small
+ * enough to stay in an L2) `reps` times, 16 bytes per lane: into registers, or with to_lds straight into LDS.
+ * Delivered bytes = workgroups * reps * bytes.  Timed by the caller. */
+int tva_ubench_reread(int32_t to_lds, const void *src, size_t bytes, int32_t reps, int32_t workgroups, float *sink,
+                         void *stream);
+
 /* One empty kernel (one wave).  Timed by the caller, back to back. */
 int tva_ubench_empty(void *stream);
 

@@ -12,6 +12,7 @@
 //   EXP      v_exp_f32 rate;  FMA  v_fma_f32 rate
 //   LDS      ds_read_b128 and ds_read_b64_tr_b16 bandwidth per CU, conflict-free addresses
 //   STREAM   read of a buffer larger than every cache: vector loads and LDS-writing loads
+//   L2       every workgroup re-reads one small buffer: what the L2 -> CU path delivers to each kind of load
 //   EMPTY    an empty kernel (launch cost is measured by the caller: back-to-back launches in a graph)
 // and one alternative kernel for comparison: attention for very few query rows on the vector ALUs only.
 #include <hip/hip_runtime.h>
@@ -136,6 +137,38 @@ __global__ void __launch_bounds__(256) stream_kernel(const u32x4 *__restrict__ s
 #pragma unroll
       for (int u = 0; u < 8; ++u) acc ^= v[u];
     }
+  }
+  if (acc[0] + acc[1] + acc[2] + acc[3] == 0x12345678u) sink[threadIdx.x] = 1.f;
+}
+
+// every workgroup reads the same small buffer `reps` times (so that all but the first reads are served by
+// the L2 of its XCD): what the L2 -> CU path delivers, into registers or straight into LDS
+template <bool TO_LDS>
+__global__ void __launch_bounds__(256) l2_stream_kernel(const u32x4 *__restrict__ src, int n16, int reps, float *sink) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  u32x4 acc = {0, 0, 0, 0};
+  const int wave = threadIdx.x >> 6;
+  for (int rep = 0; rep < reps; ++rep) {
+    // (each workgroup starts somewhere else, so that they do not all ask for the same line at once)
+    int i = (threadIdx.x + blockIdx.x * 4096) % n16;
+    for (int k = 0; k + 8 * 256 <= n16; k += 8 * 256) {
+      if (TO_LDS) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int j = (i + u * 256) % n16;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + j),
+                                           (__attribute__((address_space(3))) void *)(smem + (wave * 8 + u) * 1024), 16, 0, 0);
+        }
+      } else {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(i + u * 256) % n16];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+      }
+      i = (i + 8 * 256) % n16;
+    }
+    if (TO_LDS) __builtin_amdgcn_s_waitcnt(0);
   }
   if (acc[0] + acc[1] + acc[2] + acc[3] == 0x12345678u) sink[threadIdx.x] = 1.f;
 }
@@ -352,6 +385,15 @@ int tva_ubench_valu_attn(const tva_ubench_attn_args *a, void *stream) {
   hipStream_t st = (hipStream_t)stream;
   if (a->D == 128) return launch_checked([&] { hipLaunchKernelGGL((valu_attn_kernel<128>), grid, block, 0, st, *a); });
   return launch_checked([&] { hipLaunchKernelGGL((valu_attn_kernel<64>), grid, block, 0, st, *a); });
+}
+
+int tva_ubench_reread(int32_t to_lds, const void *src, size_t bytes, int32_t reps, int32_t workgroups, float *sink, void *stream) {
+  if (!src || bytes < 8 * 256 * 16 || bytes > (1u << 30) || reps < 1 || workgroups < 1 || !sink) return -1;
+  hipStream_t st = (hipStream_t)stream;
+  const u32x4 *p = (const u32x4 *)src;
+  const int n16 = (int)(bytes / 16);
+  if (to_lds) return launch_checked([&] { hipLaunchKernelGGL((l2_stream_kernel<true>), dim3(workgroups), dim3(256), 32 * 1024, st, p, n16, reps, sink); });
+  return launch_checked([&] { hipLaunchKernelGGL((l2_stream_kernel<false>), dim3(workgroups), dim3(256), 0, st, p, n16, reps, sink); });
 }
 
 int tva_ubench_empty(void *stream) {

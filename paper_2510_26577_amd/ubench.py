@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtva_ubench.so")
 SRC_PATH = os.path.join(_HERE, "csrc", "ubench.hip")
 INCLUDE_DIR = os.path.join(os.path.dirname(_HERE), "include")
-EXPORTS = ("tva_ubench_mfma_valu", "tva_ubench_lds", "tva_ubench_stream", "tva_ubench_empty", "tva_ubench_valu_attn")
+EXPORTS = ("tva_ubench_mfma_valu", "tva_ubench_lds", "tva_ubench_stream", "tva_ubench_empty", "tva_ubench_valu_attn", "tva_ubench_reread")
 _lib = None
 
 
@@ -40,6 +40,7 @@ def load_library():
         lib.tva_ubench_lds.argtypes = [i32, i32, i32, i32, vp, vp, vp]
         lib.tva_ubench_stream.argtypes = [i32, vp, ctypes.c_size_t, i32, vp, vp]
         lib.tva_ubench_empty.argtypes = [vp]
+        lib.tva_ubench_reread.argtypes = [i32, vp, ctypes.c_size_t, i32, i32, vp, vp]
         lib.tva_ubench_valu_attn.argtypes = [vp, vp]      # (tva_ubench_attn_args *, stream): paper_2510_26577_amd/small_rows.py
         _lib = lib
     return _lib
@@ -114,6 +115,28 @@ def run_all(n_cu: int = 256):
             stream[f"{'global_load_lds' if to_lds else 'global_load'} workgroups={wgs}"] = {"GB_per_s": nbytes / best / 1e6}
     res["stream_read_1GiB"] = stream
     del buf
+
+    # ---- L2 -> CU: every workgroup re-reads 1 MiB (it stays in the L2 of each XCD), one workgroup per CU ----
+    small = torch.empty((1 << 20) // 4, dtype=torch.int32, device=dev)
+    small.random_(0, 1 << 20)
+    l2 = {}
+    for to_lds in (0, 1):
+        for wgs in (n_cu // 2, n_cu, 2 * n_cu):
+            reps = 64
+            best = 1e30
+            for _ in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(st)
+                rc = lib.tva_ubench_reread(to_lds, small.data_ptr(), 1 << 20, reps, wgs, sink.data_ptr(), sp)
+                assert rc == 0, rc
+                e1.record(st)
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1))
+            total = wgs * reps * (1 << 20)
+            l2[f"{'global_load_lds' if to_lds else 'global_load'} workgroups={wgs}"] = {
+                "TB_per_s": total / best / 1e9, "GB_per_s_per_workgroup": total / best / 1e6 / wgs}
+    res["l2_reread_1MiB"] = l2
+    del small
 
     # ---- empty kernel: back-to-back launches replayed from one graph ----
     n = 200
