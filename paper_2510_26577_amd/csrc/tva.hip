@@ -1181,7 +1181,9 @@ bool make_plan(const tva_args *a, Plan *pl) {
       const int ckt = (tiles + s - 1) / s, nch = (tiles + ckt - 1) / ckt;
       if (nch != s) continue;  // the same split length as a smaller count
       const int64_t wgs = (int64_t)natural * nch;
-      if (nch > 1 && wgs > 512) break;
+      // (no split once the unsplit launch already has a workgroup for every CU: measured at B = 16 and 32,
+      // splitting then only adds the merge)
+      if (nch > 1 && (wgs > 512 || natural >= 256)) break;
       const int last = tiles - (nch - 1) * ckt + tree_tiles;
       const int longest = nch > 1 && ckt > last ? ckt : last;
       const double share = wgs <= 256 ? 1.0 : 1.5 * (double)((wgs + 511) / 512);

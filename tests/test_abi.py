@@ -113,6 +113,9 @@ def test_plan_and_workspace(lib):
     (8, 512, 24, 64, 1),       # 128 workgroups, eight tiles: two splits would save four, a merge pass costs more
     (8, 768, 24, 64, 2),       # ... twelve tiles: two splits save six
     (1, 512, 8, 32, 3),        # eight tiles in splits of 3, 3, 2 + the tree's own
+    (32, 2048, 9, 64, 1),      # 256 natural workgroups of 64 rows: every CU has one already, a split only adds the merge
+    (16, 2048, 20, 64, 1),     # ... the same with two row blocks at batch 16
+    (16, 2048, 9, 64, 4),      # 128 natural: split
 ])
 def test_launch_plan_bands(lib, B, L, T, rows, splits):
     """The launch planner is host arithmetic on the shapes: one case per band of its rules (Hq 32, Hkv 8)."""
