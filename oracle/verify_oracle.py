@@ -1,6 +1,6 @@
-"""CPU oracle of the two steps that close a verification pass after the attention: greedy
-(temperature 0) acceptance of a root path of the draft tree, and the commit of the accepted
-nodes' K/V rows to the end of the sequence's cache.
+"""CPU oracle of the steps that close a verification pass after the attention: acceptance of a root
+path of the draft tree (greedy, temperature 0; and by speculative sampling, accept_sampling below), and the
+commit of the accepted nodes' K/V rows to the end of the sequence's cache.
 
 TEST INFRASTRUCTURE ONLY: imported by tests/ (nothing in the product path).  Plain numpy /
 Python loops; shares no code with the HIP kernels.
@@ -54,6 +54,73 @@ def accept_greedy(parent, cu_T, draft_token, target_token, max_path=None):
             path.append(cur)
         paths.append(path)
         nxt.append(int(target_token[t0 + cur]))
+    return paths, nxt
+
+
+def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, max_path=None):
+    """Acceptance by speculative sampling on draft trees (paper, Preliminary, "Speculative Decoding": a drafted
+    token x with draft probability q(x) and target probability p(x) is accepted when a uniform number is at most
+    min(1, p(x) / q(x)); after a rejection the target distribution is replaced by the residual norm(max(0, p - q));
+    "EAGLE": with a tree draft a rejected token leaves its siblings in play).
+
+    p_target[i], q_draft[i]: float32 [V] rows per node i -- the target's distribution of the token after node
+    i's path, and the draft distribution node i's children were drawn from.  u[i]: the uniform number used when
+    node i is tested as a child; u_final[b]: the one that draws the step's last token.  The walk starts at node 0
+    (accepted).  At the current node the children are tested in index order against the current residual r
+    (r = p at first); the first accepted child becomes the current node, with a fresh r; when every child is
+    rejected, or there is none, or max_path nodes are accepted, one token is drawn from r / sum(r) and the walk
+    ends.  Returns (paths, next_token).
+
+    Readings (the paper states the rule for a chain only):
+      S1  a child is tested against the residual left by its rejected elder siblings;
+      S2  a rejection does not change q (the children of a node are independent draws from it), so the
+          residual after a rejection is norm(max(0, r - q)) with the same q every time;
+      S3  "u <= min(1, p/q)" is evaluated without a division as  r[x] > 0  and  u * q[x] * Z <= r[x],
+          r kept unnormalised with Z = sum(r) (a token the draft gave probability 0 but the residual does not
+          is accepted);
+      S4  the last token is the smallest v whose cumulative weight r[0] + .. + r[v] exceeds u_final * Z
+          (the last v with r[v] > 0 if rounding leaves none).
+    Precision: r is held in float32 as the kernel holds it; sums, products and comparisons in float64.
+    Parity unpinned against the paper (it prints no example); pinned by the chain rule written out, by the
+    theorem that the emitted token is distributed as p, and by the temperature-0 and q = p special cases."""
+    B = len(cu_T) - 1
+    paths, nxt = [], []
+    for b in range(B):
+        t0, T = int(cu_T[b]), int(cu_T[b + 1] - cu_T[b])
+        if T == 0:
+            paths.append([])
+            nxt.append(-1)
+            continue
+        cur, path = 0, [0]
+        while True:
+            r = np.array(p_target[t0 + cur], dtype=np.float32, copy=True)
+            Z = float(r.astype(np.float64).sum())
+            q = np.asarray(q_draft[t0 + cur], dtype=np.float32).astype(np.float64)
+            accepted = False
+            if max_path is None or len(path) < max_path:
+                for c in range(cur + 1, T):
+                    if int(parent[t0 + c]) != cur:
+                        continue
+                    x = int(draft_token[t0 + c])
+                    rx = float(r[x])
+                    if rx > 0.0 and float(u[t0 + c]) * float(q[x]) * Z <= rx:
+                        cur = c
+                        path.append(c)
+                        accepted = True
+                        break
+                    r_new = np.maximum(0.0, r.astype(np.float64) - Z * q).astype(np.float32)
+                    Z_new = float(r_new.astype(np.float64).sum())
+                    if not Z_new > 0.0:
+                        raise ValueError("residual vanished: q is not a distribution the child could have been drawn from")
+                    r, Z = r_new, Z_new
+            if accepted:
+                continue
+            cs = np.cumsum(r.astype(np.float64))
+            hit = np.nonzero(cs > float(u_final[b]) * Z)[0]
+            v = int(hit[0]) if len(hit) else int(np.nonzero(r > 0)[0][-1])
+            paths.append(path)
+            nxt.append(v)
+            break
     return paths, nxt
 
 

@@ -126,3 +126,106 @@ def test_commit_dense_and_paged_write_exactly_the_path_rows():
             t = L[b] + j
             assert np.array_equal(k3[perm[b, t // ps], t % ps], kt[cu_T[b] + node])
     assert int((k3 != 0).any(axis=(2, 3)).sum()) <= sum(len(p) for p in paths)
+
+
+# ---- acceptance by speculative sampling (oracle: accept_sampling) ----
+
+def dirichlet_rows(rng, n, V, conc=0.7):
+    return rng.dirichlet(np.full(V, conc), size=n).astype(np.float32)
+
+
+def test_sampling_on_a_chain_is_the_rule_of_the_paper_written_out():
+    """A chain tree is plain speculative decoding (paper, Preliminary): token i is accepted iff
+    u_i <= min(1, p_i / q_i); at the first rejection one token is drawn from norm(max(0, p - q)), after the last
+    acceptance from p.  Written here with divisions and normalised vectors, not the oracle's way."""
+    rng = np.random.Generator(np.random.PCG64(31))
+    V = 11
+    for _ in range(300):
+        T = int(rng.integers(1, 9))
+        parent = np.arange(-1, T - 1, dtype=np.int32)
+        P, Q = dirichlet_rows(rng, T, V), dirichlet_rows(rng, T, V)
+        tok = np.array([0] + [int(rng.choice(V, p=Q[i - 1].astype(np.float64) / Q[i - 1].astype(np.float64).sum()))
+                              for i in range(1, T)], np.int32)
+        u, uf = rng.random(T), rng.random(1)
+        paths, nxt = vo.accept_sampling(parent, np.array([0, T], np.int32), tok, P, Q, u, uf)
+        # the rule, directly
+        n_acc, dist = 1, P[0].astype(np.float64)
+        for i in range(1, T):
+            p, q = P[i - 1].astype(np.float64), Q[i - 1].astype(np.float64)
+            p, x = p / p.sum(), int(tok[i])
+            if u[i] <= min(1.0, p[x] / q[x]):
+                n_acc += 1
+                dist = P[i].astype(np.float64)
+            else:
+                dist = np.maximum(0.0, p - q)
+                break
+        dist = dist / dist.sum()
+        want = int(np.searchsorted(np.cumsum(dist), uf[0], side="right"))
+        assert paths[0] == list(range(n_acc))
+        # (the oracle keeps the residual in float32 and unnormalised: equal unless uf sits on a boundary)
+        cs = np.cumsum(dist)
+        if np.min(np.abs(cs - uf[0])) > 1e-6:
+            assert nxt[0] == want
+
+
+def test_sampling_emits_tokens_distributed_as_the_target():
+    """The theorem the rule rests on (paper, Preliminary: the output is a sample of the target distribution):
+    whatever q is, with k children drawn independently from q the first emitted token -- the accepted child's, or
+    the one drawn from the last residual -- has distribution p.  200 000 seeded trials, 6-token vocabulary."""
+    rng = np.random.Generator(np.random.PCG64(32))
+    V, N, k = 6, 200000, 3
+    p, q = dirichlet_rows(rng, 1, V)[0], dirichlet_rows(rng, 1, V)[0]
+    parent = np.tile(np.array([-1] + [0] * k, np.int32), N)
+    cu = (np.arange(N + 1) * (k + 1)).astype(np.int32)
+    tok = np.zeros((N, k + 1), np.int32)
+    tok[:, 1:] = rng.choice(V, size=(N, k), p=q.astype(np.float64) / q.astype(np.float64).sum())
+    P, Q = np.tile(p, ((k + 1) * N, 1)), np.tile(q, ((k + 1) * N, 1))
+    paths, nxt = vo.accept_sampling(parent, cu, tok.reshape(-1), P, Q, rng.random((k + 1) * N), rng.random(N))
+    first = np.array([tok[i, pth[1]] if len(pth) > 1 else nxt[i] for i, pth in enumerate(paths)])
+    freq = np.bincount(first, minlength=V) / N
+    sigma = np.sqrt(p.astype(np.float64) * (1 - p.astype(np.float64)) / N)
+    assert np.all(np.abs(freq - p) <= 5 * sigma + 1e-6), (freq, p)
+    # and it is not trivially so: the children alone are distributed as q, visibly different from p
+    assert np.abs(np.bincount(tok[:, 1], minlength=V) / N - p).max() > 20 * sigma.max()
+
+
+def test_sampling_special_cases():
+    rng = np.random.Generator(np.random.PCG64(33))
+    V = 9
+    for _ in range(100):
+        T = int(rng.integers(2, 30))
+        parent = random_tree(rng, T)
+        # (token V - 1 is never drafted)
+        tok = distinct_sibling_tokens(rng, parent, vocab=V - 1) if T < 8 else rng.integers(0, V - 1, T).astype(np.int32)
+        cu = np.array([0, T], np.int32)
+        P = dirichlet_rows(rng, T, V)
+        u, uf = rng.random(T), rng.random(1)
+        # q = p: the ratio is 1, so the first child of every node on the way is accepted for any u < 1
+        paths, _ = vo.accept_sampling(parent, cu, tok, P, P, np.full(T, 0.999), uf)
+        cur, want = 0, [0]
+        while True:
+            first = [c for c in range(cur + 1, T) if parent[c] == cur][:1]
+            if not first:
+                break
+            cur = first[0]
+            want.append(cur)
+        assert paths[0] == want
+        # a point-mass target (temperature 0) makes it the greedy rule: the child carrying the target's token
+        target = rng.integers(0, V - 1, T).astype(np.int32)
+        for i in rng.integers(0, T, size=6):
+            if parent[i] >= 0:
+                target[parent[i]] = tok[i]
+        onehot = np.zeros((T, V), np.float32)
+        onehot[np.arange(T), target] = 1.0
+        Q = dirichlet_rows(rng, T, V, conc=2.0)
+        gp, gn = vo.accept_greedy(parent, cu, tok, target)
+        sp, sn = vo.accept_sampling(parent, cu, tok, onehot, Q, u, uf)
+        assert sp == gp and sn == gn
+        # a token the target gives no probability is never accepted, even with u = 0
+        Pz = P.copy()
+        Pz[:, np.unique(tok)] = 0.0                              # no drafted token has target mass anywhere
+        zp, _ = vo.accept_sampling(parent, cu, tok, Pz, dirichlet_rows(rng, T, V), np.zeros(T), uf)
+        assert zp == [[0]]
+        # max_path is an interface limit
+        lp, _ = vo.accept_sampling(parent, cu, tok, P, P, np.zeros(T), uf, max_path=2)
+        assert len(lp[0]) <= 2
