@@ -1,7 +1,7 @@
 /*
- * libtva -- the two steps that close a verification pass after the attention: greedy
- * acceptance of a root path of each draft tree, and the commit of the accepted nodes' K/V rows
- * to the end of each sequence's cache.  Same conventions as tva.h: device pointers owned by the
+ * libtva -- the steps that close a verification pass after the attention: acceptance of a root
+ * path of each draft tree (greedy, or by speculative sampling), and the commit of the accepted nodes'
+ * K/V rows to the end of each sequence's cache.  Same conventions as tva.h: device pointers owned by the
  * caller, work queued on `stream` (hipStream_t as void*), nothing allocated, negative tva_status
  * on rejected arguments (then nothing is queued).
  */
@@ -37,6 +37,43 @@ extern "C" {
 int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t *draft_token,
                       const int32_t *target_token, int32_t B, int32_t max_path, int32_t *path,
                       int32_t *path_len, int32_t *next_token, void *stream);
+
+/*
+ * Acceptance by speculative sampling on draft trees (paper, Preliminary, "Speculative Decoding": a drafted
+ * token x is accepted when a uniform number is at most min(1, p(x) / q(x)), p the target's and q the draft's
+ * probability of it; after a rejection the target distribution is replaced by the residual
+ * norm(max(0, p - q)) -- the output is then a sample of the target distribution; "EAGLE": with a tree draft a
+ * rejected token leaves its siblings in play).
+ *
+ * Per sequence b the walk starts at node 0 (always accepted).  At the current node its children are tested in
+ * index order against the current residual r (r = the node's row of p_target at first, kept unnormalised with
+ * Z = sum r):  child c with token x is accepted iff  r[x] > 0  and  u[c] * q[x] * Z <= r[x]  (q = the current
+ * node's row of q_draft, the distribution its children were drawn from, independently; a rejection does not
+ * change it);  a rejected child replaces r by max(0, r - Z q).  The first accepted child becomes the current
+ * node, with a fresh r.  When every child is rejected, or there is none, or max_path nodes are accepted, the
+ * step's last token is the smallest v whose cumulative weight r[0] + .. + r[v] exceeds u_final[b] * Z, and the
+ * walk ends.  r is held in fp32; sums, products and comparisons are made in fp64.  The random numbers are
+ * inputs: the library draws none.
+ *   parent, cu_T, draft_token   as for tva_accept_greedy
+ *   p_target, q_draft   device fp32 [cu_T[B], V]  rows per node (each a distribution: non-negative, sum 1)
+ *   u                   device fp32 [cu_T[B]]     uniform number of each node's test as a child
+ *   u_final             device fp32 [B]           uniform number of each sequence's last draw
+ *   residual            device fp32 [B, V]        scratch the caller owns; contents on return unspecified
+ *   path, path_len, next_token   as for tva_accept_greedy (next_token = the drawn token)
+ *   err_flag            device int32[1] or NULL, zero on entry: stores 1 + b when a draft_token is not in
+ *                       [0, V) (that child is never accepted) or a residual vanishes (q was not the distribution
+ *                       the rejected child came from; the walk ends there with next_token -1)
+ */
+typedef struct tva_sample_args {
+  int32_t B, V, max_path;
+  const int32_t *parent, *cu_T, *draft_token;
+  const float *p_target, *q_draft, *u, *u_final;
+  float *residual;
+  int32_t *path, *path_len, *next_token, *err_flag;
+} tva_sample_args;
+
+int tva_accept_sampling(const tva_sample_args *a, void *stream);
+size_t tva_sizeof_sample_args(void);
 
 /*
  * Commit of the accepted path: accepted node j of sequence b (path order) has its K and V rows copied

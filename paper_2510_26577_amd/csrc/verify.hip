@@ -11,6 +11,11 @@
 //                   sizes a decode step has.
 //   compact_kernel  the same commit when the tree's K/V already sit in the cache behind the committed
 //                   tokens: the accepted rows move down in place, one workgroup per sequence.
+//   sample_kernel   acceptance by speculative sampling: one workgroup of 1024 threads per sequence.  The walk
+//                   and the tests of the children are a chain of dependent steps that every thread takes in
+//                   step (they read the same words); the data-parallel part is over the vocabulary: the
+//                   sum of a distribution, the residual after a rejection, the draw of the last token --
+//                   one streaming pass over V floats each.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -55,6 +60,148 @@ __global__ void __launch_bounds__(64) accept_kernel(const int32_t *__restrict__ 
   if (lane == 0) {
     path_len[b] = len;
     next_token[b] = target[t0 + cur];
+  }
+}
+
+// ---- acceptance by speculative sampling ----
+struct SampleParams {
+  const int32_t *parent, *cu_T, *token;
+  const float *p, *q, *u, *u_final;
+  float *residual;
+  int32_t *path, *path_len, *next_token, *err_flag;
+  int V, max_path;
+};
+
+constexpr int kSampleThreads = 1024, kSampleWaves = kSampleThreads / 64;
+
+// One pass over a vocabulary-long row.  Wave w owns the contiguous segment [w * seg, (w + 1) * seg) and its lanes
+// take consecutive elements (coalesced); f(v) returns element v's weight (and may store it).  wsum[w] receives the
+// segment's sum; the return value, the same in every thread, is their sum taken in segment order.
+template <class F>
+__device__ __forceinline__ double segment_pass(int V, int seg, double *wsum, F f) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int s0 = wave * seg, s1 = s0 + seg < V ? s0 + seg : V;
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+  int v = s0 + lane;
+  for (; v + 192 < s1; v += 256) {  // four loads in flight per lane
+    const double x0 = f(v), x1 = f(v + 64), x2 = f(v + 128), x3 = f(v + 192);
+    a0 += x0, a1 += x1, a2 += x2, a3 += x3;
+  }
+  for (; v < s1; v += 64) a0 += f(v);
+  double x = (a0 + a1) + (a2 + a3);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+  __syncthreads();  // (wsum may still be read from the pass before; stores of f are visible after the next barrier)
+  if (lane == 0) wsum[wave] = x;
+  __syncthreads();
+  double z = 0.0;
+  for (int w = 0; w < kSampleWaves; ++w) z += wsum[w];
+  return z;
+}
+
+__global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SampleParams p) {
+  __shared__ double wsum[kSampleWaves];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int t0 = p.cu_T[b];
+  const int T = p.cu_T[b + 1] - t0;
+  if (T <= 0) {
+    if (tid == 0) p.path_len[b] = 0, p.next_token[b] = -1;
+    return;
+  }
+  const int V = p.V, seg = (V + kSampleWaves - 1) / kSampleWaves;
+  float *const r = p.residual + (size_t)b * V;
+  int cur = 0, len = 1;
+  if (tid == 0) p.path[(size_t)b * p.max_path] = 0;
+  const float *dist;  // what the next test or the last draw reads: the current node's target row, or the residual
+  double Z;
+  while (true) {
+    dist = p.p + (size_t)(t0 + cur) * V;
+    const float *q = p.q + (size_t)(t0 + cur) * V;
+    Z = segment_pass(V, seg, wsum, [&](int v) { return (double)dist[v]; });
+    bool accepted = false;
+    if (len < p.max_path) {
+      for (int c = cur + 1; c < T; ++c) {
+        if (p.parent[t0 + c] != cur) continue;  // (the same word in every thread: the branch is uniform)
+        const int x = p.token[t0 + c];
+        if (x < 0 || x >= V) {  // not a token: flagged, never accepted, leaves the residual alone
+          if (tid == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+          continue;
+        }
+        const double rx = (double)dist[x];
+        if (rx > 0.0 && (double)p.u[t0 + c] * (double)q[x] * Z <= rx) {
+          cur = c;
+          if (tid == 0) p.path[(size_t)b * p.max_path + len] = c;
+          ++len;
+          accepted = true;
+          break;
+        }
+        // rejected: the residual max(0, r - Z q), unnormalised, and its sum
+        __syncthreads();  // every thread has read dist[x] before the residual is overwritten in place
+        const float *from = dist;
+        const double Zq = Z;
+        const double Zn = segment_pass(V, seg, wsum, [&](int v) {
+          const double d = (double)from[v] - Zq * (double)q[v];
+          const float f = d > 0.0 ? (float)d : 0.f;
+          r[v] = f;
+          return (double)f;
+        });
+        if (!(Zn > 0.0)) {
+          // q was not a distribution the child could have been drawn from: flagged; the walk ends here
+          if (tid == 0) {
+            if (p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+            p.path_len[b] = len;
+            p.next_token[b] = -1;
+          }
+          return;
+        }
+        Z = Zn;
+        dist = r;
+      }
+    }
+    if (!accepted) break;
+  }
+  // The last token: the smallest v whose cumulative weight exceeds u_final * Z.  The segments' sums of the pass
+  // that produced Z say which segment holds it; that segment's wave walks it 64 elements at a time.
+  const double target = (double)p.u_final[b] * Z;
+  int claim = -1, last_heavy = 0;
+  double before = 0.0;
+  {
+    double pre = 0.0;
+    for (int w = 0; w < kSampleWaves; ++w) {
+      const double nx = pre + wsum[w];
+      if (claim < 0 && nx > target) claim = w, before = pre;
+      if (wsum[w] > 0.0) last_heavy = w;
+      pre = nx;
+    }
+  }
+  const bool none = claim < 0;  // (u_final was not below 1: the last token that has weight)
+  if (none) claim = last_heavy;
+  const int wave = tid >> 6, lane = tid & 63;
+  if (wave != claim) return;
+  const int s0 = wave * seg, s1 = s0 + seg < V ? s0 + seg : V;
+  double acc = before;
+  int tok = -1, last_pos = -1;
+  for (int base = s0; base < s1; base += 64) {
+    const int v = base + lane;
+    const float f = v < s1 ? dist[v] : 0.f;
+    double incl = (double)f;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double y = __shfl_up(incl, o);
+      if (lane >= o) incl += y;
+    }
+    const unsigned long long heavy = __ballot(f > 0.f);
+    if (heavy) last_pos = base + 63 - __builtin_clzll(heavy);
+    const unsigned long long over = none ? 0ull : __ballot(acc + incl > target);
+    if (over) {
+      tok = base + __builtin_ctzll(over);
+      break;
+    }
+    acc += __shfl(incl, 63);
+  }
+  if (lane == 0) {
+    p.path_len[b] = len;
+    p.next_token[b] = tok >= 0 ? tok : last_pos;  // (rounding kept the running sum below the target: the segment's last)
   }
 }
 
@@ -165,6 +312,25 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
                      max_path, path, path_len, next_token);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
+
+int tva_accept_sampling(const tva_sample_args *a, void *stream) {
+  if (!a || a->B < 0 || a->V < 1 || a->max_path < 1) return TVA_INVALID_ARG;
+  if (a->B == 0) return TVA_OK;
+  if (!a->parent || !a->cu_T || !a->draft_token || !a->p_target || !a->q_draft || !a->u || !a->u_final || !a->residual ||
+      !a->path || !a->path_len || !a->next_token)
+    return TVA_INVALID_ARG;
+  SampleParams p;
+  p.parent = a->parent, p.cu_T = a->cu_T, p.token = a->draft_token;
+  p.p = a->p_target, p.q = a->q_draft, p.u = a->u, p.u_final = a->u_final;
+  p.residual = a->residual;
+  p.path = a->path, p.path_len = a->path_len, p.next_token = a->next_token, p.err_flag = a->err_flag;
+  p.V = a->V, p.max_path = a->max_path;
+  (void)hipGetLastError();  // the status below is this launch's
+  hipLaunchKernelGGL(sample_kernel, dim3(a->B), dim3(kSampleThreads), 0, (hipStream_t)stream, p);
+  return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+size_t tva_sizeof_sample_args(void) { return sizeof(tva_sample_args); }
 
 int tva_commit_path(const tva_commit_args *a, void *stream) {
   if (!a || a->B < 0 || a->Hkv < 1 || a->D < 8 || a->D % 8 || a->max_path < 1) return TVA_INVALID_ARG;

@@ -24,6 +24,13 @@ class CommitArgs(ctypes.Structure):
     ]
 
 
+class SampleArgs(ctypes.Structure):
+    """Mirror of `struct tva_sample_args`."""
+    _fields_ = [("B", ctypes.c_int32), ("V", ctypes.c_int32), ("max_path", ctypes.c_int32)] + \
+               [(n, ctypes.c_void_p) for n in ("parent", "cu_T", "draft_token", "p_target", "q_draft", "u", "u_final",
+                                               "residual", "path", "path_len", "next_token", "err_flag")]
+
+
 def _lib():
     global _ready
     lib = binding.load_library()
@@ -34,6 +41,11 @@ def _lib():
         lib.tva_commit_path.restype = ctypes.c_int
         lib.tva_commit_path.argtypes = [ctypes.POINTER(CommitArgs), vp]
         lib.tva_sizeof_commit_args.restype = ctypes.c_size_t
+        lib.tva_accept_sampling.restype = ctypes.c_int
+        lib.tva_accept_sampling.argtypes = [ctypes.POINTER(SampleArgs), vp]
+        lib.tva_sizeof_sample_args.restype = ctypes.c_size_t
+        if lib.tva_sizeof_sample_args() != ctypes.sizeof(SampleArgs):
+            raise RuntimeError("libtva.so is stale: rebuild it")
         if lib.tva_sizeof_commit_args() != ctypes.sizeof(CommitArgs):
             raise RuntimeError("libtva.so is stale: rebuild it")
         _ready = True
@@ -54,6 +66,27 @@ def accept_greedy(parent, cu_T, draft_token, target_token, max_path: int, path=N
         next_token = torch.empty(B, dtype=torch.int32, device=dev)
     _check(_lib().tva_accept_greedy(_p(parent), _p(cu_T), _p(draft_token), _p(target_token), B, int(max_path),
                                     _p(path), _p(path_len), _p(next_token), _stream_ptr(stream)))
+    return path, path_len, next_token
+
+
+def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, max_path: int, residual=None,
+                    err_flag=None, stream=None):
+    """Device tensors in (int32 trees and tokens, float32 distributions [sum_T, V] and uniform numbers); returns
+    (path [B, max_path], path_len [B], next_token [B])."""
+    import torch
+    B, V = cu_T.numel() - 1, int(p_target.shape[1])
+    dev = cu_T.device
+    path = torch.full((B, max_path), -1, dtype=torch.int32, device=dev)
+    path_len = torch.empty(B, dtype=torch.int32, device=dev)
+    next_token = torch.empty(B, dtype=torch.int32, device=dev)
+    if residual is None:
+        residual = torch.empty((max(B, 1), V), dtype=torch.float32, device=dev)
+    a = SampleArgs()
+    a.B, a.V, a.max_path = B, V, int(max_path)
+    a.parent, a.cu_T, a.draft_token = _p(parent), _p(cu_T), _p(draft_token)
+    a.p_target, a.q_draft, a.u, a.u_final = _p(p_target), _p(q_draft), _p(u), _p(u_final)
+    a.residual, a.path, a.path_len, a.next_token, a.err_flag = _p(residual), _p(path), _p(path_len), _p(next_token), _p(err_flag)
+    _check(_lib().tva_accept_sampling(ctypes.byref(a), _stream_ptr(stream)))
     return path, path_len, next_token
 
 

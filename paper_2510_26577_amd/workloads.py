@@ -173,6 +173,33 @@ def tree_star(T: int) -> np.ndarray:
     return p
 
 
+def sampling_inputs(rng: np.random.Generator, parent: np.ndarray, cu_T: np.ndarray, V: int, temperature: float = 1.0,
+                    drift: float = 1.0):
+    """Inputs of acceptance by speculative sampling for given trees: per node a target distribution and a draft
+    distribution over V tokens (softmax of normal logits divided by `temperature`; the draft's logits are the
+    target's plus normal noise of standard deviation `drift`, so the two are as close as a draft model's are),
+    the token of every non-root node drawn from its parent's draft distribution (siblings independently, as the
+    paper's EAGLE-style drafts are read here), and the uniform numbers.
+    Returns (p_target f32 [sum_T, V], q_draft f32 [sum_T, V], draft_token i32 [sum_T], u f32 [sum_T], u_final f32 [B])."""
+    sum_T, B = int(cu_T[-1]), len(cu_T) - 1
+    logit = rng.standard_normal((sum_T, V)) * 3.0
+    def softmax(z):
+        z = z / temperature
+        e = np.exp(z - z.max(axis=1, keepdims=True))
+        return (e / e.sum(axis=1, keepdims=True)).astype(np.float32)
+    p = softmax(logit)
+    q = softmax(logit + drift * rng.standard_normal((sum_T, V)))
+    tok = np.zeros(sum_T, np.int32)
+    for b in range(B):
+        t0, T = int(cu_T[b]), int(cu_T[b + 1] - cu_T[b])
+        for i in range(1, T):
+            row = q[t0 + int(parent[t0 + i])].astype(np.float64)
+            tok[t0 + i] = int(rng.choice(V, p=row / row.sum()))
+    u = rng.random(sum_T, dtype=np.float32)
+    u_final = rng.random(B, dtype=np.float32)
+    return p, q, tok, u, u_final
+
+
 # ----------------------------------------------------------------------------
 # workload container
 # ----------------------------------------------------------------------------

@@ -1,5 +1,5 @@
-"""GPU parity of greedy tree acceptance and the K/V commit (through the C ABI) against the CPU
-oracle on the same seeded inputs: integer and byte work, compared exactly."""
+"""GPU parity of tree acceptance (greedy, and by speculative sampling) and the K/V commit (through the C ABI)
+against the CPU oracle on the same seeded inputs: integer and byte work, compared exactly."""
 import numpy as np
 import pytest
 
@@ -455,3 +455,129 @@ def test_commit_of_an_8bit_cache(torch_dev, page_size):
         assert int(err.item()) == 0
         assert np.array_equal(k_d.cpu().numpy(), ek) and np.array_equal(v_d.cpu().numpy(), ev)
         assert np.array_equal(L_out.cpu().numpy(), L + plen)
+
+
+# ---- acceptance by speculative sampling ----
+
+def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True):
+    from paper_2510_26577_amd import verify
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda") if with_flag else None
+    path, n, nxt = verify.accept_sampling(d(parent, np.int32), d(cu_T, np.int32), d(tok, np.int32), d(p, np.float32),
+                                          d(q, np.float32), d(u, np.float32), d(uf, np.float32), max_path, err_flag=flag)
+    torch.cuda.synchronize()
+    return path.cpu().numpy(), n.cpu().numpy(), nxt.cpu().numpy(), (int(flag.item()) if with_flag else 0)
+
+
+def sampling_margin(parent, cu_T, tok, p, q, u, uf, paths, nxt):
+    """Smallest relative distance of any decision the oracle took from its threshold (both sides decide in fp64 on the
+    same fp32 data, but sum in different orders: a decision closer than that rounding to its threshold may differ)."""
+    # the cases below are seeded: the margin is asserted, so a case on a threshold would be seen, not hidden
+    worst = np.inf
+    for b, path in enumerate(paths):
+        t0, T = int(cu_T[b]), int(cu_T[b + 1] - cu_T[b])
+        if T == 0:
+            continue
+        for cur in path:
+            r = p[t0 + cur].astype(np.float64)
+            Z = r.sum()
+            qq = q[t0 + cur].astype(np.float64)
+            for c in range(cur + 1, T):
+                if parent[t0 + c] != cur:
+                    continue
+                x = int(tok[t0 + c])
+                if r[x] > 0:
+                    worst = min(worst, abs(float(u[t0 + c]) * qq[x] * Z - r[x]) / r[x])
+                if c in path:
+                    break
+                r = np.maximum(0.0, r - Z * qq).astype(np.float32).astype(np.float64)
+                Z = r.sum()
+    return worst
+
+
+@pytest.mark.parametrize("B,T_hi,V,temp,drift", [(1, 8, 1000, 1.0, 0.5), (4, 60, 32000, 1.0, 1.0), (33, 40, 4099, 0.7, 0.3),
+                                                 (3, 25, 128256, 0.5, 0.2), (64, 12, 517, 1.5, 2.0), (5, 1, 64, 1.0, 1.0),
+                                                 (2, 6, 7, 1.0, 1.0)])
+def test_accept_sampling_matches_oracle(torch_dev, B, T_hi, V, temp, drift):
+    """Paths, lengths and the drawn token equal the oracle's exactly on softmax-shaped distributions at vocabulary
+    sizes from 7 to Llama 3's 128256 (several segments per wave and a ragged tail), ragged trees with empty ones,
+    and path limits that cut the walk."""
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(1000 + B + T_hi + V))
+    T = rng.integers(0 if B > 4 else 1, T_hi + 1, B)
+    T[0] = T_hi
+    cu_T = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    parent = np.concatenate([wl.tree_expand_prune(rng, int(t)) if t > 4 else wl.tree_uniform(rng, int(t), 4) if t > 0
+                             else np.zeros(0, np.int32) for t in T]).astype(np.int32)
+    p, q, tok, u, uf = wl.sampling_inputs(rng, parent, cu_T, V, temperature=temp, drift=drift)
+    say(f"[case] accept_sampling B={B} T<={T_hi} V={V} temp={temp} drift={drift}")
+    longest = 0
+    for max_path in (int(T.max()) + 1, 3, 1):
+        ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf, max_path=max_path)
+        assert sampling_margin(parent, cu_T, tok, p, q, u, uf, ref_paths, ref_next) > 1e-9
+        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path)
+        assert flag == 0
+        assert list(n) == [len(x) for x in ref_paths]
+        assert list(nxt) == ref_next
+        for b, x in enumerate(ref_paths):
+            assert list(path[b, :len(x)]) == x
+        longest = max(longest, max(len(x) for x in ref_paths))
+    if T_hi >= 8 and drift <= 1.0:
+        assert longest >= 3                      # (the cases do accept drafted tokens)
+
+
+def test_accept_sampling_rejections_reach_the_residual(torch_dev):
+    """A star of children that the target gives no weight: every one is rejected, each rejection rewrites the residual,
+    and the last token comes from the residual after all of them; with q = p every child is accepted at once."""
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(77))
+    V, k, B = 3001, 9, 6
+    parent = np.tile(np.array([-1] + [0] * k, np.int32), B)
+    cu_T = (np.arange(B + 1) * (k + 1)).astype(np.int32)
+    p, q, tok, u, uf = wl.sampling_inputs(rng, parent, cu_T, V, drift=1.5)
+    for b in range(B):
+        t0 = b * (k + 1)
+        if b % 2 == 0:                           # no weight on the drafted tokens: all rejected
+            p[t0, tok[t0 + 1:t0 + k + 1]] = 0.0
+        else:                                    # q = p: the first child is accepted whatever u says
+            q[t0] = p[t0]
+            u[t0 + 1] = np.float32(0.999)
+    ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf)
+    assert [len(x) for x in ref_paths] == [1, 2] * (B // 2)
+    say(f"[case] accept_sampling star B={B} k={k} V={V}")
+    path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, k + 1)
+    assert flag == 0 and list(n) == [1, 2] * (B // 2) and list(nxt) == ref_next
+    for b in range(0, B, 2):
+        assert nxt[b] not in set(tok[b * (k + 1) + 1:(b + 1) * (k + 1)])
+    # without an error flag the call works the same
+    path2, n2, nxt2, _ = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, k + 1, with_flag=False)
+    assert np.array_equal(n, n2) and np.array_equal(nxt, nxt2) and np.array_equal(path, path2)
+
+
+def test_accept_sampling_flags_bad_input_and_leaves_other_sequences_alone(torch_dev):
+    """A drafted token outside the vocabulary is never accepted and sets the flag to 1 + its sequence; a residual that
+    vanishes (the draft distribution covers the target's whole weight and the drafted token is refused) sets it too and
+    ends that sequence with token -1; the other sequences' results are the oracle's."""
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(78))
+    V = 50
+    parent = np.array([-1, 0, 0, -1, 0, 1, -1, 0], np.int32)
+    cu_T = np.array([0, 3, 6, 8], np.int32)
+    p, q, tok, u, uf = wl.sampling_inputs(rng, parent, cu_T, V)
+    ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf)
+    # sequence 1: its first child's token is not a token
+    tok1 = tok.copy()
+    tok1[4] = V + 5
+    path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok1, p, q, u, uf, 4)
+    assert flag == 2
+    assert [int(nxt[0]), int(nxt[2])] == [ref_next[0], ref_next[2]] and [int(n[0]), int(n[2])] == [len(ref_paths[0]), len(ref_paths[2])]
+    assert n[1] == 1 and 0 <= nxt[1] < V         # nothing accepted below the root, the token drawn from the root's row
+    # sequence 2: q = 2 p at the root (no distribution) and u = 1.5 refuse the child, and the residual max(0, p - q) is empty
+    q2, u2 = q.copy(), u.copy()
+    q2[6] = 2.0 * p[6]
+    u2[7] = np.float32(1.5)
+    with pytest.raises(ValueError):
+        vo.accept_sampling(parent, cu_T, tok, p, q2, u2, uf)
+    path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q2, u2, uf, 4)
+    assert flag == 3 and nxt[2] == -1 and n[2] == 1
+    assert [int(nxt[0]), int(nxt[1])] == ref_next[:2]
