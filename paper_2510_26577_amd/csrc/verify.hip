@@ -73,25 +73,32 @@ struct SampleParams {
 };
 
 constexpr int kSampleThreads = 1024, kSampleWaves = kSampleThreads / 64;
+constexpr int kSampleTreeLds = 1024;  // nodes of a tree whose parent, token and uniform number are kept in LDS
 
 // One pass over a vocabulary-long row.  Wave w owns the contiguous segment [w * seg, (w + 1) * seg) and its lanes
-// take consecutive elements (coalesced); f(v) returns element v's weight (and may store it).  wsum[w] receives the
-// segment's sum; the return value, the same in every thread, is their sum taken in segment order.
-template <class F>
-__device__ __forceinline__ double segment_pass(int V, int seg, double *wsum, F f) {
+// take consecutive elements (coalesced; VEC = 4: consecutive groups of four, which needs seg % 4 == 0 and rows
+// aligned to 16 bytes).  load(v) fetches what element (group) v needs, use(v, t, x) handles it (it may store) and
+// adds its weight to x; U fetches are issued before the first is used.  wsum[w] receives the segment's sum; the
+// return value, the same in every thread, is their sum taken in segment order.
+template <int VEC, int U, class L, class C>
+__device__ __forceinline__ double segment_pass(int V, int seg, double *wsum, L load, C use) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int s0 = wave * seg, s1 = s0 + seg < V ? s0 + seg : V;
-  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-  int v = s0 + lane;
-  for (; v + 192 < s1; v += 256) {  // four loads in flight per lane
-    const double x0 = f(v), x1 = f(v + 64), x2 = f(v + 128), x3 = f(v + 192);
-    a0 += x0, a1 += x1, a2 += x2, a3 += x3;
+  constexpr int step = 64 * VEC;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int v = s0 + lane * VEC; v < s1; v += U * step) {
+    decltype(load(0)) t[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k)
+      if (v + k * step < s1) t[k] = load(v + k * step);
+#pragma unroll
+    for (int k = 0; k < U; ++k)
+      if (v + k * step < s1) use(v + k * step, t[k], acc[k & 3]);
   }
-  for (; v < s1; v += 64) a0 += f(v);
-  double x = (a0 + a1) + (a2 + a3);
+  double x = (acc[0] + acc[1]) + (acc[2] + acc[3]);
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-  __syncthreads();  // (wsum may still be read from the pass before; stores of f are visible after the next barrier)
+  __syncthreads();  // (wsum may still be read from the pass before; stores of use() are visible after the next barrier)
   if (lane == 0) wsum[wave] = x;
   __syncthreads();
   double z = 0.0;
@@ -99,16 +106,79 @@ __device__ __forceinline__ double segment_pass(int V, int seg, double *wsum, F f
   return z;
 }
 
+struct Float4Pair {
+  float4 a, c;
+};
+struct FloatPair {
+  float a, c;
+};
+
+// the two passes: the sum of a row, and the residual max(0, from - Z q) written to r (from may be r itself)
+template <int VEC>
+__device__ __forceinline__ double row_sum(int V, int seg, double *wsum, const float *row) {
+  if constexpr (VEC == 4) {
+    return segment_pass<4, 8>(
+        V, seg, wsum, [&](int v) { return *reinterpret_cast<const float4 *>(row + v); },  // (V % 4 == 0: no straddling)
+        [&](int, const float4 &t, double &x) { x += ((double)t.x + (double)t.y) + ((double)t.z + (double)t.w); });
+  } else {
+    return segment_pass<1, 8>(
+        V, seg, wsum, [&](int v) { return row[v]; }, [&](int, float t, double &x) { x += (double)t; });
+  }
+}
+
+template <int VEC>
+__device__ __forceinline__ double residual_pass(int V, int seg, double *wsum, const float *from, const float *q, double Z,
+                                                float *r) {
+  auto one = [&](float pv, float qv) {
+    const double d = (double)pv - Z * (double)qv;
+    return d > 0.0 ? (float)d : 0.f;
+  };
+  if constexpr (VEC == 4) {
+    return segment_pass<4, 4>(
+        V, seg, wsum,
+        [&](int v) {
+          return Float4Pair{*reinterpret_cast<const float4 *>(from + v), *reinterpret_cast<const float4 *>(q + v)};
+        },
+        [&](int v, const Float4Pair &t, double &x) {
+          float4 o;
+          o.x = one(t.a.x, t.c.x), o.y = one(t.a.y, t.c.y), o.z = one(t.a.z, t.c.z), o.w = one(t.a.w, t.c.w);
+          *reinterpret_cast<float4 *>(r + v) = o;
+          x += ((double)o.x + (double)o.y) + ((double)o.z + (double)o.w);
+        });
+  } else {
+    return segment_pass<1, 4>(
+        V, seg, wsum, [&](int v) { return FloatPair{from[v], q[v]}; },
+        [&](int v, const FloatPair &t, double &x) {
+          const float o = one(t.a, t.c);
+          r[v] = o;
+          x += (double)o;
+        });
+  }
+}
+
+template <int VEC>
 __global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SampleParams p) {
   __shared__ double wsum[kSampleWaves];
-  const int b = blockIdx.x, tid = threadIdx.x;
+  __shared__ int32_t s_parent[kSampleTreeLds], s_token[kSampleTreeLds];
+  __shared__ float s_u[kSampleTreeLds];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int t0 = p.cu_T[b];
   const int T = p.cu_T[b + 1] - t0;
   if (T <= 0) {
     if (tid == 0) p.path_len[b] = 0, p.next_token[b] = -1;
     return;
   }
-  const int V = p.V, seg = (V + kSampleWaves - 1) / kSampleWaves;
+  // the tree's words, read once (the walk is a chain of dependent reads of them); a tree too long for that is
+  // walked in global memory
+  const int32_t *parent = p.parent + t0, *token = p.token + t0;
+  const float *u = p.u + t0;
+  if (T <= kSampleTreeLds) {
+    for (int i = tid; i < T; i += kSampleThreads) s_parent[i] = parent[i], s_token[i] = token[i], s_u[i] = u[i];
+    parent = s_parent, token = s_token, u = s_u;
+    __syncthreads();
+  }
+  const int V = p.V;
+  const int seg = ((V + kSampleWaves - 1) / kSampleWaves + VEC - 1) / VEC * VEC;
   float *const r = p.residual + (size_t)b * V;
   int cur = 0, len = 1;
   if (tid == 0) p.path[(size_t)b * p.max_path] = 0;
@@ -117,45 +187,44 @@ __global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SamplePara
   while (true) {
     dist = p.p + (size_t)(t0 + cur) * V;
     const float *q = p.q + (size_t)(t0 + cur) * V;
-    Z = segment_pass(V, seg, wsum, [&](int v) { return (double)dist[v]; });
+    Z = row_sum<VEC>(V, seg, wsum, dist);
     bool accepted = false;
     if (len < p.max_path) {
-      for (int c = cur + 1; c < T; ++c) {
-        if (p.parent[t0 + c] != cur) continue;  // (the same word in every thread: the branch is uniform)
-        const int x = p.token[t0 + c];
-        if (x < 0 || x >= V) {  // not a token: flagged, never accepted, leaves the residual alone
-          if (tid == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
-          continue;
-        }
-        const double rx = (double)dist[x];
-        if (rx > 0.0 && (double)p.u[t0 + c] * (double)q[x] * Z <= rx) {
-          cur = c;
-          if (tid == 0) p.path[(size_t)b * p.max_path + len] = c;
-          ++len;
-          accepted = true;
-          break;
-        }
-        // rejected: the residual max(0, r - Z q), unnormalised, and its sum
-        __syncthreads();  // every thread has read dist[x] before the residual is overwritten in place
-        const float *from = dist;
-        const double Zq = Z;
-        const double Zn = segment_pass(V, seg, wsum, [&](int v) {
-          const double d = (double)from[v] - Zq * (double)q[v];
-          const float f = d > 0.0 ? (float)d : 0.f;
-          r[v] = f;
-          return (double)f;
-        });
-        if (!(Zn > 0.0)) {
-          // q was not a distribution the child could have been drawn from: flagged; the walk ends here
-          if (tid == 0) {
-            if (p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
-            p.path_len[b] = len;
-            p.next_token[b] = -1;
+      // the children of cur in index order, 64 candidates at a time (every wave finds the same ones)
+      for (int base = cur + 1; base < T && !accepted; base += 64) {
+        const int i = base + lane;
+        unsigned long long kids = __ballot(i < T && parent[i] == cur);
+        while (kids) {
+          const int c = base + __builtin_ctzll(kids);
+          kids &= kids - 1;
+          const int x = token[c];
+          if (x < 0 || x >= V) {  // not a token: flagged, never accepted, leaves the residual alone
+            if (tid == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+            continue;
           }
-          return;
+          const double rx = (double)dist[x];
+          if (rx > 0.0 && (double)u[c] * (double)q[x] * Z <= rx) {
+            cur = c;
+            if (tid == 0) p.path[(size_t)b * p.max_path + len] = c;
+            ++len;
+            accepted = true;
+            break;
+          }
+          // rejected: the residual max(0, r - Z q), unnormalised, and its sum
+          __syncthreads();  // every thread has read dist[x] before the residual is overwritten in place
+          const double Zn = residual_pass<VEC>(V, seg, wsum, dist, q, Z, r);
+          if (!(Zn > 0.0)) {
+            // q was not a distribution the child could have been drawn from: flagged; the walk ends here
+            if (tid == 0) {
+              if (p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+              p.path_len[b] = len;
+              p.next_token[b] = -1;
+            }
+            return;
+          }
+          Z = Zn;
+          dist = r;
         }
-        Z = Zn;
-        dist = r;
       }
     }
     if (!accepted) break;
@@ -176,7 +245,7 @@ __global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SamplePara
   }
   const bool none = claim < 0;  // (u_final was not below 1: the last token that has weight)
   if (none) claim = last_heavy;
-  const int wave = tid >> 6, lane = tid & 63;
+  const int wave = tid >> 6;
   if (wave != claim) return;
   const int s0 = wave * seg, s1 = s0 + seg < V ? s0 + seg : V;
   double acc = before;
@@ -326,7 +395,12 @@ int tva_accept_sampling(const tva_sample_args *a, void *stream) {
   p.path = a->path, p.path_len = a->path_len, p.next_token = a->next_token, p.err_flag = a->err_flag;
   p.V = a->V, p.max_path = a->max_path;
   (void)hipGetLastError();  // the status below is this launch's
-  hipLaunchKernelGGL(sample_kernel, dim3(a->B), dim3(kSampleThreads), 0, (hipStream_t)stream, p);
+  // groups of four need every row to start on 16 bytes
+  const bool vec = a->V % 4 == 0 && (((uintptr_t)a->p_target | (uintptr_t)a->q_draft | (uintptr_t)a->residual) & 15) == 0;
+  if (vec)
+    hipLaunchKernelGGL(sample_kernel<4>, dim3(a->B), dim3(kSampleThreads), 0, (hipStream_t)stream, p);
+  else
+    hipLaunchKernelGGL(sample_kernel<1>, dim3(a->B), dim3(kSampleThreads), 0, (hipStream_t)stream, p);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 

@@ -203,7 +203,87 @@ def _bench(argv=None) -> int:
         print(json.dumps({"shape": name, "accepted_nodes_per_step": accepted, "accept_us": times["accept"],
                           "commit_us": times["commit"], "both_us": times["both"], "commit_bytes": moved,
                           "commit_GBps": moved / (times["commit"] * 1e-6) / 1e9}), flush=True)
+    _bench_sampling(a.steps)
     return 0
+
+
+def _bench_sampling(steps: int) -> None:
+    """Times tva_accept_sampling on seeded synthetic steps made on the device (softmax of normal logits, the draft's
+    logits the target's plus noise, tokens drawn from the parent's draft row) and prints one JSON line per shape with
+    the vocabulary passes the walks took (counted on the host from the returned paths and the trees)."""
+    import json
+    import numpy as np
+    import torch
+    from . import workloads as wl
+
+    rng = np.random.Generator(np.random.PCG64(78))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(78)
+    stream = torch.cuda.Stream()
+    for name, B, T, V, depth in (("B=1 T=60 V=32000", 1, 60, 32000, 6), ("B=1 T=60 V=128256", 1, 60, 128256, 6),
+                                 ("B=8 T=32 V=128256", 8, 32, 128256, 6), ("B=64 T=8 V=128256", 64, 8, 128256, 8),
+                                 ("B=64 T=60 V=32000", 64, 60, 32000, 6)):
+        copies = 4
+        cases, sums, rejs = [], 0, 0
+        for c in range(copies):
+            trees = [wl.tree_expand_prune(rng, T, depth=depth) for _ in range(B)]
+            parent = np.concatenate(trees).astype(np.int32)
+            cu_T = (np.arange(B + 1) * T).astype(np.int32)
+            logit = torch.randn((B * T, V), generator=gen, device="cuda") * 3.0
+            p = torch.softmax(logit, dim=1)
+            q = torch.softmax(logit + 0.5 * torch.randn((B * T, V), generator=gen, device="cuda"), dim=1)
+            del logit
+            up = torch.from_numpy(np.concatenate([np.maximum(t, 0) + b * T for b, t in enumerate(trees)])).cuda()
+            tok = torch.multinomial(q[up], 1, generator=gen).reshape(-1).to(torch.int32)
+            d = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+            case = dict(parent=d(parent), cu_T=d(cu_T), tok=tok, p=p, q=q,
+                        u=torch.rand(B * T, generator=gen, device="cuda"), uf=torch.rand(B, generator=gen, device="cuda"),
+                        residual=torch.empty((B, V), dtype=torch.float32, device="cuda"),
+                        flag=torch.zeros(1, dtype=torch.int32, device="cuda"))
+            path, plen, _ = accept_sampling(case["parent"], case["cu_T"], tok, p, q, case["u"], case["uf"], depth + 1,
+                                            residual=case["residual"], err_flag=case["flag"])
+            torch.cuda.synchronize()
+            assert int(case["flag"].item()) == 0
+            path, plen = path.cpu().numpy(), plen.cpu().numpy()
+            for b in range(B):                      # one sum per accepted node; one residual per child refused under it
+                for j in range(int(plen[b])):
+                    sums += 1
+                    kids = np.nonzero(trees[b] == path[b, j])[0]
+                    if j + 1 < int(plen[b]):
+                        rejs += int((kids < path[b, j + 1]).sum())
+                    elif int(plen[b]) < depth + 1:
+                        rejs += len(kids)
+            cases.append(case)
+        sums, rejs = sums / copies, rejs / copies
+
+        def run():
+            for k in cases:
+                accept_sampling(k["parent"], k["cu_T"], k["tok"], k["p"], k["q"], k["u"], k["uf"], depth + 1,
+                                residual=k["residual"], err_flag=k["flag"], stream=stream)
+
+        with torch.cuda.stream(stream):
+            run()
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for _ in range(max(1, steps // copies)):
+                    run()
+            g.replay()
+            stream.synchronize()
+            best = 1e30
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                g.replay()
+                e1.record(stream)
+                e1.synchronize()
+                best = min(best, e0.elapsed_time(e1) * 1e3 / (max(1, steps // copies) * copies))
+        moved = 4.0 * V * (sums + 3 * rejs + B / 16.0)   # a sum reads a row; a residual reads two and writes one; the draw a segment
+        print(json.dumps({"shape": name, "accepted_nodes_per_step": sums, "refused_children_per_step": rejs,
+                          "sampling_us": best, "vocabulary_bytes": moved, "GBps": moved / (best * 1e-6) / 1e9,
+                          "GBps_per_workgroup": moved / (best * 1e-6) / 1e9 / B}), flush=True)
+        del cases
+        torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":

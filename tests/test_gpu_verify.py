@@ -459,12 +459,21 @@ def test_commit_of_an_8bit_cache(torch_dev, page_size):
 
 # ---- acceptance by speculative sampling ----
 
-def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True):
+def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True, misalign=False):
     from paper_2510_26577_amd import verify
     d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
     flag = torch.zeros(1, dtype=torch.int32, device="cuda") if with_flag else None
-    path, n, nxt = verify.accept_sampling(d(parent, np.int32), d(cu_T, np.int32), d(tok, np.int32), d(p, np.float32),
-                                          d(q, np.float32), d(u, np.float32), d(uf, np.float32), max_path, err_flag=flag)
+    dp, dq = d(p, np.float32), d(q, np.float32)
+    if misalign:                                 # the same rows, starting 4 bytes past a 16-byte boundary
+        shifted = []
+        for x in (dp, dq):
+            flat = torch.empty(x.numel() + 1, dtype=torch.float32, device="cuda")
+            flat[1:].copy_(x.reshape(-1))
+            shifted.append(flat[1:].view(x.shape))
+            assert shifted[-1].data_ptr() % 16 == 4
+        dp, dq = shifted
+    path, n, nxt = verify.accept_sampling(d(parent, np.int32), d(cu_T, np.int32), d(tok, np.int32), dp,
+                                          dq, d(u, np.float32), d(uf, np.float32), max_path, err_flag=flag)
     torch.cuda.synchronize()
     return path.cpu().numpy(), n.cpu().numpy(), nxt.cpu().numpy(), (int(flag.item()) if with_flag else 0)
 
@@ -497,11 +506,11 @@ def sampling_margin(parent, cu_T, tok, p, q, u, uf, paths, nxt):
 
 @pytest.mark.parametrize("B,T_hi,V,temp,drift", [(1, 8, 1000, 1.0, 0.5), (4, 60, 32000, 1.0, 1.0), (33, 40, 4099, 0.7, 0.3),
                                                  (3, 25, 128256, 0.5, 0.2), (64, 12, 517, 1.5, 2.0), (5, 1, 64, 1.0, 1.0),
-                                                 (2, 6, 7, 1.0, 1.0)])
+                                                 (2, 6, 7, 1.0, 1.0), (2, 1100, 64, 1.0, 0.3)])
 def test_accept_sampling_matches_oracle(torch_dev, B, T_hi, V, temp, drift):
     """Paths, lengths and the drawn token equal the oracle's exactly on softmax-shaped distributions at vocabulary
-    sizes from 7 to Llama 3's 128256 (several segments per wave and a ragged tail), ragged trees with empty ones,
-    and path limits that cut the walk."""
+    sizes from 7 to Llama 3's 128256 (several segments per wave and a ragged tail), ragged trees with empty ones
+    and one longer than the kernel keeps in LDS, and path limits that cut the walk."""
     torch = torch_dev
     rng = np.random.Generator(np.random.PCG64(1000 + B + T_hi + V))
     T = rng.integers(0 if B > 4 else 1, T_hi + 1, B)
@@ -522,6 +531,9 @@ def test_accept_sampling_matches_oracle(torch_dev, B, T_hi, V, temp, drift):
         for b, x in enumerate(ref_paths):
             assert list(path[b, :len(x)]) == x
         longest = max(longest, max(len(x) for x in ref_paths))
+        if max_path == 3 and V % 4 == 0:         # rows that do not start on 16 bytes take the one-element path
+            path2, n2, nxt2, flag2 = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, misalign=True)
+            assert flag2 == 0 and np.array_equal(n, n2) and np.array_equal(nxt, nxt2) and np.array_equal(path, path2)
     if T_hi >= 8 and drift <= 1.0:
         assert longest >= 3                      # (the cases do accept drafted tokens)
 
