@@ -34,7 +34,8 @@ int tva_ubench_lds(int32_t transpose_reads, int32_t waves_per_simd, int32_t work
                    float *sink, void *stream);
 
 /* Reads `bytes` of `src` once (16 bytes per lane, 8 loads in flight per lane) with `workgroups` workgroups
- * of 256 threads: into registers, or with to_lds straight into LDS.  Timed by the caller. */
+ * of 256 threads: into registers with the non-temporal hint (to_lds = 0), or straight into LDS without the
+ * hint (1) or with it (2, what the attention kernel's tile loads use).  Timed by the caller. */
 int tva_ubench_stream(int32_t to_lds, const void *src, size_t bytes, int32_t workgroups, float *sink, void *stream);
 
 /* Every one of `workgroups` workgroups of 256 threads reads the first `bytes` of `src` (a multiple of 32 KiB, small

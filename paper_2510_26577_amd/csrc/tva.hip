@@ -243,6 +243,10 @@ struct AttnCfg {
 constexpr int vm_cap(int n) { return n > 63 ? 63 : n; }  // the counter holds 6 bits; waiting for less is safe
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | (((n >> 4) & 3) << 14); }
 
+// Cache policy of the K/V tile loads and of the stores of partial results: the non-temporal hint (the `nt` bit
+// of the instruction).  A launch streams K and V through once and its partial rows are read next by another
+// kernel; without the hint both displace each other and the rest in the L2s (measured: 3 ... 10 % of the step).
+constexpr int kLoadOnce = 2;  // cache-policy operand of the LDS-writing loads: bit 1 = nt
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
@@ -504,8 +508,8 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
         const int64_t urow = cache_base + (int64_t)(base + row0_of(j)) * p.stride_tok;
         const char *ksrc = kc_bytes + urow * EB + lane_off2[j & 1];
         const char *vsrc = vc_bytes + urow * EB + lane_off2[j & 1];
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + kdst_of(j), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + vdst_of(j), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + kdst_of(j), 16, 0, kLoadOnce);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + vdst_of(j), 16, 0, kLoadOnce);
       }
     } else {
 #pragma unroll
@@ -544,8 +548,8 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
         ksrc = kc_bytes + off * EB;
         vsrc = vc_bytes + off * EB;
       }
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + kdst_of(j), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + vdst_of(j), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(ksrc), stage + kdst_of(j), 16, 0, kLoadOnce);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vsrc), stage + vdst_of(j), 16, 0, kLoadOnce);
     }
     }
   };
@@ -987,8 +991,12 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   constexpr int LPR = NDW * 8;      // lanes that cover one row piece with 16 bytes each
   constexpr int RPP = 64 / LPR;     // rows per wave-wide store
   float *tbuf = reinterpret_cast<float *>(smem + C::PATCH_OFF) + (PAIR ? wave : wm) * (32 * TP);
-  auto write_out = [&](auto d0_tag) __attribute__((always_inline)) {
+  auto write_out = [&](auto d0_tag, auto once_tag) __attribute__((always_inline)) {
     constexpr int d0 = decltype(d0_tag)::value;  // first d block of this wave's share
+    // partial rows (read next by the merge kernel, then dead) are stored with the non-temporal hint; final rows,
+    // which the caller's next kernel reads, are left to the caches.  Two copies of the loop: one store whose hint
+    // is chosen at run time would lose it.
+    constexpr bool ONCE = decltype(once_tag)::value;
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
       const float inv = l_tot[r] > 0.f ? p.v_scale / l_tot[r] : 0.f;
@@ -1009,14 +1017,22 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
         const int t = p.g_shift >= 0 ? (row >> p.g_shift) : row / p.G;
         const int64_t og = (int64_t)(tq0 + t) * p.Hq + kvh * p.G + (row - t * p.G);
         const f32x4 v = *reinterpret_cast<const f32x4 *>(tbuf + rl * TP + (lane % LPR) * 4);
-        if (row < R) *reinterpret_cast<f32x4 *>(obase + og * D + 32 * d0 + (lane % LPR) * 4) = v;
+        f32x4 *dst = reinterpret_cast<f32x4 *>(obase + og * D + 32 * d0 + (lane % LPR) * 4);
+        if (row < R) {
+          if constexpr (ONCE) __builtin_nontemporal_store(v, dst);
+          else *dst = v;
+        }
       }
       if (rvalid[r] && hh == 0 && wk == 0)
         lbase[orow[r]] = l_tot[r] > 0.f ? (m_run[r] + __builtin_amdgcn_logf(l_tot[r])) * kLn2 : -INFINITY;
     }
   };
-  if (PAIR && wk == 1) write_out(std::integral_constant<int, PAIR ? ND / 2 : 0>{});
-  else write_out(std::integral_constant<int, 0>{});
+  auto write_rows = [&](auto d0_tag) __attribute__((always_inline)) {
+    if (final_out) write_out(d0_tag, std::false_type{});
+    else write_out(d0_tag, std::true_type{});
+  };
+  if (PAIR && wk == 1) write_rows(std::integral_constant<int, PAIR ? ND / 2 : 0>{});
+  else write_rows(std::integral_constant<int, 0>{});
   TL_STAMP(5);  // key groups merged, result stores issued
   TL_STORE(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), 0, 6);
 }
@@ -1056,7 +1072,7 @@ __global__ void __launch_bounds__(256) merge_kernel(const float *__restrict__ pa
       const int s = s0 + i * GROUPS;
       const int sc = s < S ? s : s0;
       l[i] = part_lse[(size_t)sc * n_rows + row];
-      v[i] = *reinterpret_cast<const f32x4 *>(part_out + ((size_t)sc * n_rows + row) * D + col);
+      v[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(part_out + ((size_t)sc * n_rows + row) * D + col));
       if (s >= S) l[i] = -INFINITY;
     }
     float mb = m;

@@ -109,8 +109,9 @@ __global__ void __launch_bounds__(512) lds_kernel(int iters, uint64_t *out, floa
 }
 
 // streaming read: every workgroup walks its share of the buffer with 16-byte loads per lane; either into
-// registers, or directly into LDS (the way the attention kernel's tile loads work)
-template <bool TO_LDS>
+// registers (with the non-temporal hint), or directly into LDS (the way the attention kernel's tile loads work),
+// without (TO_LDS = 1) or with (TO_LDS = 2) that hint
+template <int TO_LDS>
 __global__ void __launch_bounds__(256) stream_kernel(const u32x4 *__restrict__ src, size_t n16, float *sink) {
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4 acc = {0, 0, 0, 0};
@@ -124,7 +125,8 @@ __global__ void __launch_bounds__(256) stream_kernel(const u32x4 *__restrict__ s
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + i + u * stride),
-                                         (__attribute__((address_space(3))) void *)(smem + (wave * 8 + u) * 1024), 16, 0, 0);
+                                         (__attribute__((address_space(3))) void *)(smem + (wave * 8 + u) * 1024), 16, 0,
+                                         TO_LDS == 2 ? 2 : 0);
       ++slot;
     }
     __builtin_amdgcn_s_waitcnt(0);
@@ -370,8 +372,9 @@ int tva_ubench_stream(int32_t to_lds, const void *src, size_t bytes, int32_t wor
   hipStream_t st = (hipStream_t)stream;
   const u32x4 *p = (const u32x4 *)src;
   const size_t n16 = bytes / 16;
-  if (to_lds) return launch_checked([&] { hipLaunchKernelGGL((stream_kernel<true>), dim3(workgroups), dim3(256), 32 * 1024, st, p, n16, sink); });
-  return launch_checked([&] { hipLaunchKernelGGL((stream_kernel<false>), dim3(workgroups), dim3(256), 0, st, p, n16, sink); });
+  if (to_lds == 2) return launch_checked([&] { hipLaunchKernelGGL((stream_kernel<2>), dim3(workgroups), dim3(256), 32 * 1024, st, p, n16, sink); });
+  if (to_lds) return launch_checked([&] { hipLaunchKernelGGL((stream_kernel<1>), dim3(workgroups), dim3(256), 32 * 1024, st, p, n16, sink); });
+  return launch_checked([&] { hipLaunchKernelGGL((stream_kernel<0>), dim3(workgroups), dim3(256), 0, st, p, n16, sink); });
 }
 
 int tva_ubench_valu_attn(const tva_ubench_attn_args *a, void *stream) {

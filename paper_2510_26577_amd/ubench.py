@@ -101,7 +101,7 @@ def run_all(n_cu: int = 256):
     buf = torch.empty(nbytes // 4, dtype=torch.int32, device=dev)
     buf.random_(0, 1 << 20)
     stream = {}
-    for to_lds in (0, 1):
+    for to_lds in (0, 1, 2):
         for wgs in (n_cu * 4, n_cu * 8, n_cu * 16):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             best = 1e30
@@ -112,7 +112,8 @@ def run_all(n_cu: int = 256):
                 e1.record(st)
                 torch.cuda.synchronize()
                 best = min(best, e0.elapsed_time(e1))
-            stream[f"{'global_load_lds' if to_lds else 'global_load'} workgroups={wgs}"] = {"GB_per_s": nbytes / best / 1e6}
+            name = ("global_load nt", "global_load_lds", "global_load_lds nt")[to_lds]
+            stream[f"{name} workgroups={wgs}"] = {"GB_per_s": nbytes / best / 1e6}
     res["stream_read_1GiB"] = stream
     del buf
 
