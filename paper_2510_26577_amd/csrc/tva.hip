@@ -1185,11 +1185,11 @@ bool make_plan(const tva_args *a, Plan *pl) {
     // trees of 1 .. 72 nodes on the benchmark head shape:
     //   (tiles of the longest split, the tree's own tiles counted with the last one) x time per tile
     //      x 1 while every workgroup has a CU to itself (256), x 1.5 while two share one (512),
-    //   + with splits: a merge pass (second launch, 3.5 us) and the partial rows written and read back
-    //     (0.19 us per MB).
+    //   + with splits: a merge pass (second launch, 3.0 us) and the partial rows written and read back
+    //     (0.30 us per MB).
     // Splits keep two tiles or more and together stay within 512 workgroups.
     const int tiles = max_by_len, tree_tiles = (a->max_T + pl->TK - 1) / pl->TK;
-    const double tile_us = 1.18 * a->D / 128.0;
+    const double tile_us = 1.30 * a->D / 128.0;
     const double part_mb = 2.0 * query_rows(a) * a->Hq * (a->D + 1) * sizeof(float) * 1e-6;
     double best = 0.0;
     S = 1;
@@ -1204,7 +1204,7 @@ bool make_plan(const tva_args *a, Plan *pl) {
       const int longest = nch > 1 && ckt > last ? ckt : last;
       const double share = wgs <= 256 ? 1.0 : 1.5 * (double)((wgs + 511) / 512);
       double cost = tile_us * longest * share;
-      if (nch > 1) cost += 3.5 + 0.19 * part_mb * nch;
+      if (nch > 1) cost += 3.0 + 0.30 * part_mb * nch;
       if (s == 1 || cost < best - 1e-9) best = cost, S = nch;
     }
   } else if (S == 0) {

@@ -95,7 +95,7 @@ def test_plan_and_workspace(lib):
 @pytest.mark.parametrize("B,L,T,rows,splits", [
     (1, 2048, 60, 64, 7),      # the headline shape: 32 natural workgroups of 64 rows; 7 splits of 5 tiles (224 workgroups:
                                # the tree's tile rides on the short last split) beat 8 of 4, whose last one has 5 as well
-    (4, 2048, 60, 64, 4),      # 128 natural: two per CU (512) with splits of 8 tiles beat one per CU with 16
+    (4, 2048, 60, 64, 2),      # 128 natural: one per CU (256) with splits of 16 tiles; 512 with 8 measures the same, with twice the partial rows
     (4, 4096, 60, 64, 4),
     (3, 2048, 60, 64, 5),      # 96 natural: on to 480
     (5, 2048, 60, 64, 3),      # 160 natural: 480
@@ -107,9 +107,9 @@ def test_plan_and_workspace(lib):
     (32, 2048, 60, 256, 1),
     (4, 8192, 60, 256, 8),     # few sequences, many keys
     (8, 4096, 32, 256, 4),     # exactly 128 rows
-    (16, 2048, 16, 64, 4),     # 64 rows: never the large shapes
+    (16, 2048, 16, 64, 2),     # 64 rows: never the large shapes; 128 natural -> 256 (measured: 4 splits 12 % slower)
     (64, 2048, 8, 32, 1),      # 32 rows
-    (2, 300, 8, 32, 1),        # five tiles: no split saves what its merge pass costs
+    (2, 300, 8, 32, 2),        # five tiles: two splits of three (the tree's with the last) against six in a row
     (8, 512, 24, 64, 1),       # 128 workgroups, eight tiles: two splits would save four, a merge pass costs more
     (8, 768, 24, 64, 2),       # ... twelve tiles: two splits save six
     (1, 512, 8, 32, 3),        # eight tiles in splits of 3, 3, 2 + the tree's own
