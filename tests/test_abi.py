@@ -109,10 +109,11 @@ def test_plan_and_workspace(lib):
     (8, 4096, 32, 256, 4),     # exactly 128 rows
     (16, 2048, 16, 64, 2),     # 64 rows: never the large shapes; 128 natural -> 256 (measured: 4 splits 12 % slower)
     (64, 2048, 8, 32, 1),      # 32 rows
-    (2, 300, 8, 32, 2),        # five tiles: two splits of three (the tree's with the last) against six in a row
+    (2, 300, 8, 32, 3),        # five tiles: splits of 2, 2, 1 + the tree's own against six in a row
     (8, 512, 24, 64, 1),       # 128 workgroups, eight tiles: two splits would save four, a merge pass costs more
     (8, 768, 24, 64, 2),       # ... twelve tiles: two splits save six
-    (1, 512, 8, 32, 3),        # eight tiles in splits of 3, 3, 2 + the tree's own
+    (1, 512, 8, 32, 8),        # eight tiles, eight natural workgroups: one tile per split (64 workgroups)
+    (4, 512, 1, 32, 3),        # ... 32 natural: splits of one tile would take 256, so 3, 3, 2 + the tree's own
     (32, 2048, 9, 64, 1),      # 256 natural workgroups of 64 rows: every CU has one already, a split only adds the merge
     (16, 2048, 20, 64, 1),     # ... the same with two row blocks at batch 16
     (16, 2048, 9, 64, 4),      # 128 natural: split
@@ -128,8 +129,8 @@ def test_launch_plan_bands(lib, B, L, T, rows, splits):
 def test_launch_plan_properties_over_the_cost_table_grid(lib):
     """The grid the attention cost tables are measured on (paper, Method: f(B, c, n) for c = k L, n = 1..N;
     here B = 1, 2, 4 and 8, c = 256..2048, n = 1..72, benchmark head shape).  Whatever the split count the
-    planner settles on, a split keeps two tiles or more, splits of the small shapes stay within two workgroups
-    per CU, the longest split (the tree's own tiles ride on the last one) is no longer than an unsplit pass
+    planner settles on, a split keeps two tiles or more (one tile in launches of at most 128 workgroups), splits of
+    the small shapes stay within two workgroups per CU, the longest split (the tree's own tiles ride on the last one) is no longer than an unsplit pass
     would be minus what a merge pass costs, and the rows per workgroup never shrink as the tree grows."""
     for B in (1, 2, 4, 8):
         for c in range(256, 2049, 256):
@@ -142,9 +143,10 @@ def test_launch_plan_properties_over_the_cost_table_grid(lib):
                 if S == 1:
                     continue
                 tiles, tree_tiles = -(-c // 64), -(-n // 64)
-                assert ck >= 128 and S == -(-c // ck), (B, c, n, S, ck)
+                wgs = B * 8 * -(-4 * n // rows) * S
+                assert (ck >= 128 or (ck == 64 and wgs <= 128)) and S == -(-c // ck), (B, c, n, S, ck)
                 if rows <= 64:
-                    assert B * 8 * -(-4 * n // rows) * S <= 512, (B, c, n, S)
+                    assert wgs <= 512, (B, c, n, S)
                 longest = max(ck // 64, tiles - (S - 1) * (ck // 64) + tree_tiles)
                 assert tiles + tree_tiles - longest >= 3, (B, c, n, S, ck)
 
