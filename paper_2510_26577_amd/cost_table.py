@@ -9,7 +9,7 @@ is outside this repository; a deployment adds its own measurements of those to t
 
 Timing: per grid point, R copies of the inputs, their attention calls captured into one HIP graph,
 the graph replayed a few times with the caches flushed before each replay (every call reads its K/V
-from HBM, as a layer of a real verification pass does); the cost is the best replay divided by R,
+from HBM, as a layer of a real verification pass does); the cost is the median replay divided by R,
 in microseconds.
 
     python -m paper_2510_26577_amd.cost_table --B 4 --L 256 --M 8 --N 72 --out table.txt
@@ -29,7 +29,7 @@ from . import binding, device, workloads
 
 
 def measure(B: int, L: int, M: int, N: int, Hq: int = 32, Hkv: int = 8, D: int = 128, copies: int = 8,
-            replays: int = 5, n_values=None, seed: int = 2510, log=None) -> np.ndarray:
+            replays: int = 7, n_values=None, seed: int = 2510, log=None) -> np.ndarray:
     """Returns a float64 [M, N] table of microseconds per attention call; entries for n not in
     n_values (default: all of 1..N) are filled by linear interpolation between measured ones."""
     import torch
@@ -82,7 +82,7 @@ def measure(B: int, L: int, M: int, N: int, Hq: int = 32, Hkv: int = 8, D: int =
                 for _ in range(3):                         # untimed: clocks and code caches settle
                     g.replay()
                 stream.synchronize()
-                best = float("inf")
+                times = []
                 for _ in range(replays):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     flush.fill_(1)
@@ -90,8 +90,10 @@ def measure(B: int, L: int, M: int, N: int, Hq: int = 32, Hkv: int = 8, D: int =
                     g.replay()
                     e1.record(stream)
                     e1.synchronize()
-                    best = min(best, e0.elapsed_time(e1) * 1e3 / len(cases))
-            table[r - 1, n - 1] = best
+                    times.append(e0.elapsed_time(e1) * 1e3 / len(cases))
+            # the median: where the same launch runs at two speeds from replay to replay (which CUs the workgroups of
+            # a launch smaller than the chip land on), the fastest of a few replays is the less repeatable figure
+            table[r - 1, n - 1] = float(np.median(times))
         have = np.array(n_values) - 1
         table[r - 1] = np.interp(np.arange(N), have, table[r - 1, have])
         if log:
@@ -140,15 +142,16 @@ def main(argv=None) -> int:
     ap.add_argument("--M", type=int, default=8, help="context grid rows")
     ap.add_argument("--N", type=int, default=72, help="largest number of tree tokens")
     ap.add_argument("--stride", type=int, default=1, help="measure every stride-th n, interpolate between")
+    ap.add_argument("--replays", type=int, default=7, help="timed graph replays per grid point (the median is kept)")
     ap.add_argument("--out", required=True)
     a = ap.parse_args(argv)
     t0 = time.time()
     n_values = list(range(1, a.N + 1, a.stride))
-    table = measure(a.B, a.L, a.M, a.N, n_values=n_values, log=lambda s: print(s, flush=True))
+    table = measure(a.B, a.L, a.M, a.N, replays=a.replays, n_values=n_values, log=lambda s: print(s, flush=True))
     cmd = "python -m paper_2510_26577_amd.cost_table " + " ".join(sys.argv[1:] if argv is None else argv)
     write_table(a.out, table, a.B, a.L, header_lines=[
         "attention slice of the target cost table S_T(B): tva_tree_verify_attn (split-KV attention + merge), MI355X",
-        "head shape Hq=32 Hkv=8 D=128, bf16, dense cache; best of 5 HIP-graph replays over 8 input copies, caches flushed before each",
+        f"head shape Hq=32 Hkv=8 D=128, bf16, dense cache; median of {a.replays} HIP-graph replays over 8 input copies, caches flushed before each",
         "command: " + cmd])
     print(f"wrote {a.out} in {time.time() - t0:.0f} s", flush=True)
     return 0

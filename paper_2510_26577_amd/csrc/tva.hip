@@ -1187,8 +1187,8 @@ bool make_plan(const tva_args *a, Plan *pl) {
     //      x 1 while every workgroup has a CU to itself (256), x 1.5 while two share one (512),
     //   + with splits: a merge pass (second launch, 3.0 us) and the partial rows written and read back
     //     (0.30 us per MB).
-    // Splits keep two tiles or more (one, in launches of at most 128 workgroups) and together stay within 512
-    // workgroups.
+    // Splits keep two tiles or more (one, in launches of at most 128 workgroups over six tiles or more) and
+    // together stay within 512 workgroups.
     const int tiles = max_by_len, tree_tiles = (a->max_T + pl->TK - 1) / pl->TK;
     const double tile_us = 1.30 * a->D / 128.0;
     const double part_mb = 2.0 * query_rows(a) * a->Hq * (a->D + 1) * sizeof(float) * 1e-6;
@@ -1198,7 +1198,9 @@ bool make_plan(const tva_args *a, Plan *pl) {
       const int ckt = (tiles + s - 1) / s, nch = (tiles + ckt - 1) / ckt;
       if (nch != s) continue;  // the same split length as a smaller count
       const int64_t wgs = (int64_t)natural * nch;
-      if (ckt < 2 && wgs > 128) break;  // splits of one tile only while half the CUs would stay empty otherwise
+      // splits of one tile only while half the CUs would stay empty otherwise, and not on four or five tiles
+      // (measured at 256 keys: the unsplit pass is as fast as four one-tile splits and needs no merge)
+      if (ckt < 2 && (wgs > 128 || tiles < 6)) break;
       // (no split once the unsplit launch already has a workgroup for every CU: measured at B = 16 and 32,
       // splitting then only adds the merge)
       if (nch > 1 && (wgs > 512 || natural >= 256)) break;
