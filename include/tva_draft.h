@@ -1,0 +1,83 @@
+/*
+ * libtva -- the device side of draft-tree construction: one layer of expansion (the K most probable next
+ * tokens of every selected node, the candidates' scores, the candidates in descending order of score), and the
+ * cut of a grown tree to its best-scoring nodes.  How many nodes a layer or the final tree keeps is decided by
+ * the host logic of tva_cast.h from the sorted scores these calls return.  Same conventions as tva.h: device
+ * pointers owned by the caller, work queued on `stream` (hipStream_t as void*), nothing allocated, negative
+ * tva_status on rejected arguments (then nothing is queued).
+ */
+#ifndef TVA_DRAFT_H
+#define TVA_DRAFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TVA_EXPAND_MAX_K 16           /* children per node */
+#define TVA_EXPAND_MAX_CANDIDATES 1024 /* max_N * K: the candidates of one sequence are sorted in LDS */
+#define TVA_SUBTREE_MAX_NODES 2048    /* nodes of one grown tree */
+
+/*
+ * One layer of draft-tree expansion (paper, "Tree Expansion Phase": a node's value is the product of the draft
+ * model's probabilities along its path, the root 1; every selected node is given K children, taken here as its K
+ * most probable next tokens; "Dynamic Expansion Stage", Eq. 1: the method looks at the candidates' values in
+ * descending order).  Values are carried as scores = log value.
+ *
+ * Sequence b owns rows cu_N[b] .. cu_N[b+1]-1 (its selected nodes).  For every row r the K largest entries of
+ * logp[r, :] are found (among equal ones the lower token first); child j of row r has the score
+ * score[r] + logp[r, token] (one float32 addition).  The n_b * K candidates of a sequence are returned in
+ * descending order of score (equal scores: earlier row, then lower rank under it, first) at positions
+ * cu_N[b] * K ... of the three output arrays.  Exact: no arithmetic but that one addition.  NaNs must not occur;
+ * -inf is an ordinary (smallest) value; -0.0 counts as 0.0.
+ *   B, V, K          sequences; vocabulary size (K <= V); children per row, 1 <= K <= TVA_EXPAND_MAX_K
+ *   sum_N, max_N     cu_N[B], and the largest n_b (max_N * K <= TVA_EXPAND_MAX_CANDIDATES); host copies
+ *   cu_N             device int32 [B+1]
+ *   score            device fp32 [sum_N]
+ *   logp, ld_logp    device fp32, row r at logp + r * ld_logp (elements; ld_logp >= V)
+ *   cand_score       device fp32  [sum_N * K]
+ *   cand_parent      device int32 [sum_N * K]  row within the sequence (0 .. n_b-1)
+ *   cand_token       device int32 [sum_N * K]
+ *   workspace        device, tva_expand_workspace_bytes(args) bytes (the best K of every 8192-token piece of
+ *                    every row), 8-byte aligned; contents on return unspecified
+ * The workspace query reads only B, V, K, sum_N and returns (size_t)-1 for shapes the launch would reject.
+ */
+typedef struct tva_expand_args {
+  int32_t B, V, K, sum_N, max_N;
+  const int32_t *cu_N;
+  const float *score, *logp;
+  int64_t ld_logp;
+  float *cand_score;
+  int32_t *cand_parent, *cand_token;
+  void *workspace;
+  size_t workspace_bytes;
+} tva_expand_args;
+
+size_t tva_expand_workspace_bytes(const tva_expand_args *shapes);
+int tva_expand_layer(const tva_expand_args *a, void *stream);
+size_t tva_sizeof_expand_args(void);
+
+/*
+ * The cut of a grown tree to its best nodes (paper, "Tree Reranking Phase": the m nodes of highest value are
+ * kept; since a node's value never exceeds its parent's they form a subtree).  Sequence b's tree has the nodes
+ * cu_M[b] .. cu_M[b+1]-1 (parent[i] < i local, -1 = root) and keeps cu_T[b+1] - cu_T[b] of them: the best by
+ * score, among equal scores the lower index first.  The kept nodes are renumbered in ascending old index
+ * (which keeps parents before children) and written to positions cu_T[b] ...:
+ *   old_index   device int32 [cu_T[B]]  local index the kept node had
+ *   new_parent  device int32 [cu_T[B]]  its parent in the new numbering (-1 = root): the `parent` array
+ *               tva_tree_verify_attn takes
+ *   err_flag    device int32[1] or NULL, zero on entry: stores 1 + b when a kept node's parent is not kept (a
+ *               child scored above its parent: not a tree this method grows), or a sequence is asked to keep
+ *               more nodes than it has; that sequence's outputs are then unspecified
+ * One tree has at most TVA_SUBTREE_MAX_NODES nodes (max_M, a host copy of the largest tree's size, is checked).
+ */
+int tva_tree_select_subtree(const float *score, const int32_t *parent, const int32_t *cu_M, const int32_t *cu_T,
+                            int32_t B, int32_t max_M, int32_t *old_index, int32_t *new_parent, int32_t *err_flag,
+                            void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -19,6 +19,7 @@ TIMELINE_LIB_PATH = os.path.join(_HERE, "libtva_timeline.so")  # the same source
 SRC_PATH = os.path.join(_HERE, "csrc", "tva.hip")
 CAST_SRC_PATH = os.path.join(_HERE, "csrc", "cast.cpp")  # host part: tree-size selection
 VERIFY_SRC_PATH = os.path.join(_HERE, "csrc", "verify.hip")  # acceptance + commit kernels
+DRAFT_SRC_PATH = os.path.join(_HERE, "csrc", "draft.hip")    # draft-tree expansion + subtree kernels
 INCLUDE_DIR = os.path.join(_ROOT, "include")
 
 TVA_OK = 0
@@ -40,7 +41,7 @@ def build_library(verbose: bool = False, timeline: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     out = TIMELINE_LIB_PATH if timeline else LIB_PATH
     cmd = [hipcc, *HIPCC_FLAGS, *(["-DTVA_TIMELINE"] if timeline else []), "-I", INCLUDE_DIR, "-shared", "-fPIC", "-o", out,
-           SRC_PATH, VERIFY_SRC_PATH, CAST_SRC_PATH]
+           SRC_PATH, VERIFY_SRC_PATH, DRAFT_SRC_PATH, CAST_SRC_PATH]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     lines = [l for l in res.stdout.splitlines() if "is not a recognized feature" not in l]
     if verbose or res.returncode:
@@ -77,6 +78,7 @@ class TvaArgs(ctypes.Structure):
 EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys", "tva_plan_workgroup_rows",
            "tva_tree_verify_attn", "tva_tree_verify_attn_static", "tva_static_scratch_bytes", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args", "tva_timeline_read")
 # entry points of include/tva_verify.h (bound in verify.py)
+DRAFT_EXPORTS = ("tva_expand_workspace_bytes", "tva_expand_layer", "tva_sizeof_expand_args", "tva_tree_select_subtree")
 VERIFY_EXPORTS = ("tva_accept_greedy", "tva_accept_sampling", "tva_sizeof_sample_args", "tva_commit_path", "tva_sizeof_commit_args")
 # host entry points of include/tva_cast.h (bound in cast.py)
 CAST_EXPORTS = ("tva_cast_select_context", "tva_cast_select_max_valid_index", "tva_cast_layer_utility",

@@ -1,0 +1,315 @@
+// libtva, device side of draft-tree construction (gfx950): one layer of expansion and the cut of a grown tree to
+// its best nodes.  Definitions and argument layout: include/tva_draft.h (paper, "Tree Expansion Phase", "Tree
+// Reranking Phase", "Dynamic Expansion Stage").
+//
+// Kernels:
+//   topk_parts_kernel   the HBM-bound part: every row of log-probabilities is cut into pieces of 8192 tokens, one
+//                       workgroup of 256 threads per piece holds its 32 tokens per thread in registers (one
+//                       coalesced read, nothing read twice) and finds the piece's best K.  Selection without a
+//                       sort of the piece: the K-th largest of the 256 thread maxima is a bound that at least K
+//                       tokens reach, and almost only the best K do; the few that reach it are gathered in LDS and
+//                       sorted by one wave (a bitonic network over the lanes).
+//   expand_finish_kernel  one workgroup per sequence: a wave per row merges the pieces' results into the row's best
+//                       K, adds the row's score, and the workgroup sorts the sequence's candidates in LDS.
+//   subtree_kernel      one workgroup per tree: rank of every node by (score, index), keep the best, renumber.
+// Everything is compared through one 64-bit key per element: the float mapped to an unsigned integer of the same
+// order in the high word, the complement of the index in the low word -- larger key = better, and no two keys of
+// one comparison are equal, so every selection below has exactly one answer.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tva.h"
+#include "tva_draft.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPieceThreads = 256, kPerThread = 32, kPiece = kPieceThreads * kPerThread;  // 8192 tokens
+constexpr int kMaxK = TVA_EXPAND_MAX_K;
+constexpr int kMergePerLane = 8;  // a row's pieces x K candidates are merged by one wave: at most 512
+
+// float -> unsigned of the same order (-0.0 first made +0.0, so the two compare equal as numbers do)
+__device__ __forceinline__ uint32_t ordered(float x) {
+  const uint32_t u = __float_as_uint(x + 0.0f);
+  return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float unordered(uint32_t o) {
+  return __uint_as_float(o ^ ((o >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+}
+__device__ __forceinline__ uint64_t make_key(float x, uint32_t index) { return ((uint64_t)ordered(x) << 32) | (uint32_t)~index; }
+__device__ __forceinline__ uint64_t max64(uint64_t a, uint64_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint64_t min64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+__device__ __forceinline__ uint64_t shfl_xor64(uint64_t v, int mask) {
+  const uint32_t lo = __shfl_xor((uint32_t)v, mask), hi = __shfl_xor((uint32_t)(v >> 32), mask);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// Bitonic sort of one key per lane over the 64 lanes of a wave, descending: lane 0 ends with the largest.
+__device__ __forceinline__ uint64_t wave_sort_desc(uint64_t key) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      const uint64_t other = shfl_xor64(key, j);
+      const bool keep_max = ((lane & j) == 0) == ((lane & k) == 0);
+      key = keep_max ? max64(key, other) : min64(key, other);
+    }
+  }
+  return key;
+}
+__device__ __forceinline__ uint64_t wave_max(uint64_t key) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) key = max64(key, shfl_xor64(key, o));
+  return key;
+}
+
+// ---- the best K of every piece of every row ----
+// grid (pieces, rows).  part[(row * pieces + piece) * K + j] = key of the piece's j-th best token (0 = none: the
+// piece has fewer than K tokens).
+template <bool VEC4>
+__global__ void __launch_bounds__(kPieceThreads) topk_parts_kernel(const float *__restrict__ logp, int64_t ld, int V, int K,
+                                                                  uint64_t *__restrict__ part) {
+  __shared__ uint64_t s_top[4 * kMaxK];
+  __shared__ uint64_t s_list[64];
+  __shared__ uint64_t s_bound, s_wave[4];
+  __shared__ int s_count;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int piece = blockIdx.x, row = blockIdx.y;
+  const float *src = logp + (size_t)row * ld;
+  const int base = piece * kPiece;
+  uint64_t key[kPerThread];
+  if constexpr (VEC4) {
+    // 16 bytes per lane and load: thread t holds tokens base + 1024 i + 4 t + e
+#pragma unroll
+    for (int i = 0; i < kPerThread / 4; ++i) {
+      const int v = base + i * (4 * kPieceThreads) + 4 * tid;
+      f32x4 x = {0.f, 0.f, 0.f, 0.f};
+      if (v < V) x = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + v));  // (V % 4 == 0: no straddling)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) key[4 * i + e] = v < V ? make_key(x[e], (uint32_t)(v + e)) : 0ull;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const int v = base + i * kPieceThreads + tid;
+      key[i] = v < V ? make_key(__builtin_nontemporal_load(src + v), (uint32_t)v) : 0ull;
+    }
+  }
+  uint64_t mine = 0;
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) mine = max64(mine, key[i]);
+  if (tid == 0) s_count = 0;
+  // the K-th largest of the 256 thread maxima: each wave sorts its 64, the first wave sorts the waves' best K
+  const uint64_t sorted = wave_sort_desc(mine);
+  if (lane < kMaxK) s_top[wave * kMaxK + lane] = lane < K ? sorted : 0ull;
+  __syncthreads();
+  if (wave == 0) {
+    const uint64_t all = wave_sort_desc(s_top[lane]);
+    if (lane == K - 1) s_bound = all;
+  }
+  __syncthreads();
+  // at least K tokens reach the bound (K threads' maxima do); gather them
+  const uint64_t bound = s_bound;
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    if (key[i] >= bound && key[i] != 0ull) {
+      const int pos = atomicAdd(&s_count, 1);
+      if (pos < 64) s_list[pos] = key[i];
+    }
+  }
+  __syncthreads();
+  const int count = s_count;
+  uint64_t *dst = part + ((size_t)row * gridDim.x + piece) * K;
+  if (count <= 64) {
+    if (wave == 0) {
+      const uint64_t best = wave_sort_desc(lane < count ? s_list[lane] : 0ull);
+      if (lane < K) dst[lane] = best;
+    }
+    return;
+  }
+  // more than 64 tokens reach the bound (a few threads hold most of the piece's large values, as in a row that
+  // falls or rises steadily with the token index): K rounds of a search for the maximum over what the threads hold
+  for (int j = 0; j < K; ++j) {
+    uint64_t best = 0;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) best = max64(best, key[i]);
+    best = wave_max(best);
+    if (lane == 0) s_wave[wave] = best;
+    __syncthreads();
+    const uint64_t top = max64(max64(s_wave[0], s_wave[1]), max64(s_wave[2], s_wave[3]));
+    if (tid == 0) dst[j] = top;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i)
+      if (key[i] == top) key[i] = 0ull;  // (keys are unique; 0 = nothing left)
+    __syncthreads();
+  }
+}
+
+// ---- per sequence: the rows' best K out of their pieces, the candidates' scores, the candidates sorted ----
+__global__ void __launch_bounds__(256) expand_finish_kernel(const uint64_t *__restrict__ part, int pieces, int K,
+                                                            const int32_t *__restrict__ cu_N, const float *__restrict__ score,
+                                                            float *__restrict__ cand_score, int32_t *__restrict__ cand_parent,
+                                                            int32_t *__restrict__ cand_token) {
+  __shared__ uint64_t s_key[TVA_EXPAND_MAX_CANDIDATES];
+  __shared__ int32_t s_tok[TVA_EXPAND_MAX_CANDIDATES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x;
+  const int r0 = cu_N[b], n = cu_N[b + 1] - r0;
+  if (n <= 0 || n * K > TVA_EXPAND_MAX_CANDIDATES) return;  // (more rows than the caller's max_N said: nothing written)
+  const int total = n * K;
+  int padded = 1;
+  while (padded < total) padded <<= 1;
+  for (int i = total + tid; i < padded; i += 256) s_key[i] = 0ull;
+  const int per_row = pieces * K;
+  for (int r = wave; r < n; r += 4) {
+    const uint64_t *src = part + (size_t)(r0 + r) * per_row;
+    uint64_t mine[kMergePerLane];
+#pragma unroll
+    for (int i = 0; i < kMergePerLane; ++i) mine[i] = lane + 64 * i < per_row ? src[lane + 64 * i] : 0ull;
+    const float parent_score = score[r0 + r];
+    for (int j = 0; j < K; ++j) {
+      uint64_t best = 0;
+#pragma unroll
+      for (int i = 0; i < kMergePerLane; ++i) best = max64(best, mine[i]);
+      best = wave_max(best);
+#pragma unroll
+      for (int i = 0; i < kMergePerLane; ++i)
+        if (mine[i] == best) mine[i] = 0ull;
+      if (lane == 0) {
+        // (a row has at least K tokens, so best is a real key)
+        const float child = parent_score + unordered((uint32_t)(best >> 32));
+        s_key[r * K + j] = make_key(child, (uint32_t)(r * K + j));
+        s_tok[r * K + j] = (int32_t)~(uint32_t)best;
+      }
+    }
+  }
+  __syncthreads();
+  // bitonic sort of the padded candidate keys in LDS, descending
+  for (int k = 2; k <= padded; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < padded; i += 256) {
+        const int other = i ^ j;
+        if (other > i) {
+          const uint64_t x = s_key[i], y = s_key[other];
+          const bool descending = (i & k) == 0;
+          if (descending ? x < y : x > y) s_key[i] = y, s_key[other] = x;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  const size_t out0 = (size_t)r0 * K;
+  for (int i = tid; i < total; i += 256) {
+    const uint64_t kx = s_key[i];
+    const int which = (int)~(uint32_t)kx;
+    cand_score[out0 + i] = unordered((uint32_t)(kx >> 32));
+    cand_parent[out0 + i] = which / K;
+    cand_token[out0 + i] = s_tok[which];
+  }
+}
+
+// ---- the best nodes of a grown tree, renumbered ----
+__global__ void __launch_bounds__(256) subtree_kernel(const float *__restrict__ score, const int32_t *__restrict__ parent,
+                                                      const int32_t *__restrict__ cu_M, const int32_t *__restrict__ cu_T,
+                                                      int32_t *__restrict__ old_index, int32_t *__restrict__ new_parent,
+                                                      int32_t *__restrict__ err_flag) {
+  __shared__ uint64_t s_key[TVA_SUBTREE_MAX_NODES];
+  __shared__ int16_t s_new[TVA_SUBTREE_MAX_NODES];  // new index of a kept node, -1 of a dropped one
+  const int tid = threadIdx.x, b = blockIdx.x;
+  const int m0 = cu_M[b], M = cu_M[b + 1] - m0;
+  const int t0 = cu_T[b], keep = cu_T[b + 1] - t0;
+  if (keep <= 0) return;
+  if (keep > M || M > TVA_SUBTREE_MAX_NODES) {
+    if (tid == 0 && err_flag) atomicCAS(err_flag, 0, 1 + b);
+    return;
+  }
+  for (int i = tid; i < M; i += 256) s_key[i] = make_key(score[m0 + i], (uint32_t)i);
+  __syncthreads();
+  // a node is kept iff fewer than `keep` nodes are better (keys are unique: the ranks are 0 .. M-1)
+  for (int i = tid; i < M; i += 256) {
+    const uint64_t mine = s_key[i];
+    int better = 0;
+    for (int j = 0; j < M; ++j) better += s_key[j] > mine;
+    s_new[i] = better < keep ? 0 : -1;
+  }
+  __syncthreads();
+  // new index = kept nodes before it
+  for (int i = tid; i < M; i += 256) {
+    if (s_new[i] < 0) continue;
+    int before = 0;
+    for (int j = 0; j < i; ++j) before += s_new[j] >= 0;
+    old_index[t0 + before] = i;
+  }
+  __syncthreads();  // (s_new is rewritten below: every thread has finished counting)
+  for (int i = tid; i < keep; i += 256) s_new[old_index[t0 + i]] = (int16_t)i;  // (own writes of this workgroup)
+  __syncthreads();
+  for (int i = tid; i < keep; i += 256) {
+    const int old = old_index[t0 + i];
+    const int p = parent[m0 + old];
+    int np = -1;
+    if (p >= 0) {
+      np = (p < old && s_new[p] >= 0) ? s_new[p] : -1;
+      if (np < 0 && err_flag) atomicCAS(err_flag, 0, 1 + b);
+    }
+    new_parent[t0 + i] = np;
+  }
+}
+
+int pieces_of(int V) { return (int)(((int64_t)V + kPiece - 1) / kPiece); }
+
+// TVA_OK, or why the shapes are refused (from host values only)
+int expand_shapes(const tva_expand_args *a) {
+  if (!a || a->B < 0 || a->V < 1 || a->K < 1 || a->K > a->V || a->sum_N < 0) return TVA_INVALID_ARG;
+  if (a->K > kMaxK) return TVA_UNSUPPORTED;
+  if ((int64_t)pieces_of(a->V) * a->K > 64 * kMergePerLane) return TVA_UNSUPPORTED;  // what one wave merges per row
+  return TVA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tva_expand_workspace_bytes(const tva_expand_args *a) {
+  if (expand_shapes(a) != TVA_OK) return (size_t)-1;
+  return (size_t)a->sum_N * pieces_of(a->V) * a->K * sizeof(uint64_t);
+}
+
+int tva_expand_layer(const tva_expand_args *a, void *stream) {
+  if (const int rc = expand_shapes(a)) return rc;
+  if (a->max_N < 0 || (int64_t)a->max_N * a->K > TVA_EXPAND_MAX_CANDIDATES) return TVA_UNSUPPORTED;
+  if (a->B == 0 || a->sum_N == 0) return TVA_OK;
+  if (!a->cu_N || !a->score || !a->logp || !a->cand_score || !a->cand_parent || !a->cand_token || !a->workspace ||
+      a->ld_logp < a->V || ((uintptr_t)a->workspace & 7))
+    return TVA_INVALID_ARG;
+  if (a->workspace_bytes < tva_expand_workspace_bytes(a)) return TVA_WORKSPACE_TOO_SMALL;
+  const int pieces = pieces_of(a->V);
+  uint64_t *part = static_cast<uint64_t *>(a->workspace);
+  hipStream_t st = (hipStream_t)stream;
+  (void)hipGetLastError();  // the status below is these launches'
+  const dim3 grid(pieces, a->sum_N);
+  // 16-byte loads need every row to start on 16 bytes and no group of four to straddle the row's end
+  const bool vec = a->V % 4 == 0 && a->ld_logp % 4 == 0 && ((uintptr_t)a->logp & 15) == 0;
+  if (vec) hipLaunchKernelGGL(topk_parts_kernel<true>, grid, dim3(kPieceThreads), 0, st, a->logp, a->ld_logp, a->V, a->K, part);
+  else hipLaunchKernelGGL(topk_parts_kernel<false>, grid, dim3(kPieceThreads), 0, st, a->logp, a->ld_logp, a->V, a->K, part);
+  hipLaunchKernelGGL(expand_finish_kernel, dim3(a->B), dim3(256), 0, st, part, pieces, a->K, a->cu_N, a->score, a->cand_score,
+                     a->cand_parent, a->cand_token);
+  return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+size_t tva_sizeof_expand_args(void) { return sizeof(tva_expand_args); }
+
+int tva_tree_select_subtree(const float *score, const int32_t *parent, const int32_t *cu_M, const int32_t *cu_T, int32_t B,
+                            int32_t max_M, int32_t *old_index, int32_t *new_parent, int32_t *err_flag, void *stream) {
+  if (B < 0 || max_M < 0) return TVA_INVALID_ARG;
+  if (max_M > TVA_SUBTREE_MAX_NODES) return TVA_UNSUPPORTED;
+  if (B == 0) return TVA_OK;
+  if (!score || !parent || !cu_M || !cu_T || !old_index || !new_parent) return TVA_INVALID_ARG;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(subtree_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, score, parent, cu_M, cu_T, old_index,
+                     new_parent, err_flag);
+  return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+"""Thin ctypes binding of the draft-tree construction kernels (include/tva_draft.h): argument marshalling only.
+The kernels live in libtva.so (csrc/draft.hip)."""
+from __future__ import annotations
+
+import ctypes
+
+from . import binding
+from .binding import _check, _p, _stream_ptr
+
+MAX_K, MAX_CANDIDATES, MAX_SUBTREE_NODES = 16, 1024, 2048
+
+
+class ExpandArgs(ctypes.Structure):
+    """Mirror of `struct tva_expand_args`."""
+    _fields_ = [("B", ctypes.c_int32), ("V", ctypes.c_int32), ("K", ctypes.c_int32), ("sum_N", ctypes.c_int32),
+                ("max_N", ctypes.c_int32), ("cu_N", ctypes.c_void_p), ("score", ctypes.c_void_p), ("logp", ctypes.c_void_p),
+                ("ld_logp", ctypes.c_int64), ("cand_score", ctypes.c_void_p), ("cand_parent", ctypes.c_void_p),
+                ("cand_token", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+def _lib():
+    lib = binding.load_library()
+    if not getattr(lib, "_draft_ready", False):
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        lib.tva_expand_workspace_bytes.restype = ctypes.c_size_t
+        lib.tva_expand_workspace_bytes.argtypes = [ctypes.POINTER(ExpandArgs)]
+        lib.tva_expand_layer.restype = ctypes.c_int
+        lib.tva_expand_layer.argtypes = [ctypes.POINTER(ExpandArgs), vp]
+        lib.tva_sizeof_expand_args.restype = ctypes.c_size_t
+        lib.tva_tree_select_subtree.restype = ctypes.c_int
+        lib.tva_tree_select_subtree.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        if lib.tva_sizeof_expand_args() != ctypes.sizeof(ExpandArgs):
+            raise RuntimeError("libtva.so is stale: rebuild it")
+        lib._draft_ready = True
+    return lib
+
+
+def expand_workspace_bytes(B: int, V: int, K: int, sum_N: int) -> int:
+    a = ExpandArgs()
+    a.B, a.V, a.K, a.sum_N = B, V, K, sum_N
+    n = _lib().tva_expand_workspace_bytes(ctypes.byref(a))
+    if n == ctypes.c_size_t(-1).value:
+        raise binding.TvaError(-2)
+    return n
+
+
+def make_expand_args(*, cu_N, score, logp, K: int, sum_N: int, max_N: int, cand_score, cand_parent, cand_token,
+                     workspace=None, workspace_bytes: int = 0) -> ExpandArgs:
+    a = ExpandArgs()
+    a.B, a.V, a.K, a.sum_N, a.max_N = cu_N.numel() - 1, int(logp.shape[1]), int(K), int(sum_N), int(max_N)
+    a.cu_N, a.score, a.logp, a.ld_logp = _p(cu_N), _p(score), _p(logp), int(logp.stride(0))
+    a.cand_score, a.cand_parent, a.cand_token = _p(cand_score), _p(cand_parent), _p(cand_token)
+    a.workspace, a.workspace_bytes = _p(workspace), int(workspace_bytes)
+    return a
+
+
+def expand_layer_raw(args: ExpandArgs, stream=None) -> None:
+    _check(_lib().tva_expand_layer(ctypes.byref(args), _stream_ptr(stream)))
+
+
+def expand_layer(cu_N, score, logp, K: int, max_N: int, stream=None):
+    """Device tensors in (cu_N int32 [B+1], score float32 [sum_N], logp float32 [sum_N, V]); returns the candidates
+    (cand_score float32, cand_parent int32, cand_token int32), each [sum_N * K], sequence b's at cu_N[b] * K ..."""
+    import torch
+    sum_N, V = int(logp.shape[0]), int(logp.shape[1])
+    dev = logp.device
+    cs = torch.empty(sum_N * K, dtype=torch.float32, device=dev)
+    cp = torch.empty(sum_N * K, dtype=torch.int32, device=dev)
+    ct = torch.empty(sum_N * K, dtype=torch.int32, device=dev)
+    need = expand_workspace_bytes(cu_N.numel() - 1, V, K, sum_N)
+    ws = torch.empty(max(1, need // 8), dtype=torch.int64, device=dev)
+    a = make_expand_args(cu_N=cu_N, score=score, logp=logp, K=K, sum_N=sum_N, max_N=max_N, cand_score=cs, cand_parent=cp,
+                         cand_token=ct, workspace=ws, workspace_bytes=need)
+    expand_layer_raw(a, stream)
+    return cs, cp, ct
+
+
+def select_subtree(score, parent, cu_M, cu_T, max_M: int, old_index=None, new_parent=None, err_flag=None, stream=None,
+                   total_kept: int = None):
+    """Device tensors in; returns (old_index, new_parent), each int32 [cu_T[B]] (total_kept, a host copy of cu_T[B],
+    sizes them when they are not passed)."""
+    import torch
+    B = cu_M.numel() - 1
+    if old_index is None:
+        old_index = torch.empty(max(1, total_kept), dtype=torch.int32, device=score.device)
+    if new_parent is None:
+        new_parent = torch.empty(max(1, total_kept), dtype=torch.int32, device=score.device)
+    _check(_lib().tva_tree_select_subtree(_p(score), _p(parent), _p(cu_M), _p(cu_T), B, int(max_M), _p(old_index),
+                                          _p(new_parent), _p(err_flag), _stream_ptr(stream)))
+    return old_index, new_parent

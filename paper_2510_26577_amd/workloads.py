@@ -200,6 +200,23 @@ def sampling_inputs(rng: np.random.Generator, parent: np.ndarray, cu_T: np.ndarr
     return p, q, tok, u, u_final
 
 
+def expansion_inputs(rng: np.random.Generator, n_rows, V: int, temperature: float = 1.0, levels: int = 0):
+    """Inputs of one layer of draft-tree expansion: for every selected node (n_rows[b] of them in sequence b) its
+    score (the log of its value: minus a sum of a few exponential draws) and the draft head's log-probabilities over
+    V tokens (log-softmax of normal logits of standard deviation 3 / temperature; with levels > 0 the logits are
+    rounded to that many distinct values, so that equal log-probabilities abound).
+    Returns (cu_N i32 [B+1], score f32 [sum_N], logp f32 [sum_N, V])."""
+    cu_N = np.concatenate([[0], np.cumsum(n_rows)]).astype(np.int32)
+    sum_N = int(cu_N[-1])
+    z = rng.standard_normal((sum_N, V)) * (3.0 / temperature)
+    if levels > 0:
+        z = np.round(z * levels / 12.0) * (12.0 / levels)
+    z = z - z.max(axis=1, keepdims=True) if sum_N else z
+    logp = (z - np.log(np.exp(z).sum(axis=1, keepdims=True))).astype(np.float32) if sum_N else z.astype(np.float32)
+    score = (-rng.exponential(1.0, (sum_N, 3)).sum(axis=1)).astype(np.float32)
+    return cu_N, score, logp
+
+
 # ----------------------------------------------------------------------------
 # workload container
 # ----------------------------------------------------------------------------

@@ -42,6 +42,24 @@ def test_verify_exports_match_header(lib):
     assert lib.tva_sizeof_commit_args() == ctypes.sizeof(verify.CommitArgs)
 
 
+def test_draft_exports_match_header(lib):
+    from paper_2510_26577_amd import draft
+    syms = declared_symbols("tva_draft.h")
+    assert set(syms) == set(binding.DRAFT_EXPORTS)
+    for s in syms:
+        assert getattr(lib, s) is not None
+    draft._lib()
+    assert lib.tva_sizeof_expand_args() == ctypes.sizeof(draft.ExpandArgs)
+    # shapes are refused from host values alone: nothing is launched
+    assert draft.expand_workspace_bytes(2, 128256, 12, 24) == 24 * 16 * 12 * 8
+    for kw in (dict(K=17), dict(K=0), dict(V=4, K=5), dict(V=8192 * 40, K=16)):
+        a = draft.ExpandArgs()
+        a.B, a.V, a.K, a.sum_N = 1, kw.get("V", 1000), kw.get("K", 4), 3
+        assert lib.tva_expand_workspace_bytes(ctypes.byref(a)) == ctypes.c_size_t(-1).value
+        assert lib.tva_expand_layer(ctypes.byref(a), None) < 0
+    assert lib.tva_tree_select_subtree(None, None, None, None, 1, 4096, None, None, None, None) == -2
+
+
 def test_host_exports_match_header(lib):
     syms = declared_symbols("tva_cast.h")
     assert set(syms) == set(binding.CAST_EXPORTS)

@@ -1,0 +1,162 @@
+"""GPU parity of the draft-tree construction kernels (through the C ABI) against the CPU oracles on the same seeded
+inputs: selections, orders and indices compared exactly; the one float32 addition per candidate bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import cast_oracle as co
+from oracle import draft_oracle as do
+from paper_2510_26577_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_dev():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2510_26577_amd import binding
+    binding.load_library()
+    return torch
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def run_expand(torch, cu_N, score, logp, K, ld=None, offset=0):
+    """ld: row stride of the device copy (elements); offset: elements the first row starts behind a 16-byte boundary."""
+    from paper_2510_26577_amd import draft
+    n, V = logp.shape
+    ld = ld or V
+    flat = torch.full((n * ld + offset + 4,), float("nan"), dtype=torch.float32, device="cuda")
+    rows = flat[offset:offset + n * ld].view(n, ld)[:, :V]
+    rows.copy_(torch.from_numpy(logp))
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    max_N = int(np.diff(cu_N).max()) if len(cu_N) > 1 else 0
+    cs, cp, ct = draft.expand_layer(d(cu_N, np.int32), d(score, np.float32), rows, K, max_N)
+    torch.cuda.synchronize()
+    return cs.cpu().numpy(), cp.cpu().numpy(), ct.cpu().numpy()
+
+
+def check_expand(torch, cu_N, score, logp, K, **kw):
+    ref = do.expand_layer(score, cu_N, logp, K)
+    cs, cp, ct = run_expand(torch, cu_N, score, logp, K, **kw)
+    for b, (rs, rp, rt) in enumerate(ref):
+        o0, o1 = int(cu_N[b]) * K, int(cu_N[b + 1]) * K
+        assert np.array_equal(cs[o0:o1], rs), b          # (== on floats: -0.0 equals 0.0, -inf equals -inf)
+        assert np.array_equal(cp[o0:o1], rp) and np.array_equal(ct[o0:o1], rt), b
+
+
+@pytest.mark.parametrize("n_rows,V,K,levels", [
+    ([12], 32000, 12, 0),                 # one sequence, the paper's K-sized layer, Llama 2 vocabulary: 4 pieces per row
+    ([10, 0, 7], 128256, 10, 0),          # Llama 3 vocabulary: 16 pieces, the last one ragged; a sequence without rows
+    ([5, 12, 1, 8, 12, 3, 9, 2], 4099, 8, 0),   # V % 4 != 0: one token per load
+    ([64, 40], 1000, 16, 0),              # 1024 candidates in one sequence: the whole sort
+    ([5], 2 * 8192 + 5, 8, 0),            # a last piece with fewer tokens than K
+    ([3], 7, 7, 0),                       # K = V
+    ([6, 6], 50000, 12, 9),               # a handful of distinct log-probabilities per row: the tie rules decide
+    ([4], 9000, 1, 3),                    # K = 1 with ties: the first of the equal maxima
+])
+def test_expand_layer_matches_oracle(torch_dev, n_rows, V, K, levels):
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(600 + V + K))
+    cu_N, score, logp = wl.expansion_inputs(rng, n_rows, V, levels=levels)
+    say(f"[case] expand n={n_rows} V={V} K={K} levels={levels}")
+    check_expand(torch, cu_N, score, logp, K)
+
+
+def test_expand_layer_layouts_and_special_values(torch_dev):
+    """Rows further apart than V, rows that do not start on 16 bytes (the one-token-per-load path on a vocabulary that
+    would allow four), log-probabilities of -inf (tokens of probability zero; a row with fewer finite entries than K
+    fills up with them, lowest token first) and of -0.0 next to 0.0."""
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(61))
+    cu_N, score, logp = wl.expansion_inputs(rng, [7, 5], 20000, levels=0)
+    say("[case] expand strides and offsets")
+    check_expand(torch, cu_N, score, logp, 9, ld=20480)
+    check_expand(torch, cu_N, score, logp, 9, ld=20001)
+    check_expand(torch, cu_N, score, logp, 9, offset=1)
+    say("[case] expand -inf and signed zeros")
+    logp2 = logp.copy()
+    logp2[:, 5000:] = -np.inf
+    logp2[0, 3:] = -np.inf                             # three finite entries, K = 9
+    logp2[1, :] = -np.inf
+    logp2[1, 17] = 0.0                                 # a point mass
+    logp2[2, [11, 4000]] = [-0.0, 0.0]                 # equal as numbers: token 11 first
+    score2 = score.copy()
+    score2[3] = -np.inf                                # a node of value zero: all its children too
+    check_expand(torch, cu_N, score2, logp2, 9)
+
+
+def test_expand_layer_when_few_threads_hold_the_large_values(torch_dev):
+    """The selection bound (K-th largest of the per-thread maxima) lets more than 64 tokens through when three threads
+    of a piece hold all its large values; the kernel then searches the maximum K times instead."""
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(62))
+    V, K = 3 * 8192, 4
+    cu_N, score, logp = wl.expansion_inputs(rng, [3], V)
+    logp = np.minimum(logp, np.float32(-20.0))
+    for t in range(3):                                  # thread t of a piece holds tokens 1024 i + 4 t + e
+        for piece in range(3):
+            idx = piece * 8192 + np.add.outer(1024 * np.arange(8), 4 * t + np.arange(4)).ravel()
+            logp[:, idx] = (-1.0 - rng.random((3, 32))).astype(np.float32)
+    say("[case] expand, large values held by three threads per piece")
+    check_expand(torch, cu_N, score, logp, K)
+
+
+def random_scored_tree(rng, M, ties=0.2):
+    parent = np.array([-1] + [int(rng.integers(max(0, i - 9), i)) for i in range(1, M)], np.int32)
+    score = np.zeros(M, np.float32)
+    for i in range(1, M):
+        score[i] = score[parent[i]] - (0.0 if rng.random() < ties else np.float32(rng.exponential(0.7)))
+    return parent, score
+
+
+def run_subtree(torch, score, parent, cu_M, cu_T, with_flag=True):
+    from paper_2510_26577_amd import draft
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda") if with_flag else None
+    max_M = int(np.diff(cu_M).max())
+    old, newp = draft.select_subtree(d(score, np.float32), d(parent, np.int32), d(cu_M, np.int32), d(cu_T, np.int32), max_M,
+                                     err_flag=flag, total_kept=int(cu_T[-1]))
+    torch.cuda.synchronize()
+    return old.cpu().numpy(), newp.cpu().numpy(), (int(flag.item()) if with_flag else 0)
+
+
+@pytest.mark.parametrize("sizes", [[1], [60], [300, 1, 17, 72], [2048, 5], [33] * 16])
+def test_select_subtree_matches_oracle(torch_dev, sizes):
+    torch = torch_dev
+    rng = np.random.Generator(np.random.PCG64(700 + len(sizes) + sizes[0]))
+    trees = [random_scored_tree(rng, M) for M in sizes]
+    cu_M = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    parent = np.concatenate([t[0] for t in trees])
+    score = np.concatenate([t[1] for t in trees])
+    say(f"[case] select_subtree sizes={sizes}")
+    for pick in ("some", "all", "one", "none"):
+        keep = [{"some": int(rng.integers(1, M + 1)), "all": M, "one": 1, "none": 0}[pick] for M in sizes]
+        cu_T = np.concatenate([[0], np.cumsum(keep)]).astype(np.int32)
+        old, newp, flag = run_subtree(torch, score, parent, cu_M, cu_T)
+        assert flag == 0
+        for b, (par, sc) in enumerate(trees):
+            if keep[b] == 0:
+                continue
+            ro, rp = co.select_subtree(sc, par, keep[b])
+            assert list(old[cu_T[b]:cu_T[b + 1]]) == ro and list(newp[cu_T[b]:cu_T[b + 1]]) == rp, (pick, b)
+
+
+def test_select_subtree_flags_what_is_not_a_tree_of_the_method(torch_dev):
+    torch = torch_dev
+    parent = np.array([-1, 0, 1, -1, 0, 0], np.int32)
+    score = np.array([0.0, -2.0, -1.0, 0.0, -1.0, -3.0], np.float32)     # node 2 scores above its parent 1
+    cu_M = np.array([0, 3, 6], np.int32)
+    with pytest.raises(ValueError):
+        co.select_subtree(score[:3], parent[:3], 2)
+    old, newp, flag = run_subtree(torch, score, parent, cu_M, np.array([0, 2, 4], np.int32))
+    assert flag == 1                                                    # sequence 0
+    assert list(old[2:4]) == [0, 1] and list(newp[2:4]) == [-1, 0]       # sequence 1 is untouched by it
+    old, newp, flag = run_subtree(torch, score, parent, cu_M, np.array([0, 1, 5], np.int32))
+    assert flag == 2                                                    # asked to keep 4 of 3 nodes
+    assert list(old[:1]) == [0] and list(newp[:1]) == [-1]
+    old, newp, _ = run_subtree(torch, score, parent, cu_M, np.array([0, 1, 3], np.int32), with_flag=False)
+    assert list(old) == [0, 0, 1] and list(newp) == [-1, -1, 0]
