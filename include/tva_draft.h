@@ -41,7 +41,7 @@ extern "C" {
  *   cand_parent      device int32 [sum_N * K]  row within the sequence (0 .. n_b-1)
  *   cand_token       device int32 [sum_N * K]
  *   workspace        device, tva_expand_workspace_bytes(args) bytes (the best K of every 8192-token piece of
- *                    every row), 8-byte aligned; contents on return unspecified
+ *                    every row, and of every row), 8-byte aligned; contents on return unspecified
  * The workspace query reads only B, V, K, sum_N and returns (size_t)-1 for shapes the launch would reject.
  */
 typedef struct tva_expand_args {

@@ -8,9 +8,10 @@
 //                       coalesced read, nothing read twice) and finds the piece's best K.  Selection without a
 //                       sort of the piece: the K-th largest of the 256 thread maxima is a bound that at least K
 //                       tokens reach, and almost only the best K do; the few that reach it are gathered in LDS and
-//                       sorted by one wave (a bitonic network over the lanes).
-//   expand_finish_kernel  one workgroup per sequence: a wave per row merges the pieces' results into the row's best
-//                       K, adds the row's score, and the workgroup sorts the sequence's candidates in LDS.
+//                       put in order by counting, for each, how many are larger.
+//   row_merge_kernel    a wave per row merges the pieces' results into the row's best K (skipped when a row is one piece).
+//   expand_finish_kernel  one workgroup per sequence: adds the rows' scores and orders the sequence's candidates the
+//                       same way.
 //   subtree_kernel      one workgroup per tree: rank of every node by (score, index), keep the best, renumber.
 // Everything is compared through one 64-bit key per element: the float mapped to an unsigned integer of the same
 // order in the high word, the complement of the index in the low word -- larger key = better, and no two keys of
@@ -39,38 +40,33 @@ __device__ __forceinline__ float unordered(uint32_t o) {
 }
 __device__ __forceinline__ uint64_t make_key(float x, uint32_t index) { return ((uint64_t)ordered(x) << 32) | (uint32_t)~index; }
 __device__ __forceinline__ uint64_t max64(uint64_t a, uint64_t b) { return a > b ? a : b; }
-__device__ __forceinline__ uint64_t min64(uint64_t a, uint64_t b) { return a < b ? a : b; }
 __device__ __forceinline__ uint64_t shfl_xor64(uint64_t v, int mask) {
   const uint32_t lo = __shfl_xor((uint32_t)v, mask), hi = __shfl_xor((uint32_t)(v >> 32), mask);
   return ((uint64_t)hi << 32) | lo;
 }
 
-// Bitonic sort of one key per lane over the 64 lanes of a wave, descending: lane 0 ends with the largest.
-__device__ __forceinline__ uint64_t wave_sort_desc(uint64_t key) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int k = 2; k <= 64; k <<= 1) {
-#pragma unroll
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      const uint64_t other = shfl_xor64(key, j);
-      const bool keep_max = ((lane & j) == 0) == ((lane & k) == 0);
-      key = keep_max ? max64(key, other) : min64(key, other);
-    }
-  }
-  return key;
-}
 __device__ __forceinline__ uint64_t wave_max(uint64_t key) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) key = max64(key, shfl_xor64(key, o));
   return key;
 }
 
+// rank of `mine` among n keys in LDS = how many of them are larger (every lane reads the same words: broadcasts)
+__device__ __forceinline__ int rank_among(const uint64_t *keys, int n, uint64_t mine) {
+  int larger = 0;
+#pragma unroll 8
+  for (int i = 0; i < n; ++i) larger += keys[i] > mine;
+  return larger;
+}
+
 // ---- the best K of every piece of every row ----
 // grid (pieces, rows).  part[(row * pieces + piece) * K + j] = key of the piece's j-th best token (0 = none: the
-// piece has fewer than K tokens).
+// piece has fewer than K tokens).  Orders are found by counting, for a key, the keys that are larger (keys are unique,
+// so the counts of n keys are 0 .. n-1): reads of LDS that all lanes share, no chain of dependent lane exchanges.
 template <bool VEC4>
 __global__ void __launch_bounds__(kPieceThreads) topk_parts_kernel(const float *__restrict__ logp, int64_t ld, int V, int K,
                                                                   uint64_t *__restrict__ part) {
+  __shared__ uint64_t s_max[kPieceThreads];
   __shared__ uint64_t s_top[4 * kMaxK];
   __shared__ uint64_t s_list[64];
   __shared__ uint64_t s_bound, s_wave[4];
@@ -82,35 +78,52 @@ __global__ void __launch_bounds__(kPieceThreads) topk_parts_kernel(const float *
   uint64_t key[kPerThread];
   if constexpr (VEC4) {
     // 16 bytes per lane and load: thread t holds tokens base + 1024 i + 4 t + e
+    f32x4 x[kPerThread / 4];
 #pragma unroll
     for (int i = 0; i < kPerThread / 4; ++i) {
       const int v = base + i * (4 * kPieceThreads) + 4 * tid;
-      f32x4 x = {0.f, 0.f, 0.f, 0.f};
-      if (v < V) x = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + v));  // (V % 4 == 0: no straddling)
+      x[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (v < V) x[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + v));  // (V % 4 == 0: no straddling)
+    }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) key[4 * i + e] = v < V ? make_key(x[e], (uint32_t)(v + e)) : 0ull;
+    for (int i = 0; i < kPerThread / 4; ++i) {
+      const int v = base + i * (4 * kPieceThreads) + 4 * tid;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) key[4 * i + e] = v < V ? make_key(x[i][e], (uint32_t)(v + e)) : 0ull;
     }
   } else {
+    float x[kPerThread];
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       const int v = base + i * kPieceThreads + tid;
-      key[i] = v < V ? make_key(__builtin_nontemporal_load(src + v), (uint32_t)v) : 0ull;
+      x[i] = v < V ? __builtin_nontemporal_load(src + v) : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const int v = base + i * kPieceThreads + tid;
+      key[i] = v < V ? make_key(x[i], (uint32_t)v) : 0ull;
     }
   }
   uint64_t mine = 0;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) mine = max64(mine, key[i]);
-  if (tid == 0) s_count = 0;
-  // the K-th largest of the 256 thread maxima: each wave sorts its 64, the first wave sorts the waves' best K
-  const uint64_t sorted = wave_sort_desc(mine);
-  if (lane < kMaxK) s_top[wave * kMaxK + lane] = lane < K ? sorted : 0ull;
+  s_max[tid] = mine;
+  if (tid < 4 * kMaxK) s_top[tid] = 0ull;
+  if (tid == 0) s_count = 0, s_bound = 0ull;
   __syncthreads();
-  if (wave == 0) {
-    const uint64_t all = wave_sort_desc(s_top[lane]);
-    if (lane == K - 1) s_bound = all;
+  // the K-th largest of the 256 thread maxima (0 if fewer than K threads hold a token): the best K of each wave's 64,
+  // then the K-th of those 4 K
+  if (mine != 0ull) {
+    const int r = rank_among(s_max + wave * 64, 64, mine);
+    if (r < K) s_top[wave * kMaxK + r] = mine;
   }
   __syncthreads();
-  // at least K tokens reach the bound (K threads' maxima do); gather them
+  if (tid < 4 * kMaxK) {
+    const uint64_t v = s_top[tid];
+    if (v != 0ull && rank_among(s_top, 4 * kMaxK, v) == K - 1) s_bound = v;
+  }
+  __syncthreads();
+  // at least K tokens reach the bound (K threads' maxima do) and few more: gather them
   const uint64_t bound = s_bound;
 #pragma unroll
   for (int i = 0; i < kPerThread; ++i) {
@@ -123,9 +136,12 @@ __global__ void __launch_bounds__(kPieceThreads) topk_parts_kernel(const float *
   const int count = s_count;
   uint64_t *dst = part + ((size_t)row * gridDim.x + piece) * K;
   if (count <= 64) {
-    if (wave == 0) {
-      const uint64_t best = wave_sort_desc(lane < count ? s_list[lane] : 0ull);
-      if (lane < K) dst[lane] = best;
+    if (tid < count) {
+      const uint64_t v = s_list[tid];
+      const int r = rank_among(s_list, count, v);
+      if (r < K) dst[r] = v;
+    } else if (tid < K) {
+      dst[tid] = 0ull;  // (a piece of fewer than K tokens)
     }
     return;
   }
@@ -147,66 +163,96 @@ __global__ void __launch_bounds__(kPieceThreads) topk_parts_kernel(const float *
   }
 }
 
-// ---- per sequence: the rows' best K out of their pieces, the candidates' scores, the candidates sorted ----
-__global__ void __launch_bounds__(256) expand_finish_kernel(const uint64_t *__restrict__ part, int pieces, int K,
+// ---- per row: its best K out of its pieces' ----
+// One wave per row, four rows per workgroup.  best[row * K + j] = key of the row's j-th best token.
+__global__ void __launch_bounds__(256) row_merge_kernel(const uint64_t *__restrict__ part, int pieces, int K, int rows,
+                                                        uint64_t *__restrict__ best) {
+  __shared__ uint64_t s_row[4][64 * kMergePerLane];  // a wave's row: the pieces' candidates
+  __shared__ uint64_t s_surv[4][64];                 // ... those of them that reach the row's bound
+  __shared__ uint64_t s_tau[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= rows) return;  // (no workgroup-wide barrier below: waves are on their own)
+  const int per_row = pieces * K;
+  const uint64_t *src = part + (size_t)r * per_row;
+  uint64_t mine[kMergePerLane];
+#pragma unroll
+  for (int i = 0; i < kMergePerLane; ++i) {
+    mine[i] = lane + 64 * i < per_row ? src[lane + 64 * i] : 0ull;
+    if (lane + 64 * i < per_row) s_row[wave][lane + 64 * i] = mine[i];
+  }
+  if (lane == 0) s_tau[wave] = 0ull;
+  __builtin_amdgcn_wave_barrier();  // (a wave's LDS writes, read back by its own lanes: the wave's LDS operations run in order)
+  // With K pieces or more, the K-th largest of the pieces' best tokens is a bound that K candidates reach and few
+  // more: only those can be among the row's best K.
+  if (pieces >= K) {
+#pragma unroll
+    for (int i = 0; i < kMergePerLane; ++i) {
+      const int at = lane + 64 * i;
+      if (at < per_row && at % K == 0 && mine[i] != 0ull) {
+        int larger = 0;
+        for (int q = 0; q < pieces; ++q) larger += s_row[wave][q * K] > mine[i];
+        if (larger == K - 1) s_tau[wave] = mine[i];
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+  const uint64_t tau = s_tau[wave];
+  int count = 0;
+#pragma unroll
+  for (int i = 0; i < kMergePerLane; ++i) {
+    const bool in = mine[i] != 0ull && mine[i] >= tau;
+    const uint64_t votes = __ballot(in);
+    const int pos = count + __popcll(votes & ((1ull << lane) - 1ull));
+    if (in && pos < 64) s_surv[wave][pos] = mine[i];
+    count += __popcll(votes);
+  }
+  __builtin_amdgcn_wave_barrier();
+  uint64_t *dst = best + (size_t)r * K;
+  if (count <= 64) {
+    if (lane < count) {
+      const uint64_t k = s_surv[wave][lane];
+      const int j = rank_among(s_surv[wave], count, k);
+      if (j < K) dst[j] = k;
+    }
+  } else {
+    // (more than 64 reach the bound: every candidate is ranked among all of the row's)
+#pragma unroll
+    for (int i = 0; i < kMergePerLane; ++i) {
+      if (mine[i] == 0ull) continue;
+      const int j = rank_among(s_row[wave], per_row, mine[i]);
+      if (j < K) dst[j] = mine[i];
+    }
+  }
+}
+
+// ---- per sequence: the candidates' scores, the candidates in order ----
+__global__ void __launch_bounds__(256) expand_finish_kernel(const uint64_t *__restrict__ best, int K,
                                                             const int32_t *__restrict__ cu_N, const float *__restrict__ score,
                                                             float *__restrict__ cand_score, int32_t *__restrict__ cand_parent,
                                                             int32_t *__restrict__ cand_token) {
   __shared__ uint64_t s_key[TVA_EXPAND_MAX_CANDIDATES];
   __shared__ int32_t s_tok[TVA_EXPAND_MAX_CANDIDATES];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   const int b = blockIdx.x;
   const int r0 = cu_N[b], n = cu_N[b + 1] - r0;
   if (n <= 0 || n * K > TVA_EXPAND_MAX_CANDIDATES) return;  // (more rows than the caller's max_N said: nothing written)
   const int total = n * K;
-  int padded = 1;
-  while (padded < total) padded <<= 1;
-  for (int i = total + tid; i < padded; i += 256) s_key[i] = 0ull;
-  const int per_row = pieces * K;
-  for (int r = wave; r < n; r += 4) {
-    const uint64_t *src = part + (size_t)(r0 + r) * per_row;
-    uint64_t mine[kMergePerLane];
-#pragma unroll
-    for (int i = 0; i < kMergePerLane; ++i) mine[i] = lane + 64 * i < per_row ? src[lane + 64 * i] : 0ull;
-    const float parent_score = score[r0 + r];
-    for (int j = 0; j < K; ++j) {
-      uint64_t best = 0;
-#pragma unroll
-      for (int i = 0; i < kMergePerLane; ++i) best = max64(best, mine[i]);
-      best = wave_max(best);
-#pragma unroll
-      for (int i = 0; i < kMergePerLane; ++i)
-        if (mine[i] == best) mine[i] = 0ull;
-      if (lane == 0) {
-        // (a row has at least K tokens, so best is a real key)
-        const float child = parent_score + unordered((uint32_t)(best >> 32));
-        s_key[r * K + j] = make_key(child, (uint32_t)(r * K + j));
-        s_tok[r * K + j] = (int32_t)~(uint32_t)best;
-      }
-    }
-  }
-  __syncthreads();
-  // bitonic sort of the padded candidate keys in LDS, descending
-  for (int k = 2; k <= padded; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < padded; i += 256) {
-        const int other = i ^ j;
-        if (other > i) {
-          const uint64_t x = s_key[i], y = s_key[other];
-          const bool descending = (i & k) == 0;
-          if (descending ? x < y : x > y) s_key[i] = y, s_key[other] = x;
-        }
-      }
-      __syncthreads();
-    }
-  }
   const size_t out0 = (size_t)r0 * K;
   for (int i = tid; i < total; i += 256) {
+    const uint64_t k = best[out0 + i];  // (a row has at least K tokens: a real key)
+    const float child = score[r0 + i / K] + unordered((uint32_t)(k >> 32));
+    s_key[i] = make_key(child, (uint32_t)i);
+    s_tok[i] = (int32_t)~(uint32_t)k;
+  }
+  __syncthreads();
+  // the place of a candidate in the sequence's order = the candidates that are better
+  for (int i = tid; i < total; i += 256) {
     const uint64_t kx = s_key[i];
-    const int which = (int)~(uint32_t)kx;
-    cand_score[out0 + i] = unordered((uint32_t)(kx >> 32));
-    cand_parent[out0 + i] = which / K;
-    cand_token[out0 + i] = s_tok[which];
+    const int place = rank_among(s_key, total, kx);
+    cand_score[out0 + place] = unordered((uint32_t)(kx >> 32));
+    cand_parent[out0 + place] = i / K;
+    cand_token[out0 + place] = s_tok[i];
   }
 }
 
@@ -273,7 +319,8 @@ extern "C" {
 
 size_t tva_expand_workspace_bytes(const tva_expand_args *a) {
   if (expand_shapes(a) != TVA_OK) return (size_t)-1;
-  return (size_t)a->sum_N * pieces_of(a->V) * a->K * sizeof(uint64_t);
+  // the pieces' best K, then the rows' best K
+  return (size_t)a->sum_N * (pieces_of(a->V) + 1) * a->K * sizeof(uint64_t);
 }
 
 int tva_expand_layer(const tva_expand_args *a, void *stream) {
@@ -293,7 +340,12 @@ int tva_expand_layer(const tva_expand_args *a, void *stream) {
   const bool vec = a->V % 4 == 0 && a->ld_logp % 4 == 0 && ((uintptr_t)a->logp & 15) == 0;
   if (vec) hipLaunchKernelGGL(topk_parts_kernel<true>, grid, dim3(kPieceThreads), 0, st, a->logp, a->ld_logp, a->V, a->K, part);
   else hipLaunchKernelGGL(topk_parts_kernel<false>, grid, dim3(kPieceThreads), 0, st, a->logp, a->ld_logp, a->V, a->K, part);
-  hipLaunchKernelGGL(expand_finish_kernel, dim3(a->B), dim3(256), 0, st, part, pieces, a->K, a->cu_N, a->score, a->cand_score,
+  uint64_t *best = part;
+  if (pieces > 1) {
+    best = part + (size_t)a->sum_N * pieces * a->K;
+    hipLaunchKernelGGL(row_merge_kernel, dim3((a->sum_N + 3) / 4), dim3(256), 0, st, part, pieces, a->K, a->sum_N, best);
+  }
+  hipLaunchKernelGGL(expand_finish_kernel, dim3(a->B), dim3(256), 0, st, best, a->K, a->cu_N, a->score, a->cand_score,
                      a->cand_parent, a->cand_token);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }

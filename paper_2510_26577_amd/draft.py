@@ -88,3 +88,87 @@ def select_subtree(score, parent, cu_M, cu_T, max_M: int, old_index=None, new_pa
     _check(_lib().tva_tree_select_subtree(_p(score), _p(parent), _p(cu_M), _p(cu_T), B, int(max_M), _p(old_index),
                                           _p(new_parent), _p(err_flag), _stream_ptr(stream)))
     return old_index, new_parent
+
+
+def _bench(argv=None) -> int:
+    """Times tva_expand_layer and tva_tree_select_subtree on seeded synthetic layers made on the device (log-softmax of
+    normal logits) and prints one JSON line per shape.  Plumbing only; the kernels do the work."""
+    import argparse
+    import json
+    import numpy as np
+    import torch
+
+    ap = argparse.ArgumentParser(description="time tva_expand_layer and tva_tree_select_subtree")
+    ap.add_argument("--steps", type=int, default=64)
+    a = ap.parse_args(argv)
+    assert torch.cuda.is_available(), "needs a GPU"
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(79)
+    stream = torch.cuda.Stream()
+    flush = torch.empty(1 << 28, dtype=torch.int32, device="cuda")
+
+    def timed(run, calls):
+        with torch.cuda.stream(stream):
+            run()
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for _ in range(max(1, a.steps // calls)):
+                    run()
+            g.replay()
+            stream.synchronize()
+            ts = []
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                flush.fill_(1)
+                e0.record(stream)
+                g.replay()
+                e1.record(stream)
+                e1.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e3 / (max(1, a.steps // calls) * calls))
+        return float(np.median(ts))
+
+    for B, n, V, K in ((1, 12, 32000, 12), (1, 12, 128256, 12), (8, 12, 128256, 12), (64, 12, 32000, 12), (64, 12, 128256, 12),
+                       (16, 48, 128256, 8)):
+        copies = 4 if B * n * V * 4 < (1 << 29) else 2
+        cases = []
+        for _ in range(copies):
+            logp = torch.log_softmax(torch.randn((B * n, V), generator=gen, device="cuda") * 3.0, dim=1)
+            score = -torch.rand(B * n, generator=gen, device="cuda") * 4.0
+            cu_N = (torch.arange(B + 1, device="cuda") * n).to(torch.int32)
+            need = expand_workspace_bytes(B, V, K, B * n)
+            ws = torch.empty(max(1, need // 8), dtype=torch.int64, device="cuda")
+            outs = (torch.empty(B * n * K, dtype=torch.float32, device="cuda"), torch.empty(B * n * K, dtype=torch.int32, device="cuda"),
+                    torch.empty(B * n * K, dtype=torch.int32, device="cuda"))
+            cases.append((make_expand_args(cu_N=cu_N, score=score, logp=logp, K=K, sum_N=B * n, max_N=n, cand_score=outs[0],
+                                           cand_parent=outs[1], cand_token=outs[2], workspace=ws, workspace_bytes=need),
+                          (logp, score, cu_N, ws, outs)))
+        us = timed(lambda: [expand_layer_raw(c[0], stream) for c in cases], copies)
+        nbytes = 4.0 * B * n * V
+        print(json.dumps({"kernel": "tva_expand_layer", "shape": f"B={B} rows/seq={n} V={V} K={K}", "us_per_call": us,
+                          "logp_bytes": nbytes, "GBps": nbytes / (us * 1e-6) / 1e9, "frac_of_8TBps": nbytes / (us * 1e-6) / 8e12}),
+              flush=True)
+        del cases
+        torch.cuda.empty_cache()
+
+    rng = np.random.Generator(np.random.PCG64(80))
+    for B, M, keep in ((1, 145, 60), (8, 145, 60), (64, 145, 32), (8, 1024, 72)):
+        parent = np.concatenate([np.array([-1] + [int(rng.integers(max(0, i - 9), i)) for i in range(1, M)], np.int32) for _ in range(B)])
+        score = np.zeros(B * M, np.float32)
+        for b in range(B):
+            for i in range(1, M):
+                score[b * M + i] = score[b * M + parent[b * M + i]] - np.float32(rng.exponential(0.7))
+        d = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+        ds, dp = d(score), d(parent)
+        cu_M = (torch.arange(B + 1, device="cuda") * M).to(torch.int32)
+        cu_T = (torch.arange(B + 1, device="cuda") * keep).to(torch.int32)
+        old = torch.empty(B * keep, dtype=torch.int32, device="cuda")
+        newp = torch.empty(B * keep, dtype=torch.int32, device="cuda")
+        us = timed(lambda: select_subtree(ds, dp, cu_M, cu_T, M, old_index=old, new_parent=newp, stream=stream), 1)
+        print(json.dumps({"kernel": "tva_tree_select_subtree", "shape": f"B={B} nodes={M} keep={keep}", "us_per_call": us}), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    import sys
+    sys.exit(_bench())

@@ -51,7 +51,7 @@ def test_draft_exports_match_header(lib):
     draft._lib()
     assert lib.tva_sizeof_expand_args() == ctypes.sizeof(draft.ExpandArgs)
     # shapes are refused from host values alone: nothing is launched
-    assert draft.expand_workspace_bytes(2, 128256, 12, 24) == 24 * 16 * 12 * 8
+    assert draft.expand_workspace_bytes(2, 128256, 12, 24) == 24 * (16 + 1) * 12 * 8
     for kw in (dict(K=17), dict(K=0), dict(V=4, K=5), dict(V=8192 * 40, K=16)):
         a = draft.ExpandArgs()
         a.B, a.V, a.K, a.sum_N = 1, kw.get("V", 1000), kw.get("K", 4), 3
