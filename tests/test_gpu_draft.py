@@ -160,3 +160,54 @@ def test_select_subtree_flags_what_is_not_a_tree_of_the_method(torch_dev):
     assert list(old[:1]) == [0] and list(newp[:1]) == [-1]
     old, newp, _ = run_subtree(torch, score, parent, cu_M, np.array([0, 1, 3], np.int32), with_flag=False)
     assert list(old) == [0, 0, 1] and list(newp) == [-1, -1, 0]
+
+
+def test_a_tree_grown_and_cut_on_the_gpu_is_the_oracles_and_feeds_the_attention(torch_dev):
+    """Four layers of expansion (the best 6 candidates of a layer are the next layer's rows, 4 children each), the cut to
+    the 20 best nodes, and the ancestor masks of the result: the device path and the oracle path, run side by side on the
+    same log-probabilities, grow the same tree, and the parents that come out are what tva_build_ancestor_mask takes."""
+    torch = torch_dev
+    from paper_2510_26577_amd import binding, draft
+    rng = np.random.Generator(np.random.PCG64(63))
+    B, V, K, width, depth, m = 3, 20000, 4, 6, 4, 20
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    # per sequence: nodes as (parent, token, score), root first; the current layer's node ids
+    nodes = [[(-1, 0, np.float32(0.0))] for _ in range(B)]
+    layer = [[0] for _ in range(B)]
+    say("[case] grow, cut, mask")
+    for _ in range(depth):
+        n_rows = [len(l) for l in layer]
+        cu_N, _, logp = wl.expansion_inputs(rng, n_rows, V)
+        score = np.array([nodes[b][i][2] for b in range(B) for i in layer[b]], np.float32)
+        ref = do.expand_layer(score, cu_N, logp, K)
+        cs, cp, ct = draft.expand_layer(d(cu_N, np.int32), d(score, np.float32), d(logp, np.float32), K, max(n_rows))
+        torch.cuda.synchronize()
+        cs, cp, ct = cs.cpu().numpy(), cp.cpu().numpy(), ct.cpu().numpy()
+        for b in range(B):
+            o0 = int(cu_N[b]) * K
+            rs, rp, rt = ref[b]
+            take = min(width, len(rs))
+            assert np.array_equal(cs[o0:o0 + take], rs[:take]) and np.array_equal(cp[o0:o0 + take], rp[:take])
+            assert np.array_equal(ct[o0:o0 + take], rt[:take])
+            nxt = []
+            for j in range(take):
+                nodes[b].append((layer[b][int(cp[o0 + j])], int(ct[o0 + j]), np.float32(cs[o0 + j])))
+                nxt.append(len(nodes[b]) - 1)
+            layer[b] = nxt
+    sizes = [len(x) for x in nodes]
+    cu_M = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    cu_T = (np.arange(B + 1) * m).astype(np.int32)
+    parent = np.array([x[0] for seq in nodes for x in seq], np.int32)
+    score = np.array([x[2] for seq in nodes for x in seq], np.float32)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    old, newp = draft.select_subtree(d(score, np.float32), d(parent, np.int32), d(cu_M, np.int32), d(cu_T, np.int32), max(sizes),
+                                     err_flag=flag, total_kept=B * m)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    old, newp = old.cpu().numpy(), newp.cpu().numpy()
+    for b in range(B):
+        ro, rp = co.select_subtree(score[cu_M[b]:cu_M[b + 1]], parent[cu_M[b]:cu_M[b + 1]], m)
+        assert list(old[b * m:(b + 1) * m]) == ro and list(newp[b * m:(b + 1) * m]) == rp
+    mask, status, bad = binding.build_ancestor_mask_host(newp, cu_T, m)
+    assert status == 0 and bad == -1                                   # a tree in topological order
+    assert all(int(mask[b * m, 0]) == 1 for b in range(B))             # node 0 of every tree is its own only ancestor
