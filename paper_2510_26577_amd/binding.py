@@ -35,7 +35,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
 
 
 def build_library(verbose: bool = False, timeline: bool = False) -> str:
-    """Compile csrc/tva.hip and csrc/verify.hip (gfx950 kernels + their C ABI) and csrc/cast.cpp
+    """Compile csrc/tva.hip, csrc/verify.hip and csrc/draft.hip (gfx950 kernels + their C ABI) and csrc/cast.cpp
     (host logic) into libtva.so (in-tree); timeline=True: the instrumented build libtva_timeline.so
     (paper_2510_26577_amd/timeline.py) instead."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
