@@ -75,7 +75,9 @@ def main():
                     help="do not pass the host-known sum of the cache lengths to the launch planner")
     ap.add_argument("--reps", type=int, default=5, help="timed replays per figure (median and minimum are reported)")
     ap.add_argument("--with-traffic", action="store_true",
-                    help="also measure roofline.traffic: two child runs of this command under rocprofv3 --pmc")
+                    help="also measure roofline.traffic: two child runs of this command under rocprofv3 --pmc "
+                         "(the full default run, with the CPU baseline, does so anyway)")
+    ap.add_argument("--no-traffic", action="store_true", help="leave roofline.traffic null")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="(used by profile_traffic) make one plain 64 MiB device-to-device copy first: the counters' calibration")
     ap.add_argument("--microbench", action="store_true",
@@ -319,13 +321,19 @@ def measure(a):
             tva_oracle.set_num_threads(cores)
             cpu["one_thread"] = {"value": kv_bytes / one_s / 1e9, "unit": "GB/s", "cores": 1, "ms_per_step": one_s * 1e3}
 
-    # HBM bytes per launch of the dominant kernel: only from a counter run made for this very command
-    # (--with-traffic: two child runs of this script under rocprofv3 --pmc); otherwise null
-    traffic = None
-    if a.with_traffic:
+    # HBM bytes per launch of the dominant kernel: only from a counter run made for this very command (two child
+    # runs of this script under rocprofv3 --pmc, after the timed regions); otherwise null.  The full run (the one
+    # with the CPU baseline) makes them; the short forms only with --with-traffic.
+    traffic, traffic_note = None, None
+    if a.with_traffic or not (a.no_traffic or a.no_cpu_baseline or a.traffic_probe):
         from paper_2510_26577_amd import profile_traffic
-        t = profile_traffic.measure(profile_traffic.bench_args_of(a))
-        traffic = t["attn_kernel_bytes"]
+        try:
+            t = profile_traffic.measure(profile_traffic.bench_args_of(a))
+            traffic = t["attn_kernel_bytes"]
+            traffic_note = (f"FETCH_SIZE x {t['fetch_scale']:.3f} + WRITE_SIZE x {t['write_scale']:.3f} KiB per dispatch "
+                            f"(scales from a 64 MiB copy in the same runs)")
+        except Exception as e:  # the counters are evidence beside the timing, never a reason to lose the line
+            traffic_note = "not measured: " + str(e).splitlines()[0][:200]
     value = kv_bytes / (ms_step * 1e-3) / 1e9
     achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
     tflops_kernel = flops / (ms_kernel * 1e-3) / 1e12
@@ -353,7 +361,7 @@ def measure(a):
                    "ms_per_step_warm_one_input_set": ms_step_warm, "ms_single_isolated_step": ms_single_launch,
                    "kernel_ms_median": ms_kernel, "kernel_ms_min": ms_kernel_min, "reps": REPS},
         "roofline": {"bound": "hbm", "kernel": "attn_kernel (split-KV attention)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note,
                      "kernel_ms": ms_kernel, "attn_call_ms": ms_attn_call, "merge_ms": ms_merge,
                      "mfma_tflops": tflops_kernel, "mfma_frac": tflops_kernel / MFMA_BF16_PEAK_TFLOPS},
         "cpu_baseline": cpu,

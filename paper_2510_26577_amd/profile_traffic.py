@@ -43,7 +43,7 @@ def _run(counter: str, bench_args: list, workdir: str):
     cmd = ["rocprofv3", "--pmc", counter, "-d", d, "-o", "p", "--output-format", "csv", "--",
            "python3", os.path.join(ROOT, "bench.py"), *bench_args, *PROBE]
     env = dict(os.environ, TMPDIR="/tmp")
-    res = subprocess.run(["timeout", "-s", "KILL", "180", *cmd], cwd="/tmp", env=env, stdout=subprocess.PIPE,
+    res = subprocess.run(["timeout", "-s", "KILL", "90", *cmd], cwd="/tmp", env=env, stdout=subprocess.PIPE,
                          stderr=subprocess.PIPE, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"rocprofv3 --pmc {counter} failed ({res.returncode}):\n{res.stderr[-2000:]}")
