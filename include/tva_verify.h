@@ -63,6 +63,19 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
  *   err_flag            device int32[1] or NULL, zero on entry: stores 1 + b when a draft_token is not in
  *                       [0, V) (that child is never accepted) or a residual vanishes (q was not the distribution
  *                       the rejected child came from; the walk ends there with next_token -1)
+ *   workspace, workspace_bytes   device memory of tva_sample_workspace_bytes(B) bytes, 8-byte aligned, or NULL.
+ *                       With it, the vocabulary of a sequence is spread over several workgroups that wait for one
+ *                       another between passes (a sequence's passes are a chain, and one workgroup streams a row at
+ *                       what one compute unit can): B = 1, V = 128256 runs three times faster.  The waits are
+ *                       bounded (about a second): a sequence whose workgroups do not all arrive -- they are all
+ *                       resident at once unless other work holds the compute units that long -- is flagged in
+ *                       err_flag like the cases above, and its outputs are unspecified.  Contents unspecified on
+ *                       return; calls that share a workspace must not overlap.  Without it: one workgroup per
+ *                       sequence, no waits.
+ *   workgroups_per_sequence   0: the library chooses (1 .. 16, so that B times it stays within 256; 1 for
+ *                       vocabularies below 48 K tokens, where the waits cost what the slices save); 1: as without
+ *                       a workspace; 2 .. 16: that many (TVA_UNSUPPORTED if B times it exceeds 256).  The results
+ *                       do not depend on it beyond the order in which a pass's sum is added up.
  */
 typedef struct tva_sample_args {
   int32_t B, V, max_path;
@@ -70,9 +83,13 @@ typedef struct tva_sample_args {
   const float *p_target, *q_draft, *u, *u_final;
   float *residual;
   int32_t *path, *path_len, *next_token, *err_flag;
+  void *workspace;
+  size_t workspace_bytes;
+  int32_t workgroups_per_sequence;
 } tva_sample_args;
 
 int tva_accept_sampling(const tva_sample_args *a, void *stream);
+size_t tva_sample_workspace_bytes(int32_t B);
 size_t tva_sizeof_sample_args(void);
 
 /*

@@ -77,13 +77,14 @@ constexpr int kSampleTreeLds = 1024;  // nodes of a tree whose parent, token and
 
 // One pass over a vocabulary-long row.  Wave w owns the contiguous segment [w * seg, (w + 1) * seg) and its lanes
 // take consecutive elements (coalesced; VEC = 4: consecutive groups of four, which needs seg % 4 == 0 and rows
-// aligned to 16 bytes).  load(v) fetches what element (group) v needs, use(v, t, x) handles it (it may store) and
+// aligned to 16 bytes); the row is elements lo .. V-1 (a slice of a longer one when several workgroups share a
+// row).  load(v) fetches what element (group) v needs, use(v, t, x) handles it (it may store) and
 // adds its weight to x; U fetches are issued before the first is used.  wsum[w] receives the segment's sum; the
 // return value, the same in every thread, is their sum taken in segment order.
 template <int VEC, int U, class L, class C>
-__device__ __forceinline__ double segment_pass(int V, int seg, double *wsum, L load, C use) {
+__device__ __forceinline__ double segment_pass(int lo, int V, int seg, double *wsum, L load, C use) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int s0 = wave * seg, s1 = s0 + seg < V ? s0 + seg : V;
+  const int s0 = lo + wave * seg, s1 = s0 + seg < V ? s0 + seg : V;
   constexpr int step = 64 * VEC;
   double acc[4] = {0.0, 0.0, 0.0, 0.0};
   for (int v = s0 + lane * VEC; v < s1; v += U * step) {
@@ -118,11 +119,11 @@ template <int VEC>
 __device__ __forceinline__ double row_sum(int V, int seg, double *wsum, const float *row) {
   if constexpr (VEC == 4) {
     return segment_pass<4, 8>(
-        V, seg, wsum, [&](int v) { return *reinterpret_cast<const float4 *>(row + v); },  // (V % 4 == 0: no straddling)
+        0, V, seg, wsum, [&](int v) { return *reinterpret_cast<const float4 *>(row + v); },  // (V % 4 == 0: no straddling)
         [&](int, const float4 &t, double &x) { x += ((double)t.x + (double)t.y) + ((double)t.z + (double)t.w); });
   } else {
     return segment_pass<1, 8>(
-        V, seg, wsum, [&](int v) { return row[v]; }, [&](int, float t, double &x) { x += (double)t; });
+        0, V, seg, wsum, [&](int v) { return row[v]; }, [&](int, float t, double &x) { x += (double)t; });
   }
 }
 
@@ -135,7 +136,7 @@ __device__ __forceinline__ double residual_pass(int V, int seg, double *wsum, co
   };
   if constexpr (VEC == 4) {
     return segment_pass<4, 4>(
-        V, seg, wsum,
+        0, V, seg, wsum,
         [&](int v) {
           return Float4Pair{*reinterpret_cast<const float4 *>(from + v), *reinterpret_cast<const float4 *>(q + v)};
         },
@@ -147,7 +148,7 @@ __device__ __forceinline__ double residual_pass(int V, int seg, double *wsum, co
         });
   } else {
     return segment_pass<1, 4>(
-        V, seg, wsum, [&](int v) { return FloatPair{from[v], q[v]}; },
+        0, V, seg, wsum, [&](int v) { return FloatPair{from[v], q[v]}; },
         [&](int v, const FloatPair &t, double &x) {
           const float o = one(t.a, t.c);
           r[v] = o;
@@ -274,6 +275,275 @@ __global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SamplePara
   }
 }
 
+// ---- the same walk with the vocabulary of a sequence spread over W workgroups ----
+// A sequence's passes wait for one another, and one workgroup streams a row at what one compute unit can (about
+// 45 GB/s): with few sequences the chip idles.  Here workgroup w of a sequence's W takes the w-th slice of every
+// row.  After its part of a pass it publishes its partial sum (and, after a residual pass, the residual's entry of
+// the next child's token, if that lies in its slice), arrives at a counter, and waits for the W arrivals; then
+// every workgroup adds the W partial sums in the same order and takes the same decision.  The wait is bounded:
+// a workgroup that does not see the others within about a second flags the sequence and leaves (the launch keeps
+// W x B within what the chip holds at once, so this happens only if something else is wrong).
+constexpr int kCoopMaxW = 16;
+constexpr int kCoopSpins = 1 << 20;
+
+struct CoopParams {
+  SampleParams s;
+  int W;
+  int *sync;     // [B * 32]: one arrival counter per sequence, 128 bytes apart, zero at kernel start
+  double *xchg;  // [B][2][kCoopMaxW + 1]: partial sums of the pass (two buffers in turn), and the exchanged entry
+};
+
+__global__ void zero_sync_kernel(int *sync, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) sync[i] = 0;
+}
+
+__device__ __forceinline__ void publish(double *dst, double x) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long *>(dst), (unsigned long long)__double_as_longlong(x), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // written through before this thread goes on to the barrier
+}
+__device__ __forceinline__ double fetch(const double *src) {
+  return __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long *>(src), __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT));
+}
+
+template <int VEC>
+__global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopParams cp) {
+  const SampleParams &p = cp.s;
+  __shared__ double wsum[kSampleWaves];
+  __shared__ double s_part[kCoopMaxW + 1];
+  __shared__ int s_abort;
+  __shared__ int32_t s_parent[kSampleTreeLds], s_token[kSampleTreeLds];
+  __shared__ float s_u[kSampleTreeLds];
+  const int W = cp.W;
+  const int b = blockIdx.x / W, w = blockIdx.x % W, tid = threadIdx.x, lane = tid & 63;
+  const int t0 = p.cu_T[b];
+  const int T = p.cu_T[b + 1] - t0;
+  if (T <= 0) {
+    if (w == 0 && tid == 0) p.path_len[b] = 0, p.next_token[b] = -1;
+    return;
+  }
+  const int32_t *parent = p.parent + t0, *token = p.token + t0;
+  const float *u = p.u + t0;
+  if (T <= kSampleTreeLds) {
+    for (int i = tid; i < T; i += kSampleThreads) s_parent[i] = parent[i], s_token[i] = token[i], s_u[i] = u[i];
+    parent = s_parent, token = s_token, u = s_u;
+  }
+  if (tid == 0) s_abort = 0;
+  __syncthreads();
+  const int V = p.V;
+  // this workgroup's slice of every row, and the waves' segments of it
+  const int slice = ((V + W - 1) / W + VEC - 1) / VEC * VEC;
+  const int lo = w * slice < V ? w * slice : V, hi = lo + slice < V ? lo + slice : V;
+  const int seg = ((hi - lo + kSampleWaves - 1) / kSampleWaves + VEC - 1) / VEC * VEC;
+  float *const r = p.residual + (size_t)b * V;
+  int *const ctr = cp.sync + b * 32;
+  double *const xbase = cp.xchg + (size_t)b * 2 * (kCoopMaxW + 1);
+  int epoch = 0;
+
+  // sum of the W partial sums, the same in every thread of every workgroup of the sequence; s_part[0 .. W-1] keeps
+  // them, s_part[W] what was exchanged with them.  Returns a negative number if the others did not arrive.
+  auto group_sum = [&](double local) -> double {
+    double *x = xbase + (epoch & 1) * (kCoopMaxW + 1);
+    ++epoch;
+    if (tid == 0) publish(x + w, local);
+    __syncthreads();  // (the thread that published the exchanged entry has waited for its store too)
+    if (tid == 0) {
+      __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int target = epoch * W;
+      int spins = 0;
+      while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        __builtin_amdgcn_s_sleep(2);
+        if (++spins > kCoopSpins) {
+          s_abort = 1;
+          break;
+        }
+      }
+    }
+    __syncthreads();
+    if (s_abort) return -1.0;
+    if (tid <= W) s_part[tid] = fetch(x + (tid < W ? tid : kCoopMaxW));
+    __syncthreads();
+    double z = 0.0;
+    for (int i = 0; i < W; ++i) z += s_part[i];
+    return z;
+  };
+  auto leave_flagged = [&]() {
+    if (tid == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+  };
+  // the first child of `of` behind node `after` that carries a token (others are flagged and passed over), or -1
+  auto next_child = [&](int of, int after) -> int {
+    for (int base = after + 1; base < T; base += 64) {
+      const int i = base + lane;
+      unsigned long long kids = __ballot(i < T && parent[i] == of);
+      while (kids) {
+        const int c = base + __builtin_ctzll(kids);
+        kids &= kids - 1;
+        const int x = token[c];
+        if (x >= 0 && x < V) return c;
+        leave_flagged();
+      }
+    }
+    return -1;
+  };
+
+  int cur = 0, len = 1;
+  if (w == 0 && tid == 0) p.path[(size_t)b * p.max_path] = 0;
+  const float *dist;
+  double Z;
+  while (true) {
+    const float *prow = p.p + (size_t)(t0 + cur) * V;
+    const float *q = p.q + (size_t)(t0 + cur) * V;
+    dist = prow;
+    double local;
+    if constexpr (VEC == 4) {
+      local = segment_pass<4, 8>(
+          lo, hi, seg, wsum, [&](int v) { return *reinterpret_cast<const float4 *>(prow + v); },
+          [&](int, const float4 &t, double &x) { x += ((double)t.x + (double)t.y) + ((double)t.z + (double)t.w); });
+    } else {
+      local = segment_pass<1, 8>(
+          lo, hi, seg, wsum, [&](int v) { return prow[v]; }, [&](int, float t, double &x) { x += (double)t; });
+    }
+    Z = group_sum(local);
+    if (Z < 0.0) return leave_flagged();
+    bool accepted = false;
+    if (len < p.max_path) {
+      int c = next_child(cur, cur);
+      double rx = c >= 0 ? (double)prow[token[c]] : 0.0;
+      while (c >= 0) {
+        const int x = token[c];
+        if (rx > 0.0 && (double)u[c] * (double)q[x] * Z <= rx) {
+          cur = c;
+          if (w == 0 && tid == 0) p.path[(size_t)b * p.max_path + len] = c;
+          ++len;
+          accepted = true;
+          break;
+        }
+        // rejected: the residual max(0, r - Z q) over this workgroup's slice; the entry of the next child's token
+        // goes to the others with the partial sum
+        const int cn = next_child(cur, c);
+        const int xn = cn >= 0 ? token[cn] : -1;
+        double *xslot = xbase + (epoch & 1) * (kCoopMaxW + 1) + kCoopMaxW;
+        const float *from = dist;
+        const double Zq = Z;
+        auto one = [&](float pv, float qv) {
+          const double d = (double)pv - Zq * (double)qv;
+          return d > 0.0 ? (float)d : 0.f;
+        };
+        __syncthreads();  // every thread has read what it needs of the row before the slice is overwritten in place
+        if constexpr (VEC == 4) {
+          local = segment_pass<4, 4>(
+              lo, hi, seg, wsum,
+              [&](int v) {
+                return Float4Pair{*reinterpret_cast<const float4 *>(from + v), *reinterpret_cast<const float4 *>(q + v)};
+              },
+              [&](int v, const Float4Pair &t, double &acc) {
+                float4 o;
+                o.x = one(t.a.x, t.c.x), o.y = one(t.a.y, t.c.y), o.z = one(t.a.z, t.c.z), o.w = one(t.a.w, t.c.w);
+                *reinterpret_cast<float4 *>(r + v) = o;
+                if (xn >= v && xn < v + 4) publish(xslot, (double)(xn == v ? o.x : xn == v + 1 ? o.y : xn == v + 2 ? o.z : o.w));
+                acc += ((double)o.x + (double)o.y) + ((double)o.z + (double)o.w);
+              });
+        } else {
+          local = segment_pass<1, 4>(
+              lo, hi, seg, wsum, [&](int v) { return FloatPair{from[v], q[v]}; },
+              [&](int v, const FloatPair &t, double &acc) {
+                const float o = one(t.a, t.c);
+                r[v] = o;
+                if (v == xn) publish(xslot, (double)o);
+                acc += (double)o;
+              });
+        }
+        const double Zn = group_sum(local);
+        if (Zn < 0.0) return leave_flagged();
+        if (!(Zn > 0.0)) {
+          // q was not a distribution the child could have been drawn from: flagged; the walk ends here
+          leave_flagged();
+          if (w == 0 && tid == 0) p.path_len[b] = len, p.next_token[b] = -1;
+          return;
+        }
+        Z = Zn;
+        dist = r;
+        rx = s_part[W];
+        c = cn;
+      }
+    }
+    if (!accepted) break;
+  }
+  if (w == 0 && tid == 0) p.path_len[b] = len;
+  // The last token: the workgroup whose slice holds the smallest v with cumulative weight above u_final * Z, then
+  // the wave of it whose segment does, then 64 elements at a time.
+  const double target = (double)p.u_final[b] * Z;
+  int claim = -1, last_heavy = 0;
+  double before = 0.0;
+  {
+    double pre = 0.0;
+    for (int i = 0; i < W; ++i) {
+      const double nx = pre + s_part[i];
+      if (claim < 0 && nx > target) claim = i, before = pre;
+      if (s_part[i] > 0.0) last_heavy = i;
+      pre = nx;
+    }
+  }
+  const bool none = claim < 0;  // (u_final was not below 1: the last token that has weight)
+  if (none) claim = last_heavy;
+  if (w != claim) return;
+  int wclaim = -1, wlast = 0;
+  {
+    double pre = before;
+    for (int i = 0; i < kSampleWaves; ++i) {
+      const double nx = pre + wsum[i];
+      if (wclaim < 0 && !none && nx > target) wclaim = i, before = pre;
+      if (wsum[i] > 0.0) wlast = i;
+      pre = nx;
+    }
+  }
+  const bool wnone = wclaim < 0;  // (rounding, or no claim at all: the slice's last token that has weight)
+  if (wnone) wclaim = wlast;
+  const int wave = tid >> 6;
+  if (wave != wclaim) return;
+  const int s0 = lo + wave * seg, s1 = s0 + seg < hi ? s0 + seg : hi;
+  double acc = before;
+  int tok = -1, last_pos = -1;
+  for (int base = s0; base < s1; base += 64) {
+    const int v = base + lane;
+    const float f = v < s1 ? dist[v] : 0.f;
+    double incl = (double)f;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double y = __shfl_up(incl, o);
+      if (lane >= o) incl += y;
+    }
+    const unsigned long long heavy = __ballot(f > 0.f);
+    if (heavy) last_pos = base + 63 - __builtin_clzll(heavy);
+    const unsigned long long over = wnone ? 0ull : __ballot(acc + incl > target);
+    if (over) {
+      tok = base + __builtin_ctzll(over);
+      break;
+    }
+    acc += __shfl(incl, 63);
+  }
+  if (lane == 0) p.next_token[b] = tok >= 0 ? tok : last_pos;
+}
+
+// Workgroups per sequence: as many as keep the launch within one workgroup per compute unit (all of them resident at
+// once, which the waits between passes rely on), at most 16, a power of two, slices of 4096 tokens or more, and
+// one only for vocabularies below 48 K: a wait between passes costs about 4.5 us, what one workgroup needs for
+// a pass over 32 K tokens (measured: V = 32000 30.6 us with one workgroup, 35.3 with eight).  Negative: a status.
+int sample_workgroups(const tva_sample_args *a) {
+  if (a->workgroups_per_sequence < 0 || a->workgroups_per_sequence > kCoopMaxW) return TVA_INVALID_ARG;
+  if (!a->workspace || a->workgroups_per_sequence == 1) return 1;
+  if (((uintptr_t)a->workspace & 7) || a->workspace_bytes < (size_t)a->B * 512) return TVA_WORKSPACE_TOO_SMALL;
+  int W = 1;
+  while (a->V >= 49152 && 2 * W <= kCoopMaxW && (int64_t)a->B * 2 * W <= 256 && a->V / (2 * W) >= 4096) W *= 2;
+  if (a->workgroups_per_sequence > 1) {
+    W = a->workgroups_per_sequence;
+    if ((int64_t)a->B * W > 256) return TVA_UNSUPPORTED;  // more than the chip holds at once
+  }
+  return W;
+}
+
 struct CommitParams {
   const int32_t *cu_T, *L, *path, *path_len, *cu_L, *page_table;
   const char *k_tree, *v_tree;
@@ -394,15 +664,29 @@ int tva_accept_sampling(const tva_sample_args *a, void *stream) {
   p.residual = a->residual;
   p.path = a->path, p.path_len = a->path_len, p.next_token = a->next_token, p.err_flag = a->err_flag;
   p.V = a->V, p.max_path = a->max_path;
-  (void)hipGetLastError();  // the status below is this launch's
   // groups of four need every row to start on 16 bytes
   const bool vec = a->V % 4 == 0 && (((uintptr_t)a->p_target | (uintptr_t)a->q_draft | (uintptr_t)a->residual) & 15) == 0;
-  if (vec)
-    hipLaunchKernelGGL(sample_kernel<4>, dim3(a->B), dim3(kSampleThreads), 0, (hipStream_t)stream, p);
-  else
-    hipLaunchKernelGGL(sample_kernel<1>, dim3(a->B), dim3(kSampleThreads), 0, (hipStream_t)stream, p);
+  const int W = sample_workgroups(a);
+  if (W < 0) return W;
+  (void)hipGetLastError();  // the status below is these launches'
+  hipStream_t st = (hipStream_t)stream;
+  if (W == 1) {
+    if (vec) hipLaunchKernelGGL(sample_kernel<4>, dim3(a->B), dim3(kSampleThreads), 0, st, p);
+    else hipLaunchKernelGGL(sample_kernel<1>, dim3(a->B), dim3(kSampleThreads), 0, st, p);
+  } else {
+    CoopParams cp;
+    cp.s = p, cp.W = W;
+    cp.sync = static_cast<int *>(a->workspace);
+    cp.xchg = reinterpret_cast<double *>(static_cast<char *>(a->workspace) + (size_t)a->B * 128);
+    // the arrival counters start at zero (a kernel, not a memset node: the call may be captured into a graph)
+    hipLaunchKernelGGL(zero_sync_kernel, dim3((a->B * 32 + 255) / 256), dim3(256), 0, st, cp.sync, a->B * 32);
+    if (vec) hipLaunchKernelGGL(sample_coop_kernel<4>, dim3(a->B * W), dim3(kSampleThreads), 0, st, cp);
+    else hipLaunchKernelGGL(sample_coop_kernel<1>, dim3(a->B * W), dim3(kSampleThreads), 0, st, cp);
+  }
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
+
+size_t tva_sample_workspace_bytes(int32_t B) { return B < 0 ? (size_t)-1 : (size_t)B * 512; }
 
 size_t tva_sizeof_sample_args(void) { return sizeof(tva_sample_args); }
 

@@ -28,7 +28,8 @@ class SampleArgs(ctypes.Structure):
     """Mirror of `struct tva_sample_args`."""
     _fields_ = [("B", ctypes.c_int32), ("V", ctypes.c_int32), ("max_path", ctypes.c_int32)] + \
                [(n, ctypes.c_void_p) for n in ("parent", "cu_T", "draft_token", "p_target", "q_draft", "u", "u_final",
-                                               "residual", "path", "path_len", "next_token", "err_flag")]
+                                               "residual", "path", "path_len", "next_token", "err_flag", "workspace")] + \
+               [("workspace_bytes", ctypes.c_size_t), ("workgroups_per_sequence", ctypes.c_int32)]
 
 
 def _lib():
@@ -44,6 +45,8 @@ def _lib():
         lib.tva_accept_sampling.restype = ctypes.c_int
         lib.tva_accept_sampling.argtypes = [ctypes.POINTER(SampleArgs), vp]
         lib.tva_sizeof_sample_args.restype = ctypes.c_size_t
+        lib.tva_sample_workspace_bytes.restype = ctypes.c_size_t
+        lib.tva_sample_workspace_bytes.argtypes = [ctypes.c_int32]
         if lib.tva_sizeof_sample_args() != ctypes.sizeof(SampleArgs):
             raise RuntimeError("libtva.so is stale: rebuild it")
         if lib.tva_sizeof_commit_args() != ctypes.sizeof(CommitArgs):
@@ -70,9 +73,11 @@ def accept_greedy(parent, cu_T, draft_token, target_token, max_path: int, path=N
 
 
 def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, max_path: int, residual=None,
-                    err_flag=None, stream=None):
+                    err_flag=None, stream=None, workspace="auto", workgroups_per_sequence: int = 0):
     """Device tensors in (int32 trees and tokens, float32 distributions [sum_T, V] and uniform numbers); returns
-    (path [B, max_path], path_len [B], next_token [B])."""
+    (path [B, max_path], path_len [B], next_token [B]).  workspace: "auto" allocates the one that lets several
+    workgroups share a sequence, None runs one workgroup per sequence, or a device tensor of
+    tva_sample_workspace_bytes(B) bytes."""
     import torch
     B, V = cu_T.numel() - 1, int(p_target.shape[1])
     dev = cu_T.device
@@ -86,6 +91,11 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
     a.parent, a.cu_T, a.draft_token = _p(parent), _p(cu_T), _p(draft_token)
     a.p_target, a.q_draft, a.u, a.u_final = _p(p_target), _p(q_draft), _p(u), _p(u_final)
     a.residual, a.path, a.path_len, a.next_token, a.err_flag = _p(residual), _p(path), _p(path_len), _p(next_token), _p(err_flag)
+    if isinstance(workspace, str):
+        workspace = torch.empty(max(1, _lib().tva_sample_workspace_bytes(B) // 8), dtype=torch.int64, device=dev)
+    if workspace is not None:
+        a.workspace, a.workspace_bytes = _p(workspace), workspace.numel() * workspace.element_size()
+    a.workgroups_per_sequence = int(workgroups_per_sequence)
     _check(_lib().tva_accept_sampling(ctypes.byref(a), _stream_ptr(stream)))
     return path, path_len, next_token
 
@@ -239,9 +249,10 @@ def _bench_sampling(steps: int) -> None:
             case = dict(parent=d(parent), cu_T=d(cu_T), tok=tok, p=p, q=q,
                         u=torch.rand(B * T, generator=gen, device="cuda"), uf=torch.rand(B, generator=gen, device="cuda"),
                         residual=torch.empty((B, V), dtype=torch.float32, device="cuda"),
-                        flag=torch.zeros(1, dtype=torch.int32, device="cuda"))
+                        flag=torch.zeros(1, dtype=torch.int32, device="cuda"),
+                        ws=torch.empty(max(1, _lib().tva_sample_workspace_bytes(B) // 8), dtype=torch.int64, device="cuda"))
             path, plen, _ = accept_sampling(case["parent"], case["cu_T"], tok, p, q, case["u"], case["uf"], depth + 1,
-                                            residual=case["residual"], err_flag=case["flag"])
+                                            residual=case["residual"], err_flag=case["flag"], workspace=case["ws"])
             torch.cuda.synchronize()
             assert int(case["flag"].item()) == 0
             path, plen = path.cpu().numpy(), plen.cpu().numpy()
@@ -256,32 +267,36 @@ def _bench_sampling(steps: int) -> None:
             cases.append(case)
         sums, rejs = sums / copies, rejs / copies
 
-        def run():
+        def run(shared):
             for k in cases:
                 accept_sampling(k["parent"], k["cu_T"], k["tok"], k["p"], k["q"], k["u"], k["uf"], depth + 1,
-                                residual=k["residual"], err_flag=k["flag"], stream=stream)
+                                residual=k["residual"], err_flag=k["flag"], stream=stream, workspace=k["ws"] if shared else None)
 
-        with torch.cuda.stream(stream):
-            run()
-            stream.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
-                for _ in range(max(1, steps // copies)):
-                    run()
-            g.replay()
-            stream.synchronize()
-            best = 1e30
-            for _ in range(5):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
+        times = {}
+        for shared in (True, False):
+            with torch.cuda.stream(stream):
+                run(shared)
+                stream.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for _ in range(max(1, steps // copies)):
+                        run(shared)
                 g.replay()
-                e1.record(stream)
-                e1.synchronize()
-                best = min(best, e0.elapsed_time(e1) * 1e3 / (max(1, steps // copies) * copies))
+                stream.synchronize()
+                best = 1e30
+                for _ in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    g.replay()
+                    e1.record(stream)
+                    e1.synchronize()
+                    best = min(best, e0.elapsed_time(e1) * 1e3 / (max(1, steps // copies) * copies))
+            times[shared] = best
+            assert all(int(k["flag"].item()) == 0 for k in cases)
         moved = 4.0 * V * (sums + 3 * rejs + B / 16.0)   # a sum reads a row; a residual reads two and writes one; the draw a segment
         print(json.dumps({"shape": name, "accepted_nodes_per_step": sums, "refused_children_per_step": rejs,
-                          "sampling_us": best, "vocabulary_bytes": moved, "GBps": moved / (best * 1e-6) / 1e9,
-                          "GBps_per_workgroup": moved / (best * 1e-6) / 1e9 / B}), flush=True)
+                          "sampling_us": times[True], "sampling_us_one_workgroup_per_sequence": times[False],
+                          "vocabulary_bytes": moved, "GBps": moved / (times[True] * 1e-6) / 1e9}), flush=True)
         del cases
         torch.cuda.empty_cache()
 

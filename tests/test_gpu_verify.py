@@ -459,7 +459,9 @@ def test_commit_of_an_8bit_cache(torch_dev, page_size):
 
 # ---- acceptance by speculative sampling ----
 
-def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True, misalign=False):
+def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True, misalign=False, workgroups=0):
+    """workgroups: 0 = the library spreads a sequence over as many workgroups as it sees fit, 1 = one per sequence
+    (no workspace passed), 2 .. 16 = that many."""
     from paper_2510_26577_amd import verify
     d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
     flag = torch.zeros(1, dtype=torch.int32, device="cuda") if with_flag else None
@@ -473,7 +475,8 @@ def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True
             assert shifted[-1].data_ptr() % 16 == 4
         dp, dq = shifted
     path, n, nxt = verify.accept_sampling(d(parent, np.int32), d(cu_T, np.int32), d(tok, np.int32), dp,
-                                          dq, d(u, np.float32), d(uf, np.float32), max_path, err_flag=flag)
+                                          dq, d(u, np.float32), d(uf, np.float32), max_path, err_flag=flag,
+                                          workspace=None if workgroups == 1 else "auto", workgroups_per_sequence=workgroups)
     torch.cuda.synchronize()
     return path.cpu().numpy(), n.cpu().numpy(), nxt.cpu().numpy(), (int(flag.item()) if with_flag else 0)
 
@@ -524,12 +527,15 @@ def test_accept_sampling_matches_oracle(torch_dev, B, T_hi, V, temp, drift):
     for max_path in (int(T.max()) + 1, 3, 1):
         ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf, max_path=max_path)
         assert sampling_margin(parent, cu_T, tok, p, q, u, uf, ref_paths, ref_next) > 1e-9
-        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path)
-        assert flag == 0
-        assert list(n) == [len(x) for x in ref_paths]
-        assert list(nxt) == ref_next
-        for b, x in enumerate(ref_paths):
-            assert list(path[b, :len(x)]) == x
+        for workgroups in (0, 1, 2, 16) if max_path != 3 else (0, 1):
+            if B * workgroups > 256:
+                continue
+            path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, workgroups=workgroups)
+            assert flag == 0, workgroups
+            assert list(n) == [len(x) for x in ref_paths], workgroups
+            assert list(nxt) == ref_next, workgroups
+            for b, x in enumerate(ref_paths):
+                assert list(path[b, :len(x)]) == x, workgroups
         longest = max(longest, max(len(x) for x in ref_paths))
         if max_path == 3 and V % 4 == 0:         # rows that do not start on 16 bytes take the one-element path
             path2, n2, nxt2, flag2 = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, misalign=True)
@@ -557,6 +563,9 @@ def test_accept_sampling_rejections_reach_the_residual(torch_dev):
     ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf)
     assert [len(x) for x in ref_paths] == [1, 2] * (B // 2)
     say(f"[case] accept_sampling star B={B} k={k} V={V}")
+    for workgroups in (1, 4):
+        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, k + 1, workgroups=workgroups)
+        assert flag == 0 and list(n) == [1, 2] * (B // 2) and list(nxt) == ref_next, workgroups
     path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, k + 1)
     assert flag == 0 and list(n) == [1, 2] * (B // 2) and list(nxt) == ref_next
     for b in range(0, B, 2):
@@ -580,6 +589,9 @@ def test_accept_sampling_flags_bad_input_and_leaves_other_sequences_alone(torch_
     # sequence 1: its first child's token is not a token
     tok1 = tok.copy()
     tok1[4] = V + 5
+    for workgroups in (1, 2):
+        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok1, p, q, u, uf, 4, workgroups=workgroups)
+        assert flag == 2 and n[1] == 1 and 0 <= nxt[1] < V, workgroups
     path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok1, p, q, u, uf, 4)
     assert flag == 2
     assert [int(nxt[0]), int(nxt[2])] == [ref_next[0], ref_next[2]] and [int(n[0]), int(n[2])] == [len(ref_paths[0]), len(ref_paths[2])]
@@ -590,6 +602,9 @@ def test_accept_sampling_flags_bad_input_and_leaves_other_sequences_alone(torch_
     u2[7] = np.float32(1.5)
     with pytest.raises(ValueError):
         vo.accept_sampling(parent, cu_T, tok, p, q2, u2, uf)
+    for workgroups in (1, 2):
+        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q2, u2, uf, 4, workgroups=workgroups)
+        assert flag == 3 and nxt[2] == -1 and n[2] == 1, workgroups
     path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q2, u2, uf, 4)
     assert flag == 3 and nxt[2] == -1 and n[2] == 1
     assert [int(nxt[0]), int(nxt[1])] == ref_next[:2]
