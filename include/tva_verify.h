@@ -90,6 +90,10 @@ typedef struct tva_sample_args {
 
 int tva_accept_sampling(const tva_sample_args *a, void *stream);
 size_t tva_sample_workspace_bytes(int32_t B);
+/* For tests of the bounded wait: the same call (workspace given, workgroups_per_sequence >= 2), but every wait expects
+ * one arrival more than there are workgroups and gives up after `spins` polls (1 .. 2^20).  Every workgroup then
+ * leaves at its first wait: err_flag is set, the other outputs are unspecified, and the kernel ends normally. */
+int tva_accept_sampling_wait_bound_test(const tva_sample_args *a, int32_t spins, void *stream);
 size_t tva_sizeof_sample_args(void);
 
 /*

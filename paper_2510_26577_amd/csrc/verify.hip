@@ -289,6 +289,8 @@ constexpr int kCoopSpins = 1 << 20;
 struct CoopParams {
   SampleParams s;
   int W;
+  int arrivals;  // arrivals a wait expects: W (one more in the test of the bound: then no wait ever completes)
+  int spins;     // polls after which a wait gives up
   int *sync;     // [B * 32]: one arrival counter per sequence, 128 bytes apart, zero at kernel start
   double *xchg;  // [B][2][kCoopMaxW + 1]: partial sums of the pass (two buffers in turn), and the exchanged entry
 };
@@ -351,11 +353,11 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
     __syncthreads();  // (the thread that published the exchanged entry has waited for its store too)
     if (tid == 0) {
       __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const int target = epoch * W;
+      const int target = epoch * cp.arrivals;
       int spins = 0;
       while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
         __builtin_amdgcn_s_sleep(2);
-        if (++spins > kCoopSpins) {
+        if (++spins > cp.spins) {
           s_abort = 1;
           break;
         }
@@ -652,7 +654,16 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 
-int tva_accept_sampling(const tva_sample_args *a, void *stream) {
+static int accept_sampling_impl(const tva_sample_args *a, void *stream, int missing_arrivals, int spins);
+
+int tva_accept_sampling(const tva_sample_args *a, void *stream) { return accept_sampling_impl(a, stream, 0, kCoopSpins); }
+
+int tva_accept_sampling_wait_bound_test(const tva_sample_args *a, int32_t spins, void *stream) {
+  if (!a || spins < 1 || spins > kCoopSpins || !a->workspace || a->workgroups_per_sequence < 2) return TVA_INVALID_ARG;
+  return accept_sampling_impl(a, stream, 1, spins);
+}
+
+static int accept_sampling_impl(const tva_sample_args *a, void *stream, int missing_arrivals, int spins) {
   if (!a || a->B < 0 || a->V < 1 || a->max_path < 1) return TVA_INVALID_ARG;
   if (a->B == 0) return TVA_OK;
   if (!a->parent || !a->cu_T || !a->draft_token || !a->p_target || !a->q_draft || !a->u || !a->u_final || !a->residual ||
@@ -675,7 +686,7 @@ int tva_accept_sampling(const tva_sample_args *a, void *stream) {
     else hipLaunchKernelGGL(sample_kernel<1>, dim3(a->B), dim3(kSampleThreads), 0, st, p);
   } else {
     CoopParams cp;
-    cp.s = p, cp.W = W;
+    cp.s = p, cp.W = W, cp.arrivals = W + missing_arrivals, cp.spins = spins;
     cp.sync = static_cast<int *>(a->workspace);
     cp.xchg = reinterpret_cast<double *>(static_cast<char *>(a->workspace) + (size_t)a->B * 128);
     // the arrival counters start at zero (a kernel, not a memset node: the call may be captured into a graph)

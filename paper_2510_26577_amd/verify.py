@@ -45,6 +45,8 @@ def _lib():
         lib.tva_accept_sampling.restype = ctypes.c_int
         lib.tva_accept_sampling.argtypes = [ctypes.POINTER(SampleArgs), vp]
         lib.tva_sizeof_sample_args.restype = ctypes.c_size_t
+        lib.tva_accept_sampling_wait_bound_test.restype = ctypes.c_int
+        lib.tva_accept_sampling_wait_bound_test.argtypes = [ctypes.POINTER(SampleArgs), ctypes.c_int32, vp]
         lib.tva_sample_workspace_bytes.restype = ctypes.c_size_t
         lib.tva_sample_workspace_bytes.argtypes = [ctypes.c_int32]
         if lib.tva_sizeof_sample_args() != ctypes.sizeof(SampleArgs):
@@ -73,7 +75,7 @@ def accept_greedy(parent, cu_T, draft_token, target_token, max_path: int, path=N
 
 
 def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, max_path: int, residual=None,
-                    err_flag=None, stream=None, workspace="auto", workgroups_per_sequence: int = 0):
+                    err_flag=None, stream=None, workspace="auto", workgroups_per_sequence: int = 0, wait_bound_test_spins: int = 0):
     """Device tensors in (int32 trees and tokens, float32 distributions [sum_T, V] and uniform numbers); returns
     (path [B, max_path], path_len [B], next_token [B]).  workspace: "auto" allocates the one that lets several
     workgroups share a sequence, None runs one workgroup per sequence, or a device tensor of
@@ -96,7 +98,10 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
     if workspace is not None:
         a.workspace, a.workspace_bytes = _p(workspace), workspace.numel() * workspace.element_size()
     a.workgroups_per_sequence = int(workgroups_per_sequence)
-    _check(_lib().tva_accept_sampling(ctypes.byref(a), _stream_ptr(stream)))
+    if wait_bound_test_spins:                 # (tests of the bounded wait: every wait misses one arrival and gives up)
+        _check(_lib().tva_accept_sampling_wait_bound_test(ctypes.byref(a), int(wait_bound_test_spins), _stream_ptr(stream)))
+    else:
+        _check(_lib().tva_accept_sampling(ctypes.byref(a), _stream_ptr(stream)))
     return path, path_len, next_token
 
 

@@ -608,3 +608,31 @@ def test_accept_sampling_flags_bad_input_and_leaves_other_sequences_alone(torch_
     path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q2, u2, uf, 4)
     assert flag == 3 and nxt[2] == -1 and n[2] == 1
     assert [int(nxt[0]), int(nxt[1])] == ref_next[:2]
+
+
+def test_accept_sampling_waits_are_bounded(torch_dev):
+    """The waits between the workgroups that share a sequence give up after a bounded number of polls: forced from the
+    host (every wait expects one arrival more than there are workgroups, 64 polls), every workgroup leaves at its first
+    wait, the kernel ends normally with the flag set, and the same inputs then run through as usual."""
+    torch = torch_dev
+    from paper_2510_26577_amd import verify
+    rng = np.random.Generator(np.random.PCG64(79))
+    B, V = 3, 20000
+    T = np.array([9, 5, 7])
+    cu_T = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    parent = np.concatenate([wl.tree_uniform(rng, int(t), 4) for t in T]).astype(np.int32)
+    p, q, tok, u, uf = wl.sampling_inputs(rng, parent, cu_T, V)
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    args = (d(parent, np.int32), d(cu_T, np.int32), d(tok, np.int32), d(p, np.float32), d(q, np.float32), d(u, np.float32),
+            d(uf, np.float32), 6)
+    say("[case] accept_sampling, waits that cannot complete (bounded at 64 polls)")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    verify.accept_sampling(*args, err_flag=flag, workgroups_per_sequence=4, wait_bound_test_spins=64)
+    torch.cuda.synchronize()
+    assert 1 <= int(flag.item()) <= B
+    flag.zero_()
+    path, n, nxt = verify.accept_sampling(*args, err_flag=flag, workgroups_per_sequence=4)
+    torch.cuda.synchronize()
+    ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf, max_path=6)
+    assert int(flag.item()) == 0 and list(nxt.cpu().numpy()) == ref_next
+    assert list(n.cpu().numpy()) == [len(x) for x in ref_paths]
