@@ -33,7 +33,7 @@ extern "C" {
  * cu_N[b] * K ... of the three output arrays.  Exact: no arithmetic but that one addition.  NaNs must not occur;
  * -inf is an ordinary (smallest) value; -0.0 counts as 0.0.
  *   B, V, K          sequences; vocabulary size (K <= V); children per row, 1 <= K <= TVA_EXPAND_MAX_K
- *   sum_N, max_N     cu_N[B], and the largest n_b (max_N * K <= TVA_EXPAND_MAX_CANDIDATES); host copies
+ *   sum_N, max_N     cu_N[B] (at most 65535), and the largest n_b (max_N * K <= TVA_EXPAND_MAX_CANDIDATES); host copies
  *   cu_N             device int32 [B+1]
  *   score            device fp32 [sum_N]
  *   logp, ld_logp    device fp32, row r at logp + r * ld_logp (elements; ld_logp >= V)

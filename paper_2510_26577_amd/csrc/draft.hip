@@ -310,6 +310,7 @@ int expand_shapes(const tva_expand_args *a) {
   if (!a || a->B < 0 || a->V < 1 || a->K < 1 || a->K > a->V || a->sum_N < 0) return TVA_INVALID_ARG;
   if (a->K > kMaxK) return TVA_UNSUPPORTED;
   if ((int64_t)pieces_of(a->V) * a->K > 64 * kMergePerLane) return TVA_UNSUPPORTED;  // what one wave merges per row
+  if (a->sum_N > 65535) return TVA_UNSUPPORTED;  // rows are the second grid dimension
   return TVA_OK;
 }
 
