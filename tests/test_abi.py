@@ -58,6 +58,17 @@ def test_draft_exports_match_header(lib):
         assert lib.tva_expand_workspace_bytes(ctypes.byref(a)) == ctypes.c_size_t(-1).value
         assert lib.tva_expand_layer(ctypes.byref(a), None) < 0
     assert lib.tva_tree_select_subtree(None, None, None, None, 1, 4096, None, None, None, None) == -2
+    # nothing to do is not an error, and touches no pointer
+    a = draft.ExpandArgs()
+    a.B, a.V, a.K, a.sum_N, a.max_N = 0, 1000, 4, 0, 0
+    assert lib.tva_expand_layer(ctypes.byref(a), None) == 0
+    a.B = 3
+    assert lib.tva_expand_layer(ctypes.byref(a), None) == 0          # three sequences without rows
+    a.sum_N, a.max_N = 70000, 4
+    assert lib.tva_expand_layer(ctypes.byref(a), None) == -2         # more rows than a grid dimension holds
+    a.sum_N, a.max_N = 300, 300
+    assert lib.tva_expand_layer(ctypes.byref(a), None) == -2         # 1200 candidates in one sequence
+    assert lib.tva_tree_select_subtree(None, None, None, None, 0, 0, None, None, None, None) == 0
 
 
 def test_host_exports_match_header(lib):

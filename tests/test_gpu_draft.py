@@ -57,6 +57,7 @@ def check_expand(torch, cu_N, score, logp, K, **kw):
     ([3], 7, 7, 0),                       # K = V
     ([6, 6], 50000, 12, 9),               # a handful of distinct log-probabilities per row: the tie rules decide
     ([4], 9000, 1, 3),                    # K = 1 with ties: the first of the equal maxima
+    ([2], 262144, 16, 0),                 # 32 pieces x 16: the most one wave merges per row
 ])
 def test_expand_layer_matches_oracle(torch_dev, n_rows, V, K, levels):
     torch = torch_dev
