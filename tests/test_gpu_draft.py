@@ -212,3 +212,88 @@ def test_a_tree_grown_and_cut_on_the_gpu_is_the_oracles_and_feeds_the_attention(
     mask, status, bad = binding.build_ancestor_mask_host(newp, cu_T, m)
     assert status == 0 and bad == -1                                   # a tree in topological order
     assert all(int(mask[b * m, 0]) == 1 for b in range(B))             # node 0 of every tree is its own only ancestor
+
+
+def test_draft_and_sampling_kernels_replayed_from_a_graph(torch_dev):
+    """tva_expand_layer, tva_tree_select_subtree and tva_accept_sampling (several workgroups per sequence: a
+    counter-zeroing kernel, then the walk with its waits) captured in one HIP graph: every replay, with the outputs
+    and the scratch memory overwritten by eager work in between, reproduces the eager results bit for bit."""
+    torch = torch_dev
+    from paper_2510_26577_amd import draft, verify
+    from oracle import verify_oracle as vo
+    rng = np.random.Generator(np.random.PCG64(64))
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    # expansion
+    K, V = 8, 50000
+    cu_N, score, logp = wl.expansion_inputs(rng, [9, 4, 12], V)
+    n_rows = int(cu_N[-1])
+    cs = torch.empty(n_rows * K, dtype=torch.float32, device="cuda")
+    cp = torch.empty(n_rows * K, dtype=torch.int32, device="cuda")
+    ct = torch.empty(n_rows * K, dtype=torch.int32, device="cuda")
+    need = draft.expand_workspace_bytes(3, V, K, n_rows)
+    ws = torch.empty(need // 8, dtype=torch.int64, device="cuda")
+    e_in = (d(cu_N, np.int32), d(score, np.float32), d(logp, np.float32))     # (kept alive: the argument block holds pointers)
+    eargs = draft.make_expand_args(cu_N=e_in[0], score=e_in[1], logp=e_in[2], K=K, sum_N=n_rows,
+                                   max_N=12, cand_score=cs, cand_parent=cp, cand_token=ct, workspace=ws, workspace_bytes=need)
+    # subtree cut
+    sizes, m = [90, 40], 25
+    trees = [random_scored_tree(rng, M) for M in sizes]
+    cu_M = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    cu_T = (np.arange(len(sizes) + 1) * m).astype(np.int32)
+    t_score, t_parent = d(np.concatenate([t[1] for t in trees]), np.float32), d(np.concatenate([t[0] for t in trees]), np.int32)
+    d_cu_M, d_cu_T = d(cu_M, np.int32), d(cu_T, np.int32)
+    old = torch.empty(len(sizes) * m, dtype=torch.int32, device="cuda")
+    newp = torch.empty(len(sizes) * m, dtype=torch.int32, device="cuda")
+    # sampling
+    Vs, T = 60000, np.array([14, 9])
+    s_cu_T = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    s_parent = np.concatenate([wl.tree_expand_prune(rng, int(t)) for t in T]).astype(np.int32)
+    p, q, tok, u, uf = wl.sampling_inputs(rng, s_parent, s_cu_T, Vs, drift=0.4)
+    sargs = (d(s_parent, np.int32), d(s_cu_T, np.int32), d(tok, np.int32), d(p, np.float32), d(q, np.float32), d(u, np.float32),
+             d(uf, np.float32), 6)
+    residual = torch.empty((2, Vs), dtype=torch.float32, device="cuda")
+    sws = torch.empty(2 * 512 // 8, dtype=torch.int64, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    results = {}
+
+    def one_pass(stream=None):
+        draft.expand_layer_raw(eargs, stream)
+        draft.select_subtree(t_score, t_parent, d_cu_M, d_cu_T, max(sizes), old_index=old, new_parent=newp, err_flag=flag, stream=stream)
+        results["path"], results["n"], results["next"] = verify.accept_sampling(
+            *sargs, residual=residual, err_flag=flag, stream=stream, workspace=sws, workgroups_per_sequence=8)
+
+    say("[case] draft + sampling kernels, eager")
+    one_pass()
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    ref_paths, ref_next = vo.accept_sampling(s_parent, s_cu_T, tok, p, q, u, uf, max_path=6)
+    assert results["next"].cpu().tolist() == ref_next and results["n"].cpu().tolist() == [len(x) for x in ref_paths]
+    ref = do.expand_layer(score, cu_N, logp, K)
+    assert np.array_equal(cs.cpu().numpy()[:9 * K], ref[0][0]) and np.array_equal(ct.cpu().numpy()[:9 * K], ref[0][2])
+    eager = [t.clone() for t in (cs, cp, ct, old, newp, results["path"], results["n"], results["next"])]
+
+    def scribble():
+        for t in (cs, residual):
+            t.fill_(float("nan"))
+        for t in (cp, ct, old, newp, ws, sws):
+            t.fill_(-7)
+        flag.zero_()
+
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    scribble()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=side):
+        one_pass(side)
+    graph_outs = (cs, cp, ct, old, newp, results["path"], results["n"], results["next"])
+    for replay in range(3):
+        say(f"[case] draft + sampling kernels, graph replay {replay}")
+        scribble()                                # eager work between the replays
+        for t in graph_outs[5:]:
+            t.fill_(-9)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 0
+        for name, got, want in zip("cand_score cand_parent cand_token old_index new_parent path path_len next".split(), graph_outs, eager):
+            assert torch.equal(got, want), (name, replay)
