@@ -11,7 +11,7 @@
 //                       put in order by counting, for each, how many are larger.
 //   row_merge_kernel    a wave per row merges the pieces' results into the row's best K (skipped when a row is one piece).
 //   expand_finish_kernel  one workgroup per sequence: adds the rows' scores and orders the sequence's candidates the
-//                       same way.
+//                       same way.  (expand_finish_small_kernel: both in one launch for sequences of at most 16 rows.)
 //   subtree_kernel      one workgroup per tree: rank of every node by (score, index), keep the best, renumber.
 // Everything is compared through one 64-bit key per element: the float mapped to an unsigned integer of the same
 // order in the high word, the complement of the index in the low word -- larger key = better, and no two keys of
@@ -164,24 +164,19 @@ __global__ void __launch_bounds__(kPieceThreads) topk_parts_kernel(const float *
 }
 
 // ---- per row: its best K out of its pieces' ----
-// One wave per row, four rows per workgroup.  best[row * K + j] = key of the row's j-th best token.
-__global__ void __launch_bounds__(256) row_merge_kernel(const uint64_t *__restrict__ part, int pieces, int K, int rows,
-                                                        uint64_t *__restrict__ best) {
-  __shared__ uint64_t s_row[4][64 * kMergePerLane];  // a wave's row: the pieces' candidates
-  __shared__ uint64_t s_surv[4][64];                 // ... those of them that reach the row's bound
-  __shared__ uint64_t s_tau[4];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = blockIdx.x * 4 + wave;
-  if (r >= rows) return;  // (no workgroup-wide barrier below: waves are on their own)
+// One wave merges one row: dst[j] = key of the row's j-th best token.  row, surv, tau: the wave's own LDS scratch
+// (per_row keys, 64 keys, one key).
+__device__ __forceinline__ void merge_row(const uint64_t *__restrict__ src, int pieces, int K, uint64_t *row, uint64_t *surv,
+                                          uint64_t *tau_slot, uint64_t *dst) {
+  const int lane = threadIdx.x & 63;
   const int per_row = pieces * K;
-  const uint64_t *src = part + (size_t)r * per_row;
   uint64_t mine[kMergePerLane];
 #pragma unroll
   for (int i = 0; i < kMergePerLane; ++i) {
     mine[i] = lane + 64 * i < per_row ? src[lane + 64 * i] : 0ull;
-    if (lane + 64 * i < per_row) s_row[wave][lane + 64 * i] = mine[i];
+    if (lane + 64 * i < per_row) row[lane + 64 * i] = mine[i];
   }
-  if (lane == 0) s_tau[wave] = 0ull;
+  if (lane == 0) *tau_slot = 0ull;
   __builtin_amdgcn_wave_barrier();  // (a wave's LDS writes, read back by its own lanes: the wave's LDS operations run in order)
   // With K pieces or more, the K-th largest of the pieces' best tokens is a bound that K candidates reach and few
   // more: only those can be among the row's best K.
@@ -191,28 +186,27 @@ __global__ void __launch_bounds__(256) row_merge_kernel(const uint64_t *__restri
       const int at = lane + 64 * i;
       if (at < per_row && at % K == 0 && mine[i] != 0ull) {
         int larger = 0;
-        for (int q = 0; q < pieces; ++q) larger += s_row[wave][q * K] > mine[i];
-        if (larger == K - 1) s_tau[wave] = mine[i];
+        for (int q = 0; q < pieces; ++q) larger += row[q * K] > mine[i];
+        if (larger == K - 1) *tau_slot = mine[i];
       }
     }
     __builtin_amdgcn_wave_barrier();
   }
-  const uint64_t tau = s_tau[wave];
+  const uint64_t tau = *tau_slot;
   int count = 0;
 #pragma unroll
   for (int i = 0; i < kMergePerLane; ++i) {
     const bool in = mine[i] != 0ull && mine[i] >= tau;
     const uint64_t votes = __ballot(in);
     const int pos = count + __popcll(votes & ((1ull << lane) - 1ull));
-    if (in && pos < 64) s_surv[wave][pos] = mine[i];
+    if (in && pos < 64) surv[pos] = mine[i];
     count += __popcll(votes);
   }
   __builtin_amdgcn_wave_barrier();
-  uint64_t *dst = best + (size_t)r * K;
   if (count <= 64) {
     if (lane < count) {
-      const uint64_t k = s_surv[wave][lane];
-      const int j = rank_among(s_surv[wave], count, k);
+      const uint64_t k = surv[lane];
+      const int j = rank_among(surv, count, k);
       if (j < K) dst[j] = k;
     }
   } else {
@@ -220,40 +214,85 @@ __global__ void __launch_bounds__(256) row_merge_kernel(const uint64_t *__restri
 #pragma unroll
     for (int i = 0; i < kMergePerLane; ++i) {
       if (mine[i] == 0ull) continue;
-      const int j = rank_among(s_row[wave], per_row, mine[i]);
+      const int j = rank_among(row, per_row, mine[i]);
       if (j < K) dst[j] = mine[i];
     }
   }
 }
 
+// a wave per row, four rows per workgroup; best[row * K + j]
+__global__ void __launch_bounds__(256) row_merge_kernel(const uint64_t *__restrict__ part, int pieces, int K, int rows,
+                                                        uint64_t *__restrict__ best) {
+  __shared__ uint64_t s_row[4][64 * kMergePerLane];
+  __shared__ uint64_t s_surv[4][64];
+  __shared__ uint64_t s_tau[4];
+  const int wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= rows) return;  // (no workgroup-wide barrier below: waves are on their own)
+  merge_row(part + (size_t)r * pieces * K, pieces, K, s_row[wave], s_surv[wave], &s_tau[wave], best + (size_t)r * K);
+}
+
 // ---- per sequence: the candidates' scores, the candidates in order ----
-__global__ void __launch_bounds__(256) expand_finish_kernel(const uint64_t *__restrict__ best, int K,
-                                                            const int32_t *__restrict__ cu_N, const float *__restrict__ score,
-                                                            float *__restrict__ cand_score, int32_t *__restrict__ cand_parent,
-                                                            int32_t *__restrict__ cand_token) {
-  __shared__ uint64_t s_key[TVA_EXPAND_MAX_CANDIDATES];
-  __shared__ int32_t s_tok[TVA_EXPAND_MAX_CANDIDATES];
-  const int tid = threadIdx.x;
-  const int b = blockIdx.x;
-  const int r0 = cu_N[b], n = cu_N[b + 1] - r0;
-  if (n <= 0 || n * K > TVA_EXPAND_MAX_CANDIDATES) return;  // (more rows than the caller's max_N said: nothing written)
+// best: the rows' best K (n * K keys, global memory or LDS); s_key, s_tok: LDS for n * K entries
+__device__ __forceinline__ void order_candidates(const uint64_t *best, int n, int K, int r0, const float *__restrict__ score,
+                                                 uint64_t *s_key, int32_t *s_tok, float *__restrict__ cand_score,
+                                                 int32_t *__restrict__ cand_parent, int32_t *__restrict__ cand_token) {
+  const int tid = threadIdx.x, threads = blockDim.x;
   const int total = n * K;
   const size_t out0 = (size_t)r0 * K;
-  for (int i = tid; i < total; i += 256) {
-    const uint64_t k = best[out0 + i];  // (a row has at least K tokens: a real key)
+  for (int i = tid; i < total; i += threads) {
+    const uint64_t k = best[i];  // (a row has at least K tokens: a real key)
     const float child = score[r0 + i / K] + unordered((uint32_t)(k >> 32));
     s_key[i] = make_key(child, (uint32_t)i);
     s_tok[i] = (int32_t)~(uint32_t)k;
   }
   __syncthreads();
   // the place of a candidate in the sequence's order = the candidates that are better
-  for (int i = tid; i < total; i += 256) {
+  for (int i = tid; i < total; i += threads) {
     const uint64_t kx = s_key[i];
     const int place = rank_among(s_key, total, kx);
     cand_score[out0 + place] = unordered((uint32_t)(kx >> 32));
     cand_parent[out0 + place] = i / K;
     cand_token[out0 + place] = s_tok[i];
   }
+}
+
+__global__ void __launch_bounds__(256) expand_finish_kernel(const uint64_t *__restrict__ best, int K,
+                                                            const int32_t *__restrict__ cu_N, const float *__restrict__ score,
+                                                            float *__restrict__ cand_score, int32_t *__restrict__ cand_parent,
+                                                            int32_t *__restrict__ cand_token) {
+  __shared__ uint64_t s_key[TVA_EXPAND_MAX_CANDIDATES];
+  __shared__ int32_t s_tok[TVA_EXPAND_MAX_CANDIDATES];
+  const int b = blockIdx.x;
+  const int r0 = cu_N[b], n = cu_N[b + 1] - r0;
+  if (n <= 0 || n * K > TVA_EXPAND_MAX_CANDIDATES) return;  // (more rows than the caller's max_N said: nothing written)
+  order_candidates(best + (size_t)r0 * K, n, K, r0, score, s_key, s_tok, cand_score, cand_parent, cand_token);
+}
+
+// The two steps in one launch for sequences of at most 16 rows of at most 256 piece candidates each (a sequence's
+// rows each get a wave of one workgroup of 16): what a single sequence's layer looks like, where a launch more or
+// less is a sixth of the call.
+constexpr int kSmallRows = 16, kSmallPerRow = 256;
+__global__ void __launch_bounds__(64 * kSmallRows) expand_finish_small_kernel(const uint64_t *__restrict__ part, int pieces, int K,
+                                                                             const int32_t *__restrict__ cu_N,
+                                                                             const float *__restrict__ score,
+                                                                             float *__restrict__ cand_score,
+                                                                             int32_t *__restrict__ cand_parent,
+                                                                             int32_t *__restrict__ cand_token) {
+  __shared__ uint64_t s_row[kSmallRows][kSmallPerRow];
+  __shared__ uint64_t s_surv[kSmallRows][64];
+  __shared__ uint64_t s_tau[kSmallRows];
+  __shared__ uint64_t s_best[kSmallRows * kMaxK];
+  __shared__ uint64_t s_key[kSmallRows * kMaxK];
+  __shared__ int32_t s_tok[kSmallRows * kMaxK];
+  const int wave = threadIdx.x >> 6;
+  const int b = blockIdx.x;
+  const int r0 = cu_N[b], n = cu_N[b + 1] - r0;
+  if (n <= 0 || n > kSmallRows) return;  // (more rows than the caller's max_N said: nothing written)
+  if (wave < n)
+    merge_row(part + (size_t)(r0 + wave) * pieces * K, pieces, K, s_row[wave], s_surv[wave], &s_tau[wave], s_best + wave * K);
+  __syncthreads();
+  order_candidates(s_best, n, K, r0, score, s_key, s_tok, cand_score, cand_parent, cand_token);
 }
 
 // ---- the best nodes of a grown tree, renumbered ----
@@ -342,6 +381,11 @@ int tva_expand_layer(const tva_expand_args *a, void *stream) {
   if (vec) hipLaunchKernelGGL(topk_parts_kernel<true>, grid, dim3(kPieceThreads), 0, st, a->logp, a->ld_logp, a->V, a->K, part);
   else hipLaunchKernelGGL(topk_parts_kernel<false>, grid, dim3(kPieceThreads), 0, st, a->logp, a->ld_logp, a->V, a->K, part);
   uint64_t *best = part;
+  if (pieces > 1 && a->max_N <= kSmallRows && pieces * a->K <= kSmallPerRow) {
+    hipLaunchKernelGGL(expand_finish_small_kernel, dim3(a->B), dim3(64 * kSmallRows), 0, st, part, pieces, a->K, a->cu_N, a->score,
+                       a->cand_score, a->cand_parent, a->cand_token);
+    return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+  }
   if (pieces > 1) {
     best = part + (size_t)a->sum_N * pieces * a->K;
     hipLaunchKernelGGL(row_merge_kernel, dim3((a->sum_N + 3) / 4), dim3(256), 0, st, part, pieces, a->K, a->sum_N, best);
