@@ -72,7 +72,8 @@ def main():
     ap.add_argument("--no-saturated", action="store_true",
                     help="default workload only: skip the extra kernel-level measurement of the same shape at B=32")
     ap.add_argument("--no-length-hint", action="store_true",
-                    help="do not pass the host-known sum of the cache lengths to the launch planner")
+                    help="do not pass the host-known cache lengths (their sum: launch planner; the lengths: which "
+                         "sequences share a CU) to the library")
     ap.add_argument("--reps", type=int, default=5, help="timed replays per figure (median and minimum are reported)")
     ap.add_argument("--with-traffic", action="store_true",
                     help="also measure roofline.traffic: two child runs of this command under rocprofv3 --pmc "
@@ -130,6 +131,7 @@ def measure(a):
         from paper_2510_26577_amd import workloads as wl
         w, k_scale, v_scale = wl.to_fp8_kv(w)
     sum_L = 0 if a.no_length_hint else int(w.L.sum())   # the serving side knows its sequence lengths
+    L_host = None if a.no_length_hint else np.ascontiguousarray(w.L, dtype=np.int32)
     kv_bytes, alg_bytes, flops = w.kv_bytes(), w.algorithmic_bytes(), w.algorithmic_flops()
     R = a.rotate or max(2, min(64, -(-640 * 2 ** 20 // alg_bytes)))
 
@@ -154,7 +156,7 @@ def measure(a):
                                  anc_mask=m, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale,
                                  cu_L=dw.cu_L, page_table=dw.page_table, page_size=w.page_size,
                                  strides=strides, num_splits=a.splits, out=o, lse=l, kv_fp8=a.kv_fp8, k_scale=k_scale,
-                                 v_scale=v_scale, sum_L=sum_L, plan_shape=a.shape)
+                                 v_scale=v_scale, sum_L=sum_L, plan_shape=a.shape, L_host=L_host)
         argv.append(args)
     # the same calls with the parent arrays in place of ancestor masks (the kernel derives the masks)
     argv_parent = []
@@ -163,7 +165,7 @@ def measure(a):
             q=dw.q, k_tree=dw.k_tree, v_tree=dw.v_tree, k_cache=dw.k_cache, v_cache=dw.v_cache, anc_mask=None,
             parent=dw.parent, cu_T=dw.cu_T, L=dw.L, max_T=w.max_T, max_L=w.max_L, scale=w.scale, cu_L=dw.cu_L,
             page_table=dw.page_table, page_size=w.page_size, strides=strides, num_splits=a.splits, out=o, lse=l,
-            kv_fp8=a.kv_fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L, plan_shape=a.shape))
+            kv_fp8=a.kv_fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L, plan_shape=a.shape, L_host=L_host))
     n_splits = binding.plan_splits(argv[0])
     ws_bytes = binding.workspace_bytes(argv[0])
     wss = []

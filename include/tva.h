@@ -155,6 +155,13 @@ typedef struct tva_args {
   int64_t sum_L;
 
   int32_t plan_shape; /* a tva_shape; TVA_SHAPE_AUTO (0) = the library chooses */
+
+  /* Optional placement hint: HOST int32 [B], the cache lengths L[b] as the host knows them, or NULL.  Read during
+     the call, not kept.  In a launch of one workgroup per (sequence, KV head) that fills the chip two workgroups to a
+     CU (8 KV heads, 33 .. 64 sequences, few query rows, no KV split), which sequences share a CU decides when the
+     launch ends; given the lengths, the library hands the workgroup slots out so that a long and a short sequence
+     share one (a ragged batch of 64: 8 % faster).  Results do not depend on the values. */
+  const int32_t *L_host;
 } tva_args;
 
 /*

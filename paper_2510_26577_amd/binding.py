@@ -24,7 +24,7 @@ INCLUDE_DIR = os.path.join(_ROOT, "include")
 
 TVA_OK = 0
 TVA_MAX_TREE = 128
-EXPECTED_VERSION = 5
+EXPECTED_VERSION = 6
 # tva_shape (include/tva.h): workgroup shapes a caller may name in tva_args.plan_shape
 SHAPE_AUTO, SHAPE_R32_W2, SHAPE_R64_W4, SHAPE_R64_W4_DEEP, SHAPE_R128_W8, SHAPE_R256_W8 = range(6)
 SHAPES = (SHAPE_R32_W2, SHAPE_R64_W4, SHAPE_R64_W4_DEEP, SHAPE_R128_W8, SHAPE_R256_W8)
@@ -72,6 +72,7 @@ class TvaArgs(ctypes.Structure):
         ("kv_fp8", ctypes.c_int32), ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float),
         ("sum_L", ctypes.c_int64),
         ("plan_shape", ctypes.c_int32),
+        ("L_host", ctypes.c_void_p),
     ]
 
 
@@ -204,9 +205,10 @@ def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: 
               scale: float, cu_L=None, page_table=None, page_size: int = 0, strides=(0, 0, 0),
               num_splits: int = 0, out=None, lse=None, workspace=None, parent=None, cu_Q=None, max_Q: int = 0,
               sum_T: Optional[int] = None, kv_fp8: bool = False, k_scale: float = 1.0, v_scale: float = 1.0,
-              sum_L: int = 0, plan_shape: int = 0) -> TvaArgs:
+              sum_L: int = 0, plan_shape: int = 0, L_host=None) -> TvaArgs:
     """Fill `tva_args` from tensors (q [sum_T,Hq,D], k_tree [sum_T,Hkv,D], ...).  With cu_Q (queries =
-    the last nodes of each tree) q has sum_Q rows and sum_T comes from k_tree or the sum_T argument."""
+    the last nodes of each tree) q has sum_Q rows and sum_T comes from k_tree or the sum_T argument.
+    L_host: the cache lengths as a host array (numpy int32 [B]), the optional placement hint."""
     a = TvaArgs()
     a.B = cu_T.numel() - 1
     a.sum_T, a.Hq, a.D = int(q.shape[0]), int(q.shape[1]), int(q.shape[2])
@@ -233,8 +235,13 @@ def make_args(*, q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, max_T: 
     a.kv_fp8, a.k_scale, a.v_scale = int(bool(kv_fp8)), float(k_scale), float(v_scale)
     a.sum_L = int(sum_L)
     a.plan_shape = int(plan_shape)
+    if L_host is not None:
+        import numpy as np
+        L_host = np.ascontiguousarray(L_host, dtype=np.int32)
+        assert L_host.shape == (a.B,)
+        a.L_host = L_host.ctypes.data
     # the struct holds raw addresses: keep the tensors alive as long as it lives
-    a._keep = (q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, cu_L, page_table, out, lse, workspace, parent, cu_Q)
+    a._keep = (q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, cu_L, page_table, out, lse, workspace, parent, cu_Q, L_host)
     return a
 
 
@@ -286,7 +293,7 @@ def tree_verify_attn(q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, *, 
                      scale: float, cu_L=None, page_table=None, page_size: int = 0, strides=(0, 0, 0),
                      num_splits: int = 0, out=None, lse=None, workspace=None, stream=None, parent=None, cu_Q=None,
                      max_Q: int = 0, sum_T: Optional[int] = None, kv_fp8: bool = False, k_scale: float = 1.0,
-                     v_scale: float = 1.0, sum_L: int = 0, plan_shape: int = 0):
+                     v_scale: float = 1.0, sum_L: int = 0, plan_shape: int = 0, L_host=None):
     """Tree-masked verification attention.  Returns (out fp32 [sum_T,Hq,D], lse fp32 [sum_T,Hq]).
     bf16 tensors may be torch.bfloat16 or int16/uint16 bit patterns; with kv_fp8 the K/V tensors are uint8
     (E4M3 bytes) and K = k_scale * value, V = v_scale * value.  anc_mask may be None when the
@@ -300,7 +307,7 @@ def tree_verify_attn(q, k_tree, v_tree, k_cache, v_cache, anc_mask, cu_T, L, *, 
                      cu_T=cu_T, L=L, max_T=max_T, max_L=max_L, scale=scale, cu_L=cu_L, page_table=page_table,
                      page_size=page_size, strides=strides, num_splits=num_splits, out=out, lse=lse, parent=parent,
                      cu_Q=cu_Q, max_Q=max_Q, sum_T=sum_T, kv_fp8=kv_fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L,
-                     plan_shape=plan_shape)
+                     plan_shape=plan_shape, L_host=L_host)
     need = workspace_bytes(args)
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty((need + 3) // 4, dtype=torch.float32, device=q.device)

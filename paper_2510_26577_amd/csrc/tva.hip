@@ -37,6 +37,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include <atomic>
 #include <type_traits>
 
@@ -146,6 +148,8 @@ struct AttnParams {
   float *part_out, *part_lse;  // [S, sum_Q, Hq, D], [S, sum_Q, Hq] when S > 1
   int B, Hq, Hkv, G, g_shift, sum_Q, W;  // sum_Q: query rows of the whole batch (= sum_T without cu_Q)
   int chunk_keys, n_chunks, n_row_blocks, max_L;
+  int pair_slots;          // > 0: sequences are matched to workgroup slots by length: slot j takes the sequence in
+  uint32_t slot_seq[16];   // byte j of this array
   int page_size, page_shift, max_pages;
   int64_t stride_page, stride_tok, stride_head;
   float scale_log2;  // scale * log2(e) (times the K scale of an fp8 cache)
@@ -347,8 +351,16 @@ __global__ void __launch_bounds__(WM *WK * 64, (AttnCfg<D, WM, WK, RB, PAGED, NS
   // grid = (Hkv, row blocks, B * splits): the KV head varies fastest in dispatch order
   const int kvh = blockIdx.x;
   const int rblk = blockIdx.y;
-  const int b = (int)blockIdx.z / p.n_chunks;
+  int b = (int)blockIdx.z / p.n_chunks;
   const int chunk = (int)blockIdx.z - b * p.n_chunks;
+  if (p.pair_slots > 0) {
+    // (a permutation of the sequences, made on the host: see fill_slots; picked with scalar selects, so that the
+    // argument block is never indexed by a register)
+    uint32_t word = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) word = (b >> 2) == i ? p.slot_seq[i] : word;
+    b = (int)((word >> (8 * (b & 3))) & 0xFFu);
+  }
 
   // every per-sequence scalar is requested before the first one is needed
   // (read through the constant address space: none of these arrays changes while the kernel
@@ -1126,6 +1138,7 @@ void launch_merge(const float *part_out, const float *part_lse, int S, int64_t n
 // ---------------------------------------------------------------------------------------
 // host side: validation, plan, launch
 // ---------------------------------------------------------------------------------------
+
 struct Plan {
   int variant;  // index into the kernel table
   int BM, TK;
@@ -1138,6 +1151,31 @@ enum { V_K2 = TVA_SHAPE_R32_W2 - 1, V_M2K2 = TVA_SHAPE_R64_W4 - 1, V_M2K2_3 = TV
 
 // query rows of the whole batch: every tree node, or only the nodes cu_Q selects
 inline int64_t query_rows(const tva_args *a) { return a->cu_Q ? a->sum_Q : a->sum_T; }
+
+// Which sequence each workgroup slot takes, when the host knows the cache lengths (tva_args.L_host).  An unsplit
+// launch of one workgroup per (sequence, KV head) with 8 KV heads and 33 .. 64 sequences, of a shape of which two
+// share a CU, fits the chip at once; in dispatch order the heads go round the 8 XCDs and the sequences round an XCD's
+// 32 CUs, so that slots j and j + 32 of the B share a CU for the whole launch, and a CU that got two long sequences
+// ends it (measured on 64 lengths from U{512..2048}: 73.6 us as drawn, 68.0 with a long and a short one per CU,
+// 60.3 with all lengths at their mean).  So: the CUs with one slot get the longest sequences, every other CU a long
+// and a short one.  Where workgroups land is the dispatcher's business, not a guarantee: this is a heuristic about
+// time, and slot_seq is a permutation whatever L_host holds, so no result depends on it.
+void fill_slots(const tva_args *a, const Plan &pl, AttnParams *p) {
+  p->pair_slots = 0;
+  for (uint32_t &w : p->slot_seq) w = 0;
+  const bool two_per_cu = pl.variant == V_K2 || pl.variant == V_M2K2;
+  const int n = a->B;
+  if (!a->L_host || !two_per_cu || pl.n_chunks != 1 || pl.n_row_blocks != 1 || a->Hkv != 8 || n <= 32 || n > 64) return;
+  int order[64];  // sequences, longest first (equal lengths: lower index first)
+  for (int i = 0; i < n; ++i) order[i] = i;
+  std::stable_sort(order, order + n, [&](int x, int y) { return a->L_host[x] > a->L_host[y]; });
+  const int shared = n - 32;  // CUs 0 .. shared-1 of an XCD hold two slots (j and j + 32), the others one
+  for (int j = 0; j < n; ++j) {
+    const int rank = j >= 32 ? n - 1 - (j - 32) : j < shared ? (64 - n) + j : j - shared;
+    p->slot_seq[j >> 2] |= (uint32_t)order[rank] << (8 * (j & 3));
+  }
+  p->pair_slots = n;
+}
 
 bool make_plan(const tva_args *a, Plan *pl) {
   if (!a || a->B <= 0 || a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv) return false;
@@ -1339,7 +1377,7 @@ int static_scratch(void **out) {
 
 extern "C" {
 
-int tva_version(void) { return 5; }
+int tva_version(void) { return 6; }
 
 int tva_timeline_read(uint64_t *dst, int32_t n_workgroups) {
 #ifdef TVA_TIMELINE
@@ -1513,6 +1551,7 @@ static int run_attention(const tva_args *a, void *workspace, size_t workspace_by
   p.n_chunks = pl.n_chunks;
   p.n_row_blocks = pl.n_row_blocks;
   p.max_L = a->max_L;
+  fill_slots(a, pl, &p);
   p.page_size = a->page_size > 0 ? a->page_size : 1;
   p.page_shift = -1;
   for (int sft = 0; sft < 31; ++sft)

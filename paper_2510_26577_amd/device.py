@@ -48,7 +48,7 @@ def build_mask(dw: DeviceWorkload, err_flag=None, stream=None):
 
 def attention(dw: DeviceWorkload, mask, num_splits: int = 0, max_L: Optional[int] = None, strides=(0, 0, 0),
               out=None, lse=None, workspace=None, stream=None, k_scale: float = 1.0, v_scale: float = 1.0,
-              sum_L: int = 0, plan_shape: int = 0):
+              sum_L: int = 0, plan_shape: int = 0, L_host=None):
     """mask=None: the parent arrays are passed instead and the kernel derives the ancestor sets.
     A workload whose K/V are uint8 is taken as E4M3 bytes with the two scales."""
     import torch
@@ -59,7 +59,7 @@ def attention(dw: DeviceWorkload, mask, num_splits: int = 0, max_L: Optional[int
         max_T=w.max_T, max_L=w.max_L if max_L is None else max_L, scale=w.scale, cu_L=dw.cu_L,
         page_table=dw.page_table, page_size=w.page_size, strides=strides, num_splits=num_splits,
         out=out, lse=lse, workspace=workspace, stream=stream, parent=dw.parent if mask is None else None,
-        kv_fp8=fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L, plan_shape=plan_shape)
+        kv_fp8=fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L, plan_shape=plan_shape, L_host=L_host)
 
 
 def run_path(dw: DeviceWorkload, num_splits: int = 0, sum_L: int = 0, plan_shape: int = 0):

@@ -387,6 +387,30 @@ def test_repeated_calls_are_deterministic(gpu):
     assert torch.equal(a, b) and torch.equal(la, lb)
 
 
+@pytest.mark.parametrize("B,T", [(64, 8), (48, 3), (33, 16), (64, 1)])
+def test_host_lengths_hint_changes_nothing_but_the_placement(gpu, B, T):
+    """tva_args.L_host only decides which workgroup slot takes which sequence (ragged batches of 33 .. 64 sequences
+    with 8 KV heads and up to 64 rows per KV head): the true lengths, reversed ones and nonsense all give bit for bit
+    what no hint gives, and that agrees with the oracle."""
+    import torch
+    rng = np.random.Generator(np.random.PCG64(500 + B + T))
+    L = rng.integers(0, 700, size=B)
+    L[:3] = [0, 699, 1]
+    w = wl.random_workload(900 + B, B, 32, 8, 128, L, T, max_depth=6)
+    say(f"[case] length hint B={B} T={T}")
+    dw = gpu.to_device(w)
+    mask = gpu.build_mask(dw)
+    base, lbase = gpu.attention(dw, mask)
+    torch.cuda.synchronize()
+    ro, rl = orc.tree_verify_attn(w)
+    assert np.abs(base.cpu().numpy().astype(np.float64) - ro).max() <= TOL_O
+    assert np.abs(lbase.cpu().numpy().astype(np.float64) - rl).max() <= TOL_LSE
+    for hint in (w.L, w.L[::-1], np.full(B, 7), rng.integers(-5, 10 ** 9, size=B)):
+        o, l = gpu.attention(dw, mask, L_host=np.ascontiguousarray(hint, dtype=np.int32))
+        torch.cuda.synchronize()
+        assert torch.equal(o, base) and torch.equal(l, lbase)
+
+
 @pytest.mark.parametrize("splits", [2, 3, 7])
 def test_splits_entry_point_partials_match_oracle_key_ranges(gpu, splits):
     """tva_tree_verify_attn_splits leaves per-split partials that equal the oracle restricted to
