@@ -347,6 +347,7 @@ def measure(a):
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
                    "L": [int(w.L.min()), int(w.L.max())], "T": int(w.max_T), "paged": bool(w.paged), "kv_storage": "e4m3" if a.kv_fp8 else "bf16",
                    "kv_splits": n_splits, "workgroup_rows": binding.plan_workgroup_rows(argv[0]),
+                   "host_lengths_given": not a.no_length_hint,
                    "split_keys": binding.plan_chunk_keys(argv[0]), "rotating_input_copies": R, "launch": "eager" if a.no_graph else "hip-graph",
                    "step": "one tva_tree_verify_attn call on parent arrays (ancestor sets derived in the kernel) "
                            "incl. merge of the KV splits; ms_per_step_two_calls = mask kernel + attention on masks"},
