@@ -20,8 +20,9 @@ Readings taken where the text is garbled or silent:
   * Cost tables are indexed [row of select(c)][n] with n = 1..N (1-based, as printed).
   * The batch-averaged score of the reranking stage is the rank-wise mean of the per-sample
     scores sorted in descending order (the same averaging as Eq. 1).
-  * Parity unpinned: none of these functions has a printed numeric example in the paper; the pins
-    in tests/test_cast_oracle_pins.py are the paper's theorem, closed forms and a hand-worked case.
+  * Pins: the paper prints no numeric example of these functions, so no expected value is taken from it; they
+    are pinned (tests/test_cast_oracle_pins.py) by the paper's theorem, by closed forms, by limits and
+    monotonicity, and by cases worked by hand.
 """
 from __future__ import annotations
 

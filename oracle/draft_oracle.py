@@ -18,9 +18,10 @@ Readings taken where the text is silent:
   E3. Ties: among equal log-probabilities the lower token index comes first; among candidates of equal score the one
       of the earlier parent row, then of the lower rank under that parent, comes first.  NaNs must not occur.
   E4. Every comparison is made on the float32 values as they are: nothing here rounds except the one addition of E1.
-  * Parity unpinned: the paper prints no numeric example of an expansion; tests/test_draft_oracle_pins.py pins this
-    function by selection written as repeated maximum search, by the product definition of v(u), and by the property
-    the Tree Reranking Phase relies on (a child's value never exceeds its parent's, so the best m nodes form a subtree).
+  * Pins: the paper prints no numeric example of an expansion, so no expected value is taken from it;
+    tests/test_draft_oracle_pins.py pins this function by selection written as repeated maximum search, by the
+    product definition of v(u), and by the property the Tree Reranking Phase relies on (a child's value never
+    exceeds its parent's, so the best m nodes form a subtree).
 """
 from __future__ import annotations
 

@@ -11,8 +11,8 @@ attends to the committed tokens and to its own ancestors) on those K and V.
 Every E4M3 value is k * 2^-9 with |k| <= 2^9 * 448, hence exactly a bf16 value: the oracle decodes
 the bytes, re-expresses them as bf16 bit patterns (no rounding happens) and hands them to the bf16
 attention oracle with scale * k_scale as the score scale; the output is multiplied by v_scale.
-Parity unpinned against the paper (it has no such variant); the decoder is pinned to the format's
-published values, the attention part is the pinned bf16 oracle.
+Pins: the paper has no such variant, so no expected value is taken from it; the decoder is pinned to the
+format's published values and structure, the attention part is the pinned bf16 oracle.
 """
 from __future__ import annotations
 

@@ -18,8 +18,8 @@ nodes are in topological order; when several children carry the matching token t
 taken (a draft tree's siblings are distinct tokens, so this does not arise in practice); other roots
 of a forest are unreachable.  Commit: accepted node j of sequence b (in path order) goes to cache
 position L_b + j; nothing else in the cache changes.
-Parity unpinned: the paper prints no numeric example of either step; the pins are definitions by
-another route (all-edges-match characterisation, brute force) and invariants.
+Pins: the paper prints no numeric example of either step, so no expected value is taken from it; the pins
+are definitions by another route (all-edges-match characterisation, brute force) and invariants.
 """
 from __future__ import annotations
 
@@ -81,8 +81,8 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
       S4  the last token is the smallest v whose cumulative weight r[0] + .. + r[v] exceeds u_final * Z
           (the last v with r[v] > 0 if rounding leaves none).
     Precision: r is held in float32 as the kernel holds it; sums, products and comparisons in float64.
-    Parity unpinned against the paper (it prints no example); pinned by the chain rule written out, by the
-    theorem that the emitted token is distributed as p, and by the temperature-0 and q = p special cases."""
+    Pins: the paper prints no example; pinned by the chain rule written out, by the theorem that the emitted
+    token is distributed as p, and by the temperature-0 and q = p special cases."""
     B = len(cu_T) - 1
     paths, nxt = [], []
     for b in range(B):
