@@ -51,6 +51,14 @@ __device__ __forceinline__ uint64_t wave_max(uint64_t key) {
   return key;
 }
 
+// Between a wave's LDS writes and its own lanes' reads of what other lanes wrote: the wave's LDS operations run in
+// order, so no wait is needed, but the compiler must not move one across the other.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // rank of `mine` among n keys in LDS = how many of them are larger (every lane reads the same words: broadcasts)
 __device__ __forceinline__ int rank_among(const uint64_t *keys, int n, uint64_t mine) {
   int larger = 0;
@@ -177,7 +185,7 @@ __device__ __forceinline__ void merge_row(const uint64_t *__restrict__ src, int 
     if (lane + 64 * i < per_row) row[lane + 64 * i] = mine[i];
   }
   if (lane == 0) *tau_slot = 0ull;
-  __builtin_amdgcn_wave_barrier();  // (a wave's LDS writes, read back by its own lanes: the wave's LDS operations run in order)
+  wave_lds_fence();
   // With K pieces or more, the K-th largest of the pieces' best tokens is a bound that K candidates reach and few
   // more: only those can be among the row's best K.
   if (pieces >= K) {
@@ -190,7 +198,7 @@ __device__ __forceinline__ void merge_row(const uint64_t *__restrict__ src, int 
         if (larger == K - 1) *tau_slot = mine[i];
       }
     }
-    __builtin_amdgcn_wave_barrier();
+    wave_lds_fence();
   }
   const uint64_t tau = *tau_slot;
   int count = 0;
@@ -202,7 +210,7 @@ __device__ __forceinline__ void merge_row(const uint64_t *__restrict__ src, int 
     if (in && pos < 64) surv[pos] = mine[i];
     count += __popcll(votes);
   }
-  __builtin_amdgcn_wave_barrier();
+  wave_lds_fence();
   if (count <= 64) {
     if (lane < count) {
       const uint64_t k = surv[lane];

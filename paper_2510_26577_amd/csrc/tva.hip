@@ -1277,6 +1277,17 @@ bool make_plan(const tva_args *a, Plan *pl) {
     c = (c + pl->TK - 1) / pl->TK * pl->TK;
     if (c >= 16 * pl->TK && c < ck) ck = (int)c;
   }
+  if (a->num_splits == 0 && S > 1 && a->L_host && a->B > 1) {
+    // The lengths themselves are known: the shortest split (whole tiles, 16 or more) with which the non-empty
+    // splits of the batch still number S * B, counted instead of bounded.
+    const int64_t slots = (int64_t)S * a->B;
+    auto fits = [&](int c) {
+      int64_t n = 0;
+      for (int b = 0; b < a->B; ++b) n += a->L_host[b] > 0 ? ((int64_t)a->L_host[b] + c - 1) / c : 1;
+      return n <= slots;
+    };
+    while (ck - pl->TK >= 16 * pl->TK && fits(ck - pl->TK)) ck -= pl->TK;
+  }
   pl->chunk_keys = ck;
   pl->n_chunks = a->max_L > 0 ? (a->max_L + ck - 1) / ck : 1;
   // one 2 x 2 workgroup per CU at most and long splits: a third ring stage (two tiles in flight)

@@ -256,6 +256,39 @@ def test_length_hint_shortens_long_splits_of_ragged_batches(lib):
     assert lib.tva_plan_splits(ctypes.byref(shape_args(sum_L=-1))) == -1     # the plan reads it: refused
     
 
+def test_host_lengths_give_the_shortest_split_that_fits_one_round(lib):
+    """With the lengths themselves (tva_args.L_host) the planner counts the non-empty splits instead of bounding
+    them: the split length is the smallest multiple of 64 (at least 1024) with sum ceil(L_b / c) <= S * B, never
+    longer than what the sum alone gives; nonsense lengths still give a valid plan."""
+    import numpy as np
+    L = np.array([18040, 28252, 25008, 32165], dtype=np.int32)
+    kw = dict(B=4, max_L=int(L.max()), max_T=48, sum_T=4 * 48)
+    by_sum = binding.plan_chunk_keys(shape_args(sum_L=int(L.sum()), **kw))
+    a = shape_args(sum_L=int(L.sum()), **kw)
+    a.L_host = L.ctypes.data_as(ctypes.c_void_p)
+    c = binding.plan_chunk_keys(a)
+    count = lambda c: int(np.sum(-(-L // c)))
+    assert c % 64 == 0 and 1024 <= c <= by_sum and count(c) <= 32 and count(c - 64) > 32
+    assert (by_sum, c) == (3712, 3584)
+    assert binding.plan_splits(a) == -(-int(L.max()) // c)
+    assert binding.workspace_bytes(a) == binding.plan_splits(a) * 4 * 48 * 32 * 129 * 4
+    # without the sum the count alone does the same; equal lengths, one sequence and forced splits are unchanged
+    b = shape_args(**kw)
+    b.L_host = L.ctypes.data_as(ctypes.c_void_p)
+    assert binding.plan_chunk_keys(b) == c
+    for L2, extra in ((np.full(4, 32165, np.int32), {}), (L, dict(num_splits=8)), (L[3:], dict(B=1, sum_T=48))):
+        d = shape_args(**{**kw, **extra})
+        plain = binding.plan_chunk_keys(d)
+        L2 = np.ascontiguousarray(L2)
+        d.L_host = L2.ctypes.data_as(ctypes.c_void_p)
+        assert binding.plan_chunk_keys(d) == plain
+    for junk in (np.zeros(4, np.int32), np.full(4, -7, np.int32), np.full(4, 2 ** 31 - 1, np.int32)):
+        d = shape_args(**kw)
+        d.L_host = junk.ctypes.data_as(ctypes.c_void_p)
+        ck = binding.plan_chunk_keys(d)
+        assert ck % 64 == 0 and ck >= 1024 and binding.plan_splits(d) == -(-int(L.max()) // ck)
+
+
 def test_fp8_arguments_checked_on_the_host(lib):
     assert binding.plan_splits(shape_args(kv_fp8=1)) >= 1                         # D = 128: fine
     a = shape_args(kv_fp8=1, D=64)

@@ -411,6 +411,32 @@ def test_host_lengths_hint_changes_nothing_but_the_placement(gpu, B, T):
         assert torch.equal(o, base) and torch.equal(l, lbase)
 
 
+@pytest.mark.parametrize("L,T", [([5000, 2300, 7900], 16), ([9000, 20000], 64), ([1500, 1100, 6000, 3000, 200], 40)])
+def test_host_lengths_hint_in_split_launches_matches_oracle(gpu, L, T):
+    """With KV splits the host's lengths shorten the splits (the planner counts the non-empty ones): the outputs
+    agree with the oracle with the hint, without it, and with lengths that are not the batch's."""
+    import torch
+    from paper_2510_26577_amd import binding
+    B = len(L)
+    w = wl.random_workload(700 + B + T, B, 32, 8, 128, np.array(L), T, max_depth=8)
+    say(f"[case] length hint with splits L={L} T={T}")
+    dw = gpu.to_device(w)
+    mask = gpu.build_mask(dw)
+    ro, rl = orc.tree_verify_attn(w)
+    hints = (None, np.ascontiguousarray(w.L, dtype=np.int32), np.full(B, 1234, dtype=np.int32))
+    for hint in hints:
+        o, l = gpu.attention(dw, mask, L_host=hint, sum_L=0 if hint is None else int(w.L.sum()))
+        torch.cuda.synchronize()
+        assert np.abs(o.cpu().numpy().astype(np.float64) - ro).max() <= TOL_O
+        assert np.abs(l.cpu().numpy().astype(np.float64) - rl).max() <= TOL_LSE
+    a = binding.TvaArgs()
+    a.B, a.Hq, a.Hkv, a.D, a.sum_T, a.max_T, a.mask_words, a.max_L = B, 32, 8, 128, B * T, T, (T + 63) // 64, max(L)
+    lens = np.ascontiguousarray(w.L, dtype=np.int32)
+    plain = binding.plan_chunk_keys(a)
+    a.L_host = lens.ctypes.data
+    assert binding.plan_chunk_keys(a) <= plain
+
+
 @pytest.mark.parametrize("splits", [2, 3, 7])
 def test_splits_entry_point_partials_match_oracle_key_ranges(gpu, splits):
     """tva_tree_verify_attn_splits leaves per-split partials that equal the oracle restricted to
