@@ -72,6 +72,12 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
  *                       err_flag like the cases above, and its outputs are unspecified.  Contents unspecified on
  *                       return; calls that share a workspace must not overlap.  Without it: one workgroup per
  *                       sequence, no waits.
+ *   sum_T               the number of nodes of the batch, cu_T[B], as the host knows it, or 0.  With it, and a workspace
+ *                       of tva_sample_workspace_bytes_rows(B, sum_T, V) bytes, the sums of all target rows of a small
+ *                       batch (sum_T * V * 4 bytes up to 40 MB) are made ahead of the walk by a launch that uses the
+ *                       whole chip, and the walk passes an accepted node without a pass over its row (B = 1,
+ *                       V = 128256: a third faster again).  A value that is not cu_T[B] costs time, not correctness:
+ *                       rows past cu_T[B] are not read, and a tree that reaches past sum_T is walked as without it.
  *   workgroups_per_sequence   0: the library chooses (1 .. 16, so that B times it stays within 256; 1 for
  *                       vocabularies below 48 K tokens, where the waits cost what the slices save); 1: as without
  *                       a workspace; 2 .. 16: that many (TVA_UNSUPPORTED if B times it exceeds 256).  The results
@@ -86,10 +92,12 @@ typedef struct tva_sample_args {
   void *workspace;
   size_t workspace_bytes;
   int32_t workgroups_per_sequence;
+  int32_t sum_T;
 } tva_sample_args;
 
 int tva_accept_sampling(const tva_sample_args *a, void *stream);
 size_t tva_sample_workspace_bytes(int32_t B);
+size_t tva_sample_workspace_bytes_rows(int32_t B, int32_t sum_T, int32_t V);  /* the same plus room for the row sums */
 /* For tests of the bounded wait: the same call (workspace given, workgroups_per_sequence >= 2), but every wait expects
  * one arrival more than there are workgroups and gives up after `spins` polls (1 .. 2^20).  Every workgroup then
  * leaves at its first wait: err_flag is set, the other outputs are unspecified, and the kernel ends normally. */

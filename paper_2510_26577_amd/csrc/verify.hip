@@ -16,6 +16,8 @@
 //                   step (they read the same words); the data-parallel part is over the vocabulary: the
 //                   sum of a distribution, the residual after a rejection, the draw of the last token --
 //                   one streaming pass over V floats each.
+//   row_sums_kernel the sums of all target rows of a small batch, ahead of the walk and with the whole chip: the
+//                   walk then passes an accepted node with three loads instead of a pass over its row.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -70,6 +72,14 @@ struct SampleParams {
   float *residual;
   int32_t *path, *path_len, *next_token, *err_flag;
   int V, max_path;
+  // sums of the target rows, made ahead of the walk by row_sums_kernel, or NULL: row t's sum is the sum of
+  // rowpart[t * pieces .. + pieces - 1]; rows 0 .. sum_T-1 have them
+  const double *rowpart;
+  // and, gathered by the same kernel, what a node's test as its parent's FIRST tested child reads: first[2 c] =
+  // p[parent(c)][token(c)], first[2 c + 1] = q[parent(c)][token(c)] (a walk's reads of them would each be a cold,
+  // dependent access to a row of its own)
+  const float *first;
+  int pieces, sum_T;
 };
 
 constexpr int kSampleThreads = 1024, kSampleWaves = kSampleThreads / 64;
@@ -157,6 +167,172 @@ __device__ __forceinline__ double residual_pass(int V, int seg, double *wsum, co
   }
 }
 
+// ---- the sums of all target rows, ahead of the walk ----
+// A walk that accepts a child needs of the parent's row only its sum and two entries; summing the row is the pass
+// that costs.  For a small batch (few trees, few nodes) the sums of ALL nodes' rows cost less when the whole chip
+// makes them at once than the accepted nodes' rows do one after the other.  grid (pieces, rows): a workgroup adds
+// the 8192 tokens of one piece of one row, in a fixed order; rows past cu_T[B] (a host count that was too large)
+// are left alone.  The first workgroup also clears the n_sync arrival counters of the walk that follows (one
+// launch less than with zero_sync_kernel).  One more workgroup per row (piece index = pieces) gathers the two
+// entries of the parent's rows that the node's test reads.
+constexpr int kRowPieceThreads = 256, kRowPiece = kRowPieceThreads * 32;
+
+template <int VEC>
+__global__ void __launch_bounds__(kRowPieceThreads) row_sums_kernel(const float *__restrict__ p, const int32_t *__restrict__ cu_T, int B,
+                                                                    int V, double *__restrict__ rowpart, int *__restrict__ sync,
+                                                                    int n_sync, const float *__restrict__ q,
+                                                                    const int32_t *__restrict__ parent,
+                                                                    const int32_t *__restrict__ token, float *__restrict__ first) {
+  __shared__ double s_w[kRowPieceThreads / 64];
+  const int tid = threadIdx.x, piece = blockIdx.x, row = blockIdx.y;
+  const int pieces = (int)gridDim.x - 1;
+  if (piece == 0 && row == 0)
+    for (int i = tid; i < n_sync; i += kRowPieceThreads) sync[i] = 0;
+  if (row >= cu_T[B]) return;
+  if (piece == pieces) {
+    if (tid != 0) return;
+    // the tree that holds node `row`: the last b with cu_T[b] <= row (empty trees share their start with the next)
+    int lo = 0, hi = B;  // cu_T[lo] <= row < cu_T[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (cu_T[mid] <= row) lo = mid;
+      else hi = mid;
+    }
+    const int t0 = cu_T[lo], par = parent[row], x = token[row];
+    float px = 0.f, qx = 0.f;
+    if (par >= 0 && par < row - t0 && x >= 0 && x < V) {
+      px = p[(size_t)(t0 + par) * V + x];
+      qx = q[(size_t)(t0 + par) * V + x];
+    }
+    first[2 * (size_t)row] = px, first[2 * (size_t)row + 1] = qx;
+    return;
+  }
+  const float *src = p + (size_t)row * V;
+  const int base = piece * kRowPiece;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  if constexpr (VEC == 4) {
+    float4 x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int v = base + i * (4 * kRowPieceThreads) + 4 * tid;
+      x[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (v < V) x[i] = *reinterpret_cast<const float4 *>(src + v);  // (V % 4 == 0: no straddling)
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i & 3] += ((double)x[i].x + (double)x[i].y) + ((double)x[i].z + (double)x[i].w);
+  } else {
+    float x[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const int v = base + i * kRowPieceThreads + tid;
+      x[i] = v < V ? src[v] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i & 3] += (double)x[i];
+  }
+  double z = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) z += __shfl_xor(z, o);
+  if ((tid & 63) == 0) s_w[tid >> 6] = z;
+  __syncthreads();
+  if (tid == 0) rowpart[(size_t)row * pieces + piece] = (s_w[0] + s_w[1]) + (s_w[2] + s_w[3]);
+}
+
+// the sum of row t from its pieces: the lanes of a wave fetch 64 of them at once (one round trip, not one per
+// piece), and every thread adds them in the same order
+__device__ __forceinline__ double summed_ahead(const SampleParams &p, int t) {
+  const double *part = p.rowpart + (size_t)t * p.pieces;
+  const int lane = threadIdx.x & 63;
+  double z = 0.0;
+  for (int base = 0; base < p.pieces; base += 64) {
+    const double mine = base + lane < p.pieces ? part[base + lane] : 0.0;
+    const int n = p.pieces - base < 64 ? p.pieces - base : 64;
+    for (int j = 0; j < n; ++j) z += __shfl(mine, j);
+  }
+  return z;
+}
+
+// The last token, looked for inside [lo, hi): wsum holds the waves' sums of dist over their segments of that range
+// (seg elements each), `before` is the weight in front of lo, `none` says that no place claimed the target (u_final
+// was not below 1): then, and when rounding keeps the running sum below the target, it is the last token of the range
+// that has weight.  The wave whose segment holds it walks the segment 64 elements at a time; its lane 0 stores it.
+__device__ __forceinline__ void draw_in_range(const float *dist, int lo, int hi, int seg, const double *wsum, double before,
+                                              double target, bool none, int32_t *out) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int wclaim = -1, wlast = 0;
+  {
+    double pre = before;
+    for (int i = 0; i < kSampleWaves; ++i) {
+      const double nx = pre + wsum[i];
+      if (wclaim < 0 && !none && nx > target) wclaim = i, before = pre;
+      if (wsum[i] > 0.0) wlast = i;
+      pre = nx;
+    }
+  }
+  const bool wnone = wclaim < 0;
+  if (wnone) wclaim = wlast;
+  if (wave != wclaim) return;
+  const int s0 = lo + wave * seg, s1 = s0 + seg < hi ? s0 + seg : hi;
+  double acc = before;
+  int tok = -1, last_pos = -1;
+  for (int base = s0; base < s1; base += 64) {
+    const int v = base + lane;
+    const float f = v < s1 ? dist[v] : 0.f;
+    double incl = (double)f;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double y = __shfl_up(incl, o);
+      if (lane >= o) incl += y;
+    }
+    const unsigned long long heavy = __ballot(f > 0.f);
+    if (heavy) last_pos = base + 63 - __builtin_clzll(heavy);
+    const unsigned long long over = wnone ? 0ull : __ballot(acc + incl > target);
+    if (over) {
+      tok = base + __builtin_ctzll(over);
+      break;
+    }
+    acc += __shfl(incl, 63);
+  }
+  if (lane == 0) *out = tok >= 0 ? tok : last_pos;
+}
+
+// The last token of a walk that ends at a node whose row was summed ahead (no pass has been made over it): the sums
+// of the row's pieces, added in the order that made Z, say which piece of 8192 tokens holds it; this workgroup sums
+// that piece by segments and draws inside it -- a pass over one piece, not over the row, and no wait for others.
+template <int VEC>
+__device__ __forceinline__ void draw_in_piece(const SampleParams &p, int t, const float *dist, double Z, double u_final, double *wsum,
+                                              int32_t *out) {
+  const int lane = threadIdx.x & 63;
+  const double target = u_final * Z;
+  const double *part = p.rowpart + (size_t)t * p.pieces;
+  int k = -1, klast = 0;
+  double pre = 0.0, before = 0.0;
+  for (int base = 0; base < p.pieces; base += 64) {
+    const double mine = base + lane < p.pieces ? part[base + lane] : 0.0;
+    const int n = p.pieces - base < 64 ? p.pieces - base : 64;
+    for (int j = 0; j < n; ++j) {
+      const double v = __shfl(mine, j);
+      const double nx = pre + v;
+      if (k < 0 && nx > target) k = base + j, before = pre;
+      if (v > 0.0) klast = base + j;
+      pre = nx;
+    }
+  }
+  const bool none = k < 0;
+  if (none) k = klast;
+  const int lo = k * kRowPiece, hi = lo + kRowPiece < p.V ? lo + kRowPiece : p.V;
+  const int seg = ((hi - lo + kSampleWaves - 1) / kSampleWaves + VEC - 1) / VEC * VEC;
+  if constexpr (VEC == 4) {
+    segment_pass<4, 2>(
+        lo, hi, seg, wsum, [&](int v) { return *reinterpret_cast<const float4 *>(dist + v); },
+        [&](int, const float4 &x, double &a) { a += ((double)x.x + (double)x.y) + ((double)x.z + (double)x.w); });
+  } else {
+    segment_pass<1, 8>(
+        lo, hi, seg, wsum, [&](int v) { return dist[v]; }, [&](int, float x, double &a) { a += (double)x; });
+  }
+  draw_in_range(dist, lo, hi, seg, wsum, before, target, none, out);
+}
+
 template <int VEC>
 __global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SampleParams p) {
   __shared__ double wsum[kSampleWaves];
@@ -185,94 +361,73 @@ __global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SamplePara
   if (tid == 0) p.path[(size_t)b * p.max_path] = 0;
   const float *dist;  // what the next test or the last draw reads: the current node's target row, or the residual
   double Z;
+  const bool ahead = p.rowpart != nullptr && t0 + T <= p.sum_T;  // this tree's row sums were made ahead of the walk
+  bool segments;  // wsum holds the segments' sums of dist (the last draw starts from them)
+  auto flag_sequence = [&]() {
+    if (tid == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
+  };
+  // the first child of `of` behind node `after` that carries a token (others are flagged and passed over: never
+  // accepted, and they leave the residual alone), or -1; 64 candidates at a time, every wave finds the same one
+  auto next_child = [&](int of, int after) -> int {
+    for (int base = after + 1; base < T; base += 64) {
+      const int i = base + lane;
+      unsigned long long kids = __ballot(i < T && parent[i] == of);
+      while (kids) {
+        const int c = base + __builtin_ctzll(kids);
+        kids &= kids - 1;
+        const int x = token[c];
+        if (x >= 0 && x < V) return c;
+        flag_sequence();
+      }
+    }
+    return -1;
+  };
   while (true) {
     dist = p.p + (size_t)(t0 + cur) * V;
     const float *q = p.q + (size_t)(t0 + cur) * V;
-    Z = row_sum<VEC>(V, seg, wsum, dist);
+    // the first child and the two entries its test reads: requested before the row's sum, used after it
+    int c = len < p.max_path ? next_child(cur, cur) : -1;
+    float rx0 = 0.f, qx = 0.f;
+    if (c >= 0 && ahead) rx0 = p.first[2 * (size_t)(t0 + c)], qx = p.first[2 * (size_t)(t0 + c) + 1];
+    else if (c >= 0) rx0 = dist[token[c]], qx = q[token[c]];
+    if (ahead) Z = summed_ahead(p, t0 + cur), segments = false;
+    else Z = row_sum<VEC>(V, seg, wsum, dist), segments = true;
+    double rx = (double)rx0;
     bool accepted = false;
-    if (len < p.max_path) {
-      // the children of cur in index order, 64 candidates at a time (every wave finds the same ones)
-      for (int base = cur + 1; base < T && !accepted; base += 64) {
-        const int i = base + lane;
-        unsigned long long kids = __ballot(i < T && parent[i] == cur);
-        while (kids) {
-          const int c = base + __builtin_ctzll(kids);
-          kids &= kids - 1;
-          const int x = token[c];
-          if (x < 0 || x >= V) {  // not a token: flagged, never accepted, leaves the residual alone
-            if (tid == 0 && p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
-            continue;
-          }
-          const double rx = (double)dist[x];
-          if (rx > 0.0 && (double)u[c] * (double)q[x] * Z <= rx) {
-            cur = c;
-            if (tid == 0) p.path[(size_t)b * p.max_path + len] = c;
-            ++len;
-            accepted = true;
-            break;
-          }
-          // rejected: the residual max(0, r - Z q), unnormalised, and its sum
-          __syncthreads();  // every thread has read dist[x] before the residual is overwritten in place
-          const double Zn = residual_pass<VEC>(V, seg, wsum, dist, q, Z, r);
-          if (!(Zn > 0.0)) {
-            // q was not a distribution the child could have been drawn from: flagged; the walk ends here
-            if (tid == 0) {
-              if (p.err_flag) atomicCAS(p.err_flag, 0, 1 + b);
-              p.path_len[b] = len;
-              p.next_token[b] = -1;
-            }
-            return;
-          }
-          Z = Zn;
-          dist = r;
-        }
+    while (c >= 0) {
+      if (rx > 0.0 && (double)u[c] * (double)qx * Z <= rx) {
+        cur = c;
+        if (tid == 0) p.path[(size_t)b * p.max_path + len] = c;
+        ++len;
+        accepted = true;
+        break;
       }
+      // rejected: the residual max(0, r - Z q), unnormalised, and its sum; the next child's entry of the draft's
+      // row (which stays as it is) is requested before the pass
+      const int cn = next_child(cur, c);
+      const int xn = cn >= 0 ? token[cn] : 0;
+      if (cn >= 0) qx = q[xn];
+      __syncthreads();  // every thread has read what it needs of the row before the residual is overwritten in place
+      const double Zn = residual_pass<VEC>(V, seg, wsum, dist, q, Z, r);
+      if (!(Zn > 0.0)) {
+        // q was not a distribution the child could have been drawn from: flagged; the walk ends here
+        flag_sequence();
+        if (tid == 0) p.path_len[b] = len, p.next_token[b] = -1;
+        return;
+      }
+      Z = Zn;
+      dist = r;
+      segments = true;
+      c = cn;
+      if (c >= 0) rx = (double)r[xn];
     }
     if (!accepted) break;
   }
+  if (tid == 0) p.path_len[b] = len;
+  if (!segments) return draw_in_piece<VEC>(p, t0 + cur, dist, Z, (double)p.u_final[b], wsum, &p.next_token[b]);
   // The last token: the smallest v whose cumulative weight exceeds u_final * Z.  The segments' sums of the pass
-  // that produced Z say which segment holds it; that segment's wave walks it 64 elements at a time.
-  const double target = (double)p.u_final[b] * Z;
-  int claim = -1, last_heavy = 0;
-  double before = 0.0;
-  {
-    double pre = 0.0;
-    for (int w = 0; w < kSampleWaves; ++w) {
-      const double nx = pre + wsum[w];
-      if (claim < 0 && nx > target) claim = w, before = pre;
-      if (wsum[w] > 0.0) last_heavy = w;
-      pre = nx;
-    }
-  }
-  const bool none = claim < 0;  // (u_final was not below 1: the last token that has weight)
-  if (none) claim = last_heavy;
-  const int wave = tid >> 6;
-  if (wave != claim) return;
-  const int s0 = wave * seg, s1 = s0 + seg < V ? s0 + seg : V;
-  double acc = before;
-  int tok = -1, last_pos = -1;
-  for (int base = s0; base < s1; base += 64) {
-    const int v = base + lane;
-    const float f = v < s1 ? dist[v] : 0.f;
-    double incl = (double)f;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const double y = __shfl_up(incl, o);
-      if (lane >= o) incl += y;
-    }
-    const unsigned long long heavy = __ballot(f > 0.f);
-    if (heavy) last_pos = base + 63 - __builtin_clzll(heavy);
-    const unsigned long long over = none ? 0ull : __ballot(acc + incl > target);
-    if (over) {
-      tok = base + __builtin_ctzll(over);
-      break;
-    }
-    acc += __shfl(incl, 63);
-  }
-  if (lane == 0) {
-    p.path_len[b] = len;
-    p.next_token[b] = tok >= 0 ? tok : last_pos;  // (rounding kept the running sum below the target: the segment's last)
-  }
+  // that produced Z say which segment holds it.
+  draw_in_range(dist, 0, V, seg, wsum, 0.0, (double)p.u_final[b] * Z, false, &p.next_token[b]);
 }
 
 // ---- the same walk with the vocabulary of a sequence spread over W workgroups ----
@@ -394,28 +549,39 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
   if (w == 0 && tid == 0) p.path[(size_t)b * p.max_path] = 0;
   const float *dist;
   double Z;
+  // the sum of a row from the workgroups' sums of their slices (negative: the others did not arrive)
+  auto row_total = [&](const float *row) -> double {
+    double local;
+    if constexpr (VEC == 4) {
+      local = segment_pass<4, 8>(
+          lo, hi, seg, wsum, [&](int v) { return *reinterpret_cast<const float4 *>(row + v); },
+          [&](int, const float4 &t, double &x) { x += ((double)t.x + (double)t.y) + ((double)t.z + (double)t.w); });
+    } else {
+      local = segment_pass<1, 8>(
+          lo, hi, seg, wsum, [&](int v) { return row[v]; }, [&](int, float t, double &x) { x += (double)t; });
+    }
+    return group_sum(local);
+  };
+  const bool ahead = p.rowpart != nullptr && t0 + T <= p.sum_T;  // this tree's row sums were made ahead of the walk
+  bool segments;  // wsum and s_part hold the sums of dist's segments and slices (the last draw starts from them)
   while (true) {
     const float *prow = p.p + (size_t)(t0 + cur) * V;
     const float *q = p.q + (size_t)(t0 + cur) * V;
     dist = prow;
     double local;
-    if constexpr (VEC == 4) {
-      local = segment_pass<4, 8>(
-          lo, hi, seg, wsum, [&](int v) { return *reinterpret_cast<const float4 *>(prow + v); },
-          [&](int, const float4 &t, double &x) { x += ((double)t.x + (double)t.y) + ((double)t.z + (double)t.w); });
-    } else {
-      local = segment_pass<1, 8>(
-          lo, hi, seg, wsum, [&](int v) { return prow[v]; }, [&](int, float t, double &x) { x += (double)t; });
-    }
-    Z = group_sum(local);
+    // the first child and the two entries its test reads: requested before the row's sum, used after it
+    int c = len < p.max_path ? next_child(cur, cur) : -1;
+    float rx0 = 0.f, qx = 0.f;
+    if (c >= 0 && ahead) rx0 = p.first[2 * (size_t)(t0 + c)], qx = p.first[2 * (size_t)(t0 + c) + 1];
+    else if (c >= 0) rx0 = prow[token[c]], qx = q[token[c]];
+    if (ahead) Z = summed_ahead(p, t0 + cur), segments = false;
+    else Z = row_total(prow), segments = true;
     if (Z < 0.0) return leave_flagged();
     bool accepted = false;
-    if (len < p.max_path) {
-      int c = next_child(cur, cur);
-      double rx = c >= 0 ? (double)prow[token[c]] : 0.0;
+    {
+      double rx = (double)rx0;
       while (c >= 0) {
-        const int x = token[c];
-        if (rx > 0.0 && (double)u[c] * (double)q[x] * Z <= rx) {
+        if (rx > 0.0 && (double)u[c] * (double)qx * Z <= rx) {
           cur = c;
           if (w == 0 && tid == 0) p.path[(size_t)b * p.max_path + len] = c;
           ++len;
@@ -426,6 +592,7 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
         // goes to the others with the partial sum
         const int cn = next_child(cur, c);
         const int xn = cn >= 0 ? token[cn] : -1;
+        if (cn >= 0) qx = q[xn];  // (the draft's row stays as it is: requested before the pass)
         double *xslot = xbase + (epoch & 1) * (kCoopMaxW + 1) + kCoopMaxW;
         const float *from = dist;
         const double Zq = Z;
@@ -467,6 +634,7 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
         }
         Z = Zn;
         dist = r;
+        segments = true;
         rx = s_part[W];
         c = cn;
       }
@@ -474,8 +642,12 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
     if (!accepted) break;
   }
   if (w == 0 && tid == 0) p.path_len[b] = len;
+  if (!segments) {  // (the walk ends at a node whose row was summed ahead: one workgroup draws, from one piece of the row)
+    if (w == 0) draw_in_piece<VEC>(p, t0 + cur, dist, Z, (double)p.u_final[b], wsum, &p.next_token[b]);
+    return;
+  }
   // The last token: the workgroup whose slice holds the smallest v with cumulative weight above u_final * Z, then
-  // the wave of it whose segment does, then 64 elements at a time.
+  // the wave of it whose segment does.
   const double target = (double)p.u_final[b] * Z;
   int claim = -1, last_heavy = 0;
   double before = 0.0;
@@ -490,43 +662,7 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
   }
   const bool none = claim < 0;  // (u_final was not below 1: the last token that has weight)
   if (none) claim = last_heavy;
-  if (w != claim) return;
-  int wclaim = -1, wlast = 0;
-  {
-    double pre = before;
-    for (int i = 0; i < kSampleWaves; ++i) {
-      const double nx = pre + wsum[i];
-      if (wclaim < 0 && !none && nx > target) wclaim = i, before = pre;
-      if (wsum[i] > 0.0) wlast = i;
-      pre = nx;
-    }
-  }
-  const bool wnone = wclaim < 0;  // (rounding, or no claim at all: the slice's last token that has weight)
-  if (wnone) wclaim = wlast;
-  const int wave = tid >> 6;
-  if (wave != wclaim) return;
-  const int s0 = lo + wave * seg, s1 = s0 + seg < hi ? s0 + seg : hi;
-  double acc = before;
-  int tok = -1, last_pos = -1;
-  for (int base = s0; base < s1; base += 64) {
-    const int v = base + lane;
-    const float f = v < s1 ? dist[v] : 0.f;
-    double incl = (double)f;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const double y = __shfl_up(incl, o);
-      if (lane >= o) incl += y;
-    }
-    const unsigned long long heavy = __ballot(f > 0.f);
-    if (heavy) last_pos = base + 63 - __builtin_clzll(heavy);
-    const unsigned long long over = wnone ? 0ull : __ballot(acc + incl > target);
-    if (over) {
-      tok = base + __builtin_ctzll(over);
-      break;
-    }
-    acc += __shfl(incl, 63);
-  }
-  if (lane == 0) p.next_token[b] = tok >= 0 ? tok : last_pos;
+  if (w == claim) draw_in_range(dist, lo, hi, seg, wsum, before, target, none, &p.next_token[b]);
 }
 
 // Workgroups per sequence: as many as keep the launch within one workgroup per compute unit (all of them resident at
@@ -544,6 +680,18 @@ int sample_workgroups(const tva_sample_args *a) {
     if ((int64_t)a->B * W > 256) return TVA_UNSUPPORTED;  // more than the chip holds at once
   }
   return W;
+}
+
+// Row sums ahead of the walk: where the host gave the number of nodes, the workspace has room behind the waits'
+// words, and all rows together are few enough bytes (40 MB: 5 .. 8 us with the whole chip, what the passes over two
+// accepted nodes' rows cost one after the other).
+constexpr int64_t kRowSumsMaxBytes = 40 << 20;
+inline int row_pieces(int V) { return (V + kRowPiece - 1) / kRowPiece; }
+inline size_t row_sums_offset(int B) { return (size_t)B * 512; }
+bool sums_ahead(const tva_sample_args *a) {
+  if (a->sum_T <= 0 || !a->workspace || ((uintptr_t)a->workspace & 7)) return false;
+  if ((int64_t)a->sum_T * a->V * (int64_t)sizeof(float) > kRowSumsMaxBytes || a->sum_T > 65535) return false;
+  return a->workspace_bytes >= row_sums_offset(a->B) + (size_t)a->sum_T * (row_pieces(a->V) * sizeof(double) + 2 * sizeof(float));
 }
 
 struct CommitParams {
@@ -675,12 +823,29 @@ static int accept_sampling_impl(const tva_sample_args *a, void *stream, int miss
   p.residual = a->residual;
   p.path = a->path, p.path_len = a->path_len, p.next_token = a->next_token, p.err_flag = a->err_flag;
   p.V = a->V, p.max_path = a->max_path;
+  p.rowpart = nullptr, p.first = nullptr, p.pieces = row_pieces(a->V), p.sum_T = 0;
   // groups of four need every row to start on 16 bytes
   const bool vec = a->V % 4 == 0 && (((uintptr_t)a->p_target | (uintptr_t)a->q_draft | (uintptr_t)a->residual) & 15) == 0;
+  if (a->sum_T < 0) return TVA_INVALID_ARG;
   const int W = sample_workgroups(a);
   if (W < 0) return W;
   (void)hipGetLastError();  // the status below is these launches'
   hipStream_t st = (hipStream_t)stream;
+  const bool ahead = sums_ahead(a);
+  if (ahead) {
+    double *rowpart = reinterpret_cast<double *>(static_cast<char *>(a->workspace) + row_sums_offset(a->B));
+    int *sync = static_cast<int *>(a->workspace);
+    const int n_sync = W > 1 ? a->B * 32 : 0;  // (the arrival counters of the walk start at zero)
+    float *first = reinterpret_cast<float *>(rowpart + (size_t)a->sum_T * p.pieces);
+    const dim3 grid(p.pieces + 1, a->sum_T);
+    if (vec)
+      hipLaunchKernelGGL(row_sums_kernel<4>, grid, dim3(kRowPieceThreads), 0, st, a->p_target, a->cu_T, a->B, a->V, rowpart, sync, n_sync,
+                         a->q_draft, a->parent, a->draft_token, first);
+    else
+      hipLaunchKernelGGL(row_sums_kernel<1>, grid, dim3(kRowPieceThreads), 0, st, a->p_target, a->cu_T, a->B, a->V, rowpart, sync, n_sync,
+                         a->q_draft, a->parent, a->draft_token, first);
+    p.rowpart = rowpart, p.first = first, p.sum_T = a->sum_T;
+  }
   if (W == 1) {
     if (vec) hipLaunchKernelGGL(sample_kernel<4>, dim3(a->B), dim3(kSampleThreads), 0, st, p);
     else hipLaunchKernelGGL(sample_kernel<1>, dim3(a->B), dim3(kSampleThreads), 0, st, p);
@@ -690,7 +855,7 @@ static int accept_sampling_impl(const tva_sample_args *a, void *stream, int miss
     cp.sync = static_cast<int *>(a->workspace);
     cp.xchg = reinterpret_cast<double *>(static_cast<char *>(a->workspace) + (size_t)a->B * 128);
     // the arrival counters start at zero (a kernel, not a memset node: the call may be captured into a graph)
-    hipLaunchKernelGGL(zero_sync_kernel, dim3((a->B * 32 + 255) / 256), dim3(256), 0, st, cp.sync, a->B * 32);
+    if (!ahead) hipLaunchKernelGGL(zero_sync_kernel, dim3((a->B * 32 + 255) / 256), dim3(256), 0, st, cp.sync, a->B * 32);
     if (vec) hipLaunchKernelGGL(sample_coop_kernel<4>, dim3(a->B * W), dim3(kSampleThreads), 0, st, cp);
     else hipLaunchKernelGGL(sample_coop_kernel<1>, dim3(a->B * W), dim3(kSampleThreads), 0, st, cp);
   }
@@ -698,6 +863,11 @@ static int accept_sampling_impl(const tva_sample_args *a, void *stream, int miss
 }
 
 size_t tva_sample_workspace_bytes(int32_t B) { return B < 0 ? (size_t)-1 : (size_t)B * 512; }
+
+size_t tva_sample_workspace_bytes_rows(int32_t B, int32_t sum_T, int32_t V) {
+  if (B < 0 || sum_T < 0 || V < 1) return (size_t)-1;
+  return row_sums_offset(B) + (size_t)sum_T * (row_pieces(V) * sizeof(double) + 2 * sizeof(float));  // sums, then entries
+}
 
 size_t tva_sizeof_sample_args(void) { return sizeof(tva_sample_args); }
 

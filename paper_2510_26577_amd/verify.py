@@ -29,7 +29,7 @@ class SampleArgs(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("V", ctypes.c_int32), ("max_path", ctypes.c_int32)] + \
                [(n, ctypes.c_void_p) for n in ("parent", "cu_T", "draft_token", "p_target", "q_draft", "u", "u_final",
                                                "residual", "path", "path_len", "next_token", "err_flag", "workspace")] + \
-               [("workspace_bytes", ctypes.c_size_t), ("workgroups_per_sequence", ctypes.c_int32)]
+               [("workspace_bytes", ctypes.c_size_t), ("workgroups_per_sequence", ctypes.c_int32), ("sum_T", ctypes.c_int32)]
 
 
 def _lib():
@@ -49,6 +49,8 @@ def _lib():
         lib.tva_accept_sampling_wait_bound_test.argtypes = [ctypes.POINTER(SampleArgs), ctypes.c_int32, vp]
         lib.tva_sample_workspace_bytes.restype = ctypes.c_size_t
         lib.tva_sample_workspace_bytes.argtypes = [ctypes.c_int32]
+        lib.tva_sample_workspace_bytes_rows.restype = ctypes.c_size_t
+        lib.tva_sample_workspace_bytes_rows.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         if lib.tva_sizeof_sample_args() != ctypes.sizeof(SampleArgs):
             raise RuntimeError("libtva.so is stale: rebuild it")
         if lib.tva_sizeof_commit_args() != ctypes.sizeof(CommitArgs):
@@ -75,11 +77,13 @@ def accept_greedy(parent, cu_T, draft_token, target_token, max_path: int, path=N
 
 
 def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, max_path: int, residual=None,
-                    err_flag=None, stream=None, workspace="auto", workgroups_per_sequence: int = 0, wait_bound_test_spins: int = 0):
+                    err_flag=None, stream=None, workspace="auto", workgroups_per_sequence: int = 0, wait_bound_test_spins: int = 0,
+                    sum_T: int = 0):
     """Device tensors in (int32 trees and tokens, float32 distributions [sum_T, V] and uniform numbers); returns
     (path [B, max_path], path_len [B], next_token [B]).  workspace: "auto" allocates the one that lets several
-    workgroups share a sequence, None runs one workgroup per sequence, or a device tensor of
-    tva_sample_workspace_bytes(B) bytes."""
+    workgroups share a sequence (and, with sum_T, holds the row sums made ahead of the walk), None runs one
+    workgroup per sequence, or a device tensor of tva_sample_workspace_bytes[_rows] bytes.  sum_T: the host's
+    count of the batch's nodes (cu_T[B]), or 0."""
     import torch
     B, V = cu_T.numel() - 1, int(p_target.shape[1])
     dev = cu_T.device
@@ -94,10 +98,12 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
     a.p_target, a.q_draft, a.u, a.u_final = _p(p_target), _p(q_draft), _p(u), _p(u_final)
     a.residual, a.path, a.path_len, a.next_token, a.err_flag = _p(residual), _p(path), _p(path_len), _p(next_token), _p(err_flag)
     if isinstance(workspace, str):
-        workspace = torch.empty(max(1, _lib().tva_sample_workspace_bytes(B) // 8), dtype=torch.int64, device=dev)
+        workspace = torch.empty(max(1, _lib().tva_sample_workspace_bytes_rows(B, int(sum_T), V) // 8), dtype=torch.int64,
+                                device=dev)
     if workspace is not None:
         a.workspace, a.workspace_bytes = _p(workspace), workspace.numel() * workspace.element_size()
     a.workgroups_per_sequence = int(workgroups_per_sequence)
+    a.sum_T = int(sum_T)
     if wait_bound_test_spins:                 # (tests of the bounded wait: every wait misses one arrival and gives up)
         _check(_lib().tva_accept_sampling_wait_bound_test(ctypes.byref(a), int(wait_bound_test_spins), _stream_ptr(stream)))
     else:
@@ -236,6 +242,8 @@ def _bench_sampling(steps: int) -> None:
     gen.manual_seed(78)
     stream = torch.cuda.Stream()
     for name, B, T, V, depth in (("B=1 T=60 V=32000", 1, 60, 32000, 6), ("B=1 T=60 V=128256", 1, 60, 128256, 6),
+                                 ("B=1 T=8 V=128256", 1, 8, 128256, 6), ("B=4 T=16 V=128256", 4, 16, 128256, 6),
+                                 ("B=8 T=8 V=128256", 8, 8, 128256, 6),
                                  ("B=8 T=32 V=128256", 8, 32, 128256, 6), ("B=64 T=8 V=128256", 64, 8, 128256, 8),
                                  ("B=64 T=60 V=32000", 64, 60, 32000, 6)):
         copies = 4
@@ -255,7 +263,8 @@ def _bench_sampling(steps: int) -> None:
                         u=torch.rand(B * T, generator=gen, device="cuda"), uf=torch.rand(B, generator=gen, device="cuda"),
                         residual=torch.empty((B, V), dtype=torch.float32, device="cuda"),
                         flag=torch.zeros(1, dtype=torch.int32, device="cuda"),
-                        ws=torch.empty(max(1, _lib().tva_sample_workspace_bytes(B) // 8), dtype=torch.int64, device="cuda"))
+                        ws=torch.empty(max(1, _lib().tva_sample_workspace_bytes_rows(B, B * T, V) // 8), dtype=torch.int64,
+                                       device="cuda"))
             path, plen, _ = accept_sampling(case["parent"], case["cu_T"], tok, p, q, case["u"], case["uf"], depth + 1,
                                             residual=case["residual"], err_flag=case["flag"], workspace=case["ws"])
             torch.cuda.synchronize()
@@ -272,13 +281,16 @@ def _bench_sampling(steps: int) -> None:
             cases.append(case)
         sums, rejs = sums / copies, rejs / copies
 
-        def run(shared):
+        # the three forms: row sums ahead of the walk where the library sees fit (the host's node count given), several
+        # workgroups per sequence without them, one workgroup per sequence
+        def run(form):
             for k in cases:
                 accept_sampling(k["parent"], k["cu_T"], k["tok"], k["p"], k["q"], k["u"], k["uf"], depth + 1,
-                                residual=k["residual"], err_flag=k["flag"], stream=stream, workspace=k["ws"] if shared else None)
+                                residual=k["residual"], err_flag=k["flag"], stream=stream,
+                                workspace=None if form == "one" else k["ws"], sum_T=B * T if form == "ahead" else 0)
 
         times = {}
-        for shared in (True, False):
+        for shared in ("ahead", "shared", "one"):
             with torch.cuda.stream(stream):
                 run(shared)
                 stream.synchronize()
@@ -300,8 +312,9 @@ def _bench_sampling(steps: int) -> None:
             assert all(int(k["flag"].item()) == 0 for k in cases)
         moved = 4.0 * V * (sums + 3 * rejs + B / 16.0)   # a sum reads a row; a residual reads two and writes one; the draw a segment
         print(json.dumps({"shape": name, "accepted_nodes_per_step": sums, "refused_children_per_step": rejs,
-                          "sampling_us": times[True], "sampling_us_one_workgroup_per_sequence": times[False],
-                          "vocabulary_bytes": moved, "GBps": moved / (times[True] * 1e-6) / 1e9}), flush=True)
+                          "sampling_us": times["ahead"], "sampling_us_without_the_node_count": times["shared"],
+                          "sampling_us_one_workgroup_per_sequence": times["one"],
+                          "vocabulary_bytes": moved, "GBps": moved / (times["shared"] * 1e-6) / 1e9}), flush=True)
         del cases
         torch.cuda.empty_cache()
 

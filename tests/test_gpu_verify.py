@@ -459,9 +459,10 @@ def test_commit_of_an_8bit_cache(torch_dev, page_size):
 
 # ---- acceptance by speculative sampling ----
 
-def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True, misalign=False, workgroups=0):
+def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True, misalign=False, workgroups=0, sum_T=0):
     """workgroups: 0 = the library spreads a sequence over as many workgroups as it sees fit, 1 = one per sequence
-    (no workspace passed), 2 .. 16 = that many."""
+    (no workspace passed, unless sum_T asks for the row sums ahead of the walk), 2 .. 16 = that many.
+    sum_T: the host's count of nodes (0 = not given: no row sums ahead of the walk)."""
     from paper_2510_26577_amd import verify
     d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
     flag = torch.zeros(1, dtype=torch.int32, device="cuda") if with_flag else None
@@ -476,7 +477,8 @@ def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True
         dp, dq = shifted
     path, n, nxt = verify.accept_sampling(d(parent, np.int32), d(cu_T, np.int32), d(tok, np.int32), dp,
                                           dq, d(u, np.float32), d(uf, np.float32), max_path, err_flag=flag,
-                                          workspace=None if workgroups == 1 else "auto", workgroups_per_sequence=workgroups)
+                                          workspace=None if workgroups == 1 and not sum_T else "auto",
+                                          workgroups_per_sequence=workgroups, sum_T=sum_T)
     torch.cuda.synchronize()
     return path.cpu().numpy(), n.cpu().numpy(), nxt.cpu().numpy(), (int(flag.item()) if with_flag else 0)
 
@@ -530,12 +532,17 @@ def test_accept_sampling_matches_oracle(torch_dev, B, T_hi, V, temp, drift):
         for workgroups in (0, 1, 2, 16) if max_path != 3 else (0, 1):
             if B * workgroups > 256:
                 continue
-            path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, workgroups=workgroups)
-            assert flag == 0, workgroups
-            assert list(n) == [len(x) for x in ref_paths], workgroups
-            assert list(nxt) == ref_next, workgroups
-            for b, x in enumerate(ref_paths):
-                assert list(path[b, :len(x)]) == x, workgroups
+            # the row sums made ahead of the walk (the host's node count given): the right count, one that is too
+            # small (the trees past it are walked without) and one that is too large (no row is read past the last)
+            for sum_T in (0, int(cu_T[-1])) + ((int(cu_T[-1]) // 2 + 1, int(cu_T[-1]) + 37) if workgroups in (0, 2) else ()):
+                path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, workgroups=workgroups,
+                                                  sum_T=sum_T)
+                case = (workgroups, sum_T)
+                assert flag == 0, case
+                assert list(n) == [len(x) for x in ref_paths], case
+                assert list(nxt) == ref_next, case
+                for b, x in enumerate(ref_paths):
+                    assert list(path[b, :len(x)]) == x, case
         longest = max(longest, max(len(x) for x in ref_paths))
         if max_path == 3 and V % 4 == 0:         # rows that do not start on 16 bytes take the one-element path
             path2, n2, nxt2, flag2 = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, misalign=True)
@@ -563,9 +570,9 @@ def test_accept_sampling_rejections_reach_the_residual(torch_dev):
     ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf)
     assert [len(x) for x in ref_paths] == [1, 2] * (B // 2)
     say(f"[case] accept_sampling star B={B} k={k} V={V}")
-    for workgroups in (1, 4):
-        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, k + 1, workgroups=workgroups)
-        assert flag == 0 and list(n) == [1, 2] * (B // 2) and list(nxt) == ref_next, workgroups
+    for workgroups, sum_T in ((1, 0), (4, 0), (1, B * (k + 1)), (4, B * (k + 1))):
+        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, k + 1, workgroups=workgroups, sum_T=sum_T)
+        assert flag == 0 and list(n) == [1, 2] * (B // 2) and list(nxt) == ref_next, (workgroups, sum_T)
     path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, k + 1)
     assert flag == 0 and list(n) == [1, 2] * (B // 2) and list(nxt) == ref_next
     for b in range(0, B, 2):
@@ -589,9 +596,9 @@ def test_accept_sampling_flags_bad_input_and_leaves_other_sequences_alone(torch_
     # sequence 1: its first child's token is not a token
     tok1 = tok.copy()
     tok1[4] = V + 5
-    for workgroups in (1, 2):
-        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok1, p, q, u, uf, 4, workgroups=workgroups)
-        assert flag == 2 and n[1] == 1 and 0 <= nxt[1] < V, workgroups
+    for workgroups, sum_T in ((1, 0), (2, 0), (1, 8), (2, 8)):
+        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok1, p, q, u, uf, 4, workgroups=workgroups, sum_T=sum_T)
+        assert flag == 2 and n[1] == 1 and 0 <= nxt[1] < V, (workgroups, sum_T)
     path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok1, p, q, u, uf, 4)
     assert flag == 2
     assert [int(nxt[0]), int(nxt[2])] == [ref_next[0], ref_next[2]] and [int(n[0]), int(n[2])] == [len(ref_paths[0]), len(ref_paths[2])]
@@ -602,9 +609,9 @@ def test_accept_sampling_flags_bad_input_and_leaves_other_sequences_alone(torch_
     u2[7] = np.float32(1.5)
     with pytest.raises(ValueError):
         vo.accept_sampling(parent, cu_T, tok, p, q2, u2, uf)
-    for workgroups in (1, 2):
-        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q2, u2, uf, 4, workgroups=workgroups)
-        assert flag == 3 and nxt[2] == -1 and n[2] == 1, workgroups
+    for workgroups, sum_T in ((1, 0), (2, 0), (1, 8), (2, 8)):
+        path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q2, u2, uf, 4, workgroups=workgroups, sum_T=sum_T)
+        assert flag == 3 and nxt[2] == -1 and n[2] == 1, (workgroups, sum_T)
     path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q2, u2, uf, 4)
     assert flag == 3 and nxt[2] == -1 and n[2] == 1
     assert [int(nxt[0]), int(nxt[1])] == ref_next[:2]
