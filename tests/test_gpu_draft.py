@@ -214,10 +214,12 @@ def test_a_tree_grown_and_cut_on_the_gpu_is_the_oracles_and_feeds_the_attention(
     assert all(int(mask[b * m, 0]) == 1 for b in range(B))             # node 0 of every tree is its own only ancestor
 
 
-def test_draft_and_sampling_kernels_replayed_from_a_graph(torch_dev):
+@pytest.mark.parametrize("node_count", [False, True])
+def test_draft_and_sampling_kernels_replayed_from_a_graph(torch_dev, node_count):
     """tva_expand_layer, tva_tree_select_subtree and tva_accept_sampling (several workgroups per sequence: a
-    counter-zeroing kernel, then the walk with its waits) captured in one HIP graph: every replay, with the outputs
-    and the scratch memory overwritten by eager work in between, reproduces the eager results bit for bit."""
+    counter-zeroing kernel -- with the host's node count the kernel that sums the rows ahead of the walk -- then the
+    walk with its waits) captured in one HIP graph: every replay, with the outputs and the scratch memory overwritten
+    by eager work in between, reproduces the eager results bit for bit."""
     torch = torch_dev
     from paper_2510_26577_amd import draft, verify
     from oracle import verify_oracle as vo
@@ -252,7 +254,8 @@ def test_draft_and_sampling_kernels_replayed_from_a_graph(torch_dev):
     sargs = (d(s_parent, np.int32), d(s_cu_T, np.int32), d(tok, np.int32), d(p, np.float32), d(q, np.float32), d(u, np.float32),
              d(uf, np.float32), 6)
     residual = torch.empty((2, Vs), dtype=torch.float32, device="cuda")
-    sws = torch.empty(2 * 512 // 8, dtype=torch.int64, device="cuda")
+    sum_T = int(s_cu_T[-1]) if node_count else 0
+    sws = torch.empty(verify._lib().tva_sample_workspace_bytes_rows(2, sum_T, Vs) // 8, dtype=torch.int64, device="cuda")
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
     results = {}
 
@@ -260,7 +263,7 @@ def test_draft_and_sampling_kernels_replayed_from_a_graph(torch_dev):
         draft.expand_layer_raw(eargs, stream)
         draft.select_subtree(t_score, t_parent, d_cu_M, d_cu_T, max(sizes), old_index=old, new_parent=newp, err_flag=flag, stream=stream)
         results["path"], results["n"], results["next"] = verify.accept_sampling(
-            *sargs, residual=residual, err_flag=flag, stream=stream, workspace=sws, workgroups_per_sequence=8)
+            *sargs, residual=residual, err_flag=flag, stream=stream, workspace=sws, workgroups_per_sequence=8, sum_T=sum_T)
 
     say("[case] draft + sampling kernels, eager")
     one_pass()
