@@ -75,8 +75,8 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
  *   sum_T               the number of nodes of the batch, cu_T[B], as the host knows it, or 0.  With it, and a workspace
  *                       of tva_sample_workspace_bytes_rows(B, sum_T, V) bytes, the sums of all target rows of a small
  *                       batch (sum_T * V * 4 bytes up to 40 MB) are made ahead of the walk by a launch that uses the
- *                       whole chip, and the walk passes an accepted node without a pass over its row (B = 1,
- *                       V = 128256: a third faster again).  A value that is not cu_T[B] costs time, not correctness:
+ *                       whole chip, and the walk passes an accepted node without a pass over its row (V = 128256,
+ *                       B = 1 .. 8: 6 to 26 % faster again).  A value that is not cu_T[B] costs time, not correctness:
  *                       rows past cu_T[B] are not read, and a tree that reaches past sum_T is walked as without it.
  *   workgroups_per_sequence   0: the library chooses (1 .. 16, so that B times it stays within 256; 1 for
  *                       vocabularies below 48 K tokens, where the waits cost what the slices save); 1: as without
