@@ -219,6 +219,14 @@ int32_t tva_plan_splits(const tva_args *a);
 int32_t tva_plan_chunk_keys(const tva_args *a);
 
 /*
+ * Which sequence each workgroup slot of the launch takes when tva_args.L_host is given and the launch is one the
+ * placement hint applies to (see L_host): writes slot_seq[0 .. n-1] (HOST int32, room for 64), a permutation of
+ * 0 .. n-1 with n = B, and returns n; returns 0 (nothing written) when the sequences keep their order, -1 on
+ * invalid arguments.  For tests and tools.
+ */
+int32_t tva_plan_slot_sequences(const tva_args *a, int32_t *slot_seq);
+
+/*
  * Query rows (tree nodes x query heads of one KV head) one workgroup of the attention kernel
  * covers for these shapes: 32, 64, 128 or 256.  With tva_plan_splits it names the launch
  * (workgroups = B * Hkv * ceil(max_T * Hq / Hkv / rows) * splits); meant for tools that tune

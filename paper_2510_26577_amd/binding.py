@@ -76,7 +76,7 @@ class TvaArgs(ctypes.Structure):
     ]
 
 
-EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys", "tva_plan_workgroup_rows",
+EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_workspace_bytes", "tva_plan_splits", "tva_plan_chunk_keys", "tva_plan_workgroup_rows", "tva_plan_slot_sequences",
            "tva_tree_verify_attn", "tva_tree_verify_attn_static", "tva_static_scratch_bytes", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args", "tva_timeline_read")
 # entry points of include/tva_verify.h (bound in verify.py)
 DRAFT_EXPORTS = ("tva_expand_workspace_bytes", "tva_expand_layer", "tva_sizeof_expand_args", "tva_tree_select_subtree")
@@ -125,6 +125,8 @@ def load_library():
     lib.tva_plan_splits.argtypes = [ctypes.POINTER(TvaArgs)]
     lib.tva_plan_chunk_keys.restype = ctypes.c_int32
     lib.tva_plan_chunk_keys.argtypes = [ctypes.POINTER(TvaArgs)]
+    lib.tva_plan_slot_sequences.restype = ctypes.c_int32
+    lib.tva_plan_slot_sequences.argtypes = [ctypes.POINTER(TvaArgs), ctypes.POINTER(ctypes.c_int32)]
     lib.tva_plan_workgroup_rows.restype = ctypes.c_int32
     lib.tva_plan_workgroup_rows.argtypes = [ctypes.POINTER(TvaArgs)]
     lib.tva_tree_verify_attn.restype = ctypes.c_int
@@ -264,6 +266,15 @@ def plan_chunk_keys(args: TvaArgs) -> int:
     if n < 0:
         raise TvaError(-1)
     return int(n)
+
+
+def plan_slot_sequences(args: TvaArgs):
+    """The sequence each workgroup slot takes (a list, empty when the sequences keep their order)."""
+    out = (ctypes.c_int32 * 64)()
+    n = load_library().tva_plan_slot_sequences(ctypes.byref(args), out)
+    if n < 0:
+        raise TvaError(-1)
+    return list(out[:n])
 
 
 def plan_workgroup_rows(args: TvaArgs) -> int:

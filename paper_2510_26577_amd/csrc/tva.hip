@@ -1478,6 +1478,16 @@ int32_t tva_plan_chunk_keys(const tva_args *a) {
   return pl.chunk_keys;
 }
 
+int32_t tva_plan_slot_sequences(const tva_args *a, int32_t *slot_seq) {
+  if (check_args(a, true) != TVA_OK || !slot_seq) return -1;
+  Plan pl;
+  if (!make_plan(a, &pl)) return -1;
+  AttnParams p;
+  fill_slots(a, pl, &p);
+  for (int j = 0; j < p.pair_slots; ++j) slot_seq[j] = (int32_t)((p.slot_seq[j >> 2] >> (8 * (j & 3))) & 0xFFu);
+  return p.pair_slots;
+}
+
 int32_t tva_plan_workgroup_rows(const tva_args *a) {
   if (check_args(a, true) != TVA_OK) return -1;
   Plan pl;

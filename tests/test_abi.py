@@ -289,6 +289,40 @@ def test_host_lengths_give_the_shortest_split_that_fits_one_round(lib):
         assert ck % 64 == 0 and ck >= 1024 and binding.plan_splits(d) == -(-int(L.max()) // ck)
 
 
+def test_slot_table_is_a_permutation_that_pairs_long_with_short(lib):
+    """tva_args.L_host in an unsplit launch of 33 .. 64 sequences, 8 KV heads, at most 64 rows per KV head: the slot
+    table is a permutation of the sequences whatever the lengths are (ties, zeros, nonsense); slots j and j + 32
+    (one CU) hold the sequences of ranks r and 63 - r by length, the CUs with one slot the longest ones; every
+    other launch leaves the order alone."""
+    import numpy as np
+    rng = np.random.Generator(np.random.PCG64(5))
+    for n in list(range(33, 65)) + [64, 64]:
+        L = rng.integers(0, 3000, size=n).astype(np.int32)
+        if n % 5 == 0:
+            L[: n // 2] = 777                                  # ties
+        if n == 64:
+            L = rng.integers(-2 ** 31, 2 ** 31 - 1, size=n).astype(np.int32)
+        a = shape_args(B=n, max_L=3000, max_T=8, sum_T=8 * n)
+        assert binding.plan_slot_sequences(a) == []            # no lengths given
+        a.L_host = L.ctypes.data_as(ctypes.c_void_p)
+        if binding.plan_splits(a) != 1:
+            continue
+        seq = binding.plan_slot_sequences(a)
+        assert sorted(seq) == list(range(n)), n
+        order = sorted(range(n), key=lambda i: (-int(L[i]), i))   # longest first, the lower index among equals
+        rank = {s_: r for r, s_ in enumerate(order)}
+        shared = n - 32
+        for j in range(shared):
+            assert rank[seq[j]] + rank[seq[j + 32]] == 63, (n, j)
+        assert sorted(rank[seq[j]] for j in range(shared, 32)) == list(range(64 - n)), n
+    L = np.arange(80, dtype=np.int32)
+    for kw in (dict(B=32), dict(B=64, Hkv=4), dict(B=64, max_T=40, sum_T=64 * 40), dict(B=64, num_splits=2), dict(B=65, sum_T=65 * 8)):
+        a = shape_args(**{**dict(max_L=3000, max_T=8, sum_T=8 * 64), **kw})
+        a.L_host = L.ctypes.data_as(ctypes.c_void_p)
+        assert binding.plan_slot_sequences(a) == [], kw
+    assert lib.tva_plan_slot_sequences(ctypes.byref(shape_args()), None) == -1
+
+
 def test_fp8_arguments_checked_on_the_host(lib):
     assert binding.plan_splits(shape_args(kv_fp8=1)) >= 1                         # D = 128: fine
     a = shape_args(kv_fp8=1, D=64)
