@@ -62,8 +62,8 @@ def attention(dw: DeviceWorkload, mask, num_splits: int = 0, max_L: Optional[int
         kv_fp8=fp8, k_scale=k_scale, v_scale=v_scale, sum_L=sum_L, plan_shape=plan_shape, L_host=L_host)
 
 
-def run_path(dw: DeviceWorkload, num_splits: int = 0, sum_L: int = 0, plan_shape: int = 0):
+def run_path(dw: DeviceWorkload, num_splits: int = 0, sum_L: int = 0, plan_shape: int = 0, L_host=None):
     """The whole hot path once: ancestor masks, split-KV attention, merge."""
     mask = build_mask(dw)
-    out, lse = attention(dw, mask, num_splits=num_splits, sum_L=sum_L, plan_shape=plan_shape)
+    out, lse = attention(dw, mask, num_splits=num_splits, sum_L=sum_L, plan_shape=plan_shape, L_host=L_host)
     return mask, out, lse

@@ -29,12 +29,15 @@ def say(msg):
     print(msg, flush=True)
 
 
-def check(gpu, w8, ks, vs, num_splits=0, derive=False, label="", plan_shape=0):
+def check(gpu, w8, ks, vs, num_splits=0, derive=False, label="", plan_shape=0, hints=False):
+    """hints: the host's copy of the cache lengths and their sum are passed, as the benchmark does."""
     import torch
-    say(f"[case] fp8 {label} B={w8.B} T={list(w8.T[:6])} L={list(w8.L[:6])} paged={w8.paged} splits={num_splits}")
+    say(f"[case] fp8 {label} B={w8.B} T={list(w8.T[:6])} L={list(w8.L[:6])} paged={w8.paged} splits={num_splits} hints={hints}")
     dw = gpu.to_device(w8)
     mask = None if derive else gpu.build_mask(dw)
-    out, lse = gpu.attention(dw, mask, num_splits=num_splits, k_scale=ks, v_scale=vs, plan_shape=plan_shape)
+    lens = np.ascontiguousarray(w8.L, dtype=np.int32)
+    out, lse = gpu.attention(dw, mask, num_splits=num_splits, k_scale=ks, v_scale=vs, plan_shape=plan_shape,
+                             sum_L=int(lens.sum()) if hints else 0, L_host=lens if hints else None)
     torch.cuda.synchronize()
     ro, rl = f8.tree_verify_attn_fp8(w8, ks, vs)
     o, l = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
@@ -74,14 +77,15 @@ def test_every_code_is_widened_exactly(gpu):
     check(gpu, w8, 1.0 / 4096, 1.0 / 128, label="all codes")
 
 
-@pytest.mark.parametrize("B,L,T", [(1, 2048, 60), (16, 2048, 16), (8, 2048, 60), (40, 700, 8)])
-def test_fp8_benchmark_like_shapes(gpu, B, L, T):
+@pytest.mark.parametrize("hints", [False, True])
+@pytest.mark.parametrize("B,L,T", [(1, 2048, 60), (16, 2048, 16), (8, 2048, 60), (40, 700, 8), (64, 900, 8)])
+def test_fp8_benchmark_like_shapes(gpu, B, L, T, hints):
     rng = np.random.Generator(np.random.PCG64(B + L + T))
     Ls = rng.integers(L // 2, L + 1, B)
     Ls[0] = L
     w = wl.random_workload(1320 + B, B, 32, 8, 128, Ls, T, max_depth=8)
     w8, ks, vs = wl.to_fp8_kv(w)
-    check(gpu, w8, ks, vs, label="benchmark-like")
+    check(gpu, w8, ks, vs, label="benchmark-like", hints=hints)
 
 
 def test_fp8_rejects_head_dimension_64(gpu):

@@ -30,12 +30,15 @@ def say(msg):
     sys.stdout.flush()
 
 
-def check_full(device, w, num_splits=0, label="", plan_shape=0):
+def check_full(device, w, num_splits=0, label="", plan_shape=0, hints=False):
+    """hints: the host's copy of the cache lengths and their sum are passed, as the benchmark does."""
     import torch
     say(f"[case] {label or w.name} B={w.B} Hq={w.Hq} Hkv={w.Hkv} D={w.D} T={list(w.T[:6])} L={list(w.L[:6])} "
-        f"paged={w.paged} splits={num_splits}")
+        f"paged={w.paged} splits={num_splits} hints={hints}")
     dw = device.to_device(w)
-    mask, out, lse = device.run_path(dw, num_splits=num_splits, plan_shape=plan_shape)
+    lens = np.ascontiguousarray(w.L, dtype=np.int32)
+    mask, out, lse = device.run_path(dw, num_splits=num_splits, plan_shape=plan_shape, sum_L=int(lens.sum()) if hints else 0,
+                                     L_host=lens if hints else None)
     torch.cuda.synchronize()
     ref_mask = orc.ancestor_mask(w.parent, w.cu_T, words=mask.shape[1]) if w.sum_T else np.zeros((0, 1), np.uint64)
     assert np.array_equal(mask.cpu().numpy().view(np.uint64).reshape(ref_mask.shape), ref_mask)
@@ -51,27 +54,31 @@ def check_full(device, w, num_splits=0, label="", plan_shape=0):
 
 
 # ------------------------------------------------------------------ the five configurations
-def test_config1_tiny(gpu):
-    check_full(gpu, wl.config1())
+# (with the hints: the launch configuration the benchmark times; without: what a caller that passes none gets)
+@pytest.mark.parametrize("hints", [True, False])
+def test_config1_tiny(gpu, hints):
+    check_full(gpu, wl.config1(), hints=hints)
 
 
-@pytest.mark.parametrize("splits", [0, 1, 3, 32])
-def test_config2_8b(gpu, splits):
-    check_full(gpu, wl.config2(), num_splits=splits)
+@pytest.mark.parametrize("splits,hints", [(0, True), (0, False), (1, False), (3, False), (32, False)])
+def test_config2_8b(gpu, splits, hints):
+    check_full(gpu, wl.config2(), num_splits=splits, hints=hints)
 
 
 def test_config2_shape_at_batch_32(gpu):
     """The benchmark's saturating-batch extra (config 2's shape, 32 sequences): every output compared."""
-    check_full(gpu, wl.config2(32))
+    check_full(gpu, wl.config2(32), hints=True)
 
 
+@pytest.mark.parametrize("hints", [True, False])
 @pytest.mark.parametrize("B", [1, 4, 16, 64])
-def test_config3_sweep(gpu, B):
-    check_full(gpu, wl.config3(B))
+def test_config3_sweep(gpu, B, hints):
+    check_full(gpu, wl.config3(B), hints=hints)
 
 
-def test_config4_70b(gpu):
-    check_full(gpu, wl.config4())
+@pytest.mark.parametrize("hints", [True, False])
+def test_config4_70b(gpu, hints):
+    check_full(gpu, wl.config4(), hints=hints)
 
 
 def test_config5_paged_reduced_lengths_full_compare(gpu):
@@ -86,7 +93,8 @@ def test_config5_paged_full_size(gpu):
     w = wl.config5()
     say(f"[case] cfg5 full L={list(w.L)}")
     dw = gpu.to_device(w)
-    mask, out, lse = gpu.run_path(dw, sum_L=int(w.L.sum()))   # the benchmark passes the length hint too
+    lens = np.ascontiguousarray(w.L, dtype=np.int32)
+    mask, out, lse = gpu.run_path(dw, sum_L=int(lens.sum()), L_host=lens)   # the benchmark passes the host's lengths too
     torch.cuda.synchronize()
     assert np.array_equal(mask.cpu().numpy().view(np.uint64), orc.ancestor_mask(w.parent, w.cu_T))
     ro, rl = orc.tree_verify_attn(w)
@@ -497,7 +505,7 @@ def test_seeded_random_shapes(gpu, seed):
     splits = int(rng.choice([0, 0, 1, 2, 5]))
     w = wl.random_workload(7100 + seed, B, Hkv * G, Hkv, D, L, T, max_depth=int(rng.integers(1, 14)), page_size=page)
     say(f"[case] random seed={seed} B={B} Hkv={Hkv} G={G} D={D} L={list(L)} T={list(T)} page={page} splits={splits}")
-    check_full(gpu, w, num_splits=splits, label=f"random {seed}")
+    check_full(gpu, w, num_splits=splits, label=f"random {seed}", hints=seed % 2 == 1)
     dw = gpu.to_device(w)
     out, lse = gpu.attention(dw, None, num_splits=splits, sum_L=int(L.sum()))
     torch.cuda.synchronize()
