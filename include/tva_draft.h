@@ -77,6 +77,30 @@ int tva_tree_select_subtree(const float *score, const int32_t *parent, const int
                             int32_t B, int32_t max_M, int32_t *old_index, int32_t *new_parent, int32_t *err_flag,
                             void *stream);
 
+/*
+ * How many nodes the cut keeps (paper, "Dynamic Reranking Stage": the utility of keeping the s best nodes is the
+ * running sum of the batch-averaged scores taken rank by rank, the cost the target table's row; Algorithm 1 with
+ * threshold C3 gives the count).  The device form of tva_cast_rerank_count (tva_cast.h), with the same arithmetic in
+ * the same order -- the scores are on the device when the tree has been grown there, and ranking 64 trees costs a
+ * host core more than the verification itself:
+ *   tree_scores  device fp32 [B, N_tot]  scores of all nodes of every sample's grown tree, any order, no NaN
+ *   cost_row     device fp64 [min(N_tot, m)]  the target cost table's row for the step's context (k tokens at
+ *                index k-1; the host picks the row, tva_cast_select_context); strictly increasing
+ *   m            the most nodes the cut may keep
+ *   count        device int32[1]: the number of nodes to keep, 1 .. min(N_tot, m)
+ *   cu_T         device int32 [B+1] or NULL: b * count, what tva_tree_select_subtree takes
+ *   err_flag     device int32[1] or NULL, zero on entry: stores 1 when cost_row does not increase strictly (count and
+ *                cu_T are then 0)
+ *   workspace    device, tva_rerank_workspace_bytes(B, N_tot, m) bytes (every tree's min(N_tot, m) best scores in
+ *                order), 4-byte aligned; contents on return unspecified
+ * Two launches: one workgroup per tree, then one for the batch.  N_tot <= TVA_SUBTREE_MAX_NODES, min(N_tot, m) <= 1024,
+ * else TVA_UNSUPPORTED.
+ */
+size_t tva_rerank_workspace_bytes(int32_t B, int32_t N_tot, int32_t m);
+int tva_tree_rerank_count(const float *tree_scores, int32_t B, int32_t N_tot, const double *cost_row, int32_t m, double C3,
+                          int32_t *count, int32_t *cu_T, int32_t *err_flag, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -159,3 +159,60 @@ def select_subtree(score, parent, keep: int):
     work = np.empty(len(s), np.int32)
     binding._check(_lib().tva_cast_select_subtree(_p(s), _p(par), len(s), keep, _p(old), _p(newp), _p(work)))
     return old, newp
+
+
+def _bench(argv=None) -> int:
+    """Times the host entry points at the paper's sizes (K = 12 children of up to 12 nodes per layer, trees grown to
+    145 nodes and cut to 72, cost tables of 8 context rows x 160 sizes) on this machine's CPU: one JSON line per
+    call, microseconds per call including the ctypes call itself (pointers marshalled once, outside the loop)."""
+    import argparse
+    import json
+    import time
+
+    ap = argparse.ArgumentParser(description="time the host side of the method (no GPU needed)")
+    ap.add_argument("--calls", type=int, default=20000)
+    a = ap.parse_args(argv)
+    lib = _lib()
+    rng = np.random.Generator(np.random.PCG64(9))
+    M, N_table, L, n0 = 8, 160, 256, 300
+    S_T = np.cumsum(rng.uniform(0.02, 0.2, (M, N_table)), axis=1) + 10.0 + np.arange(M)[:, None]
+    S_D = np.cumsum(rng.uniform(0.005, 0.05, (M, N_table)), axis=1) + 1.0
+    out = []
+
+    def timed(name, call):
+        call()
+        t0 = time.perf_counter()
+        for _ in range(a.calls):
+            call()
+        us = (time.perf_counter() - t0) / a.calls * 1e6
+        out.append({"call": name, "us_per_call": round(us, 3)})
+
+    for B in (1, 8, 64):
+        N = 144
+        s = -np.sort(rng.exponential(2.0, (B, N)).astype(np.float32), axis=1)       # candidates' scores, descending
+        u_at, c_at = ctypes.c_double(), ctypes.c_double()
+        work = np.empty(2 * N, np.float64)
+        args = (_p(s), B, N, _p(S_D), _p(S_T), M, N_table, L, n0, 0.35, ctypes.byref(u_at), ctypes.byref(c_at), _p(work))
+        timed(f"tva_cast_breadth_prune B={B} N={N}", lambda: lib.tva_cast_breadth_prune(*args))
+        N_tot, m = 145, 72
+        ts = -rng.exponential(3.0, (B, N_tot)).astype(np.float32)
+        work2 = np.empty(B * N_tot + 2 * m, np.float64)
+        args2 = (_p(ts), B, N_tot, _p(S_T), M, N_table, L, n0, m, 0.3, _p(work2))
+        timed(f"tva_cast_rerank_count B={B} N_tot={N_tot} m={m}", lambda: lib.tva_cast_rerank_count(*args2))
+    n, keep = 145, 72
+    parent = np.array([-1] + [int(rng.integers(0, i)) for i in range(1, n)], np.int32)
+    score = np.zeros(n, np.float32)
+    for i in range(1, n):
+        score[i] = score[parent[i]] - rng.exponential(1.0)
+    old, newp, work3 = np.empty(keep, np.int32), np.empty(keep, np.int32), np.empty(n, np.int32)
+    args3 = (_p(score), _p(parent), n, keep, _p(old), _p(newp), _p(work3))
+    timed(f"tva_cast_select_subtree n={n} keep={keep}", lambda: lib.tva_cast_select_subtree(*args3))
+    timed("tva_cast_select_context (the ctypes call alone, nearly)", lambda: lib.tva_cast_select_context(700, L, M))
+    for line in out:
+        print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    import sys
+    sys.exit(_bench())

@@ -13,6 +13,9 @@
 //   expand_finish_kernel  one workgroup per sequence: adds the rows' scores and orders the sequence's candidates the
 //                       same way.  (expand_finish_small_kernel: both in one launch for sequences of at most 16 rows.)
 //   subtree_kernel      one workgroup per tree: rank of every node by (score, index), keep the best, renumber.
+//   rank_trees_kernel, rerank_count_kernel   how many nodes the cut keeps: every tree's best scores in order (one
+//                       workgroup per tree, by counting), then one workgroup for the batch: the rank-wise means,
+//                       their running sums against the cost row, Algorithm 1.
 // Everything is compared through one 64-bit key per element: the float mapped to an unsigned integer of the same
 // order in the high word, the complement of the index in the low word -- larger key = better, and no two keys of
 // one comparison are equal, so every selection below has exactly one answer.
@@ -350,6 +353,106 @@ __global__ void __launch_bounds__(256) subtree_kernel(const float *__restrict__ 
   }
 }
 
+// ---- how many nodes the cut keeps (Dynamic Reranking Stage) ----
+// Two launches.  rank_trees_kernel, one workgroup per tree: the tree's N best scores in descending order (place of a
+// score = the scores of its tree that come before it: larger, or equal with a lower index), to best[B, N].
+// rerank_count_kernel, one workgroup: the arithmetic of the host routine (tva_cast_rerank_count) in its order -- the
+// rank-s scores are added over the samples in index order, divided by B, and accumulated over s by one thread;
+// c_k = cost[k] / cost[0]; index j stays valid unless some chord (u_j - u_i) / (c_j - c_i), i < j, is below C.
+constexpr int kRerankMaxN = 1024;
+
+__global__ void __launch_bounds__(256) rank_trees_kernel(const float *__restrict__ score, int N_tot, int N, float *__restrict__ best) {
+  __shared__ float s_x[TVA_SUBTREE_MAX_NODES + 8];
+  const int tid = threadIdx.x, j = blockIdx.x;
+  const float *row = score + (size_t)j * N_tot;
+  const int padded = (N_tot + 7) & ~7;  // (the tail reads as scores that come before nothing)
+  for (int i = tid; i < padded; i += 256) s_x[i] = i < N_tot ? row[i] : -INFINITY;
+  __syncthreads();
+  for (int idx = tid; idx < N_tot; idx += 256) {
+    const float mine = s_x[idx];
+    int before = 0;
+    // (eight reads in flight, and no branches: written with | and &, the compares stay arithmetic)
+    for (int i0 = 0; i0 < padded; i0 += 8) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = s_x[i0 + e];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) before += (int)(x[e] > mine) | ((int)(x[e] == mine) & (int)(i0 + e < idx));
+    }
+    if (before < N) best[(size_t)j * N + before] = mine;
+  }
+}
+
+constexpr int kCountThreads = 1024;
+constexpr int kCountStage = 8192;  // floats of LDS for the trees' best scores
+
+__global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float *__restrict__ best, int B, const double *__restrict__ cost, int N,
+                                                           double C, int32_t *__restrict__ count, int32_t *__restrict__ cu_T,
+                                                           int32_t *__restrict__ err_flag) {
+  __shared__ double s_u[kRerankMaxN], s_c[kRerankMaxN];
+  __shared__ float s_best[kCountStage];
+  __shared__ int s_bad, s_keep;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_bad = 0, s_keep = 1;  // (index 1 has no chord: always valid)
+  // the trees' best scores, fetched by all threads at once where they fit (one round trip, not one per sample)
+  const bool staged = B * N <= kCountStage;
+  if (staged)
+    for (int e = tid; e < B * N; e += kCountThreads) s_best[e] = best[e];
+  __syncthreads();
+  const double cost0 = cost[0];
+  for (int k = tid; k < N; k += kCountThreads) {
+    double col = 0.0;  // (added in the samples' order)
+    if (staged) {
+      for (int j = 0; j < B; ++j) col += (double)s_best[j * N + k];
+    } else {
+      for (int j = 0; j < B; ++j) col += (double)best[(size_t)j * N + k];
+    }
+    s_u[k] = col / B;  // the rank-wise batch mean; summed up below
+    s_c[k] = cost[k] / cost0;
+    if (k > 0 && !(cost[k] / cost0 > cost[k - 1] / cost0)) s_bad = 1;  // costs must grow with the size
+  }
+  __syncthreads();
+  // the running sum, one addition after the other as the definition has it: the lanes of the first wave hold 64 means
+  // at a time and hand them to the sum by lane reads (no LDS round trip per step)
+  if (tid < 64) {
+    double run = 0.0;
+    for (int base = 0; base < N; base += 64) {
+      const double v = base + tid < N ? s_u[base + tid] : 0.0;
+      const int n = N - base < 64 ? N - base : 64;
+      double mine = 0.0;
+      const uint32_t vlo = (uint32_t)__double_as_longlong(v), vhi = (uint32_t)(__double_as_longlong(v) >> 32);
+      for (int k = 0; k < n; ++k) {  // (k is the same in every lane: a lane read, not a permutation through LDS)
+        const uint32_t lo = __builtin_amdgcn_readlane(vlo, k), hi = __builtin_amdgcn_readlane(vhi, k);
+        run += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+        if (tid == k) mine = run;
+      }
+      if (base + tid < N) s_u[base + tid] = mine;
+    }
+  }
+  __syncthreads();
+  if (s_bad) {
+    if (tid == 0) {
+      if (err_flag) atomicCAS(err_flag, 0, 1);
+      *count = 0;
+    }
+    if (cu_T)
+      for (int b = tid; b <= B; b += kCountThreads) cu_T[b] = 0;
+    return;
+  }
+  // the chords into index j: the waves take the j in turn, a wave's lanes the earlier indices i
+  for (int j = 1 + (tid >> 6); j < N; j += kCountThreads / 64) {
+    const double uj = s_u[j], cj = s_c[j];
+    bool flat = false;
+    for (int i = tid & 63; i < j; i += 64) flat = flat | ((uj - s_u[i]) / (cj - s_c[i]) < C);
+    if (__ballot(flat) == 0ull && (tid & 63) == 0) atomicMax(&s_keep, j + 1);
+  }
+  __syncthreads();
+  const int keep = s_keep;
+  if (tid == 0) *count = keep;
+  if (cu_T)
+    for (int b = tid; b <= B; b += kCountThreads) cu_T[b] = b * keep;
+}
+
 int pieces_of(int V) { return (int)(((int64_t)V + kPiece - 1) / kPiece); }
 
 // TVA_OK, or why the shapes are refused (from host values only)
@@ -414,6 +517,25 @@ int tva_tree_select_subtree(const float *score, const int32_t *parent, const int
   (void)hipGetLastError();
   hipLaunchKernelGGL(subtree_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, score, parent, cu_M, cu_T, old_index,
                      new_parent, err_flag);
+  return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+size_t tva_rerank_workspace_bytes(int32_t B, int32_t N_tot, int32_t m) {
+  if (B < 1 || N_tot < 1 || m < 1) return (size_t)-1;
+  return (size_t)B * (N_tot < m ? N_tot : m) * sizeof(float);
+}
+
+int tva_tree_rerank_count(const float *tree_scores, int32_t B, int32_t N_tot, const double *cost_row, int32_t m, double C3,
+                          int32_t *count, int32_t *cu_T, int32_t *err_flag, void *workspace, size_t workspace_bytes, void *stream) {
+  if (B < 1 || N_tot < 1 || m < 1 || !tree_scores || !cost_row || !count || !workspace || ((uintptr_t)workspace & 3))
+    return TVA_INVALID_ARG;
+  const int N = N_tot < m ? N_tot : m;
+  if (N_tot > TVA_SUBTREE_MAX_NODES || N > kRerankMaxN || B > 65535) return TVA_UNSUPPORTED;
+  if (workspace_bytes < tva_rerank_workspace_bytes(B, N_tot, m)) return TVA_WORKSPACE_TOO_SMALL;
+  float *best = static_cast<float *>(workspace);
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(rank_trees_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, tree_scores, N_tot, N, best);
+  hipLaunchKernelGGL(rerank_count_kernel, dim3(1), dim3(kCountThreads), 0, (hipStream_t)stream, best, B, cost_row, N, C3, count, cu_T, err_flag);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 

@@ -29,6 +29,10 @@ def _lib():
         lib.tva_sizeof_expand_args.restype = ctypes.c_size_t
         lib.tva_tree_select_subtree.restype = ctypes.c_int
         lib.tva_tree_select_subtree.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        lib.tva_tree_rerank_count.restype = ctypes.c_int
+        lib.tva_tree_rerank_count.argtypes = [vp, i32, i32, vp, i32, ctypes.c_double, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.tva_rerank_workspace_bytes.restype = ctypes.c_size_t
+        lib.tva_rerank_workspace_bytes.argtypes = [i32, i32, i32]
         if lib.tva_sizeof_expand_args() != ctypes.sizeof(ExpandArgs):
             raise RuntimeError("libtva.so is stale: rebuild it")
         lib._draft_ready = True
@@ -88,6 +92,27 @@ def select_subtree(score, parent, cu_M, cu_T, max_M: int, old_index=None, new_pa
     _check(_lib().tva_tree_select_subtree(_p(score), _p(parent), _p(cu_M), _p(cu_T), B, int(max_M), _p(old_index),
                                           _p(new_parent), _p(err_flag), _stream_ptr(stream)))
     return old_index, new_parent
+
+
+def rerank_count(tree_scores, cost_row, m: int, C3: float, count=None, cu_T=None, err_flag=None, stream=None, workspace=None):
+    """Device tensors in (tree_scores float32 [B, N_tot], cost_row float64 [>= min(N_tot, m)]); returns the device
+    tensors (count int32 [1], cu_T int32 [B + 1] = b * count).  workspace: a device tensor of
+    tva_rerank_workspace_bytes(B, N_tot, m) bytes (allocated when not passed)."""
+    import torch
+    B, N_tot = int(tree_scores.shape[0]), int(tree_scores.shape[1])
+    if count is None:
+        count = torch.empty(1, dtype=torch.int32, device=tree_scores.device)
+    if cu_T is None:
+        cu_T = torch.empty(B + 1, dtype=torch.int32, device=tree_scores.device)
+    if workspace is None:
+        need = _lib().tva_rerank_workspace_bytes(B, N_tot, int(m))
+        if need == ctypes.c_size_t(-1).value:
+            raise binding.TvaError(-1)
+        workspace = torch.empty(max(1, need // 4), dtype=torch.float32, device=tree_scores.device)
+    _check(_lib().tva_tree_rerank_count(_p(tree_scores), B, N_tot, _p(cost_row), int(m), float(C3), _p(count), _p(cu_T),
+                                        _p(err_flag), _p(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream_ptr(stream)))
+    return count, cu_T
 
 
 def _bench(argv=None) -> int:
@@ -166,6 +191,24 @@ def _bench(argv=None) -> int:
         newp = torch.empty(B * keep, dtype=torch.int32, device="cuda")
         us = timed(lambda: select_subtree(ds, dp, cu_M, cu_T, M, old_index=old, new_parent=newp, stream=stream), 1)
         print(json.dumps({"kernel": "tva_tree_select_subtree", "shape": f"B={B} nodes={M} keep={keep}", "us_per_call": us}), flush=True)
+        if True:
+            # the count of nodes to keep, then the cut with the prefix array it wrote (room for the most it may keep)
+            cost = torch.cumsum(torch.rand(72, dtype=torch.float64, device="cuda") * 0.05 + 0.01, 0) + 5.0
+            count = torch.zeros(1, dtype=torch.int32, device="cuda")
+            cu_K = torch.zeros(B + 1, dtype=torch.int32, device="cuda")
+            old2 = torch.empty(B * 72, dtype=torch.int32, device="cuda")
+            newp2 = torch.empty(B * 72, dtype=torch.int32, device="cuda")
+            scores2 = (-ds).reshape(B, M)
+            rws = torch.empty(B * 72, dtype=torch.float32, device="cuda")
+            us = timed(lambda: rerank_count(scores2, cost, 72, 30.0, count=count, cu_T=cu_K, stream=stream, workspace=rws), 1)
+            kept = int(count.item())
+
+            def both():
+                rerank_count(scores2, cost, 72, 30.0, count=count, cu_T=cu_K, stream=stream, workspace=rws)
+                select_subtree(ds, dp, cu_M, cu_K, M, old_index=old2, new_parent=newp2, stream=stream)
+            us2 = timed(both, 1)
+            print(json.dumps({"kernel": "tva_tree_rerank_count", "shape": f"B={B} nodes={M} m=72", "us_per_call": us, "count": kept,
+                              "us_with_the_cut_behind_it": us2}), flush=True)
     return 0
 
 

@@ -163,6 +163,67 @@ def test_select_subtree_flags_what_is_not_a_tree_of_the_method(torch_dev):
     assert list(old) == [0, 0, 1] and list(newp) == [-1, -1, 0]
 
 
+@pytest.mark.parametrize("B,N_tot,m", [(1, 145, 72), (8, 145, 72), (64, 145, 72), (64, 160, 64), (3, 5, 72), (7, 37, 1),
+                                        (5, 1, 4), (16, 300, 40), (2, 2048, 600)])
+def test_rerank_count_matches_oracle(torch_dev, B, N_tot, m):
+    """The number of nodes the cut keeps (Dynamic Reranking Stage) equals the oracle's for thresholds from one that
+    keeps everything to one that keeps a single node, on trees whose scores come in any order and with ties; the
+    prefix array it writes is what the cut takes; a cost row that does not increase is flagged."""
+    torch = torch_dev
+    from paper_2510_26577_amd import draft
+    rng = np.random.Generator(np.random.PCG64(4000 + B + N_tot + m))
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    M_rows, L, n0 = 6, 256, 700
+    N = min(N_tot, m)
+    S_T = np.cumsum(rng.uniform(0.01, 0.3, (M_rows, max(N, 2))), axis=1) + 5.0 + np.arange(M_rows)[:, None]
+    row = co.select_context(n0, L, M_rows) // L - 1
+    # scores as the method makes them: log-values, a node's never above its parent's, in index (not score) order
+    scores = np.empty((B, N_tot), np.float32)
+    for j in range(B):
+        par, sc = random_scored_tree(rng, N_tot)
+        scores[j] = sc
+    if N_tot > 4:
+        scores[0, 3] = scores[0, 1]                                      # ties
+    say(f"[case] rerank_count B={B} N_tot={N_tot} m={m}")
+    counts = set()
+    for C3 in (-1e30, 0.0, 1.0, 10.0, 30.0, 100.0, 300.0, 1000.0, 1e30):
+        # (scores are logs, so utilities fall with the count: the thresholds are taken on the negated scale too)
+        for sign in (1.0, -1.0):
+            x = (sign * scores).astype(np.float32)
+            want = co.rerank_count(x.tolist(), S_T.tolist(), n0, L, M_rows, m, C3)
+            flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+            count, cu_T = draft.rerank_count(d(x, np.float32), d(S_T[row], np.float64), m, C3, err_flag=flag)
+            torch.cuda.synchronize()
+            assert int(flag.item()) == 0
+            assert int(count.item()) == want, (C3, sign)
+            assert cu_T.cpu().tolist() == [b * want for b in range(B + 1)]
+            counts.add(want)
+    if N > 3:
+        assert len(counts) >= 2 + (N <= 100)                             # (the thresholds do move the count)
+    bad = S_T[row].copy()
+    if N >= 2:
+        bad[N - 1] = bad[N - 2]
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        count, cu_T = draft.rerank_count(d(scores, np.float32), d(bad, np.float64), m, 0.1, err_flag=flag)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 1 and int(count.item()) == 0 and not any(cu_T.cpu().tolist())
+
+
+def test_rerank_count_refuses_what_does_not_fit(torch_dev):
+    torch = torch_dev
+    from paper_2510_26577_amd import binding, draft
+    x = torch.zeros((2, 3000), dtype=torch.float32, device="cuda")
+    cost = torch.arange(1, 3001, dtype=torch.float64, device="cuda")
+    with pytest.raises(binding.TvaError):
+        draft.rerank_count(x, cost, 72, 0.1)                             # a tree larger than the kernels rank
+    with pytest.raises(binding.TvaError):
+        draft.rerank_count(x[:, :1500].contiguous(), cost, 1500, 0.1)    # more ranks than the kernels weigh
+    with pytest.raises(binding.TvaError):
+        draft.rerank_count(x[:, :10].contiguous(), cost, 0, 0.1)
+    with pytest.raises(binding.TvaError):
+        draft.rerank_count(x[:, :10].contiguous(), cost, 5, 0.1, workspace=torch.empty(9, dtype=torch.float32, device="cuda"))
+
+
 def test_a_tree_grown_and_cut_on_the_gpu_is_the_oracles_and_feeds_the_attention(torch_dev):
     """Four layers of expansion (the best 6 candidates of a layer are the next layer's rows, 4 children each), the cut to
     the 20 best nodes, and the ancestor masks of the result: the device path and the oracle path, run side by side on the
