@@ -319,8 +319,15 @@ def test_draft_and_sampling_kernels_replayed_from_a_graph(torch_dev, node_count)
     sws = torch.empty(verify._lib().tva_sample_workspace_bytes_rows(2, sum_T, Vs) // 8, dtype=torch.int64, device="cuda")
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
     results = {}
+    # the count of nodes to keep (trees of equal size: the first 40 scores of each)
+    r_scores = torch.stack([t_score[:40], t_score[90:130]]).contiguous()
+    r_cost = torch.cumsum(torch.full((25,), 0.03, dtype=torch.float64, device="cuda"), 0) + 4.0
+    r_count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    r_cu = torch.zeros(3, dtype=torch.int32, device="cuda")
+    r_ws = torch.empty(2 * 25, dtype=torch.float32, device="cuda")
 
     def one_pass(stream=None):
+        draft.rerank_count(r_scores, r_cost, 25, -40.0, count=r_count, cu_T=r_cu, err_flag=flag, stream=stream, workspace=r_ws)
         draft.expand_layer_raw(eargs, stream)
         draft.select_subtree(t_score, t_parent, d_cu_M, d_cu_T, max(sizes), old_index=old, new_parent=newp, err_flag=flag, stream=stream)
         results["path"], results["n"], results["next"] = verify.accept_sampling(
@@ -334,13 +341,16 @@ def test_draft_and_sampling_kernels_replayed_from_a_graph(torch_dev, node_count)
     assert results["next"].cpu().tolist() == ref_next and results["n"].cpu().tolist() == [len(x) for x in ref_paths]
     ref = do.expand_layer(score, cu_N, logp, K)
     assert np.array_equal(cs.cpu().numpy()[:9 * K], ref[0][0]) and np.array_equal(ct.cpu().numpy()[:9 * K], ref[0][2])
-    eager = [t.clone() for t in (cs, cp, ct, old, newp, results["path"], results["n"], results["next"])]
+    want_count = co.rerank_count(r_scores.cpu().tolist(), [r_cost.cpu().tolist()], 0, 256, 1, 25, -40.0)
+    assert int(r_count.item()) == want_count and r_cu.cpu().tolist() == [0, want_count, 2 * want_count]
+    eager = [t.clone() for t in (cs, cp, ct, old, newp, results["path"], results["n"], results["next"], r_count, r_cu)]
 
     def scribble():
         for t in (cs, residual):
             t.fill_(float("nan"))
-        for t in (cp, ct, old, newp, ws, sws):
+        for t in (cp, ct, old, newp, ws, sws, r_count, r_cu):
             t.fill_(-7)
+        r_ws.fill_(float("nan"))
         flag.zero_()
 
     side = torch.cuda.Stream()
@@ -349,15 +359,15 @@ def test_draft_and_sampling_kernels_replayed_from_a_graph(torch_dev, node_count)
     torch.cuda.synchronize()
     with torch.cuda.graph(g, stream=side):
         one_pass(side)
-    graph_outs = (cs, cp, ct, old, newp, results["path"], results["n"], results["next"])
+    graph_outs = (cs, cp, ct, old, newp, results["path"], results["n"], results["next"], r_count, r_cu)
     for replay in range(3):
         say(f"[case] draft + sampling kernels, graph replay {replay}")
         scribble()                                # eager work between the replays
-        for t in graph_outs[5:]:
+        for t in graph_outs[5:8]:
             t.fill_(-9)
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
         assert int(flag.item()) == 0
-        for name, got, want in zip("cand_score cand_parent cand_token old_index new_parent path path_len next".split(), graph_outs, eager):
+        for name, got, want in zip("cand_score cand_parent cand_token old_index new_parent path path_len next count cu_T".split(), graph_outs, eager):
             assert torch.equal(got, want), (name, replay)
