@@ -79,7 +79,8 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
  *                       B = 1 .. 8: 6 to 26 % faster again).  A value that is not cu_T[B] costs time, not correctness:
  *                       rows past cu_T[B] are not read, and a tree that reaches past sum_T is walked as without it.
  *   workgroups_per_sequence   0: the library chooses (1 .. 16, so that B times it stays within 256; 1 for
- *                       vocabularies below 48 K tokens, where the waits cost what the slices save); 1: as without
+ *                       vocabularies below 48 K tokens, where the waits cost what the slices save -- below 16 K when
+ *                       the row sums are made ahead, see sum_T); 1: as without
  *                       a workspace; 2 .. 16: that many (TVA_UNSUPPORTED if B times it exceeds 256).  The results
  *                       do not depend on it beyond the order in which a pass's sum is added up.
  */

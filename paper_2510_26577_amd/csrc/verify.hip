@@ -668,13 +668,16 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
 // Workgroups per sequence: as many as keep the launch within one workgroup per compute unit (all of them resident at
 // once, which the waits between passes rely on), at most 16, a power of two, slices of 4096 tokens or more, and
 // one only for vocabularies below 48 K: a wait between passes costs about 4.5 us, what one workgroup needs for
-// a pass over 32 K tokens (measured: V = 32000 30.6 us with one workgroup, 35.3 with eight).  Negative: a status.
-int sample_workgroups(const tva_sample_args *a) {
+// a pass over 32 K tokens (measured: V = 32000 30.6 us with one workgroup, 35.3 with eight).  With the row sums made
+// ahead of the walk only refusals still cost a pass and its wait, and sharing pays from 16 K tokens on (V = 32000,
+// B = 1: 28.4 us with four workgroups against 31.2 with one; B = 4: 24.8 against 34.0).  Negative: a status.
+int sample_workgroups(const tva_sample_args *a, bool ahead) {
   if (a->workgroups_per_sequence < 0 || a->workgroups_per_sequence > kCoopMaxW) return TVA_INVALID_ARG;
   if (!a->workspace || a->workgroups_per_sequence == 1) return 1;
   if (((uintptr_t)a->workspace & 7) || a->workspace_bytes < (size_t)a->B * 512) return TVA_WORKSPACE_TOO_SMALL;
   int W = 1;
-  while (a->V >= 49152 && 2 * W <= kCoopMaxW && (int64_t)a->B * 2 * W <= 256 && a->V / (2 * W) >= 4096) W *= 2;
+  const int shared_from = ahead ? 16384 : 49152;
+  while (a->V >= shared_from && 2 * W <= kCoopMaxW && (int64_t)a->B * 2 * W <= 256 && a->V / (2 * W) >= 4096) W *= 2;
   if (a->workgroups_per_sequence > 1) {
     W = a->workgroups_per_sequence;
     if ((int64_t)a->B * W > 256) return TVA_UNSUPPORTED;  // more than the chip holds at once
@@ -827,11 +830,11 @@ static int accept_sampling_impl(const tva_sample_args *a, void *stream, int miss
   // groups of four need every row to start on 16 bytes
   const bool vec = a->V % 4 == 0 && (((uintptr_t)a->p_target | (uintptr_t)a->q_draft | (uintptr_t)a->residual) & 15) == 0;
   if (a->sum_T < 0) return TVA_INVALID_ARG;
-  const int W = sample_workgroups(a);
+  const bool ahead = sums_ahead(a);
+  const int W = sample_workgroups(a, ahead);
   if (W < 0) return W;
   (void)hipGetLastError();  // the status below is these launches'
   hipStream_t st = (hipStream_t)stream;
-  const bool ahead = sums_ahead(a);
   if (ahead) {
     double *rowpart = reinterpret_cast<double *>(static_cast<char *>(a->workspace) + row_sums_offset(a->B));
     int *sync = static_cast<int *>(a->workspace);
