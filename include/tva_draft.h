@@ -101,6 +101,23 @@ int tva_tree_rerank_count(const float *tree_scores, int32_t B, int32_t N_tot, co
                           int32_t *count, int32_t *cu_T, int32_t *err_flag, void *workspace, size_t workspace_bytes,
                           void *stream);
 
+/*
+ * How many candidates of a layer are kept (paper, "Dynamic Expansion Stage": Eq. 1, the utility of the k best
+ * candidates averaged over the batch; Eq. 2, their cost under the draft model relative to one token under the target
+ * model; Algorithm 1 with threshold C1).  The device form of tva_cast_breadth_prune, same arithmetic in the same order:
+ *   cand_score      device fp32 [B, N]  the layer's candidates of every sample in descending order of score --
+ *                   tva_expand_layer's cand_score when every sequence has the same number of selected nodes
+ *   draft_cost_row  device fp64 [N]  the draft cost table's row for the layer's context (k tokens at index k-1),
+ *                   strictly increasing
+ *   target_cost_one the target table's cost of one token for that context (host value, > 0)
+ *   count           device int32[1]: the number kept, 1 .. N
+ *   u_c_at          device fp64[2] or NULL: the utility and the cost at that count (what the depth test reads)
+ *   err_flag        device int32[1] or NULL, zero on entry: stores 1 when the cost row does not increase strictly
+ * One workgroup, one launch.  N <= 1024, else TVA_UNSUPPORTED.
+ */
+int tva_layer_breadth_count(const float *cand_score, int32_t B, int32_t N, const double *draft_cost_row, double target_cost_one,
+                            double C1, int32_t *count, double *u_c_at, int32_t *err_flag, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

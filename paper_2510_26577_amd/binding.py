@@ -80,7 +80,8 @@ EXPORTS = ("tva_build_ancestor_mask", "tva_build_ancestor_mask_host", "tva_works
            "tva_tree_verify_attn", "tva_tree_verify_attn_static", "tva_static_scratch_bytes", "tva_tree_verify_attn_splits", "tva_merge_splits", "tva_strerror", "tva_version", "tva_sizeof_args", "tva_timeline_read")
 # entry points of include/tva_verify.h (bound in verify.py)
 DRAFT_EXPORTS = ("tva_expand_workspace_bytes", "tva_expand_layer", "tva_sizeof_expand_args", "tva_tree_select_subtree",
-                 "tva_tree_rerank_count", "tva_rerank_workspace_bytes")
+                 "tva_tree_rerank_count", "tva_rerank_workspace_bytes",
+                 "tva_layer_breadth_count")
 VERIFY_EXPORTS = ("tva_accept_greedy", "tva_accept_sampling", "tva_accept_sampling_wait_bound_test", "tva_sample_workspace_bytes", "tva_sample_workspace_bytes_rows", "tva_sizeof_sample_args", "tva_commit_path",
                   "tva_sizeof_commit_args")
 # host entry points of include/tva_cast.h (bound in cast.py)

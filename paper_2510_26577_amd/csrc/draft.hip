@@ -384,11 +384,16 @@ __global__ void __launch_bounds__(256) rank_trees_kernel(const float *__restrict
 }
 
 constexpr int kCountThreads = 1024;
-constexpr int kCountStage = 8192;  // floats of LDS for the trees' best scores
+constexpr int kCountStage = 10240;  // floats of LDS for the trees' best scores (64 samples x 144 candidates fit)
 
-__global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float *__restrict__ best, int B, const double *__restrict__ cost, int N,
-                                                           double C, int32_t *__restrict__ count, int32_t *__restrict__ cu_T,
-                                                           int32_t *__restrict__ err_flag) {
+// LAYER = true is the per-layer form (Eq. 1 and Eq. 2 as tva_cast_breadth_prune writes them): best = the layer's
+// candidates' scores, already in order; the column sums are accumulated first and the running sum divided by B;
+// c_k = cost[k] / unit with the target's cost of one token passed in; at[0], at[1] receive u and c at the kept count.
+template <bool LAYER>
+__global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float *__restrict__ best, int B, const double *__restrict__ cost,
+                                                                     double unit, int N, double C, int32_t *__restrict__ count,
+                                                                     int32_t *__restrict__ cu_T, double *__restrict__ at,
+                                                                     int32_t *__restrict__ err_flag) {
   __shared__ double s_u[kRerankMaxN], s_c[kRerankMaxN];
   __shared__ float s_best[kCountStage];
   __shared__ int s_bad, s_keep;
@@ -399,7 +404,7 @@ __global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float
   if (staged)
     for (int e = tid; e < B * N; e += kCountThreads) s_best[e] = best[e];
   __syncthreads();
-  const double cost0 = cost[0];
+  const double cost0 = LAYER ? unit : cost[0];
   for (int k = tid; k < N; k += kCountThreads) {
     double col = 0.0;  // (added in the samples' order)
     if (staged) {
@@ -407,7 +412,7 @@ __global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float
     } else {
       for (int j = 0; j < B; ++j) col += (double)best[(size_t)j * N + k];
     }
-    s_u[k] = col / B;  // the rank-wise batch mean; summed up below
+    s_u[k] = LAYER ? col : col / B;  // (the rank-wise batch mean; summed up below)
     s_c[k] = cost[k] / cost0;
     if (k > 0 && !(cost[k] / cost0 > cost[k - 1] / cost0)) s_bad = 1;  // costs must grow with the size
   }
@@ -426,7 +431,7 @@ __global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float
         run += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
         if (tid == k) mine = run;
       }
-      if (base + tid < N) s_u[base + tid] = mine;
+      if (base + tid < N) s_u[base + tid] = LAYER ? mine / B : mine;  // (one division per lane, outside the chain)
     }
   }
   __syncthreads();
@@ -434,6 +439,7 @@ __global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float
     if (tid == 0) {
       if (err_flag) atomicCAS(err_flag, 0, 1);
       *count = 0;
+      if (at) at[0] = at[1] = 0.0;
     }
     if (cu_T)
       for (int b = tid; b <= B; b += kCountThreads) cu_T[b] = 0;
@@ -448,7 +454,10 @@ __global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float
   }
   __syncthreads();
   const int keep = s_keep;
-  if (tid == 0) *count = keep;
+  if (tid == 0) {
+    *count = keep;
+    if (at) at[0] = s_u[keep - 1], at[1] = s_c[keep - 1];
+  }
   if (cu_T)
     for (int b = tid; b <= B; b += kCountThreads) cu_T[b] = b * keep;
 }
@@ -535,7 +544,18 @@ int tva_tree_rerank_count(const float *tree_scores, int32_t B, int32_t N_tot, co
   float *best = static_cast<float *>(workspace);
   (void)hipGetLastError();
   hipLaunchKernelGGL(rank_trees_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, tree_scores, N_tot, N, best);
-  hipLaunchKernelGGL(rerank_count_kernel, dim3(1), dim3(kCountThreads), 0, (hipStream_t)stream, best, B, cost_row, N, C3, count, cu_T, err_flag);
+  hipLaunchKernelGGL(rerank_count_kernel<false>, dim3(1), dim3(kCountThreads), 0, (hipStream_t)stream, best, B, cost_row, 0.0, N, C3,
+                     count, cu_T, nullptr, err_flag);
+  return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
+}
+
+int tva_layer_breadth_count(const float *cand_score, int32_t B, int32_t N, const double *draft_cost_row, double target_cost_one,
+                            double C1, int32_t *count, double *u_c_at, int32_t *err_flag, void *stream) {
+  if (B < 1 || N < 1 || !cand_score || !draft_cost_row || !count || !(target_cost_one > 0.0)) return TVA_INVALID_ARG;
+  if (N > kRerankMaxN) return TVA_UNSUPPORTED;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(rerank_count_kernel<true>, dim3(1), dim3(kCountThreads), 0, (hipStream_t)stream, cand_score, B, draft_cost_row,
+                     target_cost_one, N, C1, count, nullptr, u_c_at, err_flag);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 

@@ -31,6 +31,8 @@ def _lib():
         lib.tva_tree_select_subtree.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         lib.tva_tree_rerank_count.restype = ctypes.c_int
         lib.tva_tree_rerank_count.argtypes = [vp, i32, i32, vp, i32, ctypes.c_double, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.tva_layer_breadth_count.restype = ctypes.c_int
+        lib.tva_layer_breadth_count.argtypes = [vp, i32, i32, vp, ctypes.c_double, ctypes.c_double, vp, vp, vp, vp]
         lib.tva_rerank_workspace_bytes.restype = ctypes.c_size_t
         lib.tva_rerank_workspace_bytes.argtypes = [i32, i32, i32]
         if lib.tva_sizeof_expand_args() != ctypes.sizeof(ExpandArgs):
@@ -115,6 +117,21 @@ def rerank_count(tree_scores, cost_row, m: int, C3: float, count=None, cu_T=None
     return count, cu_T
 
 
+def breadth_count(cand_score, draft_cost_row, target_cost_one: float, C1: float, count=None, u_c_at=None, err_flag=None,
+                  stream=None):
+    """Device tensors in (cand_score float32 [B, N] in descending order per sample, draft_cost_row float64 [N]);
+    returns the device tensors (count int32 [1], u_c_at float64 [2])."""
+    import torch
+    B, N = int(cand_score.shape[0]), int(cand_score.shape[1])
+    if count is None:
+        count = torch.empty(1, dtype=torch.int32, device=cand_score.device)
+    if u_c_at is None:
+        u_c_at = torch.empty(2, dtype=torch.float64, device=cand_score.device)
+    _check(_lib().tva_layer_breadth_count(_p(cand_score), B, N, _p(draft_cost_row), float(target_cost_one), float(C1),
+                                          _p(count), _p(u_c_at), _p(err_flag), _stream_ptr(stream)))
+    return count, u_c_at
+
+
 def _bench(argv=None) -> int:
     """Times tva_expand_layer and tva_tree_select_subtree on seeded synthetic layers made on the device (log-softmax of
     normal logits) and prints one JSON line per shape.  Plumbing only; the kernels do the work."""
@@ -175,6 +192,16 @@ def _bench(argv=None) -> int:
               flush=True)
         del cases
         torch.cuda.empty_cache()
+
+    for B in (1, 8, 64):
+        N = 144
+        cand = -torch.sort(-torch.exp(-torch.rand((B, N), generator=gen, device="cuda") * 6.0), dim=1).values.contiguous()
+        dcost = torch.cumsum(torch.rand(N, dtype=torch.float64, device="cuda") * 0.04 + 0.002, 0) + 0.5
+        count = torch.zeros(1, dtype=torch.int32, device="cuda")
+        at = torch.zeros(2, dtype=torch.float64, device="cuda")
+        us = timed(lambda: breadth_count(cand, dcost, 8.0, 1.0, count=count, u_c_at=at, stream=stream), 1)
+        print(json.dumps({"kernel": "tva_layer_breadth_count", "shape": f"B={B} candidates={N}", "us_per_call": us,
+                          "count": int(count.item())}), flush=True)
 
     rng = np.random.Generator(np.random.PCG64(80))
     for B, M, keep in ((1, 145, 60), (8, 145, 60), (64, 145, 32), (8, 1024, 72)):

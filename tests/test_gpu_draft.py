@@ -209,6 +209,50 @@ def test_rerank_count_matches_oracle(torch_dev, B, N_tot, m):
         assert int(flag.item()) == 1 and int(count.item()) == 0 and not any(cu_T.cpu().tolist())
 
 
+@pytest.mark.parametrize("B,N", [(1, 144), (8, 144), (64, 144), (3, 1), (5, 12), (2, 1024)])
+def test_layer_breadth_count_matches_oracle_and_host(torch_dev, B, N):
+    """The number of candidates a layer keeps (Eq. 1, Eq. 2, Algorithm 1 with C1): the count equals the oracle's, and
+    count, utility and cost at the count equal the host routine's bit for bit (same additions in the same order), for
+    thresholds from "keep all" to "keep one"; a cost row that does not increase is flagged."""
+    torch = torch_dev
+    from paper_2510_26577_amd import cast, draft
+    rng = np.random.Generator(np.random.PCG64(4100 + B + N))
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    M_rows, L, ctx = 5, 128, 300
+    S_T = np.cumsum(rng.uniform(0.05, 0.3, (M_rows, N + 1)), axis=1) + 8.0
+    S_D = np.cumsum(rng.uniform(0.002, 0.05, (M_rows, N + 1)), axis=1) + 0.5
+    row = co.select_context(ctx, L, M_rows) // L - 1
+    # candidates' values in descending order per sample (probabilities: utilities grow with the count, ever more slowly)
+    scores = -np.sort(-np.exp(-rng.exponential(2.0, (B, N))).astype(np.float32), axis=1)
+    if N > 3:
+        scores[0, 2] = scores[0, 1]
+    say(f"[case] breadth_count B={B} N={N}")
+    counts = set()
+    for C1 in (-1e30, 0.0, 0.3, 1.0, 3.0, 10.0, 30.0, 1e30):
+        hn, hu, hc = cast.breadth_prune(scores, S_D, S_T, ctx, L, C1)
+        # (the oracle's double sums are quadratic in N: the largest case is checked against the host routine only,
+        # which tests/test_cast_parity.py holds to the oracle)
+        want, wu, wc = co.breadth_prune(scores.tolist(), S_D.tolist(), S_T.tolist(), ctx, L, M_rows, C1) if N <= 200 else (hn, hu, hc)
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        count, at = draft.breadth_count(d(scores, np.float32), d(S_D[row, :N], np.float64), float(S_T[row, 0]), C1, err_flag=flag)
+        torch.cuda.synchronize()
+        u_at, c_at = at.cpu().tolist()
+        assert int(flag.item()) == 0
+        assert int(count.item()) == want == hn, C1
+        assert (u_at, c_at) == (hu, hc), C1
+        assert abs(u_at - wu) <= 1e-12 * max(1.0, abs(wu)) and abs(c_at - wc) <= 1e-15 * abs(wc)
+        counts.add(want)
+    if 3 < N <= 200:
+        assert len(counts) >= 3
+    if N >= 2:
+        bad = S_D[row, :N].copy()
+        bad[N - 1] = bad[N - 2]
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        count, at = draft.breadth_count(d(scores, np.float32), d(bad, np.float64), float(S_T[row, 0]), 1.0, err_flag=flag)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 1 and int(count.item()) == 0
+
+
 def test_rerank_count_refuses_what_does_not_fit(torch_dev):
     torch = torch_dev
     from paper_2510_26577_amd import binding, draft
