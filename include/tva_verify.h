@@ -121,6 +121,11 @@ size_t tva_sizeof_sample_args(void);
  * k_tree = v_tree = NULL selects the in-cache form: tree node i of sequence b already sits at cache
  * position L[b] + i (the layout tva_tree_verify_attn reads when its k_tree is NULL), and the accepted
  * nodes are moved down in place to L[b], L[b]+1, ...; everything behind them is left as it is.
+ *
+ * All layers of a model in one call (n_layers > 1): the lengths, the path, the page table and the offsets are the
+ * same for every layer, only the tensors differ.  Layer l's caches start layer_stride_cache elements behind layer
+ * l-1's (k_cache and v_cache each), its tree tensors layer_stride_tree elements behind (multiples of 8, counted like
+ * the other strides); the call is one launch instead of n_layers (32 layers at B = 1: 5 us against 64).
  */
 typedef struct tva_commit_args {
   int32_t B, Hkv, D;   /* D * Hkv * 2 bytes per row must be a multiple of 16 */
@@ -136,6 +141,8 @@ typedef struct tva_commit_args {
   int64_t stride_page, stride_tok, stride_head; /* elements; 0 = packed default as in tva_args */
   int32_t *L_out;      /* device [B] or NULL */
   int32_t *err_flag;   /* device int32[1] or NULL */
+  int32_t n_layers;    /* 0 or 1: one layer */
+  int64_t layer_stride_cache, layer_stride_tree; /* elements between consecutive layers' tensors (n_layers > 1) */
 } tva_commit_args;
 
 int tva_commit_path(const tva_commit_args *a, void *stream);

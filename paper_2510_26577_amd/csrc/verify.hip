@@ -704,13 +704,14 @@ struct CommitParams {
   int32_t *L_out, *err_flag;
   int Hkv, D, max_path, page_size, max_pages;
   int64_t stride_page, stride_tok, stride_head;  // elements
+  int64_t layer_cache, layer_tree;                // bytes between the tensors of consecutive layers (blockIdx.z)
 };
 
 __global__ void __launch_bounds__(256) commit_kernel(const CommitParams p) {
-  const int j = blockIdx.x, b = blockIdx.y;
+  const int j = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
   const int n = p.path_len[b];
   const int Lb = p.L[b];
-  if (j == 0 && threadIdx.x == 0 && p.L_out) p.L_out[b] = Lb + (n < p.max_path ? n : p.max_path);
+  if (j == 0 && layer == 0 && threadIdx.x == 0 && p.L_out) p.L_out[b] = Lb + (n < p.max_path ? n : p.max_path);
   if (j >= n || Lb < 0) return;
   const int node = p.path[(size_t)b * p.max_path + j];
   if (node < 0 || node >= p.cu_T[b + 1] - p.cu_T[b]) {  // not a node of this tree: nothing is copied
@@ -741,8 +742,8 @@ __global__ void __launch_bounds__(256) commit_kernel(const CommitParams p) {
     const bool is_v = q >= pieces;
     const int r = is_v ? q - pieces : q;
     const int g = r / per_head, e = (r - g * per_head) * 8;
-    const char *src = (is_v ? p.v_tree : p.k_tree) + ((src_row * p.Hkv + g) * p.D + e) * 2;
-    char *out = (is_v ? p.v_cache : p.k_cache) + (dst + (int64_t)g * p.stride_head + e) * 2;
+    const char *src = (is_v ? p.v_tree : p.k_tree) + layer * p.layer_tree + ((src_row * p.Hkv + g) * p.D + e) * 2;
+    char *out = (is_v ? p.v_cache : p.k_cache) + layer * p.layer_cache + (dst + (int64_t)g * p.stride_head + e) * 2;
     *reinterpret_cast<u32x4 *>(out) = *reinterpret_cast<const u32x4 *>(src);
   }
 }
@@ -753,11 +754,11 @@ __global__ void __launch_bounds__(256) commit_kernel(const CommitParams p) {
 // position L_b + path[j] >= L_b + j and writes L_b + j, so a later step never reads what an earlier
 // one wrote, and a read that a later step overwrites comes first in the same thread's program order.
 __global__ void __launch_bounds__(256) compact_kernel(const CommitParams p) {
-  const int b = blockIdx.x;
+  const int b = blockIdx.x, layer = blockIdx.y;
   const int n = p.path_len[b] < p.max_path ? p.path_len[b] : p.max_path;
   const int Lb = p.L[b];
   const int T = p.cu_T[b + 1] - p.cu_T[b];
-  if (threadIdx.x == 0 && p.L_out) p.L_out[b] = Lb + n;
+  if (layer == 0 && threadIdx.x == 0 && p.L_out) p.L_out[b] = Lb + n;
   if (Lb < 0) return;
   const int per_head = p.D / 8;
   const int pieces = p.Hkv * per_head;
@@ -782,7 +783,7 @@ __global__ void __launch_bounds__(256) compact_kernel(const CommitParams p) {
       const bool is_v = q >= pieces;
       const int r = is_v ? q - pieces : q;
       const int g = r / per_head, e = (r - g * per_head) * 8;
-      char *base = is_v ? p.v_cache : p.k_cache;
+      char *base = (is_v ? p.v_cache : p.k_cache) + layer * p.layer_cache;
       const int64_t inner = (int64_t)g * p.stride_head + e;
       *reinterpret_cast<u32x4 *>(base + (dst + inner) * 2) = *reinterpret_cast<const u32x4 *>(base + (src + inner) * 2);
     }
@@ -886,7 +887,11 @@ int tva_commit_path(const tva_commit_args *a, void *stream) {
   if ((a->stride_page | a->stride_tok | a->stride_head) % 8) return TVA_INVALID_ARG;
   if (a->stride_page < 0 || a->stride_tok < 0 || a->stride_head < 0) return TVA_INVALID_ARG;
   if (a->L_out == a->L) return TVA_INVALID_ARG;
-  if (a->B > 65535) return TVA_UNSUPPORTED;
+  if (a->n_layers < 0 || a->layer_stride_cache < 0 || a->layer_stride_tree < 0 ||
+      (a->layer_stride_cache | a->layer_stride_tree) % 8)
+    return TVA_INVALID_ARG;
+  const int layers = a->n_layers > 0 ? a->n_layers : 1;
+  if (a->B > 65535 || layers > 65535) return TVA_UNSUPPORTED;
   CommitParams p;
   p.cu_T = a->cu_T; p.L = a->L; p.path = a->path; p.path_len = a->path_len;
   p.cu_L = a->cu_L; p.page_table = a->page_table;
@@ -898,9 +903,10 @@ int tva_commit_path(const tva_commit_args *a, void *stream) {
   p.stride_head = a->stride_head ? a->stride_head : a->D;
   p.stride_tok = a->stride_tok ? a->stride_tok : (int64_t)a->Hkv * a->D;
   p.stride_page = a->stride_page ? a->stride_page : (int64_t)p.page_size * p.stride_tok;
+  p.layer_cache = a->layer_stride_cache * 2, p.layer_tree = a->layer_stride_tree * 2;
   (void)hipGetLastError();
-  if (in_cache) hipLaunchKernelGGL(compact_kernel, dim3(a->B), dim3(256), 0, (hipStream_t)stream, p);
-  else hipLaunchKernelGGL(commit_kernel, dim3(a->max_path, a->B), dim3(256), 0, (hipStream_t)stream, p);
+  if (in_cache) hipLaunchKernelGGL(compact_kernel, dim3(a->B, layers), dim3(256), 0, (hipStream_t)stream, p);
+  else hipLaunchKernelGGL(commit_kernel, dim3(a->max_path, a->B, layers), dim3(256), 0, (hipStream_t)stream, p);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 

@@ -21,6 +21,7 @@ class CommitArgs(ctypes.Structure):
         ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
         ("stride_page", ctypes.c_int64), ("stride_tok", ctypes.c_int64), ("stride_head", ctypes.c_int64),
         ("L_out", ctypes.c_void_p), ("err_flag", ctypes.c_void_p),
+        ("n_layers", ctypes.c_int32), ("layer_stride_cache", ctypes.c_int64), ("layer_stride_tree", ctypes.c_int64),
     ]
 
 
@@ -112,7 +113,10 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
 
 
 def make_commit_args(*, cu_T, L, path, path_len, k_tree, v_tree, k_cache, v_cache, cu_L=None, page_table=None,
-                     page_size: int = 0, strides=(0, 0, 0), L_out=None, err_flag=None) -> CommitArgs:
+                     page_size: int = 0, strides=(0, 0, 0), L_out=None, err_flag=None, n_layers: int = 0,
+                     layer_stride_cache: int = 0, layer_stride_tree: int = 0) -> CommitArgs:
+    """k_cache, v_cache (and k_tree, v_tree): one layer's tensors, or with n_layers > 1 the first layer's, the others
+    layer_stride_* elements further on each."""
     a = CommitArgs()
     a.B = cu_T.numel() - 1
     a.Hkv, a.D = int(k_cache.shape[-2]), int(k_cache.shape[-1])
@@ -128,6 +132,9 @@ def make_commit_args(*, cu_T, L, path, path_len, k_tree, v_tree, k_cache, v_cach
         assert a.D % 2 == 0 and all(int(s) % 2 == 0 for s in strides)
         a.D //= 2
         a.stride_page, a.stride_tok, a.stride_head = (int(s) // 2 for s in strides)
+        assert layer_stride_cache % 2 == 0 and layer_stride_tree % 2 == 0
+        layer_stride_cache, layer_stride_tree = layer_stride_cache // 2, layer_stride_tree // 2
+    a.n_layers, a.layer_stride_cache, a.layer_stride_tree = int(n_layers), int(layer_stride_cache), int(layer_stride_tree)
     a.L_out, a.err_flag = _p(L_out), _p(err_flag)
     # the struct holds raw addresses: keep the tensors alive as long as it lives
     a._keep = (cu_T, L, path, path_len, k_tree, v_tree, k_cache, v_cache, cu_L, page_table, L_out, err_flag)
@@ -224,8 +231,72 @@ def _bench(argv=None) -> int:
         print(json.dumps({"shape": name, "accepted_nodes_per_step": accepted, "accept_us": times["accept"],
                           "commit_us": times["commit"], "both_us": times["both"], "commit_bytes": moved,
                           "commit_GBps": moved / (times["commit"] * 1e-6) / 1e9}), flush=True)
+    _bench_layers(a.steps)
     _bench_sampling(a.steps)
     return 0
+
+
+def _bench_layers(steps: int) -> None:
+    """The commit of a whole model's layers: 32 calls of tva_commit_path against one call with n_layers = 32 (the
+    caches of the layers one allocation, a layer's tensors a fixed stride apart)."""
+    import json
+    import numpy as np
+    import torch
+    from . import workloads as wl
+
+    rng = np.random.Generator(np.random.PCG64(81))
+    stream = torch.cuda.Stream()
+    layers, Hkv, D = 32, 8, 128
+    for name, B, T, depth in (("B=1 T=60", 1, 60, 6), ("B=8 T=32", 8, 32, 6), ("B=64 T=8", 64, 8, 8)):
+        trees = [wl.tree_uniform(rng, T, depth) for _ in range(B)]
+        parent = np.concatenate(trees).astype(np.int32)
+        cu_T = (np.arange(B + 1) * T).astype(np.int32)
+        path = np.full((B, depth + 1), -1, np.int32)
+        plen = np.zeros(B, np.int32)
+        for b in range(B):                          # a root path: from a random leaf upwards
+            node, up = int(rng.integers(0, T)), []
+            while node >= 0:
+                up.append(node)
+                node = int(trees[b][node])
+            up = up[::-1][:depth + 1]
+            path[b, :len(up)], plen[b] = up, len(up)
+        L = np.full(B, 1024, np.int32)
+        cu_L = (np.arange(B + 1) * (1024 + T)).astype(np.int32)
+        d = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+        rows = B * (1024 + T)
+        kc = torch.zeros((layers, rows, Hkv, D), dtype=torch.int16, device="cuda")
+        vc = torch.zeros_like(kc)
+        kt = torch.randint(-30000, 30000, (layers, B * T, Hkv, D), dtype=torch.int16, device="cuda")
+        vt = torch.randint(-30000, 30000, (layers, B * T, Hkv, D), dtype=torch.int16, device="cuda")
+        common = dict(cu_T=d(cu_T), L=d(L), path=d(path), path_len=d(plen), cu_L=d(cu_L))
+        each = [make_commit_args(k_tree=kt[l], v_tree=vt[l], k_cache=kc[l], v_cache=vc[l], **common) for l in range(layers)]
+        one = make_commit_args(k_tree=kt[0], v_tree=vt[0], k_cache=kc[0], v_cache=vc[0], n_layers=layers,
+                               layer_stride_cache=rows * Hkv * D, layer_stride_tree=B * T * Hkv * D, **common)
+        times = {}
+        for form, run in (("calls", lambda: [commit_path_raw(c, stream) for c in each]), ("one", lambda: commit_path_raw(one, stream))):
+            with torch.cuda.stream(stream):
+                run()
+                stream.synchronize()
+                g = torch.cuda.CUDAGraph()
+                reps = max(1, steps // 8)
+                with torch.cuda.graph(g, stream=stream):
+                    for _ in range(reps):
+                        run()
+                g.replay()
+                stream.synchronize()
+                best = 1e30
+                for _ in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    g.replay()
+                    e1.record(stream)
+                    e1.synchronize()
+                    best = min(best, e0.elapsed_time(e1) * 1e3 / reps)
+            times[form] = best
+        moved = float(plen.sum()) * layers * Hkv * D * 2 * 2 * 2
+        print(json.dumps({"shape": name + f" layers={layers}", "accepted_nodes": int(plen.sum()), "commit_us_one_call_per_layer": times["calls"],
+                          "commit_us_one_call": times["one"], "commit_bytes": moved,
+                          "commit_GBps_one_call": moved / (times["one"] * 1e-6) / 1e9}), flush=True)
 
 
 def _bench_sampling(steps: int) -> None:

@@ -169,6 +169,92 @@ def test_commit_paged_matches_oracle(torch_dev, page_size):
     assert np.array_equal(L_out.cpu().numpy(), L_ref)
 
 
+@pytest.mark.parametrize("form", ["dense", "paged", "in place dense", "in place paged"])
+def test_commit_of_all_layers_in_one_call(torch_dev, form):
+    """n_layers > 1: the layers' caches (and tree tensors) lie layer_stride elements apart, with a gap of unrelated
+    data between them; one call commits every layer as the oracle commits each of them, leaves the gaps alone, and
+    writes L_out once."""
+    torch = torch_dev
+    from paper_2510_26577_amd import verify
+    rng = np.random.Generator(np.random.PCG64(61 + len(form)))
+    layers, B, Hkv, D, page_size = 5, 4, 2, 64, 4
+    paged, in_place = "paged" in form, "in place" in form
+    T = np.array([9, 1, 30, 17])
+    L = np.array([20, 0, 7, 64], np.int32)
+    ws = [wl.random_workload(1500 + l, B, Hkv, Hkv, D, L, T, max_depth=6) for l in range(layers)]   # one tree, K/V per layer
+    parent = ws[0].parent
+    draft, target = make_tokens(rng, parent, ws[0].cu_T, vocab=30, plant=0.9)
+    paths, _ = vo.accept_greedy(parent, ws[0].cu_T, draft, target, max_path=8)
+    max_path = 8
+    path = np.full((B, max_path), -1, np.int32)
+    for b, p_ in enumerate(paths):
+        path[b, :len(p_)] = p_
+    plen = np.array([len(p_) for p_ in paths], np.int32)
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    cap = L + T + 3
+    cu = np.concatenate([[0], np.cumsum(cap)]).astype(np.int32)
+    max_pages = int((cap.max() + page_size - 1) // page_size)
+    table = rng.permutation(B * max_pages).reshape(B, max_pages).astype(np.int32)
+    rows = B * max_pages * page_size if paged else int(cap.sum())
+    gap = 24                                                     # elements of unrelated data between two layers' tensors
+    per_layer = rows * Hkv * D
+    def layered(fill):
+        buf = rng.integers(0, 2 ** 16, layers * (per_layer + gap)).astype(np.uint16)
+        for l in range(layers):
+            buf[l * (per_layer + gap): l * (per_layer + gap) + per_layer] = fill(l).reshape(-1)
+        return buf
+    def pool(l, which):
+        x = rng.integers(0, 2 ** 16, (rows, Hkv, D)).astype(np.uint16)
+        if in_place:                                             # the tree's rows sit behind the committed ones
+            src = ws[l].k_tree if which == "k" else ws[l].v_tree
+            for b in range(B):
+                for i in range(int(T[b])):
+                    t = int(L[b]) + i
+                    r = table[b, t // page_size] * page_size + t % page_size if paged else cu[b] + t
+                    x[r] = src[ws[l].cu_T[b] + i]
+        return x
+    k0 = [pool(l, "k") for l in range(layers)]
+    v0 = [pool(l, "v") for l in range(layers)]
+    kbuf, vbuf = layered(lambda l: k0[l]), layered(lambda l: v0[l])
+    tree_rows = int(T.sum()) * Hkv * D
+    ktree = np.concatenate([np.concatenate([ws[l].k_tree.reshape(-1), rng.integers(0, 2 ** 16, gap).astype(np.uint16)]) for l in range(layers)])
+    vtree = np.concatenate([np.concatenate([ws[l].v_tree.reshape(-1), rng.integers(0, 2 ** 16, gap).astype(np.uint16)]) for l in range(layers)])
+    i16 = lambda a: a.view(np.int16)
+    k_d, v_d = dev(i16(kbuf)), dev(i16(vbuf))
+    first = lambda t: t[:per_layer].view((rows // page_size, page_size, Hkv, D) if paged else (rows, Hkv, D))
+    kt_d, vt_d = dev(i16(ktree)), dev(i16(vtree))
+    L_out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    say(f"[case] commit of {layers} layers in one call, {form}")
+    verify.commit_path(cu_T=dev(ws[0].cu_T), L=dev(L), path=dev(path), path_len=dev(plen),
+                       k_tree=None if in_place else kt_d[:tree_rows].view(int(T.sum()), Hkv, D),
+                       v_tree=None if in_place else vt_d[:tree_rows].view(int(T.sum()), Hkv, D),
+                       k_cache=first(k_d), v_cache=first(v_d), cu_L=None if paged else dev(cu),
+                       page_table=dev(table) if paged else None, page_size=page_size if paged else 0, L_out=L_out, err_flag=err,
+                       n_layers=layers, layer_stride_cache=per_layer + gap, layer_stride_tree=tree_rows + gap)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    assert np.array_equal(L_out.cpu().numpy(), L + plen)
+    k_ref, v_ref = kbuf.copy(), vbuf.copy()
+    for l in range(layers):
+        if in_place:
+            ek, ev = k0[l].copy(), v0[l].copy()
+            for b, p_ in enumerate(paths):
+                for j, node in enumerate(p_):
+                    t_src, t_dst = int(L[b]) + node, int(L[b]) + j
+                    rs = table[b, t_src // page_size] * page_size + t_src % page_size if paged else cu[b] + t_src
+                    rd = table[b, t_dst // page_size] * page_size + t_dst % page_size if paged else cu[b] + t_dst
+                    ek[rd], ev[rd] = k0[l][rs], v0[l][rs]
+        elif paged:
+            ek, ev, _ = vo.commit_path_paged(k0[l].reshape(-1, page_size, Hkv, D), v0[l].reshape(-1, page_size, Hkv, D), table, page_size,
+                                             L, ws[l].k_tree, ws[l].v_tree, ws[l].cu_T, paths)
+        else:
+            ek, ev, _ = vo.commit_path_dense(k0[l], v0[l], cu, L, ws[l].k_tree, ws[l].v_tree, ws[l].cu_T, paths)
+        o = l * (per_layer + gap)
+        k_ref[o:o + per_layer], v_ref[o:o + per_layer] = ek.reshape(-1), ev.reshape(-1)
+    assert np.array_equal(k_d.cpu().numpy().view(np.uint16), k_ref) and np.array_equal(v_d.cpu().numpy().view(np.uint16), v_ref)
+
+
 def test_accept_then_commit_then_attend(torch_dev):
     """The committed rows are what the next step's attention reads: after commit, attention over the longer cache
     (with a one-node tree) equals the oracle on the host-side committed cache."""
