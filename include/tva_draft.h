@@ -53,6 +53,18 @@ typedef struct tva_expand_args {
   int32_t *cand_parent, *cand_token;
   void *workspace;
   size_t workspace_bytes;
+  /* Optional, all zero = not asked for: the breadth decision on the sorted candidates in the same call (what
+     tva_layer_breadth_count computes, below; its arguments' meaning is the same), on the candidates' VALUES: a
+     candidate's utility is exp(cand_score), evaluated in double precision and rounded to float32 (the scores of
+     this call are logarithms of the values Eq. 1 adds up).  Every sequence must then have the
+     same number of rows (sum_N = B * max_N); max_N * K <= 1024.  For a batch of one sequence of at most 16 rows the
+     count rides in the call's last launch (one launch and its wait less: 28 -> 19 us per draft layer at B = 1);
+     otherwise the call ends with the launch tva_layer_breadth_count would make. */
+  const double *draft_cost_row; /* device fp64 [max_N * K] */
+  double target_cost_one, C1;
+  int32_t *count;               /* device int32[1]; NULL = no count */
+  double *u_c_at;               /* device fp64[2] or NULL */
+  int32_t *count_err_flag;      /* device int32[1] or NULL */
 } tva_expand_args;
 
 size_t tva_expand_workspace_bytes(const tva_expand_args *shapes);

@@ -70,6 +70,121 @@ __device__ __forceinline__ int rank_among(const uint64_t *keys, int n, uint64_t 
   return larger;
 }
 
+
+// ---- Algorithm 1 on a utility and a cost sequence (Dynamic Expansion Stage, Dynamic Reranking Stage) ----
+// What a count needs once the per-rank sums are known; called by every thread of a workgroup (a multiple of 64
+// threads).  On entry s_u[k] holds, for rank k, the scores of that rank added over the samples in index order (LAYER)
+// or their mean (reranking); s_u, s_c: LDS for N doubles each.  The steps and their order are the host routines'
+// (tva_cast_breadth_prune, tva_cast_rerank_count): the running sum over k by one thread's additions (LAYER: divided
+// by B afterwards), c_k = cost[k] / unit, index j valid unless some chord (u_j - u_i) / (c_j - c_i), i < j, is below C.
+struct CountOut {
+  int32_t *count;     // [1]
+  int32_t *cu_T;      // [B + 1] or NULL: b * count
+  double *at;         // [2] or NULL: u and c at the count
+  int32_t *err_flag;  // [1] or NULL: 1 when the costs do not increase strictly (count 0)
+};
+
+template <bool LAYER>
+__device__ __forceinline__ void count_tail(double *s_u, double *s_c, double *s_g, int *s_bad, int *s_keep, int B,
+                                           const double *__restrict__ cost, double unit, int N, double C, const CountOut &out) {
+  const int tid = threadIdx.x, threads = blockDim.x;
+  if (tid == 0) *s_bad = 0, *s_keep = 1;  // (index 1 has no chord: always valid)
+  if (tid == 0) reinterpret_cast<unsigned long long *>(s_g + 2 * N)[0] = 0ull;  // (the largest |u| + |C c|, as an ordered integer)
+  // (s_u holds room for a multiple of 16: the running sum below reads and writes whole groups)
+  for (int k = N + tid; k < ((N + 15) & ~15); k += threads) s_u[k] = 0.0;
+  __syncthreads();
+  for (int k = tid; k < N; k += threads) {
+    s_c[k] = cost[k] / unit;
+    if (k > 0 && !(cost[k] / unit > cost[k - 1] / unit)) *s_bad = 1;  // costs must grow with the size
+  }
+  // the running sum, one addition after the other as the definition has it: one thread, sixteen values fetched from
+  // LDS at a time so that only the additions wait for one another
+  if (tid == 0) {
+    double run = 0.0;
+    for (int k0 = 0; k0 < N; k0 += 16) {
+      double v[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) v[e] = s_u[k0 + e];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        run += v[e];
+        s_u[k0 + e] = run;  // (past N: the zeros' place, not read again)
+      }
+    }
+  }
+  __syncthreads();
+  if (LAYER) {  // (Eq. 1 divides the accumulated sums by the number of samples: one division per index, outside the chain)
+    for (int k = tid; k < N; k += threads) s_u[k] = s_u[k] / B;
+    __syncthreads();
+  }
+  if (*s_bad) {
+    if (tid == 0) {
+      if (out.err_flag) atomicCAS(out.err_flag, 0, 1);
+      *out.count = 0;
+      if (out.at) out.at[0] = out.at[1] = 0.0;
+    }
+    if (out.cu_T)
+      for (int b = tid; b <= B; b += threads) out.cu_T[b] = 0;
+    return;
+  }
+  // Which indices are valid.  The chord from i into j is too flat when (u_j - u_i) / (c_j - c_i) < C; with c rising that
+  // is g_j < g_i for g = u - C c, up to rounding.  So j is valid when g_j exceeds the largest g before it by more than
+  // a margin that covers every rounding involved (2^-45 of the largest |u| + |C c|: the quotient then clears C by
+  // more than 16 units in the last place), invalid when it falls short of it by that margin (that one chord is too
+  // flat), and only an index in between -- equal values, a threshold met exactly -- has its chords divided one by
+  // one as the definition has them.  s_g: g, then the largest g before each index.
+  double *s_G = s_g + N;
+  double a_mine = 0.0;
+  for (int k = tid; k < N; k += threads) {
+    s_g[k] = s_u[k] - C * s_c[k];
+    a_mine = fmax(a_mine, fabs(s_u[k]) + fabs(C * s_c[k]));
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) a_mine = fmax(a_mine, __shfl_xor(a_mine, o));
+  if ((tid & 63) == 0) atomicMax(reinterpret_cast<unsigned long long *>(s_G + N), (unsigned long long)__double_as_longlong(a_mine));
+  __syncthreads();
+  if (tid < 64) {
+    // the first wave: lane l takes the indices l * per .. l * per + per - 1, the lanes' maxima are scanned, and the
+    // lane walks its indices again with what came before them
+    const int per = (N + 63) / 64, k0 = tid * per, k1 = k0 + per < N ? k0 + per : N;
+    double mine = -INFINITY;
+    for (int k = k0; k < k1; ++k) mine = fmax(mine, s_g[k]);
+    double before = mine;  // becomes the largest g of the lanes below
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double y = __shfl_up(before, o);
+      if (tid >= o) before = fmax(before, y);
+    }
+    before = __shfl_up(before, 1);
+    if (tid == 0) before = -INFINITY;
+    for (int k = k0; k < k1; ++k) {
+      s_G[k] = before;
+      before = fmax(before, s_g[k]);
+    }
+  }
+  __syncthreads();
+  const double margin = __longlong_as_double((long long)reinterpret_cast<unsigned long long *>(s_G + N)[0]) * 0x1p-45 + 1e-300;
+  for (int j = 1 + tid; j < N; j += threads) {
+    const double gap = s_g[j] - s_G[j];
+    bool valid = gap > margin;
+    if (!valid && !(gap < -margin)) {
+      const double uj = s_u[j], cj = s_c[j];
+      bool flat = false;
+      for (int i = 0; i < j; ++i) flat = flat | ((uj - s_u[i]) / (cj - s_c[i]) < C);
+      valid = !flat;
+    }
+    if (valid) atomicMax(s_keep, j + 1);
+  }
+  __syncthreads();
+  const int keep = *s_keep;
+  if (tid == 0) {
+    *out.count = keep;
+    if (out.at) out.at[0] = s_u[keep - 1], out.at[1] = s_c[keep - 1];
+  }
+  if (out.cu_T)
+    for (int b = tid; b <= B; b += threads) out.cu_T[b] = b * keep;
+}
+
 // ---- the best K of every piece of every row ----
 // grid (pieces, rows).  part[(row * pieces + piece) * K + j] = key of the piece's j-th best token (0 = none: the
 // piece has fewer than K tokens).  Orders are found by counting, for a key, the keys that are larger (keys are unique,
@@ -247,7 +362,8 @@ __global__ void __launch_bounds__(256) row_merge_kernel(const uint64_t *__restri
 // best: the rows' best K (n * K keys, global memory or LDS); s_key, s_tok: LDS for n * K entries
 __device__ __forceinline__ void order_candidates(const uint64_t *best, int n, int K, int r0, const float *__restrict__ score,
                                                  uint64_t *s_key, int32_t *s_tok, float *__restrict__ cand_score,
-                                                 int32_t *__restrict__ cand_parent, int32_t *__restrict__ cand_token) {
+                                                 int32_t *__restrict__ cand_parent, int32_t *__restrict__ cand_token,
+                                                 double *s_sorted = nullptr) {
   const int tid = threadIdx.x, threads = blockDim.x;
   const int total = n * K;
   const size_t out0 = (size_t)r0 * K;
@@ -263,6 +379,9 @@ __device__ __forceinline__ void order_candidates(const uint64_t *best, int n, in
     const uint64_t kx = s_key[i];
     const int place = rank_among(s_key, total, kx);
     cand_score[out0 + place] = unordered((uint32_t)(kx >> 32));
+    // (for the count that follows in the same launch: the candidate's value, exp(score) in double precision rounded
+    // to float32, as the count's own kernel takes it)
+    if (s_sorted) s_sorted[place] = (double)(float)exp((double)unordered((uint32_t)(kx >> 32)));
     cand_parent[out0 + place] = i / K;
     cand_token[out0 + place] = s_tok[i];
   }
@@ -289,7 +408,12 @@ __global__ void __launch_bounds__(64 * kSmallRows) expand_finish_small_kernel(co
                                                                              const float *__restrict__ score,
                                                                              float *__restrict__ cand_score,
                                                                              int32_t *__restrict__ cand_parent,
-                                                                             int32_t *__restrict__ cand_token) {
+                                                                             int32_t *__restrict__ cand_token,
+                                                                             const double *__restrict__ cost, double unit, double C,
+                                                                             CountOut count_out) {
+  __shared__ double s_u[kSmallRows * kMaxK], s_c[kSmallRows * kMaxK];
+  __shared__ double s_g[2 * kSmallRows * kMaxK + 1];
+  __shared__ int s_bad, s_keep;
   __shared__ uint64_t s_row[kSmallRows][kSmallPerRow];
   __shared__ uint64_t s_surv[kSmallRows][64];
   __shared__ uint64_t s_tau[kSmallRows];
@@ -303,7 +427,10 @@ __global__ void __launch_bounds__(64 * kSmallRows) expand_finish_small_kernel(co
   if (wave < n)
     merge_row(part + (size_t)(r0 + wave) * pieces * K, pieces, K, s_row[wave], s_surv[wave], &s_tau[wave], s_best + wave * K);
   __syncthreads();
-  order_candidates(s_best, n, K, r0, score, s_key, s_tok, cand_score, cand_parent, cand_token);
+  // a batch of one sequence that also wants the breadth decision: the sorted scores stay in LDS and the count follows
+  const bool counted = count_out.count != nullptr;
+  order_candidates(s_best, n, K, r0, score, s_key, s_tok, cand_score, cand_parent, cand_token, counted ? s_u : nullptr);
+  if (counted) count_tail<true>(s_u, s_c, s_g, &s_bad, &s_keep, 1, cost, unit, n * K, C, count_out);
 }
 
 // ---- the best nodes of a grown tree, renumbered ----
@@ -391,75 +518,30 @@ constexpr int kCountStage = 10240;  // floats of LDS for the trees' best scores 
 // c_k = cost[k] / unit with the target's cost of one token passed in; at[0], at[1] receive u and c at the kept count.
 template <bool LAYER>
 __global__ void __launch_bounds__(kCountThreads) rerank_count_kernel(const float *__restrict__ best, int B, const double *__restrict__ cost,
-                                                                     double unit, int N, double C, int32_t *__restrict__ count,
-                                                                     int32_t *__restrict__ cu_T, double *__restrict__ at,
-                                                                     int32_t *__restrict__ err_flag) {
+                                                                     double unit, int N, double C, CountOut out, int logs) {
   __shared__ double s_u[kRerankMaxN], s_c[kRerankMaxN];
-  __shared__ float s_best[kCountStage];
+  __shared__ __align__(8) float s_best[kCountStage];
   __shared__ int s_bad, s_keep;
   const int tid = threadIdx.x;
-  if (tid == 0) s_bad = 0, s_keep = 1;  // (index 1 has no chord: always valid)
+  // logs: the scores are logarithms of the values the utility adds up (tva_expand_layer's): value = exp(score),
+  // evaluated in double precision and rounded to float32
+  auto value = [&](float x) { return logs ? (float)exp((double)x) : x; };
   // the trees' best scores, fetched by all threads at once where they fit (one round trip, not one per sample)
   const bool staged = B * N <= kCountStage;
   if (staged)
-    for (int e = tid; e < B * N; e += kCountThreads) s_best[e] = best[e];
+    for (int e = tid; e < B * N; e += kCountThreads) s_best[e] = value(best[e]);
   __syncthreads();
-  const double cost0 = LAYER ? unit : cost[0];
   for (int k = tid; k < N; k += kCountThreads) {
     double col = 0.0;  // (added in the samples' order)
     if (staged) {
       for (int j = 0; j < B; ++j) col += (double)s_best[j * N + k];
     } else {
-      for (int j = 0; j < B; ++j) col += (double)best[(size_t)j * N + k];
+      for (int j = 0; j < B; ++j) col += (double)value(best[(size_t)j * N + k]);
     }
-    s_u[k] = LAYER ? col : col / B;  // (the rank-wise batch mean; summed up below)
-    s_c[k] = cost[k] / cost0;
-    if (k > 0 && !(cost[k] / cost0 > cost[k - 1] / cost0)) s_bad = 1;  // costs must grow with the size
+    s_u[k] = LAYER ? col : col / B;  // (reranking: the rank-wise batch mean)
   }
-  __syncthreads();
-  // the running sum, one addition after the other as the definition has it: the lanes of the first wave hold 64 means
-  // at a time and hand them to the sum by lane reads (no LDS round trip per step)
-  if (tid < 64) {
-    double run = 0.0;
-    for (int base = 0; base < N; base += 64) {
-      const double v = base + tid < N ? s_u[base + tid] : 0.0;
-      const int n = N - base < 64 ? N - base : 64;
-      double mine = 0.0;
-      const uint32_t vlo = (uint32_t)__double_as_longlong(v), vhi = (uint32_t)(__double_as_longlong(v) >> 32);
-      for (int k = 0; k < n; ++k) {  // (k is the same in every lane: a lane read, not a permutation through LDS)
-        const uint32_t lo = __builtin_amdgcn_readlane(vlo, k), hi = __builtin_amdgcn_readlane(vhi, k);
-        run += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
-        if (tid == k) mine = run;
-      }
-      if (base + tid < N) s_u[base + tid] = LAYER ? mine / B : mine;  // (one division per lane, outside the chain)
-    }
-  }
-  __syncthreads();
-  if (s_bad) {
-    if (tid == 0) {
-      if (err_flag) atomicCAS(err_flag, 0, 1);
-      *count = 0;
-      if (at) at[0] = at[1] = 0.0;
-    }
-    if (cu_T)
-      for (int b = tid; b <= B; b += kCountThreads) cu_T[b] = 0;
-    return;
-  }
-  // the chords into index j: the waves take the j in turn, a wave's lanes the earlier indices i
-  for (int j = 1 + (tid >> 6); j < N; j += kCountThreads / 64) {
-    const double uj = s_u[j], cj = s_c[j];
-    bool flat = false;
-    for (int i = tid & 63; i < j; i += 64) flat = flat | ((uj - s_u[i]) / (cj - s_c[i]) < C);
-    if (__ballot(flat) == 0ull && (tid & 63) == 0) atomicMax(&s_keep, j + 1);
-  }
-  __syncthreads();
-  const int keep = s_keep;
-  if (tid == 0) {
-    *count = keep;
-    if (at) at[0] = s_u[keep - 1], at[1] = s_c[keep - 1];
-  }
-  if (cu_T)
-    for (int b = tid; b <= B; b += kCountThreads) cu_T[b] = b * keep;
+  __syncthreads();  // (the staged scores have been added up: their place holds g and its running maximum from here on)
+  count_tail<LAYER>(s_u, s_c, reinterpret_cast<double *>(s_best), &s_bad, &s_keep, B, cost, LAYER ? unit : cost[0], N, C, out);
 }
 
 int pieces_of(int V) { return (int)(((int64_t)V + kPiece - 1) / kPiece); }
@@ -491,6 +573,13 @@ int tva_expand_layer(const tva_expand_args *a, void *stream) {
       a->ld_logp < a->V || ((uintptr_t)a->workspace & 7))
     return TVA_INVALID_ARG;
   if (a->workspace_bytes < tva_expand_workspace_bytes(a)) return TVA_WORKSPACE_TOO_SMALL;
+  // the breadth decision on the sorted candidates, if asked for: every sequence the same number of rows
+  const bool counted = a->count != nullptr;
+  const int n_cand = a->max_N * a->K;
+  if (counted && (!a->draft_cost_row || !(a->target_cost_one > 0.0) || (int64_t)a->B * a->max_N != a->sum_N)) return TVA_INVALID_ARG;
+  if (counted && n_cand > kRerankMaxN) return TVA_UNSUPPORTED;
+  const CountOut count_out{a->count, nullptr, a->u_c_at, a->count_err_flag};
+  const CountOut no_count{nullptr, nullptr, nullptr, nullptr};
   const int pieces = pieces_of(a->V);
   uint64_t *part = static_cast<uint64_t *>(a->workspace);
   hipStream_t st = (hipStream_t)stream;
@@ -502,8 +591,14 @@ int tva_expand_layer(const tva_expand_args *a, void *stream) {
   else hipLaunchKernelGGL(topk_parts_kernel<false>, grid, dim3(kPieceThreads), 0, st, a->logp, a->ld_logp, a->V, a->K, part);
   uint64_t *best = part;
   if (pieces > 1 && a->max_N <= kSmallRows && pieces * a->K <= kSmallPerRow) {
+    // (a batch of one sequence: the count rides in the same launch)
+    const bool fused = counted && a->B == 1;
     hipLaunchKernelGGL(expand_finish_small_kernel, dim3(a->B), dim3(64 * kSmallRows), 0, st, part, pieces, a->K, a->cu_N, a->score,
-                       a->cand_score, a->cand_parent, a->cand_token);
+                       a->cand_score, a->cand_parent, a->cand_token, a->draft_cost_row, a->target_cost_one, a->C1,
+                       fused ? count_out : no_count);
+    if (counted && !fused)
+      hipLaunchKernelGGL(rerank_count_kernel<true>, dim3(1), dim3(kCountThreads), 0, st, a->cand_score, a->B, a->draft_cost_row,
+                         a->target_cost_one, n_cand, a->C1, count_out, 1);
     return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
   }
   if (pieces > 1) {
@@ -512,6 +607,9 @@ int tva_expand_layer(const tva_expand_args *a, void *stream) {
   }
   hipLaunchKernelGGL(expand_finish_kernel, dim3(a->B), dim3(256), 0, st, best, a->K, a->cu_N, a->score, a->cand_score,
                      a->cand_parent, a->cand_token);
+  if (counted)
+    hipLaunchKernelGGL(rerank_count_kernel<true>, dim3(1), dim3(kCountThreads), 0, st, a->cand_score, a->B, a->draft_cost_row,
+                       a->target_cost_one, n_cand, a->C1, count_out, 1);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 
@@ -545,7 +643,7 @@ int tva_tree_rerank_count(const float *tree_scores, int32_t B, int32_t N_tot, co
   (void)hipGetLastError();
   hipLaunchKernelGGL(rank_trees_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, tree_scores, N_tot, N, best);
   hipLaunchKernelGGL(rerank_count_kernel<false>, dim3(1), dim3(kCountThreads), 0, (hipStream_t)stream, best, B, cost_row, 0.0, N, C3,
-                     count, cu_T, nullptr, err_flag);
+                     CountOut{count, cu_T, nullptr, err_flag}, 0);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 
@@ -555,7 +653,7 @@ int tva_layer_breadth_count(const float *cand_score, int32_t B, int32_t N, const
   if (N > kRerankMaxN) return TVA_UNSUPPORTED;
   (void)hipGetLastError();
   hipLaunchKernelGGL(rerank_count_kernel<true>, dim3(1), dim3(kCountThreads), 0, (hipStream_t)stream, cand_score, B, draft_cost_row,
-                     target_cost_one, N, C1, count, nullptr, u_c_at, err_flag);
+                     target_cost_one, N, C1, CountOut{count, nullptr, u_c_at, err_flag}, 0);
   return hipPeekAtLastError() == hipSuccess ? TVA_OK : TVA_HIP_ERROR;
 }
 

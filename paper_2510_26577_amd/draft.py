@@ -15,7 +15,9 @@ class ExpandArgs(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("V", ctypes.c_int32), ("K", ctypes.c_int32), ("sum_N", ctypes.c_int32),
                 ("max_N", ctypes.c_int32), ("cu_N", ctypes.c_void_p), ("score", ctypes.c_void_p), ("logp", ctypes.c_void_p),
                 ("ld_logp", ctypes.c_int64), ("cand_score", ctypes.c_void_p), ("cand_parent", ctypes.c_void_p),
-                ("cand_token", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+                ("cand_token", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("draft_cost_row", ctypes.c_void_p), ("target_cost_one", ctypes.c_double), ("C1", ctypes.c_double),
+                ("count", ctypes.c_void_p), ("u_c_at", ctypes.c_void_p), ("count_err_flag", ctypes.c_void_p)]
 
 
 def _lib():
@@ -51,12 +53,16 @@ def expand_workspace_bytes(B: int, V: int, K: int, sum_N: int) -> int:
 
 
 def make_expand_args(*, cu_N, score, logp, K: int, sum_N: int, max_N: int, cand_score, cand_parent, cand_token,
-                     workspace=None, workspace_bytes: int = 0) -> ExpandArgs:
+                     workspace=None, workspace_bytes: int = 0, draft_cost_row=None, target_cost_one: float = 0.0,
+                     C1: float = 0.0, count=None, u_c_at=None, count_err_flag=None) -> ExpandArgs:
+    """count (device int32 [1]) asks for the breadth decision on the sorted candidates in the same call."""
     a = ExpandArgs()
     a.B, a.V, a.K, a.sum_N, a.max_N = cu_N.numel() - 1, int(logp.shape[1]), int(K), int(sum_N), int(max_N)
     a.cu_N, a.score, a.logp, a.ld_logp = _p(cu_N), _p(score), _p(logp), int(logp.stride(0))
     a.cand_score, a.cand_parent, a.cand_token = _p(cand_score), _p(cand_parent), _p(cand_token)
     a.workspace, a.workspace_bytes = _p(workspace), int(workspace_bytes)
+    a.draft_cost_row, a.target_cost_one, a.C1 = _p(draft_cost_row), float(target_cost_one), float(C1)
+    a.count, a.u_c_at, a.count_err_flag = _p(count), _p(u_c_at), _p(count_err_flag)
     return a
 
 
@@ -182,12 +188,18 @@ def _bench(argv=None) -> int:
             ws = torch.empty(max(1, need // 8), dtype=torch.int64, device="cuda")
             outs = (torch.empty(B * n * K, dtype=torch.float32, device="cuda"), torch.empty(B * n * K, dtype=torch.int32, device="cuda"),
                     torch.empty(B * n * K, dtype=torch.int32, device="cuda"))
-            cases.append((make_expand_args(cu_N=cu_N, score=score, logp=logp, K=K, sum_N=B * n, max_N=n, cand_score=outs[0],
-                                           cand_parent=outs[1], cand_token=outs[2], workspace=ws, workspace_bytes=need),
-                          (logp, score, cu_N, ws, outs)))
+            dcost = torch.cumsum(torch.rand(n * K, dtype=torch.float64, device="cuda") * 0.04 + 0.002, 0) + 0.5
+            cnt = (torch.zeros(1, dtype=torch.int32, device="cuda"), torch.zeros(2, dtype=torch.float64, device="cuda"))
+            common = dict(cu_N=cu_N, score=score, logp=logp, K=K, sum_N=B * n, max_N=n, cand_score=outs[0], cand_parent=outs[1],
+                          cand_token=outs[2], workspace=ws, workspace_bytes=need)
+            cases.append((make_expand_args(**common),
+                          (logp, score, cu_N, ws, outs, dcost, cnt),
+                          make_expand_args(draft_cost_row=dcost, target_cost_one=8.0, C1=0.01, count=cnt[0], u_c_at=cnt[1], **common)))
         us = timed(lambda: [expand_layer_raw(c[0], stream) for c in cases], copies)
+        us_counted = timed(lambda: [expand_layer_raw(c[2], stream) for c in cases], copies) if n * K <= 1024 else None
         nbytes = 4.0 * B * n * V
         print(json.dumps({"kernel": "tva_expand_layer", "shape": f"B={B} rows/seq={n} V={V} K={K}", "us_per_call": us,
+                          "us_with_the_breadth_decision": us_counted,
                           "logp_bytes": nbytes, "GBps": nbytes / (us * 1e-6) / 1e9, "frac_of_8TBps": nbytes / (us * 1e-6) / 8e12}),
               flush=True)
         del cases

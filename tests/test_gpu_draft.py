@@ -67,6 +67,70 @@ def test_expand_layer_matches_oracle(torch_dev, n_rows, V, K, levels):
     check_expand(torch, cu_N, score, logp, K)
 
 
+@pytest.mark.parametrize("B,n,V,K", [(1, 12, 50000, 12),     # one sequence, several pieces a row: the count rides in the last launch
+                                      (1, 16, 128256, 16),    # the most that form takes: 256 candidates
+                                      (1, 12, 8000, 12),      # one piece a row: the count is a launch of its own
+                                      (1, 20, 20000, 8),      # more than 16 rows: the general path
+                                      (4, 12, 32000, 12), (64, 3, 9000, 5)])
+def test_expand_layer_with_the_breadth_decision(torch_dev, B, n, V, K):
+    """tva_expand_layer asked for the breadth decision too: the candidates are the oracle's as without it, and the
+    count, utility and cost are the oracle's breadth decision (Eq. 1, Eq. 2, Algorithm 1) on the candidates' values
+    exp(score), for thresholds from "keep all" to "keep one"."""
+    torch = torch_dev
+    from paper_2510_26577_amd import draft
+    rng = np.random.Generator(np.random.PCG64(4200 + B + n + V))
+    cu_N, score, logp = wl.expansion_inputs(rng, [n] * B, V)
+    d = lambda a, t: torch.from_numpy(np.ascontiguousarray(a, dtype=t)).cuda()
+    N = n * K
+    M_rows, L, ctx = 4, 128, 200
+    S_T = np.cumsum(rng.uniform(0.05, 0.3, (M_rows, N + 1)), axis=1) + 8.0
+    S_D = np.cumsum(rng.uniform(0.002, 0.05, (M_rows, N + 1)), axis=1) + 0.5
+    row = co.select_context(ctx, L, M_rows) // L - 1
+    ref = do.expand_layer(score, cu_N, logp, K)
+    values = np.stack([np.exp(r[0].astype(np.float64)).astype(np.float32) for r in ref])      # [B, N], descending
+    say(f"[case] expand with the breadth decision B={B} n={n} V={V} K={K}")
+    e_in = (d(cu_N, np.int32), d(score, np.float32), d(logp, np.float32), d(S_D[row, :N], np.float64))
+    cs = torch.empty(B * N, dtype=torch.float32, device="cuda")
+    cp = torch.empty(B * N, dtype=torch.int32, device="cuda")
+    ct = torch.empty(B * N, dtype=torch.int32, device="cuda")
+    need = draft.expand_workspace_bytes(B, V, K, B * n)
+    ws = torch.empty(max(1, need // 8), dtype=torch.int64, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    at = torch.zeros(2, dtype=torch.float64, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    counts = set()
+    scale = float(values[:, 0].mean()) / float(S_D[row, 0] / S_T[row, 0])                     # the first candidate's slope
+    for C1 in (-1e30, 0.0, 1e-4 * scale, 1e-2 * scale, 0.1 * scale, scale, 1e30):
+        want, wu, wc = co.breadth_prune(values.tolist(), S_D.tolist(), S_T.tolist(), ctx, L, M_rows, C1)
+        args = draft.make_expand_args(cu_N=e_in[0], score=e_in[1], logp=e_in[2], K=K, sum_N=B * n, max_N=n, cand_score=cs,
+                                      cand_parent=cp, cand_token=ct, workspace=ws, workspace_bytes=need, draft_cost_row=e_in[3],
+                                      target_cost_one=float(S_T[row, 0]), C1=C1, count=count, u_c_at=at, count_err_flag=flag)
+        count.fill_(-1)
+        draft.expand_layer_raw(args)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 0
+        assert int(count.item()) == want, C1
+        u_at, c_at = at.cpu().tolist()
+        assert abs(u_at - wu) <= 1e-12 * max(1.0, abs(wu)) and abs(c_at - wc) <= 1e-15 * abs(wc), C1
+        counts.add(want)
+    assert len(counts) >= 3
+    for b, (rs, rp, rt) in enumerate(ref):
+        assert np.array_equal(cs.cpu().numpy()[b * N:(b + 1) * N], rs) and np.array_equal(ct.cpu().numpy()[b * N:(b + 1) * N], rt)
+    # refused: sequences of different sizes, no cost row
+    from paper_2510_26577_amd import binding
+    if B > 1:
+        bad = draft.make_expand_args(cu_N=e_in[0], score=e_in[1], logp=e_in[2], K=K, sum_N=B * n - 1, max_N=n, cand_score=cs,
+                                     cand_parent=cp, cand_token=ct, workspace=ws, workspace_bytes=need, draft_cost_row=e_in[3],
+                                     target_cost_one=1.0, C1=1.0, count=count)
+        with pytest.raises(binding.TvaError):
+            draft.expand_layer_raw(bad)
+    bad = draft.make_expand_args(cu_N=e_in[0], score=e_in[1], logp=e_in[2], K=K, sum_N=B * n, max_N=n, cand_score=cs,
+                                 cand_parent=cp, cand_token=ct, workspace=ws, workspace_bytes=need, target_cost_one=1.0, C1=1.0,
+                                 count=count)
+    with pytest.raises(binding.TvaError):
+        draft.expand_layer_raw(bad)
+
+
 def test_expand_layer_layouts_and_special_values(torch_dev):
     """Rows further apart than V, rows that do not start on 16 bytes (the one-token-per-load path on a vocabulary that
     would allow four), log-probabilities of -inf (tokens of probability zero; a row with fewer finite entries than K
