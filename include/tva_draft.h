@@ -59,7 +59,8 @@ typedef struct tva_expand_args {
      this call are logarithms of the values Eq. 1 adds up).  Every sequence must then have the
      same number of rows (sum_N = B * max_N); max_N * K <= 1024.  For a batch of one sequence of at most 16 rows the
      count rides in the call's last launch (one launch and its wait less: 28 -> 19 us per draft layer at B = 1);
-     otherwise the call ends with the launch tva_layer_breadth_count would make. */
+     otherwise the call ends with the launch tva_layer_breadth_count would make.  A call without rows (B = 0 or
+     sum_N = 0) writes nothing, the count included. */
   const double *draft_cost_row; /* device fp64 [max_N * K] */
   double target_cost_one, C1;
   int32_t *count;               /* device int32[1]; NULL = no count */
