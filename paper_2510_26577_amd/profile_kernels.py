@@ -4,6 +4,8 @@ summaries the design document quotes.
 
     python3 -m paper_2510_26577_amd.profile_kernels trace cfg2 cfg4 ...     profiles/kernel_trace_<workload>.txt
     python3 -m paper_2510_26577_amd.profile_kernels counters cfg2_B32 ...   profiles/counters_<workload>.txt
+    python3 -m paper_2510_26577_amd.profile_kernels module draft verify     profiles/kernel_trace_<module>_kernels.txt
+                                                                            (the kernels around the attention)
 
 Measurement aid: nothing on the hot path imports it.  The profiled program is started directly behind
 `rocprofv3 ... --` (python3 bench.py ...), as a child of this process, which itself never touches the GPU.
@@ -124,12 +126,56 @@ def counters(workload: str) -> str:
     return path
 
 
+def module_trace(module: str) -> str:
+    """Per-kernel durations of `python3 -m paper_2510_26577_amd.<module>` (the timing programs of the kernels around the
+    attention) under rocprofv3 --kernel-trace: one line per kernel and launch shape."""
+    if module not in ("draft", "verify"):
+        raise ValueError("module: draft or verify")
+    work = tempfile.mkdtemp(prefix="tva_mtrace_", dir="/tmp")
+    try:
+        d = os.path.join(work, "kt")
+        cmd = ["rocprofv3", "--kernel-trace", "-d", d, "-o", "p", "--output-format", "csv", "--", "python3", "-m",
+               "paper_2510_26577_amd." + module]
+        env = dict(os.environ, TMPDIR="/tmp", PYTHONPATH=ROOT + os.pathsep + os.environ.get("PYTHONPATH", ""))
+        res = subprocess.run(["timeout", "-s", "KILL", "600", *cmd], cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE,
+                             text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"{' '.join(cmd)} failed ({res.returncode}):\n{res.stderr[-2000:]}")
+        files = glob.glob(os.path.join(d, "**", "*kernel_trace.csv"), recursive=True)
+        if not files:
+            raise RuntimeError("no kernel_trace.csv under " + d)
+        agg = collections.defaultdict(list)
+        for row in csv.DictReader(open(files[0])):
+            name = row["Kernel_Name"]
+            if "at::" in name or "elementwise_kernel" in name or "anonymous namespace" not in name:
+                continue                                 # (torch's own kernels, which make the inputs, are left out)
+            key = (name.replace("(anonymous namespace)::", "").split("(")[0], int(row["Grid_Size_X"]) // max(int(row["Workgroup_Size_X"]), 1),
+                   int(row["Grid_Size_Y"]) // max(int(row["Workgroup_Size_Y"]), 1), int(row["Grid_Size_Z"]) // max(int(row["Workgroup_Size_Z"]), 1),
+                   int(row["Workgroup_Size_X"]))
+            agg[key].append(int(row["End_Timestamp"]) - int(row["Start_Timestamp"]))
+    finally:
+        shutil.rmtree(work, ignore_errors=True)
+    out = [f"rocprofv3 kernel-trace summary of the kernels around the attention: python3 -m paper_2510_26577_amd.{module}, MI355X (gfx950)",
+           "made by:  python3 -m paper_2510_26577_amd.profile_kernels module " + module,
+           "which runs:  " + " ".join(cmd).replace(d, "<dir>"),
+           "(one line per kernel and launch shape, in the order of the program's shapes; microseconds from the tracer's start and end",
+           " stamps of each dispatch; the program's own per-call figures, which include the gaps between launches, are in",
+           f" profiles/{module}_kernels_timing.txt)", "",
+           f"{'kernel':44s} {'workgroups (x, y, z)':>22s} {'threads':>8s} {'calls':>7s} {'median_us':>10s} {'min_us':>8s} {'max_us':>9s}"]
+    for (name, gx, gy, gz, wg), v in agg.items():
+        v.sort()
+        out.append(f"{name[:44]:44s} {f'{gx}, {gy}, {gz}':>22s} {wg:8d} {len(v):7d} {v[len(v) // 2] / 1e3:10.2f} {v[0] / 1e3:8.2f} {v[-1] / 1e3:9.2f}")
+    path = os.path.join(ROOT, "profiles", f"kernel_trace_{module}_kernels.txt")
+    open(path, "w").write("\n".join(out) + "\n")
+    return path
+
+
 def main(argv) -> int:
-    if len(argv) < 2 or argv[0] not in ("trace", "counters"):
+    if len(argv) < 2 or argv[0] not in ("trace", "counters", "module"):
         print(__doc__)
         return 2
     for wl in argv[1:]:
-        print((trace if argv[0] == "trace" else counters)(wl), flush=True)
+        print({"trace": trace, "counters": counters, "module": module_trace}[argv[0]](wl), flush=True)
     return 0
 
 
