@@ -24,7 +24,7 @@ INCLUDE_DIR = os.path.join(_ROOT, "include")
 
 TVA_OK = 0
 TVA_MAX_TREE = 128
-EXPECTED_VERSION = 6
+EXPECTED_VERSION = 7
 # tva_shape (include/tva.h): workgroup shapes a caller may name in tva_args.plan_shape
 SHAPE_AUTO, SHAPE_R32_W2, SHAPE_R64_W4, SHAPE_R64_W4_DEEP, SHAPE_R128_W8, SHAPE_R256_W8 = range(6)
 SHAPES = (SHAPE_R32_W2, SHAPE_R64_W4, SHAPE_R64_W4_DEEP, SHAPE_R128_W8, SHAPE_R256_W8)

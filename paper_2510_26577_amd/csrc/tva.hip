@@ -1388,7 +1388,7 @@ int static_scratch(void **out) {
 
 extern "C" {
 
-int tva_version(void) { return 6; }
+int tva_version(void) { return 7; }
 
 int tva_timeline_read(uint64_t *dst, int32_t n_workgroups) {
 #ifdef TVA_TIMELINE
