@@ -57,7 +57,7 @@ def accept_greedy(parent, cu_T, draft_token, target_token, max_path=None):
     return paths, nxt
 
 
-def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, max_path=None):
+def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, max_path=None, unit_rows=False):
     """Acceptance by speculative sampling on draft trees (paper, Preliminary, "Speculative Decoding": a drafted
     token x with draft probability q(x) and target probability p(x) is accepted when a uniform number is at most
     min(1, p(x) / q(x)); after a rejection the target distribution is replaced by the residual norm(max(0, p - q));
@@ -79,7 +79,11 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
           r kept unnormalised with Z = sum(r) (a token the draft gave probability 0 but the residual does not
           is accepted);
       S4  the last token is the smallest v whose cumulative weight r[0] + .. + r[v] exceeds u_final * Z
-          (the last v with r[v] > 0 if rounding leaves none).
+          (the last v with r[v] > 0 if rounding leaves none);
+      S5  unit_rows: the caller states that every target row is a distribution (sums to one), and at a node that
+          has just been reached Z is taken as 1 instead of being summed: the test is then u q(x) <= p(x) and the
+          first residual max(0, p - q), both as the paper prints them.  The last draw still divides by the sum of what
+          it draws from.
     Precision: r is held in float32 as the kernel holds it; sums, products and comparisons in float64.
     Pins: the paper prints no example; pinned by the chain rule written out, by the theorem that the emitted
     token is distributed as p, and by the temperature-0 and q = p special cases."""
@@ -94,7 +98,8 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
         cur, path = 0, [0]
         while True:
             r = np.array(p_target[t0 + cur], dtype=np.float32, copy=True)
-            Z = float(r.astype(np.float64).sum())
+            Z = 1.0 if unit_rows else float(r.astype(np.float64).sum())
+            fresh = True
             q = np.asarray(q_draft[t0 + cur], dtype=np.float32).astype(np.float64)
             accepted = False
             if max_path is None or len(path) < max_path:
@@ -112,9 +117,11 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
                     Z_new = float(r_new.astype(np.float64).sum())
                     if not Z_new > 0.0:
                         raise ValueError("residual vanished: q is not a distribution the child could have been drawn from")
-                    r, Z = r_new, Z_new
+                    r, Z, fresh = r_new, Z_new, False
             if accepted:
                 continue
+            if fresh:
+                Z = float(r.astype(np.float64).sum())          # (S5: the last draw is from r / sum(r) in either reading)
             cs = np.cumsum(r.astype(np.float64))
             hit = np.nonzero(cs > float(u_final[b]) * Z)[0]
             v = int(hit[0]) if len(hit) else int(np.nonzero(r > 0)[0][-1])

@@ -189,6 +189,71 @@ def test_sampling_emits_tokens_distributed_as_the_target():
     assert np.abs(np.bincount(tok[:, 1], minlength=V) / N - p).max() > 20 * sigma.max()
 
 
+def test_sampling_with_rows_taken_as_distributions():
+    """Reading S5 (unit_rows: a freshly reached node's Z is 1, not the row's sum).  (a) On rows whose float32 entries
+    add up to exactly one (multiples of 2^-12) the two readings are the same computation.  (b) On a chain it is the
+    rule of the paper as printed -- u <= p(x) / q(x) with the rows as they are, no division by their sums, residual
+    max(0, p - q) -- written out here.  (c) The theorem still holds: the first emitted token is distributed as p."""
+    rng = np.random.Generator(np.random.PCG64(35))
+    V = 9
+    def dyadic_rows(n):
+        cuts = np.sort(rng.integers(0, 4097, size=(n, V - 1)), axis=1)
+        w = np.diff(np.concatenate([np.zeros((n, 1), np.int64), cuts, np.full((n, 1), 4096)], axis=1), axis=1)
+        return (w / 4096.0).astype(np.float32)
+    for _ in range(200):
+        T = int(rng.integers(1, 9))
+        parent = np.array([-1] + [int(rng.integers(0, i)) for i in range(1, T)], np.int32)
+        P, Q = dyadic_rows(T), dirichlet_rows(rng, T, V)
+        assert np.all(P.astype(np.float64).sum(axis=1) == 1.0)
+        tok = rng.integers(0, V, T).astype(np.int32)
+        u, uf, cu = rng.random(T), rng.random(1), np.array([0, T], np.int32)
+        try:
+            want = vo.accept_sampling(parent, cu, tok, P, Q, u, uf)
+        except ValueError:
+            continue
+        assert vo.accept_sampling(parent, cu, tok, P, Q, u, uf, unit_rows=True) == want
+    differs = 0
+    for _ in range(300):
+        T = int(rng.integers(1, 9))
+        parent = np.arange(-1, T - 1, dtype=np.int32)
+        # (rows that sum to 0.7: the reading must not look at their sums, and the default reading decides otherwise)
+        P, Q = (0.7 * dirichlet_rows(rng, T, V)).astype(np.float32), dirichlet_rows(rng, T, V)
+        tok = np.array([0] + [int(rng.choice(V, p=Q[i - 1].astype(np.float64) / Q[i - 1].astype(np.float64).sum()))
+                              for i in range(1, T)], np.int32)
+        u, uf = rng.random(T), rng.random(1)
+        try:
+            paths, nxt = vo.accept_sampling(parent, np.array([0, T], np.int32), tok, P, Q, u, uf, unit_rows=True)
+        except ValueError:
+            continue
+        differs += vo.accept_sampling(parent, np.array([0, T], np.int32), tok, P, Q, u, uf)[0] != paths
+        n_acc, dist = 1, P[0].astype(np.float64)
+        for i in range(1, T):
+            p, q, x = P[i - 1].astype(np.float64), Q[i - 1].astype(np.float64), int(tok[i])
+            if u[i] <= min(1.0, p[x] / q[x]):
+                n_acc += 1
+                dist = P[i].astype(np.float64)
+            else:
+                dist = np.maximum(0.0, p - q)
+                break
+        assert paths[0] == list(range(n_acc))
+        cs = np.cumsum(dist / dist.sum())
+        if np.min(np.abs(cs - uf[0])) > 1e-6:
+            assert nxt[0] == int(np.searchsorted(cs, uf[0], side="right"))
+    assert differs > 20
+    N, k, V = 100000, 3, 6
+    p, q = dirichlet_rows(rng, 1, V)[0], dirichlet_rows(rng, 1, V)[0]
+    parent = np.tile(np.array([-1] + [0] * k, np.int32), N)
+    cu = (np.arange(N + 1) * (k + 1)).astype(np.int32)
+    tok = np.zeros((N, k + 1), np.int32)
+    tok[:, 1:] = rng.choice(V, size=(N, k), p=q.astype(np.float64) / q.astype(np.float64).sum())
+    P, Q = np.tile(p, ((k + 1) * N, 1)), np.tile(q, ((k + 1) * N, 1))
+    paths, nxt = vo.accept_sampling(parent, cu, tok.reshape(-1), P, Q, rng.random((k + 1) * N), rng.random(N), unit_rows=True)
+    first = np.array([tok[i, pth[1]] if len(pth) > 1 else nxt[i] for i, pth in enumerate(paths)])
+    freq = np.bincount(first, minlength=V) / N
+    sigma = np.sqrt(p.astype(np.float64) * (1 - p.astype(np.float64)) / N)
+    assert np.all(np.abs(freq - p) <= 5 * sigma + 1e-6), (freq, p)
+
+
 def test_sampling_special_cases():
     rng = np.random.Generator(np.random.PCG64(33))
     V = 9
