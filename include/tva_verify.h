@@ -78,6 +78,13 @@ int tva_accept_greedy(const int32_t *parent, const int32_t *cu_T, const int32_t 
  *                       whole chip, and the walk passes an accepted node without a pass over its row (V = 128256,
  *                       B = 1 .. 8: 6 to 26 % faster again).  A value that is not cu_T[B] costs time, not correctness:
  *                       rows past cu_T[B] are not read, and a tree that reaches past sum_T is walked as without it.
+ *   unit_rows           1: the caller states that every row of p_target sums to one (it is a distribution), and a node
+ *                       that has just been reached takes Z = 1 instead of summing its row: its children's tests are
+ *                       then u q(x) <= p(x) and the first residual max(0, p - q), as the paper prints them, and an
+ *                       accepted node costs two loads instead of a pass over V floats, at any batch size (B = 64,
+ *                       V = 128256: 76 -> 54 us; B = 8, 32-node trees: 45 -> 28 us).  The last draw still divides by the sum of the row it draws from.
+ *                       With rows that sum to one within float32 rounding the two forms differ only where a test is
+ *                       within that rounding of its threshold.  0: rows are summed.
  *   workgroups_per_sequence   0: the library chooses (1 .. 16, so that B times it stays within 256; 1 for
  *                       vocabularies below 48 K tokens, where the waits cost what the slices save -- below 16 K when
  *                       the row sums are made ahead, see sum_T); 1: as without
@@ -94,6 +101,7 @@ typedef struct tva_sample_args {
   size_t workspace_bytes;
   int32_t workgroups_per_sequence;
   int32_t sum_T;
+  int32_t unit_rows;
 } tva_sample_args;
 
 int tva_accept_sampling(const tva_sample_args *a, void *stream);

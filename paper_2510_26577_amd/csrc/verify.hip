@@ -80,6 +80,7 @@ struct SampleParams {
   // dependent access to a row of its own)
   const float *first;
   int pieces, sum_T;
+  int unit_rows;  // every target row is taken to sum to one: a freshly reached node's normaliser is 1, not summed
 };
 
 constexpr int kSampleThreads = 1024, kSampleWaves = kSampleThreads / 64;
@@ -390,7 +391,8 @@ __global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SamplePara
     float rx0 = 0.f, qx = 0.f;
     if (c >= 0 && ahead) rx0 = p.first[2 * (size_t)(t0 + c)], qx = p.first[2 * (size_t)(t0 + c) + 1];
     else if (c >= 0) rx0 = dist[token[c]], qx = q[token[c]];
-    if (ahead) Z = summed_ahead(p, t0 + cur), segments = false;
+    if (p.unit_rows) Z = 1.0, segments = false;
+    else if (ahead) Z = summed_ahead(p, t0 + cur), segments = false;
     else Z = row_sum<VEC>(V, seg, wsum, dist), segments = true;
     double rx = (double)rx0;
     bool accepted = false;
@@ -424,7 +426,10 @@ __global__ void __launch_bounds__(kSampleThreads) sample_kernel(const SamplePara
     if (!accepted) break;
   }
   if (tid == 0) p.path_len[b] = len;
-  if (!segments) return draw_in_piece<VEC>(p, t0 + cur, dist, Z, (double)p.u_final[b], wsum, &p.next_token[b]);
+  // (the last draw divides by the sum of what it draws from: a row that was taken as summing to one is summed here --
+  // from its pieces where those were made ahead -- and one whose pieces were not made ahead is passed over)
+  if (!segments && ahead) return draw_in_piece<VEC>(p, t0 + cur, dist, summed_ahead(p, t0 + cur), (double)p.u_final[b], wsum, &p.next_token[b]);
+  if (!segments) Z = row_sum<VEC>(V, seg, wsum, dist);
   // The last token: the smallest v whose cumulative weight exceeds u_final * Z.  The segments' sums of the pass
   // that produced Z say which segment holds it.
   draw_in_range(dist, 0, V, seg, wsum, 0.0, (double)p.u_final[b] * Z, false, &p.next_token[b]);
@@ -574,7 +579,8 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
     float rx0 = 0.f, qx = 0.f;
     if (c >= 0 && ahead) rx0 = p.first[2 * (size_t)(t0 + c)], qx = p.first[2 * (size_t)(t0 + c) + 1];
     else if (c >= 0) rx0 = prow[token[c]], qx = q[token[c]];
-    if (ahead) Z = summed_ahead(p, t0 + cur), segments = false;
+    if (p.unit_rows) Z = 1.0, segments = false;
+    else if (ahead) Z = summed_ahead(p, t0 + cur), segments = false;
     else Z = row_total(prow), segments = true;
     if (Z < 0.0) return leave_flagged();
     bool accepted = false;
@@ -642,9 +648,13 @@ __global__ void __launch_bounds__(kSampleThreads) sample_coop_kernel(const CoopP
     if (!accepted) break;
   }
   if (w == 0 && tid == 0) p.path_len[b] = len;
-  if (!segments) {  // (the walk ends at a node whose row was summed ahead: one workgroup draws, from one piece of the row)
-    if (w == 0) draw_in_piece<VEC>(p, t0 + cur, dist, Z, (double)p.u_final[b], wsum, &p.next_token[b]);
+  if (!segments && ahead) {  // (the walk ends at a node whose row was summed ahead: one workgroup draws, from one piece of the row)
+    if (w == 0) draw_in_piece<VEC>(p, t0 + cur, dist, summed_ahead(p, t0 + cur), (double)p.u_final[b], wsum, &p.next_token[b]);
     return;
+  }
+  if (!segments) {  // (a row taken as summing to one, its pieces not made ahead: the last draw sums it)
+    Z = row_total(dist);
+    if (Z < 0.0) return leave_flagged();
   }
   // The last token: the workgroup whose slice holds the smallest v with cumulative weight above u_final * Z, then
   // the wave of it whose segment does.
@@ -828,6 +838,7 @@ static int accept_sampling_impl(const tva_sample_args *a, void *stream, int miss
   p.path = a->path, p.path_len = a->path_len, p.next_token = a->next_token, p.err_flag = a->err_flag;
   p.V = a->V, p.max_path = a->max_path;
   p.rowpart = nullptr, p.first = nullptr, p.pieces = row_pieces(a->V), p.sum_T = 0;
+  p.unit_rows = a->unit_rows != 0;
   // groups of four need every row to start on 16 bytes
   const bool vec = a->V % 4 == 0 && (((uintptr_t)a->p_target | (uintptr_t)a->q_draft | (uintptr_t)a->residual) & 15) == 0;
   if (a->sum_T < 0) return TVA_INVALID_ARG;

@@ -30,7 +30,8 @@ class SampleArgs(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("V", ctypes.c_int32), ("max_path", ctypes.c_int32)] + \
                [(n, ctypes.c_void_p) for n in ("parent", "cu_T", "draft_token", "p_target", "q_draft", "u", "u_final",
                                                "residual", "path", "path_len", "next_token", "err_flag", "workspace")] + \
-               [("workspace_bytes", ctypes.c_size_t), ("workgroups_per_sequence", ctypes.c_int32), ("sum_T", ctypes.c_int32)]
+               [("workspace_bytes", ctypes.c_size_t), ("workgroups_per_sequence", ctypes.c_int32), ("sum_T", ctypes.c_int32),
+                ("unit_rows", ctypes.c_int32)]
 
 
 def _lib():
@@ -79,7 +80,7 @@ def accept_greedy(parent, cu_T, draft_token, target_token, max_path: int, path=N
 
 def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, max_path: int, residual=None,
                     err_flag=None, stream=None, workspace="auto", workgroups_per_sequence: int = 0, wait_bound_test_spins: int = 0,
-                    sum_T: int = 0):
+                    sum_T: int = 0, unit_rows: bool = False):
     """Device tensors in (int32 trees and tokens, float32 distributions [sum_T, V] and uniform numbers); returns
     (path [B, max_path], path_len [B], next_token [B]).  workspace: "auto" allocates the one that lets several
     workgroups share a sequence (and, with sum_T, holds the row sums made ahead of the walk), None runs one
@@ -105,6 +106,7 @@ def accept_sampling(parent, cu_T, draft_token, p_target, q_draft, u, u_final, ma
         a.workspace, a.workspace_bytes = _p(workspace), workspace.numel() * workspace.element_size()
     a.workgroups_per_sequence = int(workgroups_per_sequence)
     a.sum_T = int(sum_T)
+    a.unit_rows = int(bool(unit_rows))
     if wait_bound_test_spins:                 # (tests of the bounded wait: every wait misses one arrival and gives up)
         _check(_lib().tva_accept_sampling_wait_bound_test(ctypes.byref(a), int(wait_bound_test_spins), _stream_ptr(stream)))
     else:
@@ -358,10 +360,11 @@ def _bench_sampling(steps: int) -> None:
             for k in cases:
                 accept_sampling(k["parent"], k["cu_T"], k["tok"], k["p"], k["q"], k["u"], k["uf"], depth + 1,
                                 residual=k["residual"], err_flag=k["flag"], stream=stream,
-                                workspace=None if form == "one" else k["ws"], sum_T=B * T if form == "ahead" else 0)
+                                workspace=None if form == "one" else k["ws"], sum_T=B * T if form in ("ahead", "unit") else 0,
+                                unit_rows=form == "unit")
 
         times = {}
-        for shared in ("ahead", "shared", "one"):
+        for shared in ("unit", "ahead", "shared", "one"):
             with torch.cuda.stream(stream):
                 run(shared)
                 stream.synchronize()
@@ -383,7 +386,8 @@ def _bench_sampling(steps: int) -> None:
             assert all(int(k["flag"].item()) == 0 for k in cases)
         moved = 4.0 * V * (sums + 3 * rejs + B / 16.0)   # a sum reads a row; a residual reads two and writes one; the draw a segment
         print(json.dumps({"shape": name, "accepted_nodes_per_step": sums, "refused_children_per_step": rejs,
-                          "sampling_us": times["ahead"], "sampling_us_without_the_node_count": times["shared"],
+                          "sampling_us": times["ahead"], "sampling_us_rows_taken_as_distributions": times["unit"],
+                          "sampling_us_without_the_node_count": times["shared"],
                           "sampling_us_one_workgroup_per_sequence": times["one"],
                           "vocabulary_bytes": moved, "GBps": moved / (times["shared"] * 1e-6) / 1e9}), flush=True)
         del cases

@@ -545,7 +545,8 @@ def test_commit_of_an_8bit_cache(torch_dev, page_size):
 
 # ---- acceptance by speculative sampling ----
 
-def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True, misalign=False, workgroups=0, sum_T=0):
+def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True, misalign=False, workgroups=0, sum_T=0,
+                 unit_rows=False):
     """workgroups: 0 = the library spreads a sequence over as many workgroups as it sees fit, 1 = one per sequence
     (no workspace passed, unless sum_T asks for the row sums ahead of the walk), 2 .. 16 = that many.
     sum_T: the host's count of nodes (0 = not given: no row sums ahead of the walk)."""
@@ -564,12 +565,12 @@ def run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, with_flag=True
     path, n, nxt = verify.accept_sampling(d(parent, np.int32), d(cu_T, np.int32), d(tok, np.int32), dp,
                                           dq, d(u, np.float32), d(uf, np.float32), max_path, err_flag=flag,
                                           workspace=None if workgroups == 1 and not sum_T else "auto",
-                                          workgroups_per_sequence=workgroups, sum_T=sum_T)
+                                          workgroups_per_sequence=workgroups, sum_T=sum_T, unit_rows=unit_rows)
     torch.cuda.synchronize()
     return path.cpu().numpy(), n.cpu().numpy(), nxt.cpu().numpy(), (int(flag.item()) if with_flag else 0)
 
 
-def sampling_margin(parent, cu_T, tok, p, q, u, uf, paths, nxt):
+def sampling_margin(parent, cu_T, tok, p, q, u, uf, paths, nxt, unit_rows=False):
     """Smallest relative distance of any decision the oracle took from its threshold (both sides decide in fp64 on the
     same fp32 data, but sum in different orders: a decision closer than that rounding to its threshold may differ)."""
     # the cases below are seeded: the margin is asserted, so a case on a threshold would be seen, not hidden
@@ -580,7 +581,7 @@ def sampling_margin(parent, cu_T, tok, p, q, u, uf, paths, nxt):
             continue
         for cur in path:
             r = p[t0 + cur].astype(np.float64)
-            Z = r.sum()
+            Z = 1.0 if unit_rows else r.sum()
             qq = q[t0 + cur].astype(np.float64)
             for c in range(cur + 1, T):
                 if parent[t0 + c] != cur:
@@ -612,25 +613,26 @@ def test_accept_sampling_matches_oracle(torch_dev, B, T_hi, V, temp, drift):
     p, q, tok, u, uf = wl.sampling_inputs(rng, parent, cu_T, V, temperature=temp, drift=drift)
     say(f"[case] accept_sampling B={B} T<={T_hi} V={V} temp={temp} drift={drift}")
     longest = 0
-    for max_path in (int(T.max()) + 1, 3, 1):
-        ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf, max_path=max_path)
-        assert sampling_margin(parent, cu_T, tok, p, q, u, uf, ref_paths, ref_next) > 1e-9
-        for workgroups in (0, 1, 2, 16) if max_path != 3 else (0, 1):
+    for max_path, unit in ((int(T.max()) + 1, False), (3, False), (1, False), (int(T.max()) + 1, True), (2, True)):
+        # unit: the target rows taken as distributions (a freshly reached node's normaliser is 1)
+        ref_paths, ref_next = vo.accept_sampling(parent, cu_T, tok, p, q, u, uf, max_path=max_path, unit_rows=unit)
+        assert sampling_margin(parent, cu_T, tok, p, q, u, uf, ref_paths, ref_next, unit_rows=unit) > 1e-9
+        for workgroups in (0, 1, 2, 16) if max_path not in (2, 3) else (0, 1):
             if B * workgroups > 256:
                 continue
             # the row sums made ahead of the walk (the host's node count given): the right count, one that is too
             # small (the trees past it are walked without) and one that is too large (no row is read past the last)
             for sum_T in (0, int(cu_T[-1])) + ((int(cu_T[-1]) // 2 + 1, int(cu_T[-1]) + 37) if workgroups in (0, 2) else ()):
                 path, n, nxt, flag = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, workgroups=workgroups,
-                                                  sum_T=sum_T)
-                case = (workgroups, sum_T)
+                                                  sum_T=sum_T, unit_rows=unit)
+                case = (workgroups, sum_T, unit)
                 assert flag == 0, case
                 assert list(n) == [len(x) for x in ref_paths], case
                 assert list(nxt) == ref_next, case
                 for b, x in enumerate(ref_paths):
                     assert list(path[b, :len(x)]) == x, case
         longest = max(longest, max(len(x) for x in ref_paths))
-        if max_path == 3 and V % 4 == 0:         # rows that do not start on 16 bytes take the one-element path
+        if max_path == 3 and not unit and V % 4 == 0:   # rows that do not start on 16 bytes take the one-element path
             path2, n2, nxt2, flag2 = run_sampling(torch, parent, cu_T, tok, p, q, u, uf, max_path, misalign=True)
             assert flag2 == 0 and np.array_equal(n, n2) and np.array_equal(nxt, nxt2) and np.array_equal(path, path2)
     if T_hi >= 8 and drift <= 1.0:
