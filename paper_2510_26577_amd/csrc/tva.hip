@@ -1201,6 +1201,10 @@ bool make_plan(const tva_args *a, Plan *pl) {
   const int s128 = n128 * 3 >= 512 ? 1 : 256 / (n128 > 0 ? n128 : 1);
   int variant = V_M2K2;
   if (rows <= 32) variant = V_K2;
+  // (the draft stage's attention of one or two sequences -- queries are the newest nodes, at most 48 rows per KV head:
+  // two 32-row workgroups, the second three quarters empty, beat one of 64 rows by 0.4 .. 1.1 us of 12; from eight
+  // sequences on the 64-row shape wins)
+  else if (a->cu_Q && rows <= 48 && pairs <= 16) variant = V_K2;
   else if (rows >= 128) {
     if (n128 >= 96 && n128 <= 256 && (s128 == 1 || a->max_L / s128 >= 16 * 64)) variant = V_M4K2;
     else if (n128 > 256 || keys >= (512 << 10) || (keys >= (256 << 10) && a->max_L >= 4096)) variant = V_W8;

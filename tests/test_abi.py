@@ -323,6 +323,22 @@ def test_slot_table_is_a_permutation_that_pairs_long_with_short(lib):
     assert lib.tva_plan_slot_sequences(ctypes.byref(shape_args()), None) == -1
 
 
+def test_draft_stage_queries_of_one_or_two_sequences_take_32_row_workgroups(lib):
+    """Queries restricted to the newest nodes (cu_Q), at most 48 rows per KV head, one or two sequences: 32-row
+    workgroups; from there on, and for the verification's own calls, the 64-row shape as before."""
+    import numpy as np
+    dummy = np.zeros(4, np.int32)                              # (plan queries read shapes only)
+    def rows(B, max_Q, with_cu_Q=True):
+        a = shape_args(B=B, max_L=1024, max_T=60, sum_T=60 * B)
+        if with_cu_Q:
+            a.cu_Q, a.sum_Q, a.max_Q = dummy.ctypes.data_as(ctypes.c_void_p), max_Q * B, max_Q
+        return binding.plan_workgroup_rows(a)
+    assert rows(1, 12) == 32 and rows(2, 12) == 32 and rows(1, 9) == 32
+    assert rows(3, 12) == 64 and rows(8, 12) == 64 and rows(1, 13) == 64
+    assert rows(1, 8) == 32                                    # (32 rows or fewer: as always)
+    assert rows(1, 12, with_cu_Q=False) >= 64                  # all 60 nodes as queries: 240 rows
+
+
 def test_fp8_arguments_checked_on_the_host(lib):
     assert binding.plan_splits(shape_args(kv_fp8=1)) >= 1                         # D = 128: fine
     a = shape_args(kv_fp8=1, D=64)
